@@ -1,0 +1,133 @@
+/*
+ * tvprox -- batched total-variation proximal operators for AMD MI355X (gfx950).
+ *
+ * C ABI.  Every data pointer is a DEVICE pointer to fp32 data owned by the
+ * caller; the library allocates nothing, keeps no state between calls, and only
+ * enqueues kernels on the stream it is given (asynchronous, no implicit sync).
+ * Every function returns a tv_status; argument validation happens before any
+ * HIP call, so invalid calls fail the same way on a machine without a GPU.
+ *
+ * Letters: y = input, x = output, lam = lambda.  (The paper's Eq. 1 writes the
+ * input as x and the output as y.)
+ *
+ *   1D operator (paper Eq. 1):  x* = argmin_x 1/2||x - y||^2 + lam * sum_k |x[k+1] - x[k]|
+ *   solved per row by projected Newton on the box-constrained dual (paper Eq. 3-4);
+ *   backward by implicit differentiation (paper Eq. 5-6);
+ *   2D anisotropic operator (paper Eq. 2) by K sweeps of proximal Dykstra (paper Alg. 1).
+ */
+#ifndef TVPROX_H
+#define TVPROX_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Same declaration as HIP's own; repeated so that plain C callers need no HIP header. */
+struct ihipStream_t;
+typedef struct ihipStream_t *hipStream_t;
+
+typedef enum {
+    TV_OK = 0,
+    TV_ERR_NULL = 1,        /* a required pointer is NULL                              */
+    TV_ERR_SHAPE = 2,       /* negative count, length < 1, sweeps < 1, size overflow   */
+    TV_ERR_STRIDE = 3,      /* negative or zero stride where rows would overlap        */
+    TV_ERR_LAMBDA = 4,      /* lam.count < 1 or lam.div < 1                            */
+    TV_ERR_WORKSPACE = 5,   /* workspace NULL, misaligned or too small                 */
+    TV_ERR_UNSUPPORTED = 6, /* row length above TV_MAX_LENGTH                          */
+    TV_ERR_HIP = 7          /* a HIP runtime call (kernel launch) failed               */
+} tv_status;
+
+/* Longest row any entry point accepts. */
+#define TV_MAX_LENGTH 16384
+
+/*
+ * A batch of rows inside a dense fp32 buffer; all strides in ELEMENTS.
+ * Row id r = outer * n_inner + inner starts at
+ *     base + outer * outer_stride + inner * inner_stride
+ * and its k-th sample is elem_stride * k further on (k = 0 .. length-1).
+ * Examples for a [P, H, W] tensor:
+ *   rows    (along W): { P, H*W, H, W, W, 1 }
+ *   columns (along H): { P, H*W, W, 1, H, W }
+ * Rows must not overlap each other.
+ */
+typedef struct {
+    int64_t n_outer, outer_stride;
+    int64_t n_inner, inner_stride;
+    int64_t length, elem_stride;
+} tv_rows;
+
+/*
+ * lam: device pointer to `count` floats.  Row r uses lam[(r / div) % count].
+ *   scalar: count = 1.   per-row: count = number of rows, div = 1.
+ *   per-channel over [B, C, H, W]: count = C, div = H for the row pass (W for columns).
+ * A negative or NaN lam read on the device is treated as 0 (the identity, paper Sec. 3.1).
+ */
+typedef struct {
+    const float *lam;
+    int64_t count;
+    int64_t div;
+} tv_lambda;
+
+/*
+ * Forward 1D prox over a batch of rows (paper Eq. 1, solved through Eq. 3-4).
+ * x may alias y exactly (same pointer, same layout); any other overlap is undefined.
+ * length == 1 copies the row.  Zero rows: TV_OK without a launch.
+ * A row whose input holds NaN/Inf gets unspecified values in that row (NaN at least at
+ * the non-finite samples); other rows are unaffected and the call still terminates.
+ * Within a maximal constant run of the result all samples are bit-identical, which
+ * is what tv1d_prox_bwd relies on to recover the segments.
+ */
+int tv1d_prox_fwd(const float *y, float *x, tv_rows rows, tv_lambda lam, hipStream_t stream);
+
+/*
+ * As tv1d_prox_fwd, and additionally writes one int32 per row to `info` (device
+ * pointer, n_outer*n_inner entries, may be NULL): bits 0..15 = Newton steps taken,
+ * bit 16 = stopped on the optimality test, bit 17 = stopped because a step left
+ * the dual unchanged, bit 18 = iteration cap reached.
+ */
+int tv1d_prox_fwd_info(const float *y, float *x, int32_t *info, tv_rows rows, tv_lambda lam,
+                       hipStream_t stream);
+
+/*
+ * Backward of tv1d_prox_fwd (paper Eq. 5-6, evaluated as segment averaging).
+ *   g_up:     upstream gradient dL/dx, laid out like x.
+ *   x:        the OUTPUT of tv1d_prox_fwd for the same rows and lam.
+ *   grad_y:   receives dL/dy (may alias g_up exactly).
+ *   grad_lam: lam.count floats, OVERWRITTEN with dL/dlam summed over the rows of each
+ *             slot; may be NULL (then ws may be NULL too).
+ *   ws:       scratch of at least tv1d_bwd_workspace_bytes() bytes, 16-byte aligned;
+ *             contents undefined afterwards.  lam.lam itself is not read.
+ */
+int tv1d_prox_bwd(const float *g_up, const float *x, float *grad_y, float *grad_lam,
+                  tv_rows rows, tv_lambda lam, void *ws, size_t ws_bytes, hipStream_t stream);
+size_t tv1d_bwd_workspace_bytes(tv_rows rows, tv_lambda lam);
+
+/*
+ * 2D anisotropic TV prox on `planes` images of H x W (row-major, contiguous) by
+ * `sweeps` iterations of paper Alg. 1; plane p uses lam[p % count] (lam.div is
+ * ignored).  ws keeps every pass's output (2*sweeps tensors) plus two scratch
+ * tensors, and must be handed unchanged to tv2d_prox_bwd.  x must not alias y.
+ */
+size_t tv2d_workspace_bytes(int64_t planes, int64_t H, int64_t W, int sweeps);
+int tv2d_prox_fwd(const float *y, float *x, int64_t planes, int64_t H, int64_t W,
+                  tv_lambda lam, int sweeps, void *ws, size_t ws_bytes, hipStream_t stream);
+
+/*
+ * Reverse sweep through paper Alg. 1 (replaces autograd through the loop, paper
+ * Sec. 3.2).  ws is the buffer tv2d_prox_fwd filled; its two scratch tensors are
+ * overwritten, the saved pass outputs are only read.  grad_lam (lam.count floats,
+ * overwritten) may be NULL.  grad_y must not alias g_up.
+ */
+int tv2d_prox_bwd(const float *g_up, float *grad_y, float *grad_lam, int64_t planes, int64_t H,
+                  int64_t W, tv_lambda lam, int sweeps, void *ws, size_t ws_bytes,
+                  hipStream_t stream);
+
+const char *tv_status_str(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TVPROX_H */

@@ -1,0 +1,70 @@
+// Shared device-side types for the TV-prox kernels (gfx950 / CDNA4, wave64).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace tvk {
+
+// Solver constants.  The paper fixes none of them (Sec. 3.2 only names the Armijo
+// rule with quadratic-interpolation backtracking); these are the values chosen here.
+constexpr int   kMaxNewtonSteps  = 48;      // iteration cap per row
+constexpr int   kMaxBacktracks   = 24;      // line-search rounds per Newton step
+constexpr float kArmijoSigma     = 1e-4f;   // sufficient-decrease fraction
+constexpr float kArmijoSlackEps  = 4.0f * 1.1920929e-7f;  // slack = this * |f|
+
+// info word written per row by the *_info entry point
+constexpr int kInfoConverged = 1 << 16;
+constexpr int kInfoStalled   = 1 << 17;
+constexpr int kInfoCapped    = 1 << 18;
+
+// Row addressing, mirrored from tv_rows / tv_lambda (host guarantees the 32-bit fields fit).
+struct Layout {
+    uint32_t n_rows;
+    uint32_t n_inner;
+    int64_t  outer_stride;
+    int64_t  inner_stride;
+    int64_t  elem_stride;
+    int32_t  n;            // row length
+    uint32_t lam_count;
+    uint32_t lam_div;
+};
+
+__device__ __forceinline__ int64_t row_offset(const Layout &L, uint32_t r)
+{
+    uint32_t o = r / L.n_inner;
+    uint32_t i = r - o * L.n_inner;
+    return (int64_t)o * L.outer_stride + (int64_t)i * L.inner_stride;
+}
+
+__device__ __forceinline__ uint32_t lam_slot(const Layout &L, uint32_t r)
+{
+    if (L.lam_count == 1) return 0;
+    return (r / L.lam_div) % L.lam_count;
+}
+
+// Negative and NaN lambdas act as 0 (fmaxf returns the non-NaN operand).
+__device__ __forceinline__ float load_lambda(const float *lam, const Layout &L, uint32_t r)
+{
+    return fmaxf(lam[lam_slot(L, r)], 0.0f);
+}
+
+struct FwdParams {
+    const float *y;        // input rows
+    const float *addend;   // optional: the prox input is y + addend (Dykstra correction term)
+    float       *x;        // output rows
+    float       *resid;    // optional: receives (y + addend) - x  (next correction term)
+    const float *lam;
+    int32_t     *info;     // optional per-row info word
+    Layout       L;
+};
+
+struct BwdParams {
+    const float *g;        // upstream gradient
+    const float *sub;      // optional: the averaged quantity is g - sub, and sub is added back
+    const float *x;        // forward output (defines the segments)
+    float       *gy;       // output
+    float       *partial;  // optional: per-row dL/dlam contribution
+    Layout       L;
+};
+
+}  // namespace tvk

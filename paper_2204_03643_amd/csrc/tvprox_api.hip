@@ -1,0 +1,384 @@
+// C-ABI entry points of the TV-prox library: argument validation, path selection and
+// kernel launches.  Nothing here allocates, synchronises or keeps state.
+#include "../../include/tvprox.h"
+
+#include <hip/hip_runtime.h>
+
+#include "tv_common.hpp"
+#include "tv_long.hpp"
+#include "tv_short.hpp"
+
+namespace {
+
+using tvk::BwdParams;
+using tvk::FwdParams;
+using tvk::Layout;
+
+constexpr int64_t kMaxRows = 0x7fffffff;
+
+inline size_t align16(size_t b) { return (b + 15) & ~(size_t)15; }
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+// ---- validation -------------------------------------------------------------------
+
+// Checks the row set; on TV_OK with *n_rows == 0 there is nothing to do.
+int check_rows(const tv_rows &r, int64_t *n_rows)
+{
+    *n_rows = 0;
+    if (r.n_outer < 0 || r.n_inner < 0 || r.length < 1) return TV_ERR_SHAPE;
+    if (r.n_outer == 0 || r.n_inner == 0) return TV_OK;
+    if (r.n_outer > kMaxRows || r.n_inner > kMaxRows || r.n_outer * r.n_inner > kMaxRows)
+        return TV_ERR_SHAPE;
+    // Non-overlap: with the (stride, extent) pairs sorted by stride, every stride must
+    // cover the full span of the faster-varying ones.
+    int64_t st[3] = {r.elem_stride, r.inner_stride, r.outer_stride};
+    int64_t ex[3] = {r.length, r.n_inner, r.n_outer};
+    int cnt = 0;
+    int64_t s[3], e[3];
+    for (int i = 0; i < 3; ++i)
+        if (ex[i] > 1) {
+            if (st[i] < 1) return TV_ERR_STRIDE;
+            s[cnt] = st[i]; e[cnt] = ex[i]; ++cnt;
+        }
+    for (int i = 0; i < cnt; ++i)
+        for (int j = i + 1; j < cnt; ++j)
+            if (s[j] < s[i]) {
+                int64_t t = s[i]; s[i] = s[j]; s[j] = t;
+                t = e[i]; e[i] = e[j]; e[j] = t;
+            }
+    int64_t span = 1;
+    for (int i = 0; i < cnt; ++i) {
+        if (s[i] < span) return TV_ERR_STRIDE;
+        if (e[i] > (INT64_MAX / 8) / s[i]) return TV_ERR_SHAPE;
+        span = s[i] * e[i];
+    }
+    *n_rows = r.n_outer * r.n_inner;
+    return TV_OK;
+}
+
+int check_lambda(const tv_lambda &l)
+{
+    if (l.count < 1 || l.div < 1 || l.count > kMaxRows || l.div > kMaxRows) return TV_ERR_LAMBDA;
+    return TV_OK;
+}
+
+Layout make_layout(const tv_rows &r, const tv_lambda &l, int64_t n_rows)
+{
+    Layout L;
+    L.n_rows = (uint32_t)n_rows;
+    L.n_inner = (uint32_t)r.n_inner;
+    L.outer_stride = r.outer_stride;
+    L.inner_stride = r.inner_stride;
+    L.elem_stride = r.elem_stride;
+    L.n = (int32_t)r.length;
+    L.lam_count = (uint32_t)l.count;
+    L.lam_div = (uint32_t)l.div;
+    return L;
+}
+
+// Rows are "packed" when row r starts exactly r*length elements after the base.
+bool rows_packed(const tv_rows &r)
+{
+    if (r.length > 1 && r.elem_stride != 1) return false;
+    if (r.n_inner > 1 && r.inner_stride != r.length) return false;
+    if (r.n_outer > 1 && r.outer_stride != r.n_inner * r.length) return false;
+    return true;
+}
+
+int launch_status()
+{
+    return hipGetLastError() == hipSuccess ? TV_OK : TV_ERR_HIP;
+}
+
+// ---- short rows: one row per lane ---------------------------------------------------
+
+template <int NMAX>
+int launch_fwd_short(const FwdParams &p, bool packed_ok, hipStream_t s)
+{
+    const dim3 grid((p.L.n_rows + tvk::kShortBlock - 1) / tvk::kShortBlock), block(tvk::kShortBlock);
+    const bool full = p.L.n == NMAX;
+    if (full && packed_ok)
+        hipLaunchKernelGGL((tvk::tv1d_fwd_short_kernel<NMAX, true, true>), grid, block, 0, s, p);
+    else if (full)
+        hipLaunchKernelGGL((tvk::tv1d_fwd_short_kernel<NMAX, true, false>), grid, block, 0, s, p);
+    else
+        hipLaunchKernelGGL((tvk::tv1d_fwd_short_kernel<NMAX, false, false>), grid, block, 0, s, p);
+    return launch_status();
+}
+
+template <int NMAX>
+int launch_bwd_short(const BwdParams &p, bool packed_ok, hipStream_t s)
+{
+    const dim3 grid((p.L.n_rows + tvk::kShortBlock - 1) / tvk::kShortBlock), block(tvk::kShortBlock);
+    const bool full = p.L.n == NMAX;
+    if (full && packed_ok)
+        hipLaunchKernelGGL((tvk::tv1d_bwd_short_kernel<NMAX, true, true>), grid, block, 0, s, p);
+    else if (full)
+        hipLaunchKernelGGL((tvk::tv1d_bwd_short_kernel<NMAX, true, false>), grid, block, 0, s, p);
+    else
+        hipLaunchKernelGGL((tvk::tv1d_bwd_short_kernel<NMAX, false, false>), grid, block, 0, s, p);
+    return launch_status();
+}
+
+// ---- dispatch ---------------------------------------------------------------------
+
+int run_fwd(const float *y, const float *addend, float *x, float *resid, int32_t *info,
+            const tv_rows &r, const tv_lambda &l, int64_t n_rows, hipStream_t s)
+{
+    FwdParams p;
+    p.y = y; p.addend = addend; p.x = x; p.resid = resid; p.lam = l.lam; p.info = info;
+    p.L = make_layout(r, l, n_rows);
+    const bool packed = rows_packed(r) && aligned16(y) && aligned16(x) &&
+                        (!addend || aligned16(addend)) && (!resid || aligned16(resid));
+    if (r.length <= 8) return launch_fwd_short<8>(p, packed, s);
+    if (r.length <= 16) return launch_fwd_short<16>(p, packed, s);
+    if (r.length <= 32) return launch_fwd_short<32>(p, packed, s);
+    return tvk::launch_fwd_long(p, s) == hipSuccess ? TV_OK : TV_ERR_HIP;
+}
+
+// Sums the per-row dL/dlam contributions of every slot: one workgroup per slot.
+__global__ __launch_bounds__(256) void reduce_lambda_kernel(const float *__restrict__ partial,
+                                                            float *__restrict__ grad_lam,
+                                                            uint32_t n_rows, uint32_t count,
+                                                            uint32_t div, int accumulate)
+{
+    __shared__ double red[256];
+    const uint32_t slot = blockIdx.x;
+    double acc = 0.0;
+    // rows of this slot: r = (q*count + slot)*div + i,  i < div,  q = 0, 1, ...
+    const uint64_t groups = ((uint64_t)n_rows + div - 1) / div;           // row groups of size div
+    const uint64_t mine = groups > slot ? (groups - slot + count - 1) / count : 0;
+    const uint64_t total = mine * div;
+    for (uint64_t j = threadIdx.x; j < total; j += 256) {
+        const uint64_t q = j / div, i = j - q * div;
+        const uint64_t r = (q * count + slot) * div + i;
+        if (r < n_rows) acc += (double)partial[r];
+    }
+    red[threadIdx.x] = acc;
+    __syncthreads();
+    for (int w = 128; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w) red[threadIdx.x] += red[threadIdx.x + w];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        const float v = (float)red[0];
+        grad_lam[slot] = accumulate ? grad_lam[slot] + v : v;
+    }
+}
+
+int run_bwd(const float *g, const float *sub, const float *x, float *gy, float *grad_lam,
+            int accumulate, const tv_rows &r, const tv_lambda &l, int64_t n_rows, float *partial,
+            hipStream_t s)
+{
+    BwdParams p;
+    p.g = g; p.sub = sub; p.x = x; p.gy = gy; p.partial = grad_lam ? partial : nullptr;
+    p.L = make_layout(r, l, n_rows);
+    const bool packed = rows_packed(r) && aligned16(g) && aligned16(x) && aligned16(gy) &&
+                        (!sub || aligned16(sub));
+    int st;
+    if (r.length <= 8) st = launch_bwd_short<8>(p, packed, s);
+    else if (r.length <= 16) st = launch_bwd_short<16>(p, packed, s);
+    else if (r.length <= 32) st = launch_bwd_short<32>(p, packed, s);
+    else st = tvk::launch_bwd_long(p, s) == hipSuccess ? TV_OK : TV_ERR_HIP;
+    if (st != TV_OK) return st;
+    if (grad_lam) {
+        hipLaunchKernelGGL(reduce_lambda_kernel, dim3((uint32_t)l.count), dim3(256), 0, s, partial,
+                           grad_lam, (uint32_t)n_rows, (uint32_t)l.count, (uint32_t)l.div,
+                           accumulate);
+        st = launch_status();
+    }
+    return st;
+}
+
+// A fill kernel rather than a memset node, so that callers may capture the call in a graph.
+__global__ void zero_floats_kernel(float *p, uint32_t n)
+{
+    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0.f;
+}
+
+int zero_floats(float *p, int64_t n, hipStream_t s)
+{
+    hipLaunchKernelGGL(zero_floats_kernel, dim3((uint32_t)((n + 255) / 256)), dim3(256), 0, s, p,
+                       (uint32_t)n);
+    return launch_status();
+}
+
+int fwd_entry(const float *y, float *x, int32_t *info, tv_rows rows, tv_lambda lam, hipStream_t s)
+{
+    int st = check_lambda(lam);
+    if (st != TV_OK) return st;
+    int64_t n_rows;
+    st = check_rows(rows, &n_rows);
+    if (st != TV_OK) return st;
+    if (n_rows == 0) return TV_OK;
+    if (!y || !x || !lam.lam) return TV_ERR_NULL;
+    if (rows.length > TV_MAX_LENGTH) return TV_ERR_UNSUPPORTED;
+    return run_fwd(y, nullptr, x, nullptr, info, rows, lam, n_rows, s);
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *tv_status_str(int status)
+{
+    switch (status) {
+    case TV_OK: return "ok";
+    case TV_ERR_NULL: return "null pointer";
+    case TV_ERR_SHAPE: return "bad shape";
+    case TV_ERR_STRIDE: return "bad stride";
+    case TV_ERR_LAMBDA: return "bad lambda descriptor";
+    case TV_ERR_WORKSPACE: return "bad workspace";
+    case TV_ERR_UNSUPPORTED: return "unsupported size";
+    case TV_ERR_HIP: return "HIP runtime error";
+    default: return "unknown status";
+    }
+}
+
+int tv1d_prox_fwd(const float *y, float *x, tv_rows rows, tv_lambda lam, hipStream_t stream)
+{
+    return fwd_entry(y, x, nullptr, rows, lam, stream);
+}
+
+int tv1d_prox_fwd_info(const float *y, float *x, int32_t *info, tv_rows rows, tv_lambda lam,
+                       hipStream_t stream)
+{
+    return fwd_entry(y, x, info, rows, lam, stream);
+}
+
+size_t tv1d_bwd_workspace_bytes(tv_rows rows, tv_lambda lam)
+{
+    (void)lam;
+    int64_t n_rows;
+    if (check_rows(rows, &n_rows) != TV_OK) return 0;
+    return align16((size_t)n_rows * sizeof(float));
+}
+
+int tv1d_prox_bwd(const float *g_up, const float *x, float *grad_y, float *grad_lam, tv_rows rows,
+                  tv_lambda lam, void *ws, size_t ws_bytes, hipStream_t stream)
+{
+    int st = check_lambda(lam);
+    if (st != TV_OK) return st;
+    int64_t n_rows;
+    st = check_rows(rows, &n_rows);
+    if (st != TV_OK) return st;
+    if (n_rows == 0) {
+        // no rows: every slot's gradient is zero, which needs a device write
+        return grad_lam ? zero_floats(grad_lam, lam.count, stream) : TV_OK;
+    }
+    if (!g_up || !x || !grad_y) return TV_ERR_NULL;
+    if (rows.length > TV_MAX_LENGTH) return TV_ERR_UNSUPPORTED;
+    if (grad_lam) {
+        if (!ws || !aligned16(ws) || ws_bytes < align16((size_t)n_rows * sizeof(float)))
+            return TV_ERR_WORKSPACE;
+    }
+    return run_bwd(g_up, nullptr, x, grad_y, grad_lam, 0, rows, lam, n_rows, (float *)ws, stream);
+}
+
+// ---- 2D: proximal Dykstra (paper Alg. 1) ----------------------------------------------
+
+static int check_2d(int64_t planes, int64_t H, int64_t W, int sweeps, size_t *tensor_bytes,
+                    size_t *partial_bytes)
+{
+    if (planes < 0 || H < 1 || W < 1 || sweeps < 1 || sweeps > 4096) return TV_ERR_SHAPE;
+    if (planes > kMaxRows || H > kMaxRows || W > kMaxRows) return TV_ERR_SHAPE;
+    if (planes > 0 && (planes * H > kMaxRows || planes * W > kMaxRows)) return TV_ERR_SHAPE;
+    if (planes > 0 && H * W > (INT64_MAX / 64) / planes) return TV_ERR_SHAPE;
+    *tensor_bytes = align16((size_t)(planes * H * W) * sizeof(float));
+    const int64_t mr = planes * (H > W ? H : W);
+    *partial_bytes = align16((size_t)mr * sizeof(float));
+    return TV_OK;
+}
+
+size_t tv2d_workspace_bytes(int64_t planes, int64_t H, int64_t W, int sweeps)
+{
+    size_t tb, pb;
+    if (check_2d(planes, H, W, sweeps, &tb, &pb) != TV_OK) return 0;
+    return tb * (size_t)(2 * sweeps + 2) + pb;
+}
+
+int tv2d_prox_fwd(const float *y, float *x, int64_t planes, int64_t H, int64_t W, tv_lambda lam,
+                  int sweeps, void *ws, size_t ws_bytes, hipStream_t stream)
+{
+    if (lam.count < 1 || lam.count > kMaxRows) return TV_ERR_LAMBDA;
+    size_t tb, pb;
+    int st = check_2d(planes, H, W, sweeps, &tb, &pb);
+    if (st != TV_OK) return st;
+    if (planes == 0) return TV_OK;
+    if (!y || !x || !lam.lam) return TV_ERR_NULL;
+    if (H > TV_MAX_LENGTH || W > TV_MAX_LENGTH) return TV_ERR_UNSUPPORTED;
+    if (!ws || !aligned16(ws) || ws_bytes < tb * (size_t)(2 * sweeps + 2) + pb)
+        return TV_ERR_WORKSPACE;
+
+    char *base = (char *)ws;
+    auto saved = [&](int i) { return (float *)(base + tb * (size_t)i); };
+    float *P = saved(2 * sweeps), *Q = saved(2 * sweeps + 1);
+    const tv_rows rrow = {planes, H * W, H, W, W, 1};
+    const tv_rows rcol = {planes, H * W, W, 1, H, W};
+    const tv_lambda lrow = {lam.lam, lam.count, H};
+    const tv_lambda lcol = {lam.lam, lam.count, W};
+
+    for (int k = 0; k < sweeps; ++k) {
+        const bool last = (k == sweeps - 1);
+        const float *Yk = (k == 0) ? y : saved(2 * k - 1);
+        float *Z = saved(2 * k), *Yn = saved(2 * k + 1);
+        // Z = proxRows(Y + P);  P <- (Y + P) - Z      (P = 0 in the first sweep)
+        st = run_fwd(Yk, k == 0 ? nullptr : P, Z, last ? nullptr : P, nullptr, rrow, lrow,
+                     planes * H, stream);
+        if (st != TV_OK) return st;
+        // Y' = proxCols(Z + Q);  Q <- (Z + Q) - Y'
+        st = run_fwd(Z, k == 0 ? nullptr : Q, Yn, last ? nullptr : Q, nullptr, rcol, lcol,
+                     planes * W, stream);
+        if (st != TV_OK) return st;
+    }
+    if (hipMemcpyAsync(x, saved(2 * sweeps - 1), (size_t)(planes * H * W) * sizeof(float),
+                       hipMemcpyDeviceToDevice, stream) != hipSuccess)
+        return TV_ERR_HIP;
+    return TV_OK;
+}
+
+int tv2d_prox_bwd(const float *g_up, float *grad_y, float *grad_lam, int64_t planes, int64_t H,
+                  int64_t W, tv_lambda lam, int sweeps, void *ws, size_t ws_bytes,
+                  hipStream_t stream)
+{
+    if (lam.count < 1 || lam.count > kMaxRows) return TV_ERR_LAMBDA;
+    size_t tb, pb;
+    int st = check_2d(planes, H, W, sweeps, &tb, &pb);
+    if (st != TV_OK) return st;
+    if (planes == 0) {
+        return grad_lam ? zero_floats(grad_lam, lam.count, stream) : TV_OK;
+    }
+    if (!g_up || !grad_y) return TV_ERR_NULL;
+    if (H > TV_MAX_LENGTH || W > TV_MAX_LENGTH) return TV_ERR_UNSUPPORTED;
+    if (!ws || !aligned16(ws) || ws_bytes < tb * (size_t)(2 * sweeps + 2) + pb)
+        return TV_ERR_WORKSPACE;
+
+    char *base = (char *)ws;
+    auto saved = [&](int i) { return (float *)(base + tb * (size_t)i); };
+    float *Ab = saved(2 * sweeps), *Bb = saved(2 * sweeps + 1);
+    float *partial = (float *)(base + tb * (size_t)(2 * sweeps + 2));
+    const tv_rows rrow = {planes, H * W, H, W, W, 1};
+    const tv_rows rcol = {planes, H * W, W, 1, H, W};
+    const tv_lambda lrow = {lam.lam, lam.count, H};
+    const tv_lambda lcol = {lam.lam, lam.count, W};
+
+    // Adjoint of one sweep (A = Y + P, Z = R(A), P' = A - Z, B = Z + Q, Y' = C(B), Q' = B - Y'):
+    //   Bbar = Qbar' + C^T(Ybar' - Qbar'),   Qbar = Bbar,
+    //   Abar = Pbar' + R^T(Bbar - Pbar'),    Ybar = Pbar = Abar.
+    // Ybar and Pbar coincide from the second reverse step on, so two tensors carry the state.
+    int acc = 0;
+    for (int k = sweeps - 1; k >= 0; --k) {
+        const bool first = (k == sweeps - 1);
+        st = run_bwd(first ? g_up : Ab, first ? nullptr : Bb, saved(2 * k + 1), Bb, grad_lam, acc,
+                     rcol, lcol, planes * W, partial, stream);
+        if (st != TV_OK) return st;
+        acc = 1;
+        st = run_bwd(Bb, first ? nullptr : Ab, saved(2 * k), k == 0 ? grad_y : Ab, grad_lam, acc,
+                     rrow, lrow, planes * H, partial, stream);
+        if (st != TV_OK) return st;
+    }
+    return TV_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,83 @@
+"""Helpers for the GPU tests: run the HIP path (through the C ABI) on numpy inputs."""
+from __future__ import annotations
+
+import numpy as np
+
+
+def run_1d(y, lam, lam_div, g=None, axis=-1, want_info=False, in_place=False):
+    """Forward (+ backward when g is given) along `axis` of a contiguous array.
+    Returns dict with x, gy, gl, info (numpy)."""
+    import torch
+
+    import paper_2204_03643_amd as tv
+
+    dev = torch.device("cuda:0")
+    yt = torch.from_numpy(np.ascontiguousarray(y, dtype=np.float32)).to(dev)
+    lt = torch.from_numpy(np.ascontiguousarray(lam, dtype=np.float32).ravel()).to(dev)
+    rows = tv.rows_along(y.shape, axis)
+    L = tv.tv_lambda(lt.data_ptr(), lt.numel(), lam_div)
+    n_rows = rows.n_outer * rows.n_inner
+    xt = yt if in_place else torch.full_like(yt, float("nan"))
+    out = {}
+    if want_info:
+        info = torch.zeros(max(n_rows, 1), dtype=torch.int32, device=dev)
+        tv.tv1d_prox_fwd_info(yt, xt, info, rows, L)
+        out["info"] = info.cpu().numpy()[:n_rows]
+    else:
+        tv.tv1d_prox_fwd(yt, xt, rows, L)
+    torch.cuda.synchronize()
+    out["x"] = xt.cpu().numpy()
+    if g is not None:
+        gt = torch.from_numpy(np.ascontiguousarray(g, dtype=np.float32)).to(dev)
+        gy = torch.full_like(gt, float("nan"))
+        gl = torch.full((lt.numel(),), float("nan"), device=dev)
+        wsb = tv.tv1d_bwd_workspace_bytes(rows, L)
+        ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device=dev)
+        tv.tv1d_prox_bwd(gt, xt, gy, gl, rows, L, ws, wsb)
+        torch.cuda.synchronize()
+        out["gy"] = gy.cpu().numpy()
+        out["gl"] = gl.cpu().numpy()
+    return out
+
+
+def rows_view(a, axis):
+    """[R, N] view-copy of `a` with rows taken along `axis`, in the library's row-id order."""
+    a = np.moveaxis(a, axis, -1)
+    return np.ascontiguousarray(a).reshape(-1, a.shape[-1])
+
+
+def lam_per_row(lam, n_rows, lam_div):
+    lam = np.asarray(lam).ravel()
+    return lam[(np.arange(n_rows) // lam_div) % lam.size]
+
+
+def run_2d(y, lam, sweeps, g=None):
+    """2D prox on y[..., H, W] with per-plane lam (plane p uses lam[p % len(lam)])."""
+    import torch
+
+    import paper_2204_03643_amd as tv
+
+    dev = torch.device("cuda:0")
+    H, W = y.shape[-2:]
+    planes = int(np.prod(y.shape[:-2], dtype=np.int64))
+    yt = torch.from_numpy(np.ascontiguousarray(y, dtype=np.float32)).to(dev)
+    lt = torch.from_numpy(np.ascontiguousarray(lam, dtype=np.float32).ravel()).to(dev)
+    L = tv.tv_lambda(lt.data_ptr(), lt.numel(), 1)
+    wsb = tv.tv2d_workspace_bytes(planes, H, W, sweeps)
+    ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device=dev)
+    xt = torch.full_like(yt, float("nan"))
+    tv.tv2d_prox_fwd(yt, xt, planes, H, W, L, sweeps, ws, wsb)
+    torch.cuda.synchronize()
+    out = {"x": xt.cpu().numpy()}
+    if g is not None:
+        gt = torch.from_numpy(np.ascontiguousarray(g, dtype=np.float32)).to(dev)
+        gy = torch.full_like(gt, float("nan"))
+        gl = torch.full((lt.numel(),), float("nan"), device=dev)
+        tv.tv2d_prox_bwd(gt, gy, gl, planes, H, W, L, sweeps, ws, wsb)
+        torch.cuda.synchronize()
+        out["gy"] = gy.cpu().numpy()
+        out["gl"] = gl.cpu().numpy()
+        nt = planes * H * W
+        saved = ws[: 2 * sweeps * ((nt * 4 + 15) // 16 * 16)].view(torch.float32)
+        out["saved"] = saved.cpu().numpy().reshape(2 * sweeps, -1)[:, :nt].reshape((2 * sweeps,) + y.shape)
+    return out

@@ -1,0 +1,108 @@
+"""The C-ABI library loads, exports every symbol include/tvprox.h declares, and rejects
+invalid arguments before touching the device (so these run without a GPU)."""
+import os
+import re
+
+import pytest
+
+import paper_2204_03643_amd as tv
+
+HEADER = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include", "tvprox.h")
+
+
+def _declared_functions():
+    src = open(HEADER).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    names = re.findall(r"\b(tv[0-9a-z_]+)\s*\(", src)
+    return sorted(set(names))
+
+
+def test_every_declared_symbol_is_exported():
+    names = _declared_functions()
+    assert {"tv1d_prox_fwd", "tv1d_prox_bwd", "tv2d_prox_fwd", "tv2d_prox_bwd",
+            "tv1d_bwd_workspace_bytes", "tv2d_workspace_bytes", "tv_status_str",
+            "tv1d_prox_fwd_info"} <= set(names)
+    L = tv.lib()
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_status_strings():
+    assert tv.status_str(0) == "ok"
+    for s in range(1, 8):
+        assert tv.status_str(s) not in ("ok", "unknown status")
+    assert tv.status_str(99) == "unknown status"
+
+
+FAKE = 0x1000  # non-null, 16-byte aligned, never dereferenced: validation fails first
+
+
+def _fwd(y, x, rows, lam):
+    return tv.lib().tv1d_prox_fwd(y, x, rows, lam, None)
+
+
+def test_forward_validation():
+    ok_rows = tv.tv_rows(4, 32, 1, 1, 32, 1)
+    lam = tv.tv_lambda(FAKE, 1, 1)
+    assert _fwd(None, FAKE, ok_rows, lam) == 1          # TV_ERR_NULL
+    assert _fwd(FAKE, None, ok_rows, lam) == 1
+    assert _fwd(FAKE, FAKE, ok_rows, tv.tv_lambda(None, 1, 1)) == 1
+    assert _fwd(FAKE, FAKE, tv.tv_rows(4, 32, 1, 1, 0, 1), lam) == 2     # length < 1
+    assert _fwd(FAKE, FAKE, tv.tv_rows(-1, 32, 1, 1, 32, 1), lam) == 2   # negative count
+    assert _fwd(FAKE, FAKE, tv.tv_rows(1 << 20, 32, 1 << 20, 1, 32, 1), lam) == 2  # too many rows
+    assert _fwd(FAKE, FAKE, tv.tv_rows(4, 32, 1, 1, 32, 0), lam) == 3    # zero element stride
+    assert _fwd(FAKE, FAKE, tv.tv_rows(4, 16, 1, 1, 32, 1), lam) == 3    # rows overlap
+    assert _fwd(FAKE, FAKE, tv.tv_rows(4, 1024, 8, 16, 32, 1), lam) == 3  # inner rows overlap
+    assert _fwd(FAKE, FAKE, tv.tv_rows(2, 64, 8, 1, 8, 4), lam) == 3     # columns: stride < extent
+    assert _fwd(FAKE, FAKE, ok_rows, tv.tv_lambda(FAKE, 0, 1)) == 4      # TV_ERR_LAMBDA
+    assert _fwd(FAKE, FAKE, ok_rows, tv.tv_lambda(FAKE, 1, 0)) == 4
+    assert _fwd(FAKE, FAKE, tv.tv_rows(1, 1 << 20, 1, 1, 16385, 1), lam) == 6  # TV_ERR_UNSUPPORTED
+    # zero rows: nothing to do, no device access
+    assert _fwd(None, None, tv.tv_rows(0, 32, 1, 1, 32, 1), lam) == 0
+    assert _fwd(None, None, tv.tv_rows(4, 32, 0, 1, 32, 1), lam) == 0
+
+
+def test_backward_validation():
+    L = tv.lib()
+    rows = tv.tv_rows(4, 32, 1, 1, 32, 1)
+    lam = tv.tv_lambda(FAKE, 1, 1)
+    assert tv.tv1d_bwd_workspace_bytes(rows, lam) == 16
+    assert tv.tv1d_bwd_workspace_bytes(tv.tv_rows(100, 32, 1, 1, 32, 1), lam) == 400
+    assert L.tv1d_prox_bwd(None, FAKE, FAKE, FAKE, rows, lam, FAKE, 64, None) == 1
+    assert L.tv1d_prox_bwd(FAKE, None, FAKE, FAKE, rows, lam, FAKE, 64, None) == 1
+    assert L.tv1d_prox_bwd(FAKE, FAKE, None, FAKE, rows, lam, FAKE, 64, None) == 1
+    assert L.tv1d_prox_bwd(FAKE, FAKE, FAKE, FAKE, rows, lam, None, 64, None) == 5   # no workspace
+    assert L.tv1d_prox_bwd(FAKE, FAKE, FAKE, FAKE, rows, lam, FAKE, 8, None) == 5    # too small
+    assert L.tv1d_prox_bwd(FAKE, FAKE, FAKE, FAKE, rows, lam, FAKE + 4, 64, None) == 5  # misaligned
+    assert L.tv1d_prox_bwd(FAKE, FAKE, FAKE, FAKE, tv.tv_rows(4, 32, 1, 1, 0, 1), lam, FAKE, 64, None) == 2
+
+
+def test_2d_validation():
+    L = tv.lib()
+    lam = tv.tv_lambda(FAKE, 3, 1)
+    need = tv.tv2d_workspace_bytes(6, 32, 32, 2)
+    assert need == 6 * 32 * 32 * 4 * (2 * 2 + 2) + 6 * 32 * 4
+    assert tv.tv2d_workspace_bytes(6, 0, 32, 2) == 0
+    assert L.tv2d_prox_fwd(None, FAKE, 6, 32, 32, lam, 2, FAKE, need, None) == 1
+    assert L.tv2d_prox_fwd(FAKE, FAKE, 6, 32, 32, lam, 0, FAKE, need, None) == 2
+    assert L.tv2d_prox_fwd(FAKE, FAKE, 6, 32, 0, lam, 2, FAKE, need, None) == 2
+    assert L.tv2d_prox_fwd(FAKE, FAKE, 6, 32, 32, tv.tv_lambda(FAKE, 0, 1), 2, FAKE, need, None) == 4
+    assert L.tv2d_prox_fwd(FAKE, FAKE, 6, 32, 32, lam, 2, FAKE, need - 1, None) == 5
+    assert L.tv2d_prox_fwd(FAKE, FAKE, 6, 32, 32, lam, 2, None, need, None) == 5
+    assert L.tv2d_prox_fwd(FAKE, FAKE, 1, 32, 20000, lam, 1, FAKE, 1 << 40, None) == 6
+    assert L.tv2d_prox_fwd(None, None, 0, 32, 32, lam, 2, None, 0, None) == 0
+    assert L.tv2d_prox_bwd(None, FAKE, FAKE, 6, 32, 32, lam, 2, FAKE, need, None) == 1
+    assert L.tv2d_prox_bwd(FAKE, FAKE, FAKE, 6, 32, 32, lam, 2, FAKE, need - 1, None) == 5
+
+
+def test_binding_raises():
+    with pytest.raises(tv.TVError) as e:
+        tv.tv1d_prox_fwd(FAKE, FAKE, tv.tv_rows(4, 32, 1, 1, 0, 1), tv.tv_lambda(FAKE, 1, 1), stream=0)
+    assert e.value.status == 2
+
+
+def test_rows_along():
+    r = tv.rows_along((2, 3, 5, 7), -1)
+    assert (r.n_outer, r.outer_stride, r.n_inner, r.inner_stride, r.length, r.elem_stride) == (30, 7, 1, 1, 7, 1)
+    r = tv.rows_along((2, 3, 5, 7), -2)
+    assert (r.n_outer, r.outer_stride, r.n_inner, r.inner_stride, r.length, r.elem_stride) == (6, 35, 7, 1, 5, 7)

@@ -1,0 +1,152 @@
+"""GPU parity: row-per-lane path (length <= 32) against the oracle, through the C ABI."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads
+from gpuutil import lam_per_row, rows_view, run_1d
+from parity import FWD_TOL, check_batch, forward_errors
+from refmath import certificate
+
+pytestmark = pytest.mark.gpu
+
+
+def _check(y, lam, lam_div, g, axis, label):
+    out = run_1d(y, lam, lam_div, g, axis=axis)
+    yr, gr = rows_view(y, axis), rows_view(g, axis)
+    lr = lam_per_row(lam, len(yr), lam_div)
+    return check_batch(yr, lr, gr, rows_view(out["x"], axis), rows_view(out["gy"], axis),
+                       gl_gpu=out["gl"], lam_count=np.asarray(lam).size, lam_div=lam_div, label=label)
+
+
+def test_config3_reduced_rows_and_columns():
+    # same distribution as the 2^20-row workload; several 256-row workgroups + per-channel lam
+    y, lam, g = workloads.config3(B=3, C=128)
+    st = _check(y, lam, 32, g, -1, "cfg3 rows")
+    assert st["near_degenerate"] < 0.02 * st["rows"]
+    _check(y, lam, 32, g, -2, "cfg3 columns")
+
+
+def test_config2_reduced_rows_and_columns():
+    # post-ReLU maps: about half the samples are exact zeros, so inputs are full of ties
+    y, lam, g = workloads.config2(B=4, C=64)
+    _check(y, lam, 32, g, -1, "cfg2 rows")
+    _check(y, lam, 32, g, -2, "cfg2 columns")
+
+
+def test_timing_batch_shape():
+    y, lam, g = workloads.timing_batch(rows=1000)        # ragged: not a multiple of 64
+    _check(y, lam, 1, g, -1, "timing")
+
+
+@pytest.mark.parametrize("n", [1, 2, 3, 5, 7, 8, 9, 13, 16, 17, 24, 31, 32])
+def test_every_short_length(n):
+    rng = np.random.default_rng(300 + n)
+    rows = 333                                            # ragged tail inside a workgroup
+    y = rng.normal(size=(rows, n)).astype(np.float32)
+    g = rng.normal(size=(rows, n)).astype(np.float32)
+    lam = (10 ** rng.uniform(-3, 1, size=rows)).astype(np.float32)
+    _check(y, lam, 1, g, -1, "n=%d" % n)
+
+
+def test_strided_columns_odd_shape():
+    rng = np.random.default_rng(41)
+    y = rng.normal(size=(5, 3, 19, 11)).astype(np.float32)
+    g = rng.normal(size=y.shape).astype(np.float32)
+    lam = np.array([0.05, 0.4, 2.0], dtype=np.float32)
+    _check(y, lam, 11, g, -2, "columns 19x11")
+    _check(y, lam, 19, g, -1, "rows 19x11")
+
+
+def test_lambda_extremes_and_identity():
+    rng = np.random.default_rng(42)
+    y = rng.normal(size=(200, 32)).astype(np.float32)
+    g = rng.normal(size=y.shape).astype(np.float32)
+    out = run_1d(y, np.array([0.0], np.float32), 1, g)
+    assert np.array_equal(out["x"], y)                    # lam = 0 is the identity (paper Sec. 3.1)
+    assert np.array_equal(out["gy"], g)
+    out = run_1d(y, np.array([1e4], np.float32), 1, g)
+    np.testing.assert_allclose(out["x"], np.repeat(y.astype(np.float64).mean(1, keepdims=True), 32, 1),
+                               atol=1e-5)
+    assert np.all(out["x"] == out["x"][:, :1])            # one segment, bit-identical
+    np.testing.assert_allclose(out["gy"], np.repeat(g.astype(np.float64).mean(1, keepdims=True), 32, 1),
+                               atol=1e-5)
+    assert abs(out["gl"][0]) == 0.0
+    out = run_1d(y, np.array([-3.0], np.float32), 1)      # negative lam acts as 0
+    assert np.array_equal(out["x"], y)
+
+
+def test_in_place_and_sum_preserved():
+    y, lam, g = workloads.config3(B=1, C=16)
+    a = run_1d(y, lam, 32)
+    b = run_1d(y, lam, 32, in_place=True)
+    assert np.array_equal(a["x"], b["x"])
+    np.testing.assert_allclose(a["x"].astype(np.float64).sum(-1), y.astype(np.float64).sum(-1), atol=2e-4)
+
+
+def test_constant_and_tied_rows():
+    y = np.zeros((130, 32), np.float32)
+    y[1] = 3.0
+    y[2, 16:] = 1.0                                       # exact unit step
+    y[3] = np.tile([0.0, 1.0], 16)                        # alternating
+    y[4:] = np.round(np.random.default_rng(43).normal(size=(126, 32)) * 2) / 2   # many exact ties
+    g = np.random.default_rng(44).normal(size=y.shape).astype(np.float32)
+    lam = np.array([0.25], np.float32)
+    out = run_1d(y, lam, 1, g, want_info=True)
+    x_ref = oracle.prox1d_batch(y.astype(np.float64), lam.astype(np.float64))
+    assert forward_errors(out["x"], x_ref, y).max() <= FWD_TOL
+    assert np.array_equal(out["x"][0], y[0]) and np.array_equal(out["x"][1], y[1])
+    assert not np.any(out["info"] & (1 << 18))            # nobody hit the iteration cap
+
+
+def test_nan_row_stays_in_its_row():
+    rng = np.random.default_rng(45)
+    y = rng.normal(size=(128, 32)).astype(np.float32)
+    y[5, 7] = np.nan
+    out = run_1d(y, np.array([0.3], np.float32), 1)
+    assert np.isnan(out["x"][5, 7])                      # confined to its own row
+    ok = np.delete(np.arange(128), 5)
+    x_ref = oracle.prox1d_batch(y[ok].astype(np.float64), np.array([0.3]))
+    assert forward_errors(out["x"][ok], x_ref, y[ok]).max() <= FWD_TOL
+
+
+def test_empty_batch():
+    out = run_1d(np.zeros((0, 32), np.float32), np.array([0.5], np.float32), 1,
+                 np.zeros((0, 32), np.float32))
+    assert out["x"].shape == (0, 32) and out["gl"][0] == 0.0
+
+
+def test_info_word_reports_convergence():
+    y, lam, g = workloads.config3(B=2, C=128)
+    out = run_1d(y, lam, 32, want_info=True)
+    info = out["info"]
+    assert np.all((info & (3 << 16)) != 0)                # every row: optimality test or no-change stop
+    assert not np.any(info & (1 << 18))
+    assert (info & 0xffff).max() <= 16
+
+
+def test_full_size_config3_sampled():
+    """The 2^20-row workload in the launch configuration the benchmark times: sampled rows
+    against the oracle, the certificate on further samples, and global properties."""
+    y, lam, g = workloads.config3()
+    out = run_1d(y, lam, 32, g, want_info=True)
+    x, gy = out["x"], out["gy"]
+    assert np.all(np.isfinite(x)) and np.all(np.isfinite(gy))
+    assert not np.any(out["info"] & (1 << 18))
+    yr, xr, gr, gyr = (a.reshape(-1, 32) for a in (y, x, g, gy))
+    lr = lam_per_row(lam, len(yr), 32)
+    rng = np.random.default_rng(46)
+    idx = np.sort(rng.choice(len(yr), size=20000, replace=False))
+    idx = np.concatenate((idx, [0, 1, len(yr) - 2, len(yr) - 1]))
+    check_batch(yr[idx], lr[idx], gr[idx], xr[idx], gyr[idx], label="cfg3 full sampled")
+    for r in rng.choice(len(yr), size=300, replace=False):
+        gap, resid, viol = certificate(xr[r], yr[r], float(lr[r]))
+        assert gap < 1e-4 and abs(resid) < 1e-3 and viol < 1e-4
+    # properties that hold at any size
+    np.testing.assert_allclose(xr.astype(np.float64).sum(1), yr.astype(np.float64).sum(1), atol=3e-4)
+    np.testing.assert_allclose(gyr.astype(np.float64).sum(1), gr.astype(np.float64).sum(1), atol=3e-4)
+    assert np.all(xr.max(1) <= yr.max(1) + 1e-5) and np.all(xr.min(1) >= yr.min(1) - 1e-5)
+    # grad_lam against per-row oracle contributions computed from the GPU's own segments
+    xs, gs = xr.astype(np.float64), gr.astype(np.float64)
+    _, gl_ref = oracle.prox1d_bwd_batch(gs, xs, lam_count=128, lam_div=32)
+    np.testing.assert_allclose(out["gl"], gl_ref, rtol=1e-4, atol=1e-2)
