@@ -1,7 +1,567 @@
-// placeholder (replaced below)
+// Kernels for rows longer than 32 samples: T threads share one row, C contiguous samples
+// (and duals) per thread, G rows per workgroup.
+//
+// T = 64 keeps a row inside one wavefront (G rows per workgroup); T = 256 and T = 1024 put
+// one row on a whole workgroup.  The row, its dual and the Newton direction stay in
+// registers for the entire solve; only chunk edges, the interface system and row-wide
+// reductions go through LDS.
+//
+// The masked tridiagonal system of paper Eq. 4 is solved by substructuring:
+//   1. every thread eliminates the interior of its chunk with the Thomas recurrences
+//      (pivots from a table: they depend only on the position inside a free run);
+//   2. the last dual of every chunk is a separator; the T separators obey a tridiagonal
+//      Schur-complement system whose entries follow from step 1 and from the closed-form
+//      corner entries of the inverse of tridiag(-1,2,-1): (A^-1)_11 = m/(m+1),
+//      (A^-1)_1m = 1/(m+1); it is solved by parallel cyclic reduction in LDS, stopping as
+//      soon as every equation has decoupled;
+//   3. every thread back-substitutes its interior with the separator values as boundary
+//      terms (a second Thomas pass).
+//
+// Thread mapping: ROWS (unit element stride): tid = row_in_group * T + t, so a wave reads
+// one row's consecutive chunks; COLS (strided samples, e.g. image columns): tid = t * G +
+// row_in_group, so adjacent lanes read adjacent columns and global accesses coalesce.
 #pragma once
 #include "tv_common.hpp"
+
 namespace tvk {
-inline hipError_t launch_fwd_long(const FwdParams &, hipStream_t) { return hipErrorNotSupported; }
-inline hipError_t launch_bwd_long(const BwdParams &, hipStream_t) { return hipErrorNotSupported; }
+
+template <int T, int G, bool COLS>
+struct LongMap {
+    static constexpr int NT = T * G;
+    static constexpr int NW = NT / 64;
+    static constexpr int RG = COLS ? G : 1;            // rows interleaved inside a wave
+    static constexpr int WPR = COLS ? NW : T / 64;     // waves holding parts of one row
+    __device__ static __forceinline__ int row_of(int tid) { return COLS ? tid % G : tid / T; }
+    __device__ static __forceinline__ int t_of(int tid) { return COLS ? tid / G : tid % T; }
+};
+
+// Sums NV values over the T threads of each row; every thread of the row gets the totals.
+// Deterministic: fixed shuffle tree inside a wave, then a fixed-order sum over waves.
+template <int T, int G, bool COLS, int NV>
+__device__ __forceinline__ void row_sum(float (&v)[NV], float *red, int j, int tid)
+{
+    using Mp = LongMap<T, G, COLS>;
+#pragma unroll
+    for (int off = 32; off >= Mp::RG; off >>= 1) {
+#pragma unroll
+        for (int q = 0; q < NV; ++q) v[q] += __shfl_xor(v[q], off);
+    }
+    if (Mp::WPR == 1) return;
+    const int wave = tid >> 6, lane = tid & 63;
+    __syncthreads();
+    if (lane < Mp::RG) {
+#pragma unroll
+        for (int q = 0; q < NV; ++q) red[(q * Mp::NW + wave) * Mp::RG + (COLS ? j : 0)] = v[q];
+    }
+    __syncthreads();
+    const int w0 = COLS ? 0 : j * Mp::WPR;
+#pragma unroll
+    for (int q = 0; q < NV; ++q) {
+        float s = 0.f;
+        for (int w = 0; w < Mp::WPR; ++w) s += red[(q * Mp::NW + w0 + w) * Mp::RG + (COLS ? j : 0)];
+        v[q] = s;
+    }
 }
+
+// Segmented exclusive scan over the T threads of a row, from t = 0 upwards (DIR = +1) or
+// from t = T-1 downwards (DIR = -1).  Each thread contributes (closed, s, n): `closed`
+// says its chunk holds a segment boundary, and (s, n) describe the part of the chunk
+// beyond its last boundary in scan direction (the whole chunk if there is none).
+// ADD: open parts accumulate (sums and counts).  !ADD: the value of the nearest closed
+// chunk is copied forward.  Returns what arrives at this thread from the scan's origin
+// side; zero at the origin.  buf: [2][3][G][T] floats.
+template <int T, int G, int DIR, bool ADD>
+__device__ __forceinline__ void seg_scan(bool closed, float s, float n, float *buf, int j, int t,
+                                         float &cs, float &cn)
+{
+#define TV_B(c, q, tt) buf[(((c) * 3 + (q)) * G + j) * T + (tt)]
+    float f = closed ? 1.f : 0.f;
+    int cur = 0;
+    for (int d = 1; d < T; d <<= 1) {
+        TV_B(cur, 0, t) = f; TV_B(cur, 1, t) = s; TV_B(cur, 2, t) = n;
+        __syncthreads();
+        const int o = t - DIR * d;
+        if (o >= 0 && o < T && f == 0.f) {
+            const float of = TV_B(cur, 0, o), os = TV_B(cur, 1, o), on = TV_B(cur, 2, o);
+            if (ADD) { s += os; n += on; } else { s = os; n = on; }
+            f = of;
+        }
+        cur ^= 1;
+    }
+    TV_B(cur, 1, t) = s; TV_B(cur, 2, t) = n;
+    __syncthreads();
+    const int o = t - DIR;
+    cs = 0.f; cn = 0.f;
+    if (o >= 0 && o < T) { cs = TV_B(cur, 1, o); cn = TV_B(cur, 2, o); }
+    __syncthreads();
+#undef TV_B
+}
+
+template <int T, int C, int G, bool COLS>
+struct LongSmem {
+    using Mp = LongMap<T, G, COLS>;
+    static constexpr int TP = T + 2;                   // one zero sentinel on either side
+    float gtab[C + 2];
+    float ex[5][G][TP];
+    float buf[2 * 3 * G * T];
+    float red[4 * Mp::NW * Mp::RG];
+};
+
+// ---------------------------------------------------------------------------------
+// Forward: projected Newton on the dual (paper Eq. 3-4), one row per T threads.
+// ---------------------------------------------------------------------------------
+template <int T, int C, int G, bool COLS>
+__global__ __launch_bounds__(T *G) void tv1d_fwd_long_kernel(FwdParams p)
+{
+    using Mp = LongMap<T, G, COLS>;
+    __shared__ LongSmem<T, C, G, COLS> sm;
+    const int tid = threadIdx.x;
+    const int j = Mp::row_of(tid), t = Mp::t_of(tid);
+#define TV_EX(q, tt) sm.ex[q][j][(tt) + 1]
+#define TV_PB(c, q, tt) sm.buf[(((c) * 3 + (q)) * G + j) * T + (tt)]
+
+    const uint32_t row = blockIdx.x * G + j;
+    const bool rvalid = row < p.L.n_rows;
+    const int n = p.L.n, M = n - 1;
+    const int k0 = t * C;
+
+    if (tid <= C) sm.gtab[tid] = (float)tid / (float)(tid + 1);
+    if (t == 0) {
+#pragma unroll
+        for (int q = 0; q < 5; ++q) { sm.ex[q][j][0] = 0.f; sm.ex[q][j][T + 1] = 0.f; }
+    }
+
+    const int64_t off = rvalid ? row_offset(p.L, row) : 0;
+    const int64_t es = p.L.elem_stride;
+    const float lam = rvalid ? load_lambda(p.lam, p.L, row) : 0.f;
+    float y[C];
+#pragma unroll
+    for (int i = 0; i < C; ++i) {
+        float v = 0.f;
+        if (rvalid && k0 + i < n) {
+            v = p.y[off + (int64_t)(k0 + i) * es];
+            if (p.addend) v += p.addend[off + (int64_t)(k0 + i) * es];
+        }
+        y[i] = v;
+    }
+    // duals past the end of the row get an empty box and never move
+#define TV_LK(i) ((k0 + (i) < M) ? lam : 0.0f)
+
+    TV_EX(0, t) = y[0];
+    __syncthreads();
+    const float ynext0 = TV_EX(0, t + 1);
+    __syncthreads();
+
+    // ---- starting point: every dual at the bound its local difference points to
+    float u[C];
+    float fcur;
+    {
+#pragma unroll
+        for (int i = 0; i < C; ++i) {
+            const float l = TV_LK(i);
+            const float dy = ((i + 1 < C) ? y[i + 1] : ynext0) - y[i];
+            u[i] = __builtin_amdgcn_fmed3f(dy * 1e30f, -l, l);
+        }
+        TV_EX(0, t) = u[C - 1];
+        __syncthreads();
+        const float uleft = TV_EX(0, t - 1);
+        float acc[1] = {0.f};
+#pragma unroll
+        for (int i = 0; i < C; ++i) {
+            const float xi = y[i] + u[i] - (i > 0 ? u[i - 1] : uleft);
+            acc[0] = fmaf(xi, xi, acc[0]);
+        }
+        row_sum<T, G, COLS, 1>(acc, sm.red, j, tid);
+        fcur = 0.5f * acc[0];
+        __syncthreads();
+    }
+
+    bool active = rvalid;
+    bool prev_unclipped = false;
+    int steps = 0, flags = 0;
+
+    for (int it = 0;; ++it) {
+        // ---- chunk edges of the dual
+        TV_EX(0, t) = u[C - 1];
+        TV_EX(1, t) = u[0];
+        __syncthreads();
+        const float uleft = TV_EX(0, t - 1);
+        const float unext0 = TV_EX(1, t + 1);
+
+        // ---- gradient, bound set, optimality test, interior elimination (Thomas, pass 1)
+        float g[C], gam[C], w[C];
+        bool bsep;
+        int pos = 0, a = 0;
+        bool seen_bound = false;
+        float viof[1] = {0.f};
+        {
+            float wprev = 0.f, gprev = 0.f;
+            float xi = y[0] + u[0] - uleft;
+#pragma unroll
+            for (int i = 0; i < C; ++i) {
+                const float xn = (i + 1 < C) ? (y[i + 1] + u[i + 1] - u[i])
+                                             : (ynext0 + unext0 - u[C - 1]);
+                const float gi = xi - xn;
+                g[i] = gi;
+                const float s = copysignf(TV_LK(i), gi);
+                const bool bnd = (u[i] == -s);
+                if (k0 + i < M && u[i] == s && gi != 0.f) viof[0] += 1.f;
+                if (i < C - 1) {
+                    pos = bnd ? 0 : pos + 1;
+                    const float gm = sm.gtab[pos];
+                    const float wi = fmaf(gprev, wprev, gi);
+                    gam[i] = gm; w[i] = wi;
+                    wprev = wi; gprev = gm;
+                    if (!seen_bound) { if (bnd) seen_bound = true; else a += 1; }
+                } else {
+                    bsep = bnd;
+                }
+                xi = xn;
+            }
+        }
+        float p0, pl;
+        {
+            float pn = 0.f;
+            pl = 0.f;
+#pragma unroll
+            for (int i = C - 2; i >= 0; --i) {
+                pn = gam[i] * (w[i] + pn);
+                if (i == C - 2) pl = pn;
+            }
+            p0 = pn;
+        }
+        const float c_alpha = sm.gtab[a];                       // (A^-1)_{first,first}
+        const float c_delta = sm.gtab[pos];                     // (A^-1)_{last,last}
+        const float c_beta = (a == C - 1) ? (1.0f / (float)C) : 0.f;  // (A^-1)_{first,last}
+        TV_EX(2, t) = p0;
+        TV_EX(3, t) = c_alpha;
+        TV_EX(4, t) = c_beta;
+        row_sum<T, G, COLS, 1>(viof, sm.red, j, tid);
+        __syncthreads();
+        const float p0n = TV_EX(2, t + 1), alphan = TV_EX(3, t + 1), betan = TV_EX(4, t + 1);
+
+        if (active && prev_unclipped && viof[0] == 0.f) { active = false; flags = kInfoConverged; }
+        if (active && it >= kMaxNewtonSteps) { active = false; flags = kInfoCapped; }
+        if (!__syncthreads_or(active ? 1 : 0)) break;
+        steps += active ? 1 : 0;
+
+        // ---- separator system (normalised to unit diagonal) and PCR
+        float ea = 0.f, ec = 0.f, er = 0.f;
+        if (!bsep) {
+            const float inv = 1.0f / (2.0f - c_delta - alphan);
+            ea = -c_beta * inv;
+            ec = -betan * inv;
+            er = (g[C - 1] + pl + p0n) * inv;
+        }
+        {
+            int cur = 0;
+            for (int s = 1; s < T; s <<= 1) {
+                TV_PB(cur, 0, t) = ea; TV_PB(cur, 1, t) = ec; TV_PB(cur, 2, t) = er;
+                if (!__syncthreads_or((ea != 0.f || ec != 0.f) ? 1 : 0)) break;
+                float la = 0.f, lc = 0.f, lr = 0.f, ra = 0.f, rc = 0.f, rr = 0.f;
+                if (t - s >= 0) { la = TV_PB(cur, 0, t - s); lc = TV_PB(cur, 1, t - s); lr = TV_PB(cur, 2, t - s); }
+                if (t + s < T) { ra = TV_PB(cur, 0, t + s); rc = TV_PB(cur, 1, t + s); rr = TV_PB(cur, 2, t + s); }
+                const float inv = 1.0f / (1.0f - ea * lc - ec * ra);
+                er = (er - ea * lr - ec * rr) * inv;
+                const float na = -ea * la * inv, nc = -ec * rc * inv;
+                ea = na; ec = nc;
+                cur ^= 1;
+            }
+        }
+        const float sigma = er;
+        TV_EX(0, t) = sigma;
+        __syncthreads();
+        const float sleft = TV_EX(0, t - 1);
+
+        // ---- interior back-substitution with the separators as boundary terms (pass 2);
+        //      w becomes the Newton direction d
+        float decp = 0.f;
+        {
+            float wprev = 0.f, gprev = 0.f;
+#pragma unroll
+            for (int i = 0; i < C - 1; ++i) {
+                float rhs = g[i];
+                if (i == 0) rhs += sleft;
+                if (i == C - 2) rhs += sigma;
+                const float wi = fmaf(gprev, wprev, rhs);
+                w[i] = wi; wprev = wi; gprev = gam[i];
+            }
+            float dn = 0.f;
+#pragma unroll
+            for (int i = C - 2; i >= 0; --i) {
+                dn = gam[i] * (w[i] + dn);
+                w[i] = dn;
+                decp = fmaf(g[i], dn, decp);
+            }
+            w[C - 1] = sigma;
+            decp = fmaf(g[C - 1], sigma, decp);
+        }
+
+        // ---- projected step with Armijo backtracking (quadratic interpolation)
+        float alpha = active ? 1.f : 0.f;
+        float uc[C];
+        float fc = 0.f, dec = 0.f;
+        bool clipped = false, changed = false;
+        for (int ls = 0;; ++ls) {
+            float v[4] = {0.f, decp, 0.f, 0.f};
+#pragma unroll
+            for (int i = 0; i < C; ++i) {
+                const float l = TV_LK(i);
+                const float tt = fmaf(-alpha, w[i], u[i]);
+                const float cc = __builtin_amdgcn_fmed3f(tt, -l, l);
+                if (cc != tt) v[2] += 1.f;
+                if (cc != u[i]) v[3] += 1.f;
+                uc[i] = cc;
+            }
+            TV_EX(1, t) = uc[C - 1];
+            __syncthreads();
+            const float ucleft = TV_EX(1, t - 1);
+#pragma unroll
+            for (int i = 0; i < C; ++i) {
+                const float xc = y[i] + uc[i] - (i > 0 ? uc[i - 1] : ucleft);
+                v[0] = fmaf(xc, xc, v[0]);
+            }
+            row_sum<T, G, COLS, 4>(v, sm.red, j, tid);
+            fc = 0.5f * v[0]; dec = v[1]; clipped = v[2] > 0.f; changed = v[3] > 0.f;
+            const bool ok = !active || alpha == 0.f || (alpha == 1.f && !clipped) ||
+                            (fc <= fcur - kArmijoSigma * alpha * dec + kArmijoSlackEps * fabsf(fcur));
+            if (!__syncthreads_or(ok ? 0 : 1)) break;
+            if (!ok) {
+                if (ls >= kMaxBacktracks) {
+                    alpha = 0.f;
+                } else {
+                    const float den = 2.f * (fc - fcur + dec * alpha);
+                    const float an = den > 0.f ? dec * alpha * alpha / den : 0.5f * alpha;
+                    alpha = fminf(fmaxf(an, 0.1f * alpha), 0.5f * alpha);
+                }
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < C; ++i) u[i] = uc[i];
+        prev_unclipped = (alpha == 1.f) && !clipped;
+        if (active) fcur = fc;
+        if (active && !changed) { active = false; flags = kInfoStalled; }
+        if (!__syncthreads_or(active ? 1 : 0)) break;
+    }
+
+    // ---- primal recovery x = y - D^T u, then every block between two bound duals takes
+    //      the value of its first sample, so that constant runs are bit-identical
+    float xs[C];
+    {
+        TV_EX(0, t) = u[C - 1];
+        TV_EX(1, t) = u[0];
+        __syncthreads();
+        const float uleft = TV_EX(0, t - 1);
+        const float unext0 = TV_EX(1, t + 1);
+        bool bnd[C];
+        float xi = y[0] + u[0] - uleft;
+#pragma unroll
+        for (int i = 0; i < C; ++i) {
+            const float xn = (i + 1 < C) ? (y[i + 1] + u[i + 1] - u[i]) : (ynext0 + unext0 - u[C - 1]);
+            const float gi = xi - xn;
+            bnd[i] = (u[i] == -copysignf(TV_LK(i), gi));
+            xs[i] = xi;
+            xi = xn;
+        }
+        // a sample starts a block when the dual on its left is bound; chunk-local pass first
+        TV_EX(2, t) = bnd[C - 1] ? 1.f : 0.f;
+        __syncthreads();
+        const bool start0 = (t == 0) || (TV_EX(2, t - 1) != 0.f);
+        bool closed = start0;
+        float last = xs[0];
+#pragma unroll
+        for (int i = 1; i < C; ++i)
+            if (bnd[i - 1]) { closed = true; last = xs[i]; }
+        // `last` = first sample of the chunk's last block (valid when closed)
+        float cv, cdummy;
+        seg_scan<T, G, +1, false>(closed, last, 0.f, sm.buf, j, t, cv, cdummy);
+        float val = start0 ? xs[0] : cv;
+        float dev[1] = {0.f};
+#pragma unroll
+        for (int i = 0; i < C; ++i) {
+            if (i > 0 && bnd[i - 1]) val = xs[i];
+            if (fabsf(val - xs[i]) > 2e-5f * (1.f + fabsf(y[i]) + lam)) dev[0] += 1.f;
+            u[i] = val;       // u is dead from here on: reuse it for the block values
+        }
+        row_sum<T, G, COLS, 1>(dev, sm.red, j, tid);
+        const bool use_blocks = !(flags & kInfoCapped) && dev[0] == 0.f;
+        if (use_blocks) {
+#pragma unroll
+            for (int i = 0; i < C; ++i) xs[i] = u[i];
+        } else {
+            flags |= 1 << 19;
+        }
+    }
+
+#pragma unroll
+    for (int i = 0; i < C; ++i) {
+        if (rvalid && k0 + i < n) {
+            p.x[off + (int64_t)(k0 + i) * es] = xs[i];
+            if (p.resid) p.resid[off + (int64_t)(k0 + i) * es] = y[i] - xs[i];
+        }
+    }
+    if (p.info && rvalid && t == 0) p.info[row] = steps | flags;
+#undef TV_EX
+#undef TV_PB
+#undef TV_LK
+}
+
+// ---------------------------------------------------------------------------------
+// Backward (paper Eq. 5-6 as segment averaging), one row per T threads.
+// ---------------------------------------------------------------------------------
+template <int T, int C, int G, bool COLS>
+__global__ __launch_bounds__(T *G) void tv1d_bwd_long_kernel(BwdParams p)
+{
+    using Mp = LongMap<T, G, COLS>;
+    __shared__ LongSmem<T, C, G, COLS> sm;
+    const int tid = threadIdx.x;
+    const int j = Mp::row_of(tid), t = Mp::t_of(tid);
+#define TV_EX(q, tt) sm.ex[q][j][(tt) + 1]
+    const uint32_t row = blockIdx.x * G + j;
+    const bool rvalid = row < p.L.n_rows;
+    const int n = p.L.n;
+    const int k0 = t * C;
+    if (t == 0) {
+#pragma unroll
+        for (int q = 0; q < 5; ++q) { sm.ex[q][j][0] = 0.f; sm.ex[q][j][T + 1] = 0.f; }
+    }
+    const int64_t off = rvalid ? row_offset(p.L, row) : 0;
+    const int64_t es = p.L.elem_stride;
+
+    float g[C], x[C], sb[C];
+#pragma unroll
+    for (int i = 0; i < C; ++i) {
+        float gv = 0.f, xv = 0.f, sv = 0.f;
+        if (rvalid && k0 + i < n) {
+            const int64_t o = off + (int64_t)(k0 + i) * es;
+            gv = p.g[o];
+            xv = p.x[o];
+            if (p.sub) { sv = p.sub[o]; gv -= sv; }
+        }
+        g[i] = gv; x[i] = xv; sb[i] = sv;
+    }
+    TV_EX(0, t) = x[0];
+    __syncthreads();
+    const float xnext0 = TV_EX(0, t + 1);
+
+    // jump after sample i (always at the end of the row; samples past the end are their
+    // own segments and contribute nothing)
+    bool jump[C];
+#pragma unroll
+    for (int i = 0; i < C; ++i) {
+        const float xn = (i + 1 < C) ? x[i + 1] : xnext0;
+        jump[i] = (k0 + i >= n - 1) || (xn != x[i]);
+    }
+    // chunk-local pieces: head = samples up to and including the first jump, tail = samples
+    // after the last jump; both are the whole chunk when it holds no jump
+    bool any = false;
+    float head_s = 0.f, head_n = 0.f, tail_s = 0.f, tail_n = 0.f;
+#pragma unroll
+    for (int i = 0; i < C; ++i) {
+        if (!any) { head_s += g[i]; head_n += 1.f; }
+        tail_s += g[i]; tail_n += 1.f;
+        if (jump[i]) { any = true; tail_s = 0.f; tail_n = 0.f; }
+    }
+    float ls, ln, rs, rn;
+    seg_scan<T, G, +1, true>(any, tail_s, tail_n, sm.buf, j, t, ls, ln);   // open part on the left
+    seg_scan<T, G, -1, true>(any, head_s, head_n, sm.buf, j, t, rs, rn);   // open part on the right
+
+    // per-sample means: forward pass accumulates, backward pass broadcasts
+    float mean[C];
+    {
+        float s = ls, c = ln;
+#pragma unroll
+        for (int i = 0; i < C; ++i) {
+            s += g[i]; c += 1.f;
+            mean[i] = 0.f;
+            if (jump[i]) { mean[i] = s / c; s = 0.f; c = 0.f; }
+        }
+        // trailing open part continues into the next chunks
+        const float open_mean = (c > 0.f) ? (s + rs) / (c + rn) : 0.f;
+        float carry = open_mean;
+#pragma unroll
+        for (int i = C - 1; i >= 0; --i) {
+            if (jump[i]) carry = mean[i];
+            mean[i] = carry;
+        }
+    }
+    // a head piece that is closed inside this chunk still needs nothing from the right; a
+    // head piece open to the left got (ls, ln) above.  dL/dlam needs the next chunk's first mean.
+    TV_EX(1, t) = mean[0];
+    __syncthreads();
+    const float mnext0 = TV_EX(1, t + 1);
+    float gl[1] = {0.f};
+#pragma unroll
+    for (int i = 0; i < C; ++i) {
+        if (k0 + i < n - 1) {
+            const float xn = (i + 1 < C) ? x[i + 1] : xnext0;
+            const float mn = (i + 1 < C) ? mean[i + 1] : mnext0;
+            const float dx = xn - x[i];
+            const float sg = (dx > 0.f) ? 1.f : ((dx < 0.f) ? -1.f : 0.f);
+            gl[0] = fmaf(sg, mean[i] - mn, gl[0]);
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < C; ++i)
+        if (rvalid && k0 + i < n) p.gy[off + (int64_t)(k0 + i) * es] = mean[i] + sb[i];
+    if (p.partial) {
+        row_sum<T, G, COLS, 1>(gl, sm.red, j, tid);
+        if (rvalid && t == 0) p.partial[row] = gl[0];
+    }
+#undef TV_EX
+}
+
+// ---------------------------------------------------------------------------------
+// Launchers: pick threads-per-row T and samples-per-thread C from the row length.
+// ---------------------------------------------------------------------------------
+template <int T, int C, int G, bool COLS>
+inline hipError_t launch_fwd_long_t(const FwdParams &p, hipStream_t s)
+{
+    const dim3 grid((p.L.n_rows + G - 1) / G), block(T * G);
+    hipLaunchKernelGGL((tv1d_fwd_long_kernel<T, C, G, COLS>), grid, block, 0, s, p);
+    return hipGetLastError();
+}
+
+template <int T, int C, int G, bool COLS>
+inline hipError_t launch_bwd_long_t(const BwdParams &p, hipStream_t s)
+{
+    const dim3 grid((p.L.n_rows + G - 1) / G), block(T * G);
+    hipLaunchKernelGGL((tv1d_bwd_long_kernel<T, C, G, COLS>), grid, block, 0, s, p);
+    return hipGetLastError();
+}
+
+#define TV_LONG_DISPATCH(FN, p, s)                                                        \
+    do {                                                                                  \
+        const int n = (p).L.n;                                                            \
+        const bool cols = (p).L.elem_stride != 1;                                         \
+        if (cols) {                                                                       \
+            if (n <= 128) return FN<64, 2, 16, true>(p, s);                               \
+            if (n <= 256) return FN<64, 4, 16, true>(p, s);                               \
+            if (n <= 512) return FN<64, 8, 16, true>(p, s);                               \
+            if (n <= 1024) return FN<64, 16, 16, true>(p, s);                             \
+            if (n <= 2048) return FN<256, 8, 4, true>(p, s);                              \
+            if (n <= 4096) return FN<256, 16, 4, true>(p, s);                             \
+            if (n <= 8192) return FN<1024, 8, 1, true>(p, s);                             \
+            return FN<1024, 16, 1, true>(p, s);                                           \
+        }                                                                                 \
+        if (n <= 128) return FN<64, 2, 4, false>(p, s);                                   \
+        if (n <= 256) return FN<64, 4, 4, false>(p, s);                                   \
+        if (n <= 512) return FN<64, 8, 4, false>(p, s);                                   \
+        if (n <= 1024) return FN<64, 16, 4, false>(p, s);                                 \
+        if (n <= 2048) return FN<256, 8, 1, false>(p, s);                                 \
+        if (n <= 4096) return FN<256, 16, 1, false>(p, s);                                \
+        if (n <= 8192) return FN<1024, 8, 1, false>(p, s);                                \
+        return FN<1024, 16, 1, false>(p, s);                                              \
+    } while (0)
+
+inline hipError_t launch_fwd_long(const FwdParams &p, hipStream_t s)
+{
+    TV_LONG_DISPATCH(launch_fwd_long_t, p, s);
+}
+
+inline hipError_t launch_bwd_long(const BwdParams &p, hipStream_t s)
+{
+    TV_LONG_DISPATCH(launch_bwd_long_t, p, s);
+}
+
+}  // namespace tvk

@@ -1,0 +1,106 @@
+"""GPU parity: rows longer than 32 samples (T threads per row, Thomas + PCR) against the
+oracle, through the C ABI."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads
+from gpuutil import lam_per_row, rows_view, run_1d
+from parity import FWD_TOL, check_batch, forward_errors
+
+pytestmark = pytest.mark.gpu
+
+
+def _check(y, lam, lam_div, g, axis, label, want_info=True):
+    out = run_1d(y, lam, lam_div, g, axis=axis, want_info=want_info)
+    yr, gr = rows_view(y, axis), rows_view(g, axis)
+    lr = lam_per_row(lam, len(yr), lam_div)
+    st = check_batch(yr, lr, gr, rows_view(out["x"], axis), rows_view(out["gy"], axis),
+                     gl_gpu=out["gl"], lam_count=np.asarray(lam).size, lam_div=lam_div, label=label)
+    if want_info:
+        assert not np.any(out["info"] & (1 << 18)), label       # nobody hit the iteration cap
+        st["max_steps"] = int((out["info"] & 0xffff).max())
+    return st
+
+
+def _mixed_rows(rng, rows, n):
+    """Half random-walk rows with jumps, half white noise around steps."""
+    y = np.empty((rows, n), np.float32)
+    for r in range(rows):
+        if r % 2 == 0:
+            steps = rng.normal(0, 0.05, size=n)
+            jumps = (rng.random(n) < 5e-3) * rng.uniform(0.5, 2, size=n) * rng.choice([-1, 1], size=n)
+            y[r] = np.cumsum(steps + jumps)
+        else:
+            y[r] = np.repeat(rng.uniform(-1, 1, size=(n + 15) // 16), 16)[:n] + rng.normal(0, 0.1, size=n)
+    return y
+
+
+def test_config1_full():
+    y, lam, g = workloads.config1()
+    st = _check(y, lam, 1, g, -1, "cfg1")
+    assert st["max_steps"] <= 40
+
+
+@pytest.mark.parametrize("n", [33, 64, 65, 100, 128, 129, 255, 256, 300, 512, 513, 1000, 1024, 1025,
+                               2048, 3000, 4096, 5000, 8192, 10000, 16384])
+def test_every_long_length(n):
+    rng = np.random.default_rng(500 + n)
+    rows = 7 if n <= 4096 else 3
+    y = _mixed_rows(rng, rows, n)
+    g = rng.normal(size=y.shape).astype(np.float32)
+    lam = (10 ** rng.uniform(-2.5, 1, size=rows)).astype(np.float32)
+    _check(y, lam, 1, g, -1, "n=%d" % n)
+
+
+@pytest.mark.parametrize("n,width", [(40, 37), (64, 16), (200, 20), (512, 48), (1500, 9), (4096, 6), (9000, 3)])
+def test_long_columns(n, width):
+    rng = np.random.default_rng(600 + n)
+    y = np.stack([_mixed_rows(rng, width, n).T for _ in range(2)])        # [2, n, width]
+    g = rng.normal(size=y.shape).astype(np.float32)
+    lam = np.array([0.08, 1.3], np.float32)
+    _check(y, lam, width, g, -2, "cols n=%d" % n)
+
+
+def test_config5_reduced():
+    y, lam, g = workloads.config5(rows=24, n=16384)
+    st = _check(y, lam, 1, g, -1, "cfg5 reduced")
+    assert st["max_steps"] <= 48
+
+
+def test_config4_single_passes():
+    y, lam, g = workloads.config4(B=1, C=2, H=512, W=512, n_poly=6)
+    _check(y, lam, 1, g, -1, "cfg4 rows")
+    _check(y, lam, 1, g, -2, "cfg4 columns")
+
+
+def test_long_lambda_extremes_and_in_place():
+    rng = np.random.default_rng(47)
+    y = _mixed_rows(rng, 6, 700)
+    g = rng.normal(size=y.shape).astype(np.float32)
+    out = run_1d(y, np.array([0.0], np.float32), 1, g)
+    assert np.array_equal(out["x"], y) and np.array_equal(out["gy"], g)
+    out = run_1d(y, np.array([1e5], np.float32), 1, g)
+    np.testing.assert_allclose(out["x"], np.repeat(y.astype(np.float64).mean(1, keepdims=True), 700, 1),
+                               atol=1e-4 * (1 + np.abs(y).max()))
+    assert np.all(out["x"] == out["x"][:, :1])
+    assert out["gl"][0] == 0.0
+    lam = np.array([0.3], np.float32)
+    a = run_1d(y, lam, 1)
+    b = run_1d(y, lam, 1, in_place=True)
+    assert np.array_equal(a["x"], b["x"])
+
+
+def test_long_constant_and_tied_rows():
+    n = 400
+    y = np.zeros((5, n), np.float32)
+    y[1] = -2.5
+    y[2, n // 2:] = 1.0
+    y[3] = np.tile([0.0, 1.0], n // 2)
+    y[4] = np.round(np.random.default_rng(48).normal(size=n) * 2) / 2
+    g = np.random.default_rng(49).normal(size=y.shape).astype(np.float32)
+    lam = np.array([0.25], np.float32)
+    out = run_1d(y, lam, 1, g, want_info=True)
+    x_ref = oracle.prox1d_batch(y.astype(np.float64), lam.astype(np.float64))
+    assert forward_errors(out["x"], x_ref, y).max() <= FWD_TOL
+    assert not np.any(out["info"] & (1 << 18))

@@ -1,0 +1,75 @@
+"""GPU parity for the 2D operator (paper Alg. 1) and its reverse sweep.
+
+Forward: element-wise against the oracle's K-sweep result.  Backward: (a) exactly the
+oracle's reverse sweep replayed on the GPU's own saved pass outputs (same segments, so
+the arithmetic must agree to rounding); (b) against the oracle's own gradient, where one
+near-degenerate row anywhere in the 2K passes changes a gradient entry by O(1), so the
+assertion is on the bulk of the entries."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads
+from gpuutil import run_2d
+
+pytestmark = pytest.mark.gpu
+
+
+def _check_2d(y, lam, K, g, label, bulk=0.9):
+    out = run_2d(y, lam, K, g)
+    y64, lam64, g64 = y.astype(np.float64), lam.astype(np.float64), g.astype(np.float64)
+    x_ref, saved_ref = oracle.prox2d_fwd(y64, lam64, K)
+    scale = 1.0 + np.abs(y).max()
+    assert np.all(np.isfinite(out["x"])), label
+    err = np.abs(out["x"] - x_ref).max() / scale
+    assert err <= 1e-4, (label, "forward", err)
+    perr = np.abs(out["saved"] - saved_ref).max() / scale
+    assert perr <= 1e-4, (label, "saved passes", perr)
+    assert np.array_equal(out["saved"][-1], out["x"])
+    # (a) reverse-sweep arithmetic on the GPU's own segments
+    gy_rep, gl_rep = oracle.prox2d_bwd(g64, out["saved"].astype(np.float64), lam.size, K)
+    gscale = np.abs(gy_rep).max()
+    assert np.abs(out["gy"] - gy_rep).max() <= 1e-4 * gscale, (label, "grad_y replay")
+    assert np.all(np.abs(out["gl"] - gl_rep) <= 1e-4 * (np.abs(gl_rep) + np.sqrt(y.size))), (label, "grad_lam replay")
+    # (b) against the oracle's own gradient: the bulk must agree
+    gy_ref, gl_ref = oracle.prox2d_bwd(g64, saved_ref, lam.size, K)
+    close = np.abs(out["gy"] - gy_ref) <= 1e-3 * np.abs(gy_ref).max()
+    assert close.mean() >= bulk, (label, "grad_y bulk", close.mean())
+    return err, close.mean()
+
+
+def test_small_maps_k1_and_k3():
+    y, lam, g = workloads.config2(B=2, C=8)
+    _check_2d(y, lam, 1, g, "cfg2 K=1")
+    _check_2d(y, lam, 3, g, "cfg2 K=3")
+
+
+def test_config3_planes_k1():
+    y, lam, g = workloads.config3(B=2, C=128)
+    _check_2d(y, lam, 1, g, "cfg3 K=1")
+
+
+def test_odd_sizes_mixed_paths():
+    rng = np.random.default_rng(71)
+    y = rng.normal(size=(3, 19, 45)).astype(np.float32)         # rows of 45 (long path), columns of 19
+    g = rng.normal(size=y.shape).astype(np.float32)
+    lam = np.array([0.1, 0.5, 2.0], np.float32)
+    _check_2d(y, lam, 4, g, "19x45 K=4")
+    y = rng.normal(size=(2, 70, 33)).astype(np.float32)
+    g = rng.normal(size=y.shape).astype(np.float32)
+    _check_2d(y, lam[:2], 2, g, "70x33 K=2")
+
+
+def test_config4_reduced():
+    y, lam, g = workloads.config4(B=1, C=3, H=512, W=512, n_poly=8)
+    _check_2d(y, lam, 3, g, "cfg4 reduced K=3", bulk=0.8)
+
+
+def test_lambda_zero_identity_and_mass():
+    rng = np.random.default_rng(72)
+    y = rng.normal(size=(4, 32, 32)).astype(np.float32)
+    g = rng.normal(size=y.shape).astype(np.float32)
+    out = run_2d(y, np.array([0.0], np.float32), 3, g)
+    assert np.array_equal(out["x"], y) and np.array_equal(out["gy"], g)
+    out = run_2d(y, np.array([0.4], np.float32), 4)
+    np.testing.assert_allclose(out["x"].astype(np.float64).sum((-1, -2)), y.astype(np.float64).sum((-1, -2)), atol=2e-3)
