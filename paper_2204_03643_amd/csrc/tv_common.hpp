@@ -7,7 +7,7 @@ namespace tvk {
 
 // Solver constants.  The paper fixes none of them (Sec. 3.2 only names the Armijo
 // rule with quadratic-interpolation backtracking); these are the values chosen here.
-constexpr int   kMaxNewtonSteps  = 48;      // iteration cap per row
+constexpr int   kMaxNewtonSteps  = 64;      // iteration cap per row
 constexpr int   kMaxBacktracks   = 24;      // line-search rounds per Newton step
 constexpr float kArmijoSigma     = 1e-4f;   // sufficient-decrease fraction
 constexpr float kArmijoSlackEps  = 4.0f * 1.1920929e-7f;  // slack = this * |f|
@@ -16,6 +16,7 @@ constexpr float kArmijoSlackEps  = 4.0f * 1.1920929e-7f;  // slack = this * |f|
 constexpr int kInfoConverged = 1 << 16;
 constexpr int kInfoStalled   = 1 << 17;
 constexpr int kInfoCapped    = 1 << 18;
+constexpr int kInfoPlain     = 1 << 19;   // output is y - D^T u, segments not bit-constant
 
 // Row addressing, mirrored from tv_rows / tv_lambda (host guarantees the 32-bit fields fit).
 struct Layout {

@@ -106,18 +106,25 @@ int launch_fwd_short(const FwdParams &p, bool packed_ok, hipStream_t s)
     return launch_status();
 }
 
-template <int NMAX>
+template <int NMAX, bool HAS_SUB>
 int launch_bwd_short(const BwdParams &p, bool packed_ok, hipStream_t s)
 {
     const dim3 grid((p.L.n_rows + tvk::kShortBlock - 1) / tvk::kShortBlock), block(tvk::kShortBlock);
     const bool full = p.L.n == NMAX;
     if (full && packed_ok)
-        hipLaunchKernelGGL((tvk::tv1d_bwd_short_kernel<NMAX, true, true>), grid, block, 0, s, p);
+        hipLaunchKernelGGL((tvk::tv1d_bwd_short_kernel<NMAX, true, true, HAS_SUB>), grid, block, 0, s, p);
     else if (full)
-        hipLaunchKernelGGL((tvk::tv1d_bwd_short_kernel<NMAX, true, false>), grid, block, 0, s, p);
+        hipLaunchKernelGGL((tvk::tv1d_bwd_short_kernel<NMAX, true, false, HAS_SUB>), grid, block, 0, s, p);
     else
-        hipLaunchKernelGGL((tvk::tv1d_bwd_short_kernel<NMAX, false, false>), grid, block, 0, s, p);
+        hipLaunchKernelGGL((tvk::tv1d_bwd_short_kernel<NMAX, false, false, HAS_SUB>), grid, block, 0, s, p);
     return launch_status();
+}
+
+template <int NMAX>
+int launch_bwd_short(const BwdParams &p, bool packed_ok, hipStream_t s)
+{
+    return p.sub ? launch_bwd_short<NMAX, true>(p, packed_ok, s)
+                 : launch_bwd_short<NMAX, false>(p, packed_ok, s);
 }
 
 // ---- dispatch ---------------------------------------------------------------------
@@ -136,7 +143,8 @@ int run_fwd(const float *y, const float *addend, float *x, float *resid, int32_t
     return tvk::launch_fwd_long(p, s) == hipSuccess ? TV_OK : TV_ERR_HIP;
 }
 
-// Sums the per-row dL/dlam contributions of every slot: one workgroup per slot.
+// Sums the per-row dL/dlam contributions of every slot: one workgroup per slot, fp64
+// accumulation in a fixed order (deterministic).
 __global__ __launch_bounds__(256) void reduce_lambda_kernel(const float *__restrict__ partial,
                                                             float *__restrict__ grad_lam,
                                                             uint32_t n_rows, uint32_t count,
@@ -144,17 +152,27 @@ __global__ __launch_bounds__(256) void reduce_lambda_kernel(const float *__restr
 {
     __shared__ double red[256];
     const uint32_t slot = blockIdx.x;
-    double acc = 0.0;
     // rows of this slot: r = (q*count + slot)*div + i,  i < div,  q = 0, 1, ...
-    const uint64_t groups = ((uint64_t)n_rows + div - 1) / div;           // row groups of size div
-    const uint64_t mine = groups > slot ? (groups - slot + count - 1) / count : 0;
-    const uint64_t total = mine * div;
-    for (uint64_t j = threadIdx.x; j < total; j += 256) {
-        const uint64_t q = j / div, i = j - q * div;
-        const uint64_t r = (q * count + slot) * div + i;
-        if (r < n_rows) acc += (double)partial[r];
+    // thread t walks the pairs (q, i) with q*div + i = t, t + 256, ... without dividing
+    uint32_t q = threadIdx.x / div, i = threadIdx.x - q * div;
+    const uint32_t dq = 256 / div, di = 256 - dq * div;
+    const uint64_t stride = (uint64_t)count * div;
+    const uint64_t base = (uint64_t)slot * div;
+    double acc0 = 0.0, acc1 = 0.0;
+    for (;;) {
+        // group starts grow with q, so once a group starts past the end this thread is done
+        if (q * stride + base >= n_rows) break;
+        const uint64_t r = q * stride + base + i;
+        if (r < n_rows) acc0 += (double)partial[r];
+        q += dq; i += di;
+        if (i >= div) { i -= div; q += 1; }
+        if (q * stride + base >= n_rows) break;
+        const uint64_t r1 = q * stride + base + i;
+        if (r1 < n_rows) acc1 += (double)partial[r1];
+        q += dq; i += di;
+        if (i >= div) { i -= div; q += 1; }
     }
-    red[threadIdx.x] = acc;
+    red[threadIdx.x] = acc0 + acc1;
     __syncthreads();
     for (int w = 128; w > 0; w >>= 1) {
         if ((int)threadIdx.x < w) red[threadIdx.x] += red[threadIdx.x + w];
