@@ -30,6 +30,29 @@ struct Layout {
     uint32_t lam_div;
 };
 
+// Which 64 rows a wave of the row-per-lane forward kernel works on.  Row t of a tile is
+//     first + (t >> lg) * hop + (t & ((1 << lg) - 1)).
+// Identity: lg = 6, tile w starts at row 64 w (grid.y = 1).  Grouped by lambda slot (lam.div
+// = 2^lg < 64 and every slot owning a whole number of tiles): tile (x = slot, y = qb) takes
+// the 64 >> lg consecutive row groups qb * (64 >> lg) ... of ONE slot, which lie hop =
+// lam.count << lg rows apart, so that all 64 rows share their lambda and tend to need the
+// same number of Newton steps.
+struct TileMap {
+    uint32_t lg;
+    uint32_t hop;
+    uint32_t grouped;     // 0: identity
+    uint32_t count;       // lam.count (grouped only)
+    __device__ __forceinline__ uint32_t first(uint32_t x, uint32_t y) const
+    {
+        if (!grouped) return x * 64u;
+        return ((y * (64u >> lg)) * count + x) << lg;
+    }
+    __device__ __forceinline__ uint32_t row(uint32_t first_row, uint32_t t) const
+    {
+        return first_row + (t >> lg) * hop + (t & ((1u << lg) - 1u));
+    }
+};
+
 __device__ __forceinline__ int64_t row_offset(const Layout &L, uint32_t r)
 {
     uint32_t o = r / L.n_inner;
@@ -57,6 +80,7 @@ struct FwdParams {
     const float *lam;
     int32_t     *info;     // optional per-row info word
     Layout       L;
+    TileMap      tm;       // row-per-lane kernels only
 };
 
 struct BwdParams {

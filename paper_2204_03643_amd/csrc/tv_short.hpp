@@ -18,14 +18,17 @@ namespace tvk {
 #ifndef TV_FWD_ATTR
 #define TV_FWD_ATTR
 #endif
-constexpr int kShortBlock = 64;    // one wave of 64 rows per workgroup: a finished wave frees its slot at once
+#ifndef TV_SHORT_WAVES
+#define TV_SHORT_WAVES 1
+#endif
+constexpr int kShortBlock = 64 * TV_SHORT_WAVES;   // waves per workgroup; waves never wait for each other
 
 template <int NMAX>
 struct ShortSmem {
     static constexpr int kPitch      = NMAX + 1;
     static constexpr int kTileFloats = 64 * kPitch;
     static constexpr int kTabFloats  = NMAX + 2;
-    static constexpr int kFloats     = kTileFloats + 2 * kTabFloats;
+    static constexpr int kFloats     = (kShortBlock / 64) * kTileFloats + 2 * kTabFloats;
 };
 
 // gtab[j] = j/(j+1): reciprocal Thomas pivot at position j of a free run (gtab[0] = 0
@@ -62,16 +65,17 @@ struct TileRegs {
 
 // Global -> registers, in tile order (coalesced).  Rows past the end of the batch read as 0.
 template <int NMAX>
-__device__ __forceinline__ void tile_fetch(const float *__restrict__ src, uint32_t r0,
-                                           uint32_t n_rows, int lane, TileRegs<NMAX> &t)
+__device__ __forceinline__ void tile_fetch(const float *__restrict__ src, const TileMap &tm,
+                                           uint32_t first_row, uint32_t n_rows, int lane,
+                                           TileRegs<NMAX> &t)
 {
-    const uint32_t valid_rows = r0 < n_rows ? min(64u, n_rows - r0) : 0u;
-    const float4 *s4 = reinterpret_cast<const float4 *>(src + (size_t)r0 * NMAX);
 #pragma unroll
     for (int i = 0; i < NMAX / 4; ++i) {
         const int e4 = i * 64 + lane;
-        const uint32_t row = (uint32_t)(e4 * 4) / NMAX;
-        t.q[i] = row < valid_rows ? s4[e4] : make_float4(0.f, 0.f, 0.f, 0.f);
+        const uint32_t g = tm.row(first_row, (uint32_t)(e4 * 4) / NMAX);
+        t.q[i] = g < n_rows
+                     ? *reinterpret_cast<const float4 *>(src + (size_t)g * NMAX + (e4 * 4) % NMAX)
+                     : make_float4(0.f, 0.f, 0.f, 0.f);
     }
 }
 
@@ -112,15 +116,16 @@ __device__ __forceinline__ void rows_to_tile(const float (&v)[NMAX], float *tile
 }
 
 template <int NMAX>
-__device__ __forceinline__ void tile_put(float *__restrict__ dst, uint32_t r0, uint32_t n_rows,
-                                         int lane, const TileRegs<NMAX> &t)
+__device__ __forceinline__ void tile_put(float *__restrict__ dst, const TileMap &tm,
+                                         uint32_t first_row, uint32_t n_rows, int lane,
+                                         const TileRegs<NMAX> &t)
 {
-    const uint32_t valid_rows = r0 < n_rows ? min(64u, n_rows - r0) : 0u;
-    float4 *d4 = reinterpret_cast<float4 *>(dst + (size_t)r0 * NMAX);
 #pragma unroll
     for (int i = 0; i < NMAX / 4; ++i) {
         const int e4 = i * 64 + lane;
-        if ((uint32_t)(e4 * 4) / NMAX < valid_rows) d4[e4] = t.q[i];
+        const uint32_t g = tm.row(first_row, (uint32_t)(e4 * 4) / NMAX);
+        if (g < n_rows)
+            *reinterpret_cast<float4 *>(dst + (size_t)g * NMAX + (e4 * 4) % NMAX) = t.q[i];
     }
 }
 
@@ -165,29 +170,33 @@ __device__ __forceinline__ void row_store_strided(float *__restrict__ dst, int64
 //   dual (minimisation form): f(u) = 1/2 ||x(u)||^2 - 1/2 ||y||^2,  x(u) = y - D^T u,
 //   |u_k| <= lam; gradient g_k = x_k - x_{k+1}; Hessian tridiag(-1, 2, -1).
 //
-// The dual u, the Newton direction and the pivots live in registers.  The input row is
-// read-only after the start, so it is parked in LDS, sample-major: yl[k * 64] is sample k
-// of this lane's row (consecutive lanes -> consecutive banks, no conflicts); that keeps the
-// kernel at four waves per SIMD.  Samples k >= n must be 0.  On return xs holds the minimiser of paper Eq. 1.
+// Registers hold the dual, x(u), the Newton direction and the pivots.  The input row is read-only
+// after the start and is parked in LDS, sample-major: yl[k * 64] is sample k of this lane's
+// row (consecutive lanes -> consecutive banks).  Samples k >= n must be 0.
 // ---------------------------------------------------------------------------------
 template <int NMAX, bool FULL>
-__device__ __forceinline__ int pn_solve_row(const float *yl,
-                                            float (&xs)[NMAX], float lam, int n, bool valid,
-                                            const float *gtab, const float *rtab)
-{
-    constexpr int M = NMAX - 1;
-    const int m = n - 1;
-    // duals past the end of a shorter row get an empty box and never move
-#define TV_LK(k) ((FULL || (k) < m) ? lam : 0.0f)
-#define TV_Y(k) yl[(k) * 64]
-#define TV_TAB(tab, off4) (*reinterpret_cast<const float *>(reinterpret_cast<const char *>(tab) + (off4)))
-    // The parked row must be re-read in every pass; without this the compiler hoists the
-    // (loop-invariant) LDS loads back into registers and the occupancy gain is lost.
-#define TV_REREAD() asm volatile("" ::: "memory")
+struct RowSolver {
+    static constexpr int M = NMAX - 1;
+    static constexpr int MA = M > 0 ? M : 1;
 
-    float u[M > 0 ? M : 1];
-    float X[NMAX];          // x(u) = y - D^T u for the current dual, carried between passes
-    float fcur;
+    float X[NMAX];      // x(u) for the current dual, carried between passes
+    float u[MA];        // the dual
+    float D[MA];        // g, then gamma*w, then the Newton direction d
+    float G[MA];        // pivots gamma (0 exactly at bound duals), then the previous dual
+    const float *yl, *gtab;
+    float lam, fcur, alpha_try;
+    int m, steps, flags, nfail;
+    bool active, prev_unclipped;
+
+    __device__ __forceinline__ float lk(int k) const { return (FULL || k < m) ? lam : 0.0f; }
+    __device__ __forceinline__ float yk(int k) const { return yl[k * 64]; }
+    __device__ __forceinline__ float tab(const float *t, int off4) const
+    {
+        return *reinterpret_cast<const float *>(reinterpret_cast<const char *>(t) + off4);
+    }
+    // The parked row must be re-read where it is used; without this the compiler hoists the
+    // loop-invariant LDS loads into registers for the whole solve and occupancy drops.
+    static __device__ __forceinline__ void reread() { asm volatile("" ::: "memory"); }
 
     // ---- starting point, one of two feasible candidates:
     //      A = one full Newton step from u = 0 with every dual free, clipped into the box
@@ -195,80 +204,84 @@ __device__ __forceinline__ int pn_solve_row(const float *yl,
     //      B = every dual at the bound its local difference points to (exact for small lam).
     //      A is taken when lam >= lam_max / 4, which picks the candidate with the lower dual
     //      objective in all but a few percent of rows (measured on the five workloads).
+    __device__ __forceinline__ void start(const float (&y)[NMAX], float inv_n)
     {
-        TV_REREAD();
         float sum = 0.f;
 #pragma unroll
-        for (int k = 0; k < NMAX; ++k) sum += TV_Y(k);
-        const float ybar = sum * rtab[n];
-        float uB[M > 0 ? M : 1];
+        for (int k = 0; k < NMAX; ++k) sum += y[k];
+        const float ybar = sum * inv_n;
         float run = 0.f, rmax = 0.f;
-        TV_REREAD();
-        float yk = TV_Y(0);
 #pragma unroll
         for (int k = 0; k < M; ++k) {
-            const float l = TV_LK(k);
-            const float yn = TV_Y(k + 1);
-            run += ybar - yk;
+            run += ybar - y[k];
             if (FULL || k < m) rmax = fmaxf(rmax, fabsf(run));
-            u[k] = __builtin_amdgcn_fmed3f(run, -l, l);
-            uB[k] = __builtin_amdgcn_fmed3f((yn - yk) * 1e30f, -l, l);
-            yk = yn;
+            D[k] = run;
         }
         const bool pickA = lam >= 0.25f * rmax;
-        TV_REREAD();
         float acc = 0.f, prev = 0.f;
 #pragma unroll
         for (int k = 0; k < M; ++k) {
-            const float c = pickA ? u[k] : uB[k];
-            const float xc = TV_Y(k) + c - prev;
+            const float l = lk(k);
+            const float v = pickA ? D[k] : (y[k + 1] - y[k]) * 1e30f;
+            const float c = __builtin_amdgcn_fmed3f(v, -l, l);
+            const float xc = y[k] + c - prev;
             acc = fmaf(xc, xc, acc);
             u[k] = c; X[k] = xc; prev = c;
         }
         {
-            const float xc = TV_Y(M) - prev;
+            const float xc = y[M] - prev;
             acc = fmaf(xc, xc, acc);
             X[M] = xc;
         }
         fcur = 0.5f * acc;
     }
 
-    bool active = valid;
-    bool prev_unclipped = false;
-    int steps = 0, flags = 0, nfail = 0;
-    float alpha_try = 1.f;
-    // D: gamma*w after the forward elimination, then the Newton direction.  G: the pivots
-    // gamma (0 exactly at bound duals); during the line search it keeps the previous dual.
-    float D[M > 0 ? M : 1], G[M > 0 ? M : 1];
-
-    for (int it = 0;; ++it) {
+    // One projected-Newton iteration.  Returns true when every row of the wave has stopped;
+    // G[k] == 0 then flags the bound duals of each row's final dual and X is its x.
+    __device__ __forceinline__ bool iterate(int it)
+    {
         // ---- gradient, bound set (Bertsekas' sign test with exact comparisons: a clipped
-        //      dual is bit-equal to +-lam), optimality test, Thomas forward elimination
-        //      w_k = g_k + gamma_{k-1} w_{k-1}, kept as t_k = gamma_k w_k
+        //      dual is bit-equal to +-lam) and optimality test.  The pivot of every dual is
+        //      fetched from the table as soon as its position in the free run is known.
         bool vio = false;
-        float dec = 0.f, tprev = 0.f;
-        int pos4 = 0;                               // 4 * position inside the free run
+        {
+            int pos4 = 0;                           // 4 * position inside the free run
 #pragma unroll
-        for (int k = 0; k < M; ++k) {
-            const float g = X[k] - X[k + 1];
-            const float s = copysignf(TV_LK(k), g);
-            const bool bnd = (u[k] == -s);          // at a bound and pushed outwards
-            if (FULL || k < m) vio |= (u[k] == s) && (g != 0.f);  // at a bound, pushed inwards
-            pos4 = bnd ? 0 : pos4 + 4;
-            const float gam = TV_TAB(gtab, pos4);
-            const float w = g + tprev;
-            const float t = gam * w;
-            dec = fmaf(t, w, dec);                  // accumulates g^T H_S^-1 g
-            D[k] = t; G[k] = gam;
-            tprev = t;
+            for (int k = 0; k < M; ++k) {
+                const float g = X[k] - X[k + 1];
+                const float s = copysignf(lk(k), g);
+                const bool bnd = (u[k] == -s);      // at a bound and pushed outwards
+                if (FULL || k < m) vio |= (u[k] == s) && (g != 0.f);  // at a bound, pushed inwards
+                pos4 = bnd ? 0 : pos4 + 4;
+                D[k] = g;
+                G[k] = tab(gtab, pos4);
+            }
+        }
+        // ---- Thomas forward elimination w_k = g_k + gamma_{k-1} w_{k-1}, kept as t_k = gamma_k w_k
+        float dec = 0.f;
+        {
+            float tprev = 0.f;
+#pragma unroll
+            for (int k = 0; k < M; ++k) {
+                const float w = D[k] + tprev;
+                const float t = G[k] * w;
+                dec = fmaf(t, w, dec);              // accumulates g^T H_S^-1 g
+                D[k] = t;
+                tprev = t;
+            }
         }
         // A full, unclipped Newton step zeroes the gradient on the free set; if no dual
         // sits on a bound with the gradient pointing inwards, the KKT conditions hold.
         if (active && prev_unclipped && !vio) { active = false; flags = kInfoConverged; }
         if (active && it >= kMaxNewtonSteps) { active = false; flags = kInfoCapped; }
-        if (!__any(active)) break;
+        if (!__any(active)) return true;
         steps += active ? 1 : 0;
 
+        // ---- the old x is spent (its differences are in D): fetch the row into the same
+        //      registers while the back substitution runs
+        reread();
+#pragma unroll
+        for (int k = 0; k < NMAX; ++k) X[k] = yk(k);
         // ---- back substitution d_k = gamma_k (w_k + d_{k+1}) = t_k + gamma_k d_{k+1}
         {
             float dn = 0.f;
@@ -278,32 +291,30 @@ __device__ __forceinline__ int pn_solve_row(const float *yl,
                 D[k] = dn;
             }
         }
-
         // ---- projected step u(alpha) = clip(u - alpha d); alpha = 1 is taken outright when
         //      nothing clips (it is the exact minimiser over the free subspace), otherwise it
         //      must pass the Armijo test (paper Sec. 3.2).  The trial moves the previous dual
         //      into G (the pivots are spent once d is known) and writes the new dual and its x
-        //      in place.  A row that fails the test takes its dual back and retries in the next
-        //      round with a step length from quadratic interpolation; that is rare (under one
-        //      row in a hundred), so the direction is simply recomputed there.
+        //      in place.  A row that fails takes its dual back and retries in the next
+        //      iteration with a step length from quadratic interpolation; that is rare (under
+        //      one row in a hundred), so the direction is simply recomputed there.
         const float alpha = active ? alpha_try : 0.f;
         bool changed = false;
         float acc = 0.f, prev = 0.f, tmax = 0.f;
-        TV_REREAD();
 #pragma unroll
         for (int k = 0; k < M; ++k) {
-            const float l = TV_LK(k);
+            const float l = lk(k);
             const float uo = u[k];
             const float t = fmaf(-alpha, D[k], uo);
             const float c = __builtin_amdgcn_fmed3f(t, -l, l);
             tmax = fmaxf(tmax, fabsf(t));
             changed |= (c != uo);
-            const float xc = TV_Y(k) + c - prev;
+            const float xc = X[k] + c - prev;       // X[k] holds y_k here
             acc = fmaf(xc, xc, acc);
             G[k] = uo; u[k] = c; X[k] = xc; prev = c;
         }
         {
-            const float xc = TV_Y(M) - prev;
+            const float xc = X[M] - prev;
             acc = fmaf(xc, xc, acc);
             X[M] = xc;
         }
@@ -312,16 +323,16 @@ __device__ __forceinline__ int pn_solve_row(const float *yl,
         const bool ok = !active || (alpha == 1.f && !clipped) ||
                         (fc <= fcur - kArmijoSigma * alpha * dec + kArmijoSlackEps * fabsf(fcur));
         if (__any(!ok)) {
-            TV_REREAD();
+            reread();
             float pv = 0.f;
 #pragma unroll
             for (int k = 0; k < M; ++k) {
                 const float c = ok ? u[k] : G[k];
                 u[k] = c;
-                X[k] = TV_Y(k) + c - pv;
+                X[k] = yk(k) + c - pv;
                 pv = c;
             }
-            X[M] = TV_Y(M) - pv;
+            X[M] = yk(M) - pv;
             if (!ok) {
                 const float den = 2.f * (fc - fcur + dec * alpha);
                 const float an = den > 0.f ? dec * alpha * alpha / den : 0.5f * alpha;
@@ -343,67 +354,72 @@ __device__ __forceinline__ int pn_solve_row(const float *yl,
             }
         }
         if (!__any(active)) {
-            // G holds the previous dual now: rebuild the bound flags of the final iterate
+            // G holds the previous dual now: rebuild the bound flags of the final one
 #pragma unroll
             for (int k = 0; k < M; ++k) {
                 const float g = X[k] - X[k + 1];
-                G[k] = (u[k] == -copysignf(TV_LK(k), g)) ? 0.f : 1.f;
+                G[k] = (u[k] == -copysignf(lk(k), g)) ? 0.f : 1.f;
             }
-            break;
+            return true;
         }
+        return false;
     }
 
-    // ---- primal recovery.  X is x = y - D^T u at the final dual, and G[k] == 0 exactly at
-    //      its bound duals.  Between two bound duals x is constant up to rounding; every
+    // ---- primal recovery.  X is x = y - D^T u at the final dual, bound duals are known; at
+    //      its bound duals (flagged by G[k] == 0).  Between two bound duals x is constant up to rounding; every
     //      sample takes the value of the first sample of its block, so that constant runs are
     //      bit-identical, which is what the backward pass keys on.  Rows that stopped without
-    //      reaching a KKT point (iteration cap, failed line search) keep the plain x.
+    //      reaching a KKT point (iteration cap, line search run dry) keep the plain x.
+    __device__ __forceinline__ void recover(float (&xs)[NMAX])
     {
-        const bool plain = (flags & (kInfoCapped | kInfoPlain)) != 0;
         float val = X[0];
         xs[0] = val;
 #pragma unroll
         for (int k = 1; k < NMAX; ++k) {
-            const bool start = plain || (G[k - 1] == 0.f);
-            val = start ? X[k] : val;
+            val = (G[k - 1] == 0.f) ? X[k] : val;
             xs[k] = val;
         }
+        const bool plain = (flags & (kInfoCapped | kInfoPlain)) != 0;
+        if (__any(plain)) {
+#pragma unroll
+            for (int k = 0; k < NMAX; ++k) xs[k] = plain ? X[k] : xs[k];
+        }
     }
-#undef TV_LK
-#undef TV_Y
-#undef TV_TAB
-#undef TV_REREAD
-    return steps | flags;
-}
+};
 
 // ---------------------------------------------------------------------------------
-// Forward kernel: one row per lane, one wave per workgroup.
+// Forward kernel: one row per lane.  Grid: x = tile within its group, y = tile group
+// (see TileMap); waves of a workgroup never wait for each other.
 // ---------------------------------------------------------------------------------
 template <int NMAX, bool FULL, bool PACKED>
 __global__ __launch_bounds__(kShortBlock) TV_FWD_ATTR void tv1d_fwd_short_kernel(FwdParams p)
 {
     using S = ShortSmem<NMAX>;
     __shared__ float smem[S::kFloats];
-    const int lane = threadIdx.x;
-    float *tile = smem;
-    float *gtab = smem + S::kTileFloats;
+    const int lane = threadIdx.x & 63;
+    float *tile = smem + (threadIdx.x >> 6) * S::kTileFloats;
+    float *gtab = smem + (kShortBlock / 64) * S::kTileFloats;
     float *rtab = gtab + S::kTabFloats;
     fill_tables<NMAX>(gtab, rtab);
+    if (kShortBlock > 64) __syncthreads();      // tables are shared by the workgroup's waves
 
-    const uint32_t row = blockIdx.x * kShortBlock + threadIdx.x;
-    const uint32_t r0 = row - lane;
+    const uint32_t wave_x = blockIdx.x * (kShortBlock / 64) + (threadIdx.x >> 6);
+    const uint32_t r0 = p.tm.first(wave_x, blockIdx.y);
+    const uint32_t row = p.tm.row(r0, lane);
     const bool valid = row < p.L.n_rows;
     const int n = FULL ? NMAX : p.L.n;
-    const float lam = valid ? load_lambda(p.lam, p.L, row) : 0.f;
+    float lam = 0.f;
+    if (p.tm.grouped) lam = fmaxf(p.lam[wave_x], 0.f);          // one slot per tile
+    else if (valid) lam = load_lambda(p.lam, p.L, row);
     const int64_t off = (!PACKED && valid) ? row_offset(p.L, row) : 0;
 
     float y[NMAX], xs[NMAX];
     if constexpr (PACKED) {
         TileRegs<NMAX> t;
-        tile_fetch<NMAX>(p.y, r0, p.L.n_rows, lane, t);
+        tile_fetch<NMAX>(p.y, p.tm, r0, p.L.n_rows, lane, t);
         if (p.addend) {
             TileRegs<NMAX> a;
-            tile_fetch<NMAX>(p.addend, r0, p.L.n_rows, lane, a);
+            tile_fetch<NMAX>(p.addend, p.tm, r0, p.L.n_rows, lane, a);
             tile_add<NMAX>(t, a, 1.f);
         }
         tile_to_rows<NMAX>(t, tile, lane, y);
@@ -416,7 +432,13 @@ __global__ __launch_bounds__(kShortBlock) TV_FWD_ATTR void tv1d_fwd_short_kernel
     for (int k = 0; k < NMAX; ++k) tile[k * 64 + lane] = y[k];
     wave_lds_sync();
 
-    const int info = pn_solve_row<NMAX, FULL>(tile + lane, xs, lam, n, valid, gtab, rtab);
+    RowSolver<NMAX, FULL> sv;
+    sv.yl = tile + lane; sv.gtab = gtab; sv.lam = lam; sv.m = n - 1;
+    sv.alpha_try = 1.f; sv.steps = 0; sv.flags = 0; sv.nfail = 0;
+    sv.active = valid; sv.prev_unclipped = false;
+    sv.start(y, rtab[n]);
+    for (int it = 0; !sv.iterate(it); ++it) {}
+    sv.recover(xs);
 
     const bool want_resid = p.resid != nullptr;
     float rs[NMAX];
@@ -427,16 +449,16 @@ __global__ __launch_bounds__(kShortBlock) TV_FWD_ATTR void tv1d_fwd_short_kernel
     if constexpr (PACKED) {
         TileRegs<NMAX> t;
         rows_to_tile<NMAX>(xs, tile, lane, t);
-        tile_put<NMAX>(p.x, r0, p.L.n_rows, lane, t);
+        tile_put<NMAX>(p.x, p.tm, r0, p.L.n_rows, lane, t);
         if (want_resid) {
             rows_to_tile<NMAX>(rs, tile, lane, t);
-            tile_put<NMAX>(p.resid, r0, p.L.n_rows, lane, t);
+            tile_put<NMAX>(p.resid, p.tm, r0, p.L.n_rows, lane, t);
         }
     } else {
         row_store_strided<NMAX, FULL>(p.x, off, p.L.elem_stride, n, valid, xs);
         if (want_resid) row_store_strided<NMAX, FULL>(p.resid, off, p.L.elem_stride, n, valid, rs);
     }
-    if (p.info && valid) p.info[row] = info;
+    if (p.info && valid) p.info[row] = sv.steps | sv.flags;
 }
 
 // ---------------------------------------------------------------------------------
@@ -450,14 +472,16 @@ __global__ __launch_bounds__(kShortBlock) void tv1d_bwd_short_kernel(BwdParams p
 {
     using S = ShortSmem<NMAX>;
     __shared__ float smem[S::kFloats];
-    const int lane = threadIdx.x;
-    float *tile = smem;
-    float *gtab = smem + S::kTileFloats;
+    const int lane = threadIdx.x & 63;
+    float *tile = smem + (threadIdx.x >> 6) * S::kTileFloats;
+    float *gtab = smem + (kShortBlock / 64) * S::kTileFloats;
     float *rtab = gtab + S::kTabFloats;
     fill_tables<NMAX>(gtab, rtab);
+    if (kShortBlock > 64) __syncthreads();      // tables are shared by the workgroup's waves
 
-    const uint32_t row = blockIdx.x * kShortBlock + threadIdx.x;
-    const uint32_t r0 = row - lane;
+    const TileMap tm = {6u, 0u, 0u, 1u};
+    const uint32_t r0 = (blockIdx.x * (kShortBlock / 64) + (threadIdx.x >> 6)) * 64u;
+    const uint32_t row = r0 + lane;
     const bool valid = row < p.L.n_rows;
     const int n = FULL ? NMAX : p.L.n;
     const int64_t off = (!PACKED && valid) ? row_offset(p.L, row) : 0;
@@ -467,10 +491,10 @@ __global__ __launch_bounds__(kShortBlock) void tv1d_bwd_short_kernel(BwdParams p
     TileRegs<NMAX> st;                // sub in tile order, kept until the store (packed path)
     if constexpr (PACKED) {
         TileRegs<NMAX> tg, tx;
-        tile_fetch<NMAX>(p.g, r0, p.L.n_rows, lane, tg);
-        tile_fetch<NMAX>(p.x, r0, p.L.n_rows, lane, tx);
+        tile_fetch<NMAX>(p.g, tm, r0, p.L.n_rows, lane, tg);
+        tile_fetch<NMAX>(p.x, tm, r0, p.L.n_rows, lane, tx);
         if constexpr (HAS_SUB) {
-            tile_fetch<NMAX>(p.sub, r0, p.L.n_rows, lane, st);
+            tile_fetch<NMAX>(p.sub, tm, r0, p.L.n_rows, lane, st);
             tile_add<NMAX>(tg, st, -1.f);
         }
         tile_to_rows<NMAX>(tg, tile, lane, g);
@@ -523,7 +547,7 @@ __global__ __launch_bounds__(kShortBlock) void tv1d_bwd_short_kernel(BwdParams p
         TileRegs<NMAX> t;
         rows_to_tile<NMAX>(g, tile, lane, t);
         if constexpr (HAS_SUB) tile_add<NMAX>(t, st, 1.f);
-        tile_put<NMAX>(p.gy, r0, p.L.n_rows, lane, t);
+        tile_put<NMAX>(p.gy, tm, r0, p.L.n_rows, lane, t);
     } else {
         if constexpr (HAS_SUB) {
 #pragma unroll

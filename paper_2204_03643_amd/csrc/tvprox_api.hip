@@ -76,6 +76,25 @@ Layout make_layout(const tv_rows &r, const tv_lambda &l, int64_t n_rows)
     return L;
 }
 
+// Tiles of 64 rows for the row-per-lane forward kernel: grouped by lambda slot when the slot
+// pattern allows it (lam.div a power of two below 64, every slot a whole number of tiles).
+tvk::TileMap make_tile_map(const tv_lambda &l, int64_t n_rows)
+{
+    tvk::TileMap tm = {6u, 0u, 0u, 1u};
+    const int64_t div = l.div, count = l.count;
+    constexpr int64_t wpb = tvk::kShortBlock / 64;
+    if (count > 1 && div < 64 && (div & (div - 1)) == 0 && n_rows % (64 * count) == 0 &&
+        count * div <= 0x7fffffff && count % wpb == 0 && n_rows / (64 * count) <= 65535) {
+        uint32_t lg = 0;
+        while ((1 << lg) < div) ++lg;
+        tm.lg = lg;
+        tm.hop = (uint32_t)(count * div);
+        tm.grouped = 1u;
+        tm.count = (uint32_t)count;
+    }
+    return tm;
+}
+
 // Rows are "packed" when row r starts exactly r*length elements after the base.
 bool rows_packed(const tv_rows &r)
 {
@@ -95,7 +114,10 @@ int launch_status()
 template <int NMAX>
 int launch_fwd_short(const FwdParams &p, bool packed_ok, hipStream_t s)
 {
-    const dim3 grid((p.L.n_rows + tvk::kShortBlock - 1) / tvk::kShortBlock), block(tvk::kShortBlock);
+    constexpr uint32_t wpb = tvk::kShortBlock / 64;
+    const uint32_t n_tiles = (p.L.n_rows + 63u) / 64u;
+    dim3 grid((n_tiles + wpb - 1) / wpb), block(tvk::kShortBlock);
+    if (p.tm.grouped) grid = dim3(p.tm.count / wpb, n_tiles / p.tm.count);
     const bool full = p.L.n == NMAX;
     if (full && packed_ok)
         hipLaunchKernelGGL((tvk::tv1d_fwd_short_kernel<NMAX, true, true>), grid, block, 0, s, p);
@@ -135,6 +157,7 @@ int run_fwd(const float *y, const float *addend, float *x, float *resid, int32_t
     FwdParams p;
     p.y = y; p.addend = addend; p.x = x; p.resid = resid; p.lam = l.lam; p.info = info;
     p.L = make_layout(r, l, n_rows);
+    p.tm = make_tile_map(l, n_rows);
     const bool packed = rows_packed(r) && aligned16(y) && aligned16(x) &&
                         (!addend || aligned16(addend)) && (!resid || aligned16(resid));
     if (r.length <= 8) return launch_fwd_short<8>(p, packed, s);
@@ -144,37 +167,40 @@ int run_fwd(const float *y, const float *addend, float *x, float *resid, int32_t
 }
 
 // Sums the per-row dL/dlam contributions of every slot: one workgroup per slot, fp64
-// accumulation in a fixed order (deterministic).
-__global__ __launch_bounds__(256) void reduce_lambda_kernel(const float *__restrict__ partial,
-                                                            float *__restrict__ grad_lam,
-                                                            uint32_t n_rows, uint32_t count,
-                                                            uint32_t div, int accumulate)
+// accumulation in a fixed order (deterministic).  Four independent loads are kept in
+// flight per thread; the walk over the slot's rows needs no division.
+template <int kReduceThreads>
+__global__ __launch_bounds__(kReduceThreads) void reduce_lambda_kernel(
+    const float *__restrict__ partial, float *__restrict__ grad_lam, uint32_t n_rows,
+    uint32_t count, uint32_t div, int accumulate)
 {
-    __shared__ double red[256];
+    __shared__ double red[kReduceThreads];
     const uint32_t slot = blockIdx.x;
     // rows of this slot: r = (q*count + slot)*div + i,  i < div,  q = 0, 1, ...
-    // thread t walks the pairs (q, i) with q*div + i = t, t + 256, ... without dividing
+    // thread t visits the pairs (q, i) with q*div + i = t, t + T, t + 2T, ...
     uint32_t q = threadIdx.x / div, i = threadIdx.x - q * div;
-    const uint32_t dq = 256 / div, di = 256 - dq * div;
+    const uint32_t dq = kReduceThreads / div, di = kReduceThreads - dq * div;
     const uint64_t stride = (uint64_t)count * div;
     const uint64_t base = (uint64_t)slot * div;
-    double acc0 = 0.0, acc1 = 0.0;
-    for (;;) {
-        // group starts grow with q, so once a group starts past the end this thread is done
-        if (q * stride + base >= n_rows) break;
-        const uint64_t r = q * stride + base + i;
-        if (r < n_rows) acc0 += (double)partial[r];
-        q += dq; i += di;
-        if (i >= div) { i -= div; q += 1; }
-        if (q * stride + base >= n_rows) break;
-        const uint64_t r1 = q * stride + base + i;
-        if (r1 < n_rows) acc1 += (double)partial[r1];
-        q += dq; i += di;
-        if (i >= div) { i -= div; q += 1; }
+    double acc[4] = {0.0, 0.0, 0.0, 0.0};
+    bool more = true;
+    while (more) {
+        float v[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            // group starts grow with q: once a group starts past the end, nothing follows
+            const uint64_t g0 = q * stride + base;
+            more = more && (g0 < n_rows);
+            v[j] = (more && g0 + i < n_rows) ? partial[g0 + i] : 0.f;
+            q += dq; i += di;
+            if (i >= div) { i -= div; q += 1; }
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[j] += (double)v[j];
     }
-    red[threadIdx.x] = acc0 + acc1;
+    red[threadIdx.x] = (acc[0] + acc[1]) + (acc[2] + acc[3]);
     __syncthreads();
-    for (int w = 128; w > 0; w >>= 1) {
+    for (int w = kReduceThreads / 2; w > 0; w >>= 1) {
         if ((int)threadIdx.x < w) red[threadIdx.x] += red[threadIdx.x + w];
         __syncthreads();
     }
@@ -182,6 +208,39 @@ __global__ __launch_bounds__(256) void reduce_lambda_kernel(const float *__restr
         const float v = (float)red[0];
         grad_lam[slot] = accumulate ? grad_lam[slot] + v : v;
     }
+}
+
+// Slots that own only a handful of rows (e.g. one lambda per row): one thread per slot.
+__global__ __launch_bounds__(256) void reduce_lambda_small_kernel(
+    const float *__restrict__ partial, float *__restrict__ grad_lam, uint32_t n_rows,
+    uint32_t count, uint32_t div, int accumulate)
+{
+    const uint32_t slot = blockIdx.x * 256 + threadIdx.x;
+    if (slot >= count) return;
+    const uint64_t stride = (uint64_t)count * div;
+    double acc = 0.0;
+    for (uint64_t g0 = (uint64_t)slot * div; g0 < n_rows; g0 += stride)
+        for (uint32_t i = 0; i < div && g0 + i < n_rows; ++i) acc += (double)partial[g0 + i];
+    const float v = (float)acc;
+    grad_lam[slot] = accumulate ? grad_lam[slot] + v : v;
+}
+
+int launch_reduce_lambda(const float *partial, float *grad_lam, int64_t n_rows, const tv_lambda &l,
+                         int accumulate, hipStream_t s)
+{
+    const uint32_t count = (uint32_t)l.count, div = (uint32_t)l.div, nr = (uint32_t)n_rows;
+    const uint64_t groups = ((uint64_t)nr + div - 1) / div;
+    const uint64_t rows_per_slot = ((groups + count - 1) / count) * div;
+    if (rows_per_slot <= 32)
+        hipLaunchKernelGGL(reduce_lambda_small_kernel, dim3((count + 255) / 256), dim3(256), 0, s,
+                           partial, grad_lam, nr, count, div, accumulate);
+    else if (rows_per_slot <= 2048)
+        hipLaunchKernelGGL(reduce_lambda_kernel<256>, dim3(count), dim3(256), 0, s, partial, grad_lam,
+                           nr, count, div, accumulate);
+    else
+        hipLaunchKernelGGL(reduce_lambda_kernel<1024>, dim3(count), dim3(1024), 0, s, partial,
+                           grad_lam, nr, count, div, accumulate);
+    return launch_status();
 }
 
 int run_bwd(const float *g, const float *sub, const float *x, float *gy, float *grad_lam,
@@ -199,12 +258,7 @@ int run_bwd(const float *g, const float *sub, const float *x, float *gy, float *
     else if (r.length <= 32) st = launch_bwd_short<32>(p, packed, s);
     else st = tvk::launch_bwd_long(p, s) == hipSuccess ? TV_OK : TV_ERR_HIP;
     if (st != TV_OK) return st;
-    if (grad_lam) {
-        hipLaunchKernelGGL(reduce_lambda_kernel, dim3((uint32_t)l.count), dim3(256), 0, s, partial,
-                           grad_lam, (uint32_t)n_rows, (uint32_t)l.count, (uint32_t)l.div,
-                           accumulate);
-        st = launch_status();
-    }
+    if (grad_lam) st = launch_reduce_lambda(partial, grad_lam, n_rows, l, accumulate, s);
     return st;
 }
 
