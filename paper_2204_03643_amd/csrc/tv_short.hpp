@@ -64,11 +64,30 @@ struct TileRegs {
 };
 
 // Global -> registers, in tile order (coalesced).  Rows past the end of the batch read as 0.
+// One 64-lane float4 access covers 256 / NMAX whole rows; when that divides the row-group
+// size and the tile is full, every access is "wave-uniform base + lane * 16 bytes".
+template <int NMAX>
+__device__ __forceinline__ bool tile_is_simple(const TileMap &tm, uint32_t first_row, uint32_t n_rows)
+{
+    constexpr uint32_t R = 256 / NMAX;
+    return ((1u << tm.lg) % R) == 0 && tm.row(first_row, 63) < n_rows;
+}
+
 template <int NMAX>
 __device__ __forceinline__ void tile_fetch(const float *__restrict__ src, const TileMap &tm,
                                            uint32_t first_row, uint32_t n_rows, int lane,
                                            TileRegs<NMAX> &t)
 {
+    constexpr uint32_t R = 256 / NMAX;
+    if (tile_is_simple<NMAX>(tm, first_row, n_rows)) {
+        const float *ls = src + lane * 4;
+#pragma unroll
+        for (int i = 0; i < NMAX / 4; ++i) {
+            const uint32_t g0 = __builtin_amdgcn_readfirstlane(tm.row(first_row, i * R));
+            t.q[i] = *reinterpret_cast<const float4 *>(ls + (size_t)g0 * NMAX);
+        }
+        return;
+    }
 #pragma unroll
     for (int i = 0; i < NMAX / 4; ++i) {
         const int e4 = i * 64 + lane;
@@ -120,6 +139,16 @@ __device__ __forceinline__ void tile_put(float *__restrict__ dst, const TileMap 
                                          uint32_t first_row, uint32_t n_rows, int lane,
                                          const TileRegs<NMAX> &t)
 {
+    constexpr uint32_t R = 256 / NMAX;
+    if (tile_is_simple<NMAX>(tm, first_row, n_rows)) {
+        float *ld = dst + lane * 4;
+#pragma unroll
+        for (int i = 0; i < NMAX / 4; ++i) {
+            const uint32_t g0 = __builtin_amdgcn_readfirstlane(tm.row(first_row, i * R));
+            *reinterpret_cast<float4 *>(ld + (size_t)g0 * NMAX) = t.q[i];
+        }
+        return;
+    }
 #pragma unroll
     for (int i = 0; i < NMAX / 4; ++i) {
         const int e4 = i * 64 + lane;
