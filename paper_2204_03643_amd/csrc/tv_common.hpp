@@ -11,6 +11,10 @@ constexpr int   kMaxNewtonSteps  = 64;      // iteration cap per row
 constexpr int   kMaxBacktracks   = 24;      // line-search rounds per Newton step
 constexpr float kArmijoSigma     = 1e-4f;   // sufficient-decrease fraction
 constexpr float kArmijoSlackEps  = 4.0f * 1.1920929e-7f;  // slack = this * |f|
+// A gradient entry below kGradNoise * (max|y| + lam) is rounding noise of x = y - D^T u: a
+// dual that sits on its bound with such a gradient satisfies the KKT conditions (zero
+// multiplier) and must not keep the optimality test from firing.
+constexpr float kGradNoise       = 16.0f * 1.1920929e-7f;
 
 // info word written per row by the *_info entry point
 constexpr int kInfoConverged = 1 << 16;

@@ -63,6 +63,24 @@ __device__ __forceinline__ void row_sum(float (&v)[NV], float *red, int j, int t
     }
 }
 
+// Maximum of one non-negative value over the T threads of each row.
+template <int T, int G, bool COLS>
+__device__ __forceinline__ void row_max(float (&v)[1], float *red, int j, int tid)
+{
+    using Mp = LongMap<T, G, COLS>;
+#pragma unroll
+    for (int off = 32; off >= Mp::RG; off >>= 1) v[0] = fmaxf(v[0], __shfl_xor(v[0], off));
+    if (Mp::WPR == 1) return;
+    const int wave = tid >> 6, lane = tid & 63;
+    __syncthreads();
+    if (lane < Mp::RG) red[wave * Mp::RG + (COLS ? j : 0)] = v[0];
+    __syncthreads();
+    const int w0 = COLS ? 0 : j * Mp::WPR;
+    float s = 0.f;
+    for (int w = 0; w < Mp::WPR; ++w) s = fmaxf(s, red[(w0 + w) * Mp::RG + (COLS ? j : 0)]);
+    v[0] = s;
+}
+
 // Segmented exclusive scan over the T threads of a row, from t = 0 upwards (DIR = +1) or
 // from t = T-1 downwards (DIR = -1).  Each thread contributes (closed, s, n): `closed`
 // says its chunk holds a segment boundary, and (s, n) describe the part of the chunk
@@ -151,6 +169,16 @@ __global__ __launch_bounds__(T *G) void tv1d_fwd_long_kernel(FwdParams p)
     __syncthreads();
     const float ynext0 = TV_EX(0, t + 1);
     __syncthreads();
+    // rounding floor of a difference of two x values (|x| <= max|y|, |u| <= lam)
+    float gtol;
+    {
+        float ym[1] = {0.f};
+#pragma unroll
+        for (int i = 0; i < C; ++i) ym[0] = fmaxf(ym[0], fabsf(y[i]));
+        row_max<T, G, COLS>(ym, sm.red, j, tid);
+        gtol = kGradNoise * (ym[0] + lam);
+        __syncthreads();
+    }
 
     // ---- starting point: every dual at the bound its local difference points to
     float u[C];
@@ -205,7 +233,7 @@ __global__ __launch_bounds__(T *G) void tv1d_fwd_long_kernel(FwdParams p)
                 g[i] = gi;
                 const float s = copysignf(TV_LK(i), gi);
                 const bool bnd = (u[i] == -s);
-                if (k0 + i < M && u[i] == s && gi != 0.f) viof[0] += 1.f;
+                if (k0 + i < M && u[i] == s && fabsf(gi) > gtol) viof[0] += 1.f;
                 if (i < C - 1) {
                     pos = bnd ? 0 : pos + 1;
                     const float gm = sm.gtab[pos];

@@ -213,7 +213,7 @@ struct RowSolver {
     float D[MA];        // g, then gamma*w, then the Newton direction d
     float G[MA];        // pivots gamma (0 exactly at bound duals), then the previous dual
     const float *yl, *gtab;
-    float lam, fcur, alpha_try;
+    float lam, fcur, alpha_try, gtol;
     int m, steps, flags, nfail;
     bool active, prev_unclipped;
 
@@ -235,9 +235,10 @@ struct RowSolver {
     //      objective in all but a few percent of rows (measured on the five workloads).
     __device__ __forceinline__ void start(const float (&y)[NMAX], float inv_n)
     {
-        float sum = 0.f;
+        float sum = 0.f, ymax = 0.f;
 #pragma unroll
-        for (int k = 0; k < NMAX; ++k) sum += y[k];
+        for (int k = 0; k < NMAX; ++k) { sum += y[k]; ymax = fmaxf(ymax, fabsf(y[k])); }
+        gtol = kGradNoise * (ymax + lam);     // rounding floor of a difference of two x values
         const float ybar = sum * inv_n;
         float run = 0.f, rmax = 0.f;
 #pragma unroll
@@ -280,7 +281,7 @@ struct RowSolver {
                 const float g = X[k] - X[k + 1];
                 const float s = copysignf(lk(k), g);
                 const bool bnd = (u[k] == -s);      // at a bound and pushed outwards
-                if (FULL || k < m) vio |= (u[k] == s) && (g != 0.f);  // at a bound, pushed inwards
+                if (FULL || k < m) vio |= (u[k] == s) && (fabsf(g) > gtol);  // at a bound, pushed inwards
                 pos4 = bnd ? 0 : pos4 + 4;
                 D[k] = g;
                 G[k] = tab(gtab, pos4);
