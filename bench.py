@@ -50,6 +50,71 @@ def cpu_baseline(sample_rows: int):
                       "over rows), %.2f s of wall time" % (rows, n_chunks, dt)}
 
 
+def other_workloads(dev, reps: int = 5):
+    """fwd / bwd times of the other four workloads (context beside the headline number)."""
+    import torch
+
+    import paper_2204_03643_amd as tv
+    import workloads
+
+    def timed(fn):
+        for _ in range(2):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps * 1e3          # microseconds
+
+    def one_d(y, lam, g, axis, lam_div):
+        yt, lt, gt = (torch.from_numpy(a).to(dev) for a in (y, lam, g))
+        xt, gy, gl = torch.empty_like(yt), torch.empty_like(yt), torch.empty_like(lt)
+        rows = tv.rows_along(y.shape, axis)
+        L = tv.tv_lambda(lt.data_ptr(), lt.numel(), lam_div)
+        wsb = tv.tv1d_bwd_workspace_bytes(rows, L)
+        ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device=dev)
+        tf = timed(lambda: tv.tv1d_prox_fwd(yt, xt, rows, L))
+        tb = timed(lambda: tv.tv1d_prox_bwd(gt, xt, gy, gl, rows, L, ws, wsb))
+        n_rows = rows.n_outer * rows.n_inner
+        return {"rows": n_rows, "length": rows.length, "fwd_us": tf, "bwd_us": tb,
+                "rows_per_s": n_rows / ((tf + tb) * 1e-6),
+                "effective_gbs": 20 * y.size / ((tf + tb) * 1e-6) / 1e9,
+                "frac_of_hbm_peak": 20 * y.size / ((tf + tb) * 1e-6) / 1e9 / HBM_PEAK_GBS}
+
+    def two_d(y, lam, g, sweeps):
+        H, W = y.shape[-2:]
+        planes = y.size // (H * W)
+        yt, lt, gt = (torch.from_numpy(a).to(dev) for a in (y, lam, g))
+        xt, gy, gl = torch.empty_like(yt), torch.empty_like(yt), torch.empty_like(lt)
+        L = tv.tv_lambda(lt.data_ptr(), lt.numel(), 1)
+        wsb = tv.tv2d_workspace_bytes(planes, H, W, sweeps)
+        ws = torch.empty(wsb, dtype=torch.uint8, device=dev)
+        tf = timed(lambda: tv.tv2d_prox_fwd(yt, xt, planes, H, W, L, sweeps, ws, wsb))
+        tb = timed(lambda: tv.tv2d_prox_bwd(gt, gy, gl, planes, H, W, L, sweeps, ws, wsb))
+        return {"planes": planes, "H": H, "W": W, "sweeps": sweeps, "fwd_us": tf, "bwd_us": tb,
+                "images_per_s": planes / ((tf + tb) * 1e-6)}
+
+    out = {}
+    y, lam, g = workloads.config1()
+    out["config1_1d_64x256"] = one_d(y, lam, g, -1, 1)
+    y, lam, g = workloads.config2()
+    out["config2_rows"] = one_d(y, lam, g, -1, 32)
+    out["config2_columns"] = one_d(y, lam, g, -2, 32)
+    out["config2_2d_k1"] = two_d(y, lam, g, 1)
+    y, lam, g = workloads.config4()
+    out["config4_rows"] = one_d(y, lam, g, -1, 1)
+    out["config4_columns"] = one_d(y, lam, g, -2, 1)
+    out["config4_2d_k10"] = two_d(y, lam, g, 10)
+    del y, lam, g
+    torch.cuda.empty_cache()
+    y, lam, g = workloads.config5()
+    out["config5_1d_4096x16384"] = one_d(y, lam, g, -1, 1)
+    return out
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -57,6 +122,10 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-rows", type=int, default=1 << 23)
+    ap.add_argument("--headline-only", action="store_true", help="skip the other four workloads")
+    ap.add_argument("--traffic-probe", action="store_true",
+                    help="run fwd, bwd and a plain copy of the same tensor three times each and "
+                         "exit (for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (rows are independent; see DESIGN.md for "
@@ -94,6 +163,13 @@ def main() -> int:
         tv.tv1d_prox_bwd(gt, xt, gy, gl, rows, L, ws, wsb, stream)
         if evs is not None:
             evs[2].record(stream)
+
+    if args.traffic_probe:
+        for _ in range(3):
+            step()
+            xt.copy_(yt)            # plain copy kernel: reads and writes y.numel() * 4 bytes
+        torch.cuda.synchronize()
+        return 0
 
     for _ in range(args.warmup):
         step()
@@ -147,6 +223,26 @@ def main() -> int:
                          "frac": bwd_gbs / HBM_PEAK_GBS, "launch_us": bwd_ms * 1e3,
                          "algorithmic_bytes_per_launch": bwd_bytes},
     }
+    if not args.headline_only:
+        # the same tensor taken along H (the column pass), then the other workloads
+        rc = tv.rows_along(y.shape, -2)
+        Lc = tv.tv_lambda(lt.data_ptr(), C, W)
+        e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        tv.tv1d_prox_fwd(yt, xt, rc, Lc, stream)
+        tv.tv1d_prox_bwd(gt, xt, gy, gl, rc, Lc, ws, wsb, stream)
+        e[0].record(stream)
+        for _ in range(5):
+            tv.tv1d_prox_fwd(yt, xt, rc, Lc, stream)
+        e[1].record(stream)
+        for _ in range(5):
+            tv.tv1d_prox_bwd(gt, xt, gy, gl, rc, Lc, ws, wsb, stream)
+        e[2].record(stream)
+        torch.cuda.synchronize()
+        out["config3_columns"] = {"fwd_us": e[0].elapsed_time(e[1]) * 200.0,
+                                  "bwd_us": e[1].elapsed_time(e[2]) * 200.0}
+        del yt, gt, xt, gy
+        torch.cuda.empty_cache()
+        out["other_workloads"] = other_workloads(dev)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.cpu_sample_rows)
     print(json.dumps(out))
