@@ -36,20 +36,24 @@ struct Layout {
 
 // Which 64 rows a wave of the row-per-lane forward kernel works on.  Row t of a tile is
 //     first + (t >> lg) * hop + (t & ((1 << lg) - 1)).
-// Identity: lg = 6, tile w starts at row 64 w (grid.y = 1).  Grouped by lambda slot (lam.div
-// = 2^lg < 64 and every slot owning a whole number of tiles): tile (x = slot, y = qb) takes
-// the 64 >> lg consecutive row groups qb * (64 >> lg) ... of ONE slot, which lie hop =
-// lam.count << lg rows apart, so that all 64 rows share their lambda and tend to need the
-// same number of Newton steps.
+// Identity: lg = 6, tile w starts at row 64 w, the grid is one-dimensional.  Grouped by
+// lambda slot (lam.div = 2^lg < 64 and every slot owning a whole number of tiles): tile
+// (qb, slot) takes the 64 >> lg consecutive row groups qb * (64 >> lg) ... of ONE slot,
+// which lie hop = lam.count << lg rows apart, so that all 64 rows share their lambda and tend
+// to need the same number of Newton steps.  The grid is then (tiles per slot, slots) with qb
+// as the fast index: the cost of a tile depends mostly on its lambda, and workgroups go to
+// the 8 XCDs round-robin in linear order, so with the slot as the fast index an XCD would
+// keep getting the same few slots and the XCDs with the expensive ones would finish late.
 struct TileMap {
     uint32_t lg;
     uint32_t hop;
     uint32_t grouped;     // 0: identity
     uint32_t count;       // lam.count (grouped only)
-    __device__ __forceinline__ uint32_t first(uint32_t x, uint32_t y) const
+    // first row of tile (qb, slot)
+    __device__ __forceinline__ uint32_t first(uint32_t qb, uint32_t slot) const
     {
-        if (!grouped) return x * 64u;
-        return ((y * (64u >> lg)) * count + x) << lg;
+        if (!grouped) return qb * 64u;
+        return ((qb * (64u >> lg)) * count + slot) << lg;
     }
     __device__ __forceinline__ uint32_t row(uint32_t first_row, uint32_t t) const
     {

@@ -82,9 +82,8 @@ tvk::TileMap make_tile_map(const tv_lambda &l, int64_t n_rows)
 {
     tvk::TileMap tm = {6u, 0u, 0u, 1u};
     const int64_t div = l.div, count = l.count;
-    constexpr int64_t wpb = tvk::kShortBlock / 64;
     if (count > 1 && div < 64 && (div & (div - 1)) == 0 && n_rows % (64 * count) == 0 &&
-        count * div <= 0x7fffffff && count % wpb == 0 && n_rows / (64 * count) <= 65535) {
+        count * div <= 0x7fffffff && count <= 65535) {
         uint32_t lg = 0;
         while ((1 << lg) < div) ++lg;
         tm.lg = lg;
@@ -117,7 +116,8 @@ int launch_fwd_short(const FwdParams &p, bool packed_ok, hipStream_t s)
     constexpr uint32_t wpb = tvk::kShortBlock / 64;
     const uint32_t n_tiles = (p.L.n_rows + 63u) / 64u;
     dim3 grid((n_tiles + wpb - 1) / wpb), block(tvk::kShortBlock);
-    if (p.tm.grouped) grid = dim3(p.tm.count / wpb, n_tiles / p.tm.count);
+    static_assert(wpb == 1, "the grouped grid below assumes one tile per workgroup");
+    if (p.tm.grouped) grid = dim3(n_tiles / p.tm.count, p.tm.count);
     const bool full = p.L.n == NMAX;
     if (full && packed_ok)
         hipLaunchKernelGGL((tvk::tv1d_fwd_short_kernel<NMAX, true, true>), grid, block, 0, s, p);
