@@ -86,7 +86,9 @@ int tv1d_prox_fwd(const float *y, float *x, tv_rows rows, tv_lambda lam, hipStre
  * As tv1d_prox_fwd, and additionally writes one int32 per row to `info` (device
  * pointer, n_outer*n_inner entries, may be NULL): bits 0..15 = Newton steps taken,
  * bit 16 = stopped on the optimality test, bit 17 = stopped because a step left
- * the dual unchanged, bit 18 = iteration cap reached.
+ * the dual unchanged, bit 18 = iteration cap reached, bit 19 = the row stopped short of an
+ * optimal point (cap, or line search run dry) and its output is the plain y - D^T u, whose
+ * segments are constant only up to rounding.
  */
 int tv1d_prox_fwd_info(const float *y, float *x, int32_t *info, tv_rows rows, tv_lambda lam,
                        hipStream_t stream);
@@ -104,6 +106,24 @@ int tv1d_prox_fwd_info(const float *y, float *x, int32_t *info, tv_rows rows, tv
 int tv1d_prox_bwd(const float *g_up, const float *x, float *grad_y, float *grad_lam,
                   tv_rows rows, tv_lambda lam, void *ws, size_t ws_bytes, hipStream_t stream);
 size_t tv1d_bwd_workspace_bytes(tv_rows rows, tv_lambda lam);
+
+/*
+ * Forward/backward pair for rows of at most TV_SEG_MAX_LENGTH samples in which the
+ * backward pass does not read x again.  All that paper Eq. 5-6 need from the solution is
+ * its partition into constant segments and the direction of every jump; the forward call
+ * writes that as one 64-bit code per row and the backward call reads the code (8 bytes per
+ * row) instead of x (4 * length bytes per row).  Results are bit-identical to
+ * tv1d_prox_fwd / tv1d_prox_bwd.
+ *   seg: device pointer, 8-byte aligned, one uint64 per row in row order
+ *        (entry o * n_inner + i for the row at o * outer_stride + i * inner_stride);
+ *        bit k (k < 31) is set when x[k+1] != x[k], bit 32 + k when x[k+1] > x[k].
+ * Longer rows: TV_ERR_UNSUPPORTED.  Everything else as in the plain pair.
+ */
+#define TV_SEG_MAX_LENGTH 32
+int tv1d_prox_fwd_seg(const float *y, float *x, uint64_t *seg, tv_rows rows, tv_lambda lam,
+                      hipStream_t stream);
+int tv1d_prox_bwd_seg(const float *g_up, const uint64_t *seg, float *grad_y, float *grad_lam,
+                      tv_rows rows, tv_lambda lam, void *ws, size_t ws_bytes, hipStream_t stream);
 
 /*
  * 2D anisotropic TV prox on `planes` images of H x W (row-major, contiguous) by

@@ -80,6 +80,8 @@ __device__ __forceinline__ float load_lambda(const float *lam, const Layout &L, 
     return fmaxf(lam[lam_slot(L, r)], 0.0f);
 }
 
+// Segment code of a row of n <= 32 samples: .x bit k is set when x[k+1] != x[k] (a jump after
+// sample k), .y bit k when x[k+1] > x[k].  It carries everything the backward pass reads from x.
 struct FwdParams {
     const float *y;        // input rows
     const float *addend;   // optional: the prox input is y + addend (Dykstra correction term)
@@ -87,6 +89,7 @@ struct FwdParams {
     float       *resid;    // optional: receives (y + addend) - x  (next correction term)
     const float *lam;
     int32_t     *info;     // optional per-row info word
+    uint2       *seg;      // optional per-row segment code (rows of up to 32 samples only)
     Layout       L;
     TileMap      tm;       // row-per-lane kernels only
 };
@@ -94,7 +97,8 @@ struct FwdParams {
 struct BwdParams {
     const float *g;        // upstream gradient
     const float *sub;      // optional: the averaged quantity is g - sub, and sub is added back
-    const float *x;        // forward output (defines the segments)
+    const float *x;        // forward output (defines the segments) ...
+    const uint2 *seg;      // ... or the segment code the forward pass wrote (row-per-lane kernels)
     float       *gy;       // output
     float       *partial;  // optional: per-row dL/dlam contribution
     Layout       L;

@@ -519,15 +519,27 @@ __global__ __launch_bounds__(kShortBlock) TV_FWD_ATTR void tv1d_fwd_short_kernel
         if (want_resid) row_store_strided<NMAX, FULL>(p.resid, off, p.L.elem_stride, n, valid, rs);
     }
     if (p.info && valid) p.info[row] = sv.steps | sv.flags;
+    if (p.seg) {
+        // built from the highest dual down, one shift-in per dual: bit k ends up at position k
+        uint32_t jm = 0, up = 0;
+#pragma unroll
+        for (int k = NMAX - 2; k >= 0; --k) {
+            const bool in = FULL || k < n - 1;
+            jm = jm + jm + ((in && xs[k + 1] != xs[k]) ? 1u : 0u);
+            up = up + up + ((in && xs[k + 1] > xs[k]) ? 1u : 0u);
+        }
+        if (valid) p.seg[row] = make_uint2(jm, up);
+    }
 }
 
 // ---------------------------------------------------------------------------------
 // Backward kernel (paper Eq. 5-6 as segment averaging): one row per lane.
-//   segments = maximal runs of bit-equal neighbours in the forward output x;
+//   segments = maximal runs of bit-equal neighbours in the forward output x, read either
+//              from x itself or (SEG) from the code the forward pass wrote for the row;
 //   grad_y   = per-segment mean of (g - sub), plus sub;
 //   dL/dlam  = sum over jumps k of sign(x[k+1]-x[k]) * (mean_left - mean_right).
 // ---------------------------------------------------------------------------------
-template <int NMAX, bool FULL, bool PACKED, bool HAS_SUB>
+template <int NMAX, bool FULL, bool PACKED, bool HAS_SUB, bool SEG>
 __global__ __launch_bounds__(kShortBlock) void tv1d_bwd_short_kernel(BwdParams p)
 {
     using S = ShortSmem<NMAX>;
@@ -547,21 +559,23 @@ __global__ __launch_bounds__(kShortBlock) void tv1d_bwd_short_kernel(BwdParams p
     const int64_t off = (!PACKED && valid) ? row_offset(p.L, row) : 0;
 
     float g[NMAX], x[NMAX];
+    uint2 code = make_uint2(0u, 0u);
+    if constexpr (SEG) { if (valid) code = p.seg[row]; }
     float sb[NMAX];                   // sub per row (strided path)
     TileRegs<NMAX> st;                // sub in tile order, kept until the store (packed path)
     if constexpr (PACKED) {
         TileRegs<NMAX> tg, tx;
         tile_fetch<NMAX>(p.g, tm, r0, p.L.n_rows, lane, tg);
-        tile_fetch<NMAX>(p.x, tm, r0, p.L.n_rows, lane, tx);
+        if constexpr (!SEG) tile_fetch<NMAX>(p.x, tm, r0, p.L.n_rows, lane, tx);
         if constexpr (HAS_SUB) {
             tile_fetch<NMAX>(p.sub, tm, r0, p.L.n_rows, lane, st);
             tile_add<NMAX>(tg, st, -1.f);
         }
         tile_to_rows<NMAX>(tg, tile, lane, g);
-        tile_to_rows<NMAX>(tx, tile, lane, x);
+        if constexpr (!SEG) tile_to_rows<NMAX>(tx, tile, lane, x);
     } else {
         row_load_strided<NMAX, FULL>(p.g, nullptr, off, p.L.elem_stride, n, valid, g);
-        row_load_strided<NMAX, FULL>(p.x, nullptr, off, p.L.elem_stride, n, valid, x);
+        if constexpr (!SEG) row_load_strided<NMAX, FULL>(p.x, nullptr, off, p.L.elem_stride, n, valid, x);
         if constexpr (HAS_SUB) {
             row_load_strided<NMAX, FULL>(p.sub, nullptr, off, p.L.elem_stride, n, valid, sb);
 #pragma unroll
@@ -570,6 +584,15 @@ __global__ __launch_bounds__(kShortBlock) void tv1d_bwd_short_kernel(BwdParams p
         wave_lds_sync();                  // the tables are ready
     }
 
+    // jump after sample k / its direction
+    auto jump = [&](int k) -> bool {
+        if constexpr (SEG) return (code.x & (1u << k)) != 0u;
+        else return x[k + 1] != x[k];
+    };
+    auto signed_by_jump = [&](int k, float v) -> float {
+        if constexpr (SEG) return (code.y & (1u << k)) != 0u ? v : -v;
+        else return copysignf(1.f, x[k + 1] - x[k]) * v;
+    };
     // forward sweep: segment sums; a segment ends at k when x jumps after k (or the row ends);
     // g[k] is overwritten by the mean of the segment that ends at k
     {
@@ -580,7 +603,7 @@ __global__ __launch_bounds__(kShortBlock) void tv1d_bwd_short_kernel(BwdParams p
             s += g[k];
             c4 += 4;
             const bool last = FULL ? (k == NMAX - 1) : (k >= n - 1);
-            const bool end = last || (k + 1 < NMAX && x[k + 1] != x[k]);
+            const bool end = last || (k + 1 < NMAX && jump(k));
             g[k] = s * *reinterpret_cast<const float *>(reinterpret_cast<const char *>(rtab) + c4);
             if (end) { s = 0.f; c4 = 0; }
         }
@@ -594,13 +617,10 @@ __global__ __launch_bounds__(kShortBlock) void tv1d_bwd_short_kernel(BwdParams p
         for (int k = NMAX - 1; k >= 0; --k) {
             const float right = carry;
             const bool last = FULL ? (k == NMAX - 1) : (k >= n - 1);
-            const bool end = last || (k + 1 < NMAX && x[k + 1] != x[k]);
+            const bool end = last || (k + 1 < NMAX && jump(k));
             carry = end ? g[k] : carry;
             g[k] = carry;
-            if (k + 1 < NMAX && (FULL || k < n - 1)) {
-                const float dx = x[k + 1] - x[k];
-                glam = fmaf(copysignf(1.f, dx), carry - right, glam);
-            }
+            if (k + 1 < NMAX && (FULL || k < n - 1)) glam += signed_by_jump(k, carry - right);
         }
     }
     if constexpr (PACKED) {

@@ -128,34 +128,36 @@ int launch_fwd_short(const FwdParams &p, bool packed_ok, hipStream_t s)
     return launch_status();
 }
 
-template <int NMAX, bool HAS_SUB>
+template <int NMAX, bool HAS_SUB, bool SEG>
 int launch_bwd_short(const BwdParams &p, bool packed_ok, hipStream_t s)
 {
     const dim3 grid((p.L.n_rows + tvk::kShortBlock - 1) / tvk::kShortBlock), block(tvk::kShortBlock);
     const bool full = p.L.n == NMAX;
     if (full && packed_ok)
-        hipLaunchKernelGGL((tvk::tv1d_bwd_short_kernel<NMAX, true, true, HAS_SUB>), grid, block, 0, s, p);
+        hipLaunchKernelGGL((tvk::tv1d_bwd_short_kernel<NMAX, true, true, HAS_SUB, SEG>), grid, block, 0, s, p);
     else if (full)
-        hipLaunchKernelGGL((tvk::tv1d_bwd_short_kernel<NMAX, true, false, HAS_SUB>), grid, block, 0, s, p);
+        hipLaunchKernelGGL((tvk::tv1d_bwd_short_kernel<NMAX, true, false, HAS_SUB, SEG>), grid, block, 0, s, p);
     else
-        hipLaunchKernelGGL((tvk::tv1d_bwd_short_kernel<NMAX, false, false, HAS_SUB>), grid, block, 0, s, p);
+        hipLaunchKernelGGL((tvk::tv1d_bwd_short_kernel<NMAX, false, false, HAS_SUB, SEG>), grid, block, 0, s, p);
     return launch_status();
 }
 
 template <int NMAX>
 int launch_bwd_short(const BwdParams &p, bool packed_ok, hipStream_t s)
 {
-    return p.sub ? launch_bwd_short<NMAX, true>(p, packed_ok, s)
-                 : launch_bwd_short<NMAX, false>(p, packed_ok, s);
+    if (p.seg) return launch_bwd_short<NMAX, false, true>(p, packed_ok, s);   // never with sub
+    return p.sub ? launch_bwd_short<NMAX, true, false>(p, packed_ok, s)
+                 : launch_bwd_short<NMAX, false, false>(p, packed_ok, s);
 }
 
 // ---- dispatch ---------------------------------------------------------------------
 
 int run_fwd(const float *y, const float *addend, float *x, float *resid, int32_t *info,
-            const tv_rows &r, const tv_lambda &l, int64_t n_rows, hipStream_t s)
+            uint2 *seg, const tv_rows &r, const tv_lambda &l, int64_t n_rows, hipStream_t s)
 {
     FwdParams p;
     p.y = y; p.addend = addend; p.x = x; p.resid = resid; p.lam = l.lam; p.info = info;
+    p.seg = seg;
     p.L = make_layout(r, l, n_rows);
     p.tm = make_tile_map(l, n_rows);
     const bool packed = rows_packed(r) && aligned16(y) && aligned16(x) &&
@@ -243,14 +245,15 @@ int launch_reduce_lambda(const float *partial, float *grad_lam, int64_t n_rows, 
     return launch_status();
 }
 
-int run_bwd(const float *g, const float *sub, const float *x, float *gy, float *grad_lam,
-            int accumulate, const tv_rows &r, const tv_lambda &l, int64_t n_rows, float *partial,
-            hipStream_t s)
+int run_bwd(const float *g, const float *sub, const float *x, const uint2 *seg, float *gy,
+            float *grad_lam, int accumulate, const tv_rows &r, const tv_lambda &l, int64_t n_rows,
+            float *partial, hipStream_t s)
 {
     BwdParams p;
-    p.g = g; p.sub = sub; p.x = x; p.gy = gy; p.partial = grad_lam ? partial : nullptr;
+    p.g = g; p.sub = sub; p.x = x; p.seg = seg; p.gy = gy;
+    p.partial = grad_lam ? partial : nullptr;
     p.L = make_layout(r, l, n_rows);
-    const bool packed = rows_packed(r) && aligned16(g) && aligned16(x) && aligned16(gy) &&
+    const bool packed = rows_packed(r) && aligned16(g) && (!x || aligned16(x)) && aligned16(gy) &&
                         (!sub || aligned16(sub));
     int st;
     if (r.length <= 8) st = launch_bwd_short<8>(p, packed, s);
@@ -276,7 +279,8 @@ int zero_floats(float *p, int64_t n, hipStream_t s)
     return launch_status();
 }
 
-int fwd_entry(const float *y, float *x, int32_t *info, tv_rows rows, tv_lambda lam, hipStream_t s)
+int fwd_entry(const float *y, float *x, int32_t *info, uint64_t *seg, bool want_seg, tv_rows rows,
+              tv_lambda lam, hipStream_t s)
 {
     int st = check_lambda(lam);
     if (st != TV_OK) return st;
@@ -286,7 +290,39 @@ int fwd_entry(const float *y, float *x, int32_t *info, tv_rows rows, tv_lambda l
     if (n_rows == 0) return TV_OK;
     if (!y || !x || !lam.lam) return TV_ERR_NULL;
     if (rows.length > TV_MAX_LENGTH) return TV_ERR_UNSUPPORTED;
-    return run_fwd(y, nullptr, x, nullptr, info, rows, lam, n_rows, s);
+    if (want_seg) {
+        if (!seg) return TV_ERR_NULL;
+        if (rows.length > TV_SEG_MAX_LENGTH) return TV_ERR_UNSUPPORTED;
+        if ((uintptr_t)seg % 8 != 0) return TV_ERR_STRIDE;
+    }
+    return run_fwd(y, nullptr, x, nullptr, info, reinterpret_cast<uint2 *>(seg), rows, lam, n_rows, s);
+}
+
+int bwd_entry(const float *g_up, const float *x, const uint64_t *seg, bool with_seg, float *grad_y,
+              float *grad_lam, tv_rows rows, tv_lambda lam, void *ws, size_t ws_bytes, hipStream_t stream)
+{
+    int st = check_lambda(lam);
+    if (st != TV_OK) return st;
+    int64_t n_rows;
+    st = check_rows(rows, &n_rows);
+    if (st != TV_OK) return st;
+    if (n_rows == 0) {
+        // no rows: every slot's gradient is zero, which needs a device write
+        return grad_lam ? zero_floats(grad_lam, lam.count, stream) : TV_OK;
+    }
+    if (!g_up || !grad_y || (with_seg ? !seg : !x)) return TV_ERR_NULL;
+    if (rows.length > TV_MAX_LENGTH) return TV_ERR_UNSUPPORTED;
+    if (with_seg) {
+        if (rows.length > TV_SEG_MAX_LENGTH) return TV_ERR_UNSUPPORTED;
+        if ((uintptr_t)seg % 8 != 0) return TV_ERR_STRIDE;
+    }
+    if (grad_lam) {
+        if (!ws || !aligned16(ws) || ws_bytes < align16((size_t)n_rows * sizeof(float)))
+            return TV_ERR_WORKSPACE;
+    }
+    return run_bwd(g_up, nullptr, with_seg ? nullptr : x,
+                   with_seg ? reinterpret_cast<const uint2 *>(seg) : nullptr, grad_y, grad_lam, 0,
+                   rows, lam, n_rows, (float *)ws, stream);
 }
 
 }  // namespace
@@ -310,13 +346,19 @@ const char *tv_status_str(int status)
 
 int tv1d_prox_fwd(const float *y, float *x, tv_rows rows, tv_lambda lam, hipStream_t stream)
 {
-    return fwd_entry(y, x, nullptr, rows, lam, stream);
+    return fwd_entry(y, x, nullptr, nullptr, false, rows, lam, stream);
 }
 
 int tv1d_prox_fwd_info(const float *y, float *x, int32_t *info, tv_rows rows, tv_lambda lam,
                        hipStream_t stream)
 {
-    return fwd_entry(y, x, info, rows, lam, stream);
+    return fwd_entry(y, x, info, nullptr, false, rows, lam, stream);
+}
+
+int tv1d_prox_fwd_seg(const float *y, float *x, uint64_t *seg, tv_rows rows, tv_lambda lam,
+                      hipStream_t stream)
+{
+    return fwd_entry(y, x, nullptr, seg, true, rows, lam, stream);
 }
 
 size_t tv1d_bwd_workspace_bytes(tv_rows rows, tv_lambda lam)
@@ -330,22 +372,13 @@ size_t tv1d_bwd_workspace_bytes(tv_rows rows, tv_lambda lam)
 int tv1d_prox_bwd(const float *g_up, const float *x, float *grad_y, float *grad_lam, tv_rows rows,
                   tv_lambda lam, void *ws, size_t ws_bytes, hipStream_t stream)
 {
-    int st = check_lambda(lam);
-    if (st != TV_OK) return st;
-    int64_t n_rows;
-    st = check_rows(rows, &n_rows);
-    if (st != TV_OK) return st;
-    if (n_rows == 0) {
-        // no rows: every slot's gradient is zero, which needs a device write
-        return grad_lam ? zero_floats(grad_lam, lam.count, stream) : TV_OK;
-    }
-    if (!g_up || !x || !grad_y) return TV_ERR_NULL;
-    if (rows.length > TV_MAX_LENGTH) return TV_ERR_UNSUPPORTED;
-    if (grad_lam) {
-        if (!ws || !aligned16(ws) || ws_bytes < align16((size_t)n_rows * sizeof(float)))
-            return TV_ERR_WORKSPACE;
-    }
-    return run_bwd(g_up, nullptr, x, grad_y, grad_lam, 0, rows, lam, n_rows, (float *)ws, stream);
+    return bwd_entry(g_up, x, nullptr, false, grad_y, grad_lam, rows, lam, ws, ws_bytes, stream);
+}
+
+int tv1d_prox_bwd_seg(const float *g_up, const uint64_t *seg, float *grad_y, float *grad_lam,
+                      tv_rows rows, tv_lambda lam, void *ws, size_t ws_bytes, hipStream_t stream)
+{
+    return bwd_entry(g_up, nullptr, seg, true, grad_y, grad_lam, rows, lam, ws, ws_bytes, stream);
 }
 
 // ---- 2D: proximal Dykstra (paper Alg. 1) ----------------------------------------------
@@ -396,11 +429,11 @@ int tv2d_prox_fwd(const float *y, float *x, int64_t planes, int64_t H, int64_t W
         const float *Yk = (k == 0) ? y : saved(2 * k - 1);
         float *Z = saved(2 * k), *Yn = saved(2 * k + 1);
         // Z = proxRows(Y + P);  P <- (Y + P) - Z      (P = 0 in the first sweep)
-        st = run_fwd(Yk, k == 0 ? nullptr : P, Z, last ? nullptr : P, nullptr, rrow, lrow,
+        st = run_fwd(Yk, k == 0 ? nullptr : P, Z, last ? nullptr : P, nullptr, nullptr, rrow, lrow,
                      planes * H, stream);
         if (st != TV_OK) return st;
         // Y' = proxCols(Z + Q);  Q <- (Z + Q) - Y'
-        st = run_fwd(Z, k == 0 ? nullptr : Q, Yn, last ? nullptr : Q, nullptr, rcol, lcol,
+        st = run_fwd(Z, k == 0 ? nullptr : Q, Yn, last ? nullptr : Q, nullptr, nullptr, rcol, lcol,
                      planes * W, stream);
         if (st != TV_OK) return st;
     }
@@ -442,11 +475,11 @@ int tv2d_prox_bwd(const float *g_up, float *grad_y, float *grad_lam, int64_t pla
     int acc = 0;
     for (int k = sweeps - 1; k >= 0; --k) {
         const bool first = (k == sweeps - 1);
-        st = run_bwd(first ? g_up : Ab, first ? nullptr : Bb, saved(2 * k + 1), Bb, grad_lam, acc,
+        st = run_bwd(first ? g_up : Ab, first ? nullptr : Bb, saved(2 * k + 1), nullptr, Bb, grad_lam, acc,
                      rcol, lcol, planes * W, partial, stream);
         if (st != TV_OK) return st;
         acc = 1;
-        st = run_bwd(Bb, first ? nullptr : Ab, saved(2 * k), k == 0 ? grad_y : Ab, grad_lam, acc,
+        st = run_bwd(Bb, first ? nullptr : Ab, saved(2 * k), nullptr, k == 0 ? grad_y : Ab, grad_lam, acc,
                      rrow, lrow, planes * H, partial, stream);
         if (st != TV_OK) return st;
     }

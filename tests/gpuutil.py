@@ -4,9 +4,10 @@ from __future__ import annotations
 import numpy as np
 
 
-def run_1d(y, lam, lam_div, g=None, axis=-1, want_info=False, in_place=False):
+def run_1d(y, lam, lam_div, g=None, axis=-1, want_info=False, in_place=False, use_seg=False):
     """Forward (+ backward when g is given) along `axis` of a contiguous array.
-    Returns dict with x, gy, gl, info (numpy)."""
+    use_seg: the pair tv1d_prox_fwd_seg / tv1d_prox_bwd_seg instead of the plain one.
+    Returns dict with x, gy, gl, info, seg (numpy)."""
     import torch
 
     import paper_2204_03643_amd as tv
@@ -23,6 +24,10 @@ def run_1d(y, lam, lam_div, g=None, axis=-1, want_info=False, in_place=False):
         info = torch.zeros(max(n_rows, 1), dtype=torch.int32, device=dev)
         tv.tv1d_prox_fwd_info(yt, xt, info, rows, L)
         out["info"] = info.cpu().numpy()[:n_rows]
+    elif use_seg:
+        seg = torch.full((max(n_rows, 1),), -1, dtype=torch.int64, device=dev)
+        tv.tv1d_prox_fwd_seg(yt, xt, seg, rows, L)
+        out["seg"] = seg.cpu().numpy()[:n_rows].view(np.uint64)
     else:
         tv.tv1d_prox_fwd(yt, xt, rows, L)
     torch.cuda.synchronize()
@@ -33,7 +38,11 @@ def run_1d(y, lam, lam_div, g=None, axis=-1, want_info=False, in_place=False):
         gl = torch.full((lt.numel(),), float("nan"), device=dev)
         wsb = tv.tv1d_bwd_workspace_bytes(rows, L)
         ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device=dev)
-        tv.tv1d_prox_bwd(gt, xt, gy, gl, rows, L, ws, wsb)
+        if use_seg:
+            xt.fill_(float("nan"))             # the backward call must not depend on x
+            tv.tv1d_prox_bwd_seg(gt, seg, gy, gl, rows, L, ws, wsb)
+        else:
+            tv.tv1d_prox_bwd(gt, xt, gy, gl, rows, L, ws, wsb)
         torch.cuda.synchronize()
         out["gy"] = gy.cpu().numpy()
         out["gl"] = gl.cpu().numpy()

@@ -9,7 +9,10 @@ consistent with the KKT conditions is a valid generalised Jacobian.  A row is ca
 near-degenerate when, in the oracle's solution, min over non-jumps of (lam - |u_k|) or min
 over jumps of |x_{k+1} - x_k| is below tau = 1e-4 * (1 + max|y|).  On those rows the GPU
 gradient must equal the oracle's segment averaging applied to the GPU's own output.
-grad_lam: |delta| <= 1e-3 * (|ref| + l2 norm of the per-row contributions) per slot.
+grad_lam: |delta| <= 1e-3 * (|ref| + l2 norm of the per-row contributions) per slot, plus
+the rounding floor of an fp32 sum, 32 * eps32 * (sum of the magnitudes of the jump terms
+that enter the slot): the terms are O(1) with both signs, and where they cancel the result
+cannot be resolved below that floor in the kernel's precision.
 """
 from __future__ import annotations
 
@@ -64,6 +67,7 @@ def check_batch(y, lam_rows, g, x_gpu, gy_gpu, part_slots=None, gl_gpu=None, lam
     for r in range(R):
         src = x_gpu64[r] if deg[r] else x_ref[r]
         gy_ref[r], part_ref[r] = oracle.prox1d_bwd(g64[r], src)
+    term_mag = np.abs(np.diff(gy_ref, axis=-1)).sum(axis=-1)       # sum over jumps |mean_l - mean_r|
     gerr = np.max(np.abs(gy_gpu.astype(np.float64) - gy_ref), axis=-1)
     gscale = np.maximum(np.max(np.abs(gy_ref), axis=-1), 1e-30)
     rel = gerr / gscale
@@ -77,8 +81,10 @@ def check_batch(y, lam_rows, g, x_gpu, gy_gpu, part_slots=None, gl_gpu=None, lam
         np.add.at(ref, slots, part_ref)
         np.add.at(nrm, slots, part_ref ** 2)
         nrm = np.sqrt(nrm)
+        mag = np.zeros(lam_count)
+        np.add.at(mag, slots, term_mag)
         d = np.abs(gl_gpu.astype(np.float64) - ref)
-        bound = GRAD_TOL * (np.abs(ref) + nrm) + 1e-12
+        bound = GRAD_TOL * (np.abs(ref) + nrm) + 32 * np.finfo(np.float32).eps * mag + 1e-12
         assert np.all(d <= bound), (label, "grad_lam", float((d / bound).max()))
         stats["grad_lam_max_ratio"] = float((d / bound).max())
     return stats

@@ -21,7 +21,7 @@ def test_every_declared_symbol_is_exported():
     names = _declared_functions()
     assert {"tv1d_prox_fwd", "tv1d_prox_bwd", "tv2d_prox_fwd", "tv2d_prox_bwd",
             "tv1d_bwd_workspace_bytes", "tv2d_workspace_bytes", "tv_status_str",
-            "tv1d_prox_fwd_info"} <= set(names)
+            "tv1d_prox_fwd_info", "tv1d_prox_fwd_seg", "tv1d_prox_bwd_seg"} <= set(names)
     L = tv.lib()
     for n in names:
         assert hasattr(L, n), n
@@ -75,6 +75,20 @@ def test_backward_validation():
     assert L.tv1d_prox_bwd(FAKE, FAKE, FAKE, FAKE, rows, lam, FAKE, 8, None) == 5    # too small
     assert L.tv1d_prox_bwd(FAKE, FAKE, FAKE, FAKE, rows, lam, FAKE + 4, 64, None) == 5  # misaligned
     assert L.tv1d_prox_bwd(FAKE, FAKE, FAKE, FAKE, tv.tv_rows(4, 32, 1, 1, 0, 1), lam, FAKE, 64, None) == 2
+
+
+def test_seg_pair_validation():
+    L = tv.lib()
+    rows = tv.tv_rows(4, 32, 1, 1, 32, 1)
+    lam = tv.tv_lambda(FAKE, 1, 1)
+    long_rows = tv.tv_rows(4, 33, 1, 1, 33, 1)
+    assert L.tv1d_prox_fwd_seg(FAKE, FAKE, None, rows, lam, None) == 1
+    assert L.tv1d_prox_fwd_seg(FAKE, FAKE, FAKE + 4, rows, lam, None) == 3       # code misaligned
+    assert L.tv1d_prox_fwd_seg(FAKE, FAKE, FAKE, long_rows, lam, None) == 6      # rows too long
+    assert L.tv1d_prox_bwd_seg(FAKE, None, FAKE, FAKE, rows, lam, FAKE, 64, None) == 1
+    assert L.tv1d_prox_bwd_seg(FAKE, FAKE, FAKE, FAKE, long_rows, lam, FAKE, 64, None) == 6
+    assert L.tv1d_prox_bwd_seg(FAKE, FAKE, FAKE, FAKE, rows, lam, None, 64, None) == 5
+    assert L.tv1d_prox_bwd_seg(None, None, None, None, tv.tv_rows(0, 32, 1, 1, 32, 1), lam, None, 0, None) == 0
 
 
 def test_2d_validation():

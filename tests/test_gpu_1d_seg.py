@@ -1,0 +1,77 @@
+"""GPU: the forward/backward pair that hands the segments over as a per-row code
+(tv1d_prox_fwd_seg / tv1d_prox_bwd_seg) against the oracle and against the plain pair."""
+import numpy as np
+import pytest
+
+import workloads
+from gpuutil import lam_per_row, rows_view, run_1d
+from parity import check_batch
+
+pytestmark = pytest.mark.gpu
+
+
+def _codes_from_x(xr):
+    """The code as the header defines it, computed from the forward output in numpy."""
+    n = xr.shape[1]
+    code = np.zeros(len(xr), dtype=np.uint64)
+    for k in range(n - 1):
+        code |= (xr[:, k + 1] != xr[:, k]).astype(np.uint64) << np.uint64(k)
+        code |= (xr[:, k + 1] > xr[:, k]).astype(np.uint64) << np.uint64(32 + k)
+    return code
+
+
+def _check(y, lam, lam_div, g, axis, label):
+    seg = run_1d(y, lam, lam_div, g, axis=axis, use_seg=True)
+    ref = run_1d(y, lam, lam_div, g, axis=axis)
+    # same kernels, same arithmetic: nothing may differ from the plain pair, bit for bit
+    assert np.array_equal(seg["x"], ref["x"]), label
+    assert np.array_equal(seg["gy"], ref["gy"]), label
+    assert np.array_equal(seg["gl"], ref["gl"]), label
+    assert np.array_equal(seg["seg"], _codes_from_x(rows_view(seg["x"], axis))), label
+    yr, gr = rows_view(y, axis), rows_view(g, axis)
+    lr = lam_per_row(lam, len(yr), lam_div)
+    check_batch(yr, lr, gr, rows_view(seg["x"], axis), rows_view(seg["gy"], axis), gl_gpu=seg["gl"],
+                lam_count=np.asarray(lam).size, lam_div=lam_div, label=label)
+
+
+def test_config3_reduced_rows_and_columns():
+    y, lam, g = workloads.config3(B=3, C=128)
+    _check(y, lam, 32, g, -1, "cfg3 rows (seg)")
+    _check(y, lam, 32, g, -2, "cfg3 columns (seg)")
+
+
+def test_config2_reduced_ties():
+    y, lam, g = workloads.config2(B=4, C=64)
+    _check(y, lam, 32, g, -1, "cfg2 rows (seg)")
+
+
+@pytest.mark.parametrize("n", [1, 2, 3, 8, 9, 16, 17, 31, 32])
+def test_short_lengths_ragged(n):
+    rng = np.random.default_rng(700 + n)
+    rows = 333
+    y = rng.normal(size=(rows, n)).astype(np.float32)
+    g = rng.normal(size=(rows, n)).astype(np.float32)
+    lam = (10 ** rng.uniform(-3, 1, size=rows)).astype(np.float32)
+    _check(y, lam, 1, g, -1, "seg n=%d" % n)
+
+
+def test_lambda_zero_and_huge():
+    rng = np.random.default_rng(43)
+    y = rng.normal(size=(130, 32)).astype(np.float32)
+    y[:, 5] = y[:, 4]                                    # a tie: no jump although lam = 0
+    g = rng.normal(size=y.shape).astype(np.float32)
+    out = run_1d(y, np.array([0.0], np.float32), 1, g, use_seg=True)
+    assert np.array_equal(out["x"], y)
+    assert np.all((out["seg"] >> np.uint64(4)) & np.uint64(1) == 0)
+    assert np.array_equal(out["seg"], _codes_from_x(y))
+    out = run_1d(y, np.array([1e4], np.float32), 1, g, use_seg=True)
+    assert np.all(out["seg"] == 0)
+    np.testing.assert_allclose(out["gy"], np.repeat(g.astype(np.float64).mean(1, keepdims=True), 32, 1),
+                               atol=1e-5)
+    assert abs(out["gl"][0]) == 0.0
+
+
+def test_zero_rows():
+    y = np.zeros((0, 32), np.float32)
+    out = run_1d(y, np.array([0.5, 0.25], np.float32), 1, y, use_seg=True)
+    assert out["x"].shape == (0, 32) and np.array_equal(out["gl"], np.zeros(2, np.float32))
