@@ -1,10 +1,13 @@
 #!/usr/bin/env python3
 """Benchmark of the hot path: batched 1D TV prox, forward + backward, on one MI355X.
 
-A step is one pass of the whole path (tv1d_prox_fwd then tv1d_prox_bwd with dL/dlam) over
-the 2^20-row workload ([256,128,32,32] fp32 viewed as rows of length 32, per-channel lam
+A step is one pass of the whole path (forward, then backward with dL/dlam) over the
+2^20-row workload ([256,128,32,32] fp32 viewed as rows of length 32, per-channel lam
 log-uniform in [1e-3, 10]); inputs are resident in HBM before the timed region starts.
-Prints ONE JSON line.
+The step is tv1d_prox_fwd_ex (writing each row's 8-byte segment code, with the workspace
+that lets it visit the lambda slots in the order of decreasing predicted cost) followed by
+tv1d_prox_bwd_seg (which reads the codes instead of x); the plain pair tv1d_prox_fwd /
+tv1d_prox_bwd is timed beside it.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline]
 """
@@ -23,6 +26,8 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0           # MI355X published HBM3E peak
 FWD_BYTES_PER_ELEM = 8          # read y, write x
 BWD_BYTES_PER_ELEM = 12         # read g_up and x, write grad_y
+BWD_SEG_BYTES_PER_ELEM = 8      # read g_up, write grad_y ...
+BWD_SEG_BYTES_PER_ROW = 12      # ... plus the row's segment code (8) and its dL/dlam term (4)
 
 
 def cpu_baseline(sample_rows: int):
@@ -118,8 +123,8 @@ def other_workloads(dev, reps: int = 5):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=500)
+    ap.add_argument("--warmup", type=int, default=200)     # ~30 ms: lets the clocks settle
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-rows", type=int, default=1 << 23)
     ap.add_argument("--headline-only", action="store_true", help="skip the other four workloads")
@@ -152,9 +157,22 @@ def main() -> int:
     L = tv.tv_lambda(lt.data_ptr(), C, H)
     wsb = tv.tv1d_bwd_workspace_bytes(rows, L)
     ws = torch.empty(wsb, dtype=torch.uint8, device=dev)
+    seg = torch.empty(n_rows, dtype=torch.int64, device=dev)
+    fwsb = tv.tv1d_fwd_workspace_bytes(rows, L)
+    fws = torch.empty(max(fwsb, 16), dtype=torch.uint8, device=dev)
     stream = torch.cuda.current_stream()
 
     def step(evs=None):
+        if evs is not None:
+            evs[0].record(stream)
+        tv.tv1d_prox_fwd_ex(yt, xt, rows, L, seg=seg, ws=fws, ws_bytes=fwsb, stream=stream)
+        if evs is not None:
+            evs[1].record(stream)
+        tv.tv1d_prox_bwd_seg(gt, seg, gy, gl, rows, L, ws, wsb, stream)
+        if evs is not None:
+            evs[2].record(stream)
+
+    def plain_step(evs=None):
         if evs is not None:
             evs[0].record(stream)
         tv.tv1d_prox_fwd(yt, xt, rows, L, stream)
@@ -167,6 +185,7 @@ def main() -> int:
     if args.traffic_probe:
         for _ in range(3):
             step()
+            plain_step()
             xt.copy_(yt)            # plain copy kernel: reads and writes y.numel() * 4 bytes
         torch.cuda.synchronize()
         return 0
@@ -187,9 +206,21 @@ def main() -> int:
     ms_per_step = wall * 1e3 / args.steps
     value = n_rows * args.steps / wall
 
+    # the plain pair (backward reads x), same number of steps
+    pe = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    plain_step()
+    for k in range(args.steps):
+        plain_step(pe[k])
+    torch.cuda.synchronize()
+    pf_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in pe]))
+    pb_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in pe]))
+
+    # algorithmic bytes of the method (read y, write x; read g_up and x, write grad_y) ...
     fwd_bytes, bwd_bytes = n_elem * FWD_BYTES_PER_ELEM, n_elem * BWD_BYTES_PER_ELEM
+    # ... and what the backward kernel of the timed pair has to move
+    bwd_seg_bytes = n_elem * BWD_SEG_BYTES_PER_ELEM + n_rows * BWD_SEG_BYTES_PER_ROW
     fwd_gbs = fwd_bytes / (fwd_ms * 1e-3) / 1e9
-    bwd_gbs = bwd_bytes / (bwd_ms * 1e-3) / 1e9
+    bwd_gbs = bwd_seg_bytes / (bwd_ms * 1e-3) / 1e9
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic_tv1d_fwd_short_config3.json")
     if os.path.exists(tpath):
@@ -210,18 +241,27 @@ def main() -> int:
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": "config 3: 2^20 rows x 32 fp32 ([256,128,32,32] ~N(0,1), per-channel "
-                               "lam log-uniform [1e-3,10]), tv1d_prox_fwd + tv1d_prox_bwd",
+                               "lam log-uniform [1e-3,10]), tv1d_prox_fwd_ex (seg + ws) + tv1d_prox_bwd_seg",
                    "rows": n_rows, "length": W, "lam_slots": C},
+        # the method's 20 bytes per element over the time of the timed pair (which moves fewer)
         "effective_gbs_fwd_bwd": (fwd_bytes + bwd_bytes) / ((fwd_ms + bwd_ms) * 1e-3) / 1e9,
         "effective_frac_of_hbm_peak": (fwd_bytes + bwd_bytes) / ((fwd_ms + bwd_ms) * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "moved_gbs_fwd_bwd": (fwd_bytes + 8 * n_rows + bwd_seg_bytes) / ((fwd_ms + bwd_ms) * 1e-3) / 1e9,
+        # launch_us of the forward call includes its two small slot-order kernels
         "roofline": {"kernel": "tv1d_fwd_short_kernel<32>", "bound": "hbm", "achieved": fwd_gbs,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": fwd_gbs / HBM_PEAK_GBS,
                      "traffic": traffic, "launch_us": fwd_ms * 1e3,
                      "algorithmic_bytes_per_launch": fwd_bytes},
-        "roofline_bwd": {"kernel": "tv1d_bwd_short_kernel<32> + reduce_lambda_kernel", "bound": "hbm",
-                         "achieved": bwd_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "roofline_bwd": {"kernel": "tv1d_bwd_short_kernel<32, SEG> + reduce_lambda_kernel",
+                         "bound": "hbm", "achieved": bwd_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                          "frac": bwd_gbs / HBM_PEAK_GBS, "launch_us": bwd_ms * 1e3,
-                         "algorithmic_bytes_per_launch": bwd_bytes},
+                         "algorithmic_bytes_per_launch": bwd_seg_bytes,
+                         "note": "bytes of this variant: g_up + grad_y + 12 B/row (code, dL/dlam term)"},
+        "plain_pair": {"calls": "tv1d_prox_fwd + tv1d_prox_bwd (backward reads x)",
+                       "fwd_us": pf_ms * 1e3, "bwd_us": pb_ms * 1e3,
+                       "rows_per_s": n_rows / ((pf_ms + pb_ms) * 1e-3),
+                       "effective_gbs_fwd_bwd": (fwd_bytes + bwd_bytes) / ((pf_ms + pb_ms) * 1e-3) / 1e9,
+                       "bwd_achieved_gbs": bwd_bytes / (pb_ms * 1e-3) / 1e9},
     }
     if not args.headline_only:
         # the same tensor taken along H (the column pass), then the other workloads

@@ -94,6 +94,28 @@ int tv1d_prox_fwd_info(const float *y, float *x, int32_t *info, tv_rows rows, tv
                        hipStream_t stream);
 
 /*
+ * The general forward call: tv1d_prox_fwd plus optional outputs and scratch, each of which
+ * may be NULL.
+ *   info: as in tv1d_prox_fwd_info.
+ *   seg:  as in tv1d_prox_fwd_seg (below).
+ *   ws:   device scratch of at least tv1d_fwd_workspace_bytes() bytes, 16-byte aligned
+ *         (TV_ERR_WORKSPACE otherwise), contents undefined afterwards.  With it, rows of up to
+ *         32 samples whose lambda slots form whole groups of 64 rows are processed slot by
+ *         slot in the order of decreasing predicted cost, which shortens the call when the
+ *         slots' lambdas differ widely; results are bit-identical with or without it.
+ *         tv1d_fwd_workspace_bytes() returns 0 where this does not apply (ws is then unused).
+ */
+typedef struct {
+    int32_t *info;
+    uint64_t *seg;
+    void *ws;
+    size_t ws_bytes;
+} tv_fwd_extra;
+int tv1d_prox_fwd_ex(const float *y, float *x, tv_rows rows, tv_lambda lam, tv_fwd_extra extra,
+                     hipStream_t stream);
+size_t tv1d_fwd_workspace_bytes(tv_rows rows, tv_lambda lam);
+
+/*
  * Backward of tv1d_prox_fwd (paper Eq. 5-6, evaluated as segment averaging).
  *   g_up:     upstream gradient dL/dx, laid out like x.
  *   x:        the OUTPUT of tv1d_prox_fwd for the same rows and lam.

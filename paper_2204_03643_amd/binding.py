@@ -19,6 +19,10 @@ class tv_lambda(ctypes.Structure):
     _fields_ = [("lam", _vp), ("count", _i64), ("div", _i64)]
 
 
+class tv_fwd_extra(ctypes.Structure):
+    _fields_ = [("info", _vp), ("seg", _vp), ("ws", _vp), ("ws_bytes", ctypes.c_size_t)]
+
+
 class TVError(RuntimeError):
     def __init__(self, status: int):
         self.status = status
@@ -45,6 +49,10 @@ def lib() -> ctypes.CDLL:
         L.tv1d_prox_bwd.restype = ctypes.c_int
         L.tv1d_prox_fwd_seg.argtypes = [_vp, _vp, _vp, tv_rows, tv_lambda, _vp]
         L.tv1d_prox_fwd_seg.restype = ctypes.c_int
+        L.tv1d_prox_fwd_ex.argtypes = [_vp, _vp, tv_rows, tv_lambda, tv_fwd_extra, _vp]
+        L.tv1d_prox_fwd_ex.restype = ctypes.c_int
+        L.tv1d_fwd_workspace_bytes.argtypes = [tv_rows, tv_lambda]
+        L.tv1d_fwd_workspace_bytes.restype = ctypes.c_size_t
         L.tv1d_prox_bwd_seg.argtypes = [_vp, _vp, _vp, _vp, tv_rows, tv_lambda, _vp, ctypes.c_size_t, _vp]
         L.tv1d_prox_bwd_seg.restype = ctypes.c_int
         L.tv1d_bwd_workspace_bytes.argtypes = [tv_rows, tv_lambda]
@@ -121,6 +129,16 @@ def tv1d_prox_bwd(g_up, x, grad_y, grad_lam, rows: tv_rows, lam: tv_lambda, ws, 
 
 def tv1d_prox_fwd_seg(y, x, seg, rows: tv_rows, lam: tv_lambda, stream=None):
     _check(lib().tv1d_prox_fwd_seg(_ptr(y), _ptr(x), _ptr(seg), rows, lam, _stream(stream)))
+
+
+def tv1d_fwd_workspace_bytes(rows: tv_rows, lam: tv_lambda) -> int:
+    return int(lib().tv1d_fwd_workspace_bytes(rows, lam))
+
+
+def tv1d_prox_fwd_ex(y, x, rows: tv_rows, lam: tv_lambda, info=None, seg=None, ws=None,
+                     ws_bytes: int = 0, stream=None):
+    extra = tv_fwd_extra(_ptr(info), _ptr(seg), _ptr(ws), int(ws_bytes))
+    _check(lib().tv1d_prox_fwd_ex(_ptr(y), _ptr(x), rows, lam, extra, _stream(stream)))
 
 
 def tv1d_prox_bwd_seg(g_up, seg, grad_y, grad_lam, rows: tv_rows, lam: tv_lambda, ws, ws_bytes: int,

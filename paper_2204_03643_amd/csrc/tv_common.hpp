@@ -90,6 +90,7 @@ struct FwdParams {
     const float *lam;
     int32_t     *info;     // optional per-row info word
     uint2       *seg;      // optional per-row segment code (rows of up to 32 samples only)
+    const uint32_t *order; // optional: grid row j of the grouped grid works on slot order[j]
     Layout       L;
     TileMap      tm;       // row-per-lane kernels only
 };

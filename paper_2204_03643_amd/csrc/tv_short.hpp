@@ -448,7 +448,7 @@ struct RowSolver {
 
 // ---------------------------------------------------------------------------------
 // Forward kernel: one row per lane.  Grid: see TileMap; waves of a workgroup never wait
-// for each other.
+// for each other.  With a grouped grid the slots may be visited in a given order (p.order).
 // ---------------------------------------------------------------------------------
 template <int NMAX, bool FULL, bool PACKED>
 __global__ __launch_bounds__(kShortBlock) TV_FWD_ATTR void tv1d_fwd_short_kernel(FwdParams p)
@@ -462,7 +462,7 @@ __global__ __launch_bounds__(kShortBlock) TV_FWD_ATTR void tv1d_fwd_short_kernel
     fill_tables<NMAX>(gtab, rtab);
     if (kShortBlock > 64) __syncthreads();      // tables are shared by the workgroup's waves
 
-    const uint32_t slot = blockIdx.y;
+    const uint32_t slot = p.order ? p.order[blockIdx.y] : blockIdx.y;
     const uint32_t r0 = p.tm.first(
         __builtin_amdgcn_readfirstlane(blockIdx.x * (kShortBlock / 64) + (threadIdx.x >> 6)), slot);
     const uint32_t row = p.tm.row(r0, lane);
@@ -520,13 +520,19 @@ __global__ __launch_bounds__(kShortBlock) TV_FWD_ATTR void tv1d_fwd_short_kernel
     }
     if (p.info && valid) p.info[row] = sv.steps | sv.flags;
     if (p.seg) {
-        // built from the highest dual down, one shift-in per dual: bit k ends up at position k
+        // built from the highest dual down, one shift-in per dual, so that bit k ends up at
+        // position k.  d = x[k] - x[k+1] is +0 exactly inside a segment (its samples are
+        // bit-identical) and carries the sign bit iff x rises; 0 - |d| carries it iff d != 0.
         uint32_t jm = 0, up = 0;
 #pragma unroll
         for (int k = NMAX - 2; k >= 0; --k) {
-            const bool in = FULL || k < n - 1;
-            jm = jm + jm + ((in && xs[k + 1] != xs[k]) ? 1u : 0u);
-            up = up + up + ((in && xs[k + 1] > xs[k]) ? 1u : 0u);
+            const float d = xs[k] - xs[k + 1];
+            up = __builtin_amdgcn_alignbit(up, __float_as_uint(d), 31);
+            jm = __builtin_amdgcn_alignbit(jm, __float_as_uint(0.0f - fabsf(d)), 31);
+        }
+        if (!FULL) {
+            const uint32_t in = n > 1 ? (0xffffffffu >> (33 - n)) : 0u;   // duals 0 .. n-2
+            jm &= in; up &= in;
         }
         if (valid) p.seg[row] = make_uint2(jm, up);
     }

@@ -150,16 +150,108 @@ int launch_bwd_short(const BwdParams &p, bool packed_ok, hipStream_t s)
                  : launch_bwd_short<NMAX, false, false>(p, packed_ok, s);
 }
 
+// ---- slot order for the grouped grid -----------------------------------------------
+//
+// A tile's cost is its largest Newton step count, which depends mostly on where the slot's
+// lambda lies relative to the scale of its rows: one step when every dual ends up on a bound
+// (small lambda) or none does (large lambda), many in between.  Workgroups are dispatched in
+// grid order, and whatever runs last determines how long the chip drains with idle SIMDs, so
+// the expensive slots are dispatched first (longest processing time first).  The cost is
+// predicted from a few rows of each slot: with p the fraction of duals that the unconstrained
+// Newton step from u = 0 (the prefix sums of mean(y) - y) puts outside the box, the measured
+// step count follows p (1 - p).  One workgroup, one thread per slot; ranks by counting.
+constexpr int kOrderMaxSlots = 1024;
+
+// Step 1, one wave per slot: lane i reads row i of the slot's first tile (a grouped tile is
+// always full) and counts its out-of-box prefix sums; key[slot] = p (1 - p).
+__global__ __launch_bounds__(64) void slot_cost_kernel(
+    const float *__restrict__ y, const float *__restrict__ addend, const float *__restrict__ lam,
+    tvk::Layout L, tvk::TileMap tm, float *__restrict__ key)
+{
+    __shared__ int total;
+    const uint32_t s = blockIdx.x;
+    const float l = fmaxf(lam[s], 0.f);
+    const int n = L.n;                                    // <= 32
+    const uint32_t r = tm.row(tm.first(0u, s), threadIdx.x);
+    const int64_t off = tvk::row_offset(L, r);
+    float v[32];
+#pragma unroll
+    for (int j = 0; j < 32; ++j) {
+        v[j] = 0.f;
+        if (j < n) {
+            const int64_t a = off + j * L.elem_stride;
+            v[j] = y[a];
+            if (addend) v[j] += addend[a];
+        }
+    }
+    float sum = 0.f;
+#pragma unroll
+    for (int j = 0; j < 32; ++j) sum += v[j];             // samples past the row are 0
+    const float mean = sum / (float)n;
+    float run = 0.f;
+    int out = 0;
+#pragma unroll
+    for (int j = 0; j < 31; ++j) {
+        run += mean - v[j];
+        out += (j < n - 1 && fabsf(run) > l) ? 1 : 0;
+    }
+    if (threadIdx.x == 0) total = 0;
+    __syncthreads();
+    atomicAdd(&total, out);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const float p = (float)total / (float)(64 * (n > 1 ? n - 1 : 1));
+        key[s] = p * (1.f - p);
+    }
+}
+
+// Step 2, one workgroup, one thread per slot: order[rank] = slot, ranks by counting the
+// slots with a larger key (ties by index), so equal inputs always give the same order.
+__global__ __launch_bounds__(kOrderMaxSlots) void slot_rank_kernel(
+    const float *__restrict__ key_in, uint32_t count, uint32_t *__restrict__ order)
+{
+    __shared__ float key[kOrderMaxSlots];
+    const uint32_t s = threadIdx.x;
+    const float k = s < count ? key_in[s] : 0.f;
+    key[s] = k;
+    __syncthreads();
+    if (s < count) {
+        uint32_t rank = 0;
+        for (uint32_t j = 0; j < count; ++j) {
+            const float kj = key[j];
+            rank += (kj > k || (kj == k && j < s)) ? 1u : 0u;
+        }
+        order[rank] = s;
+    }
+}
+
+bool order_applies(const tvk::TileMap &tm)
+{
+    return tm.grouped && tm.count <= (uint32_t)kOrderMaxSlots;
+}
+
 // ---- dispatch ---------------------------------------------------------------------
 
 int run_fwd(const float *y, const float *addend, float *x, float *resid, int32_t *info,
-            uint2 *seg, const tv_rows &r, const tv_lambda &l, int64_t n_rows, hipStream_t s)
+            uint2 *seg, uint32_t *order_ws, const tv_rows &r, const tv_lambda &l, int64_t n_rows,
+            hipStream_t s)
 {
     FwdParams p;
     p.y = y; p.addend = addend; p.x = x; p.resid = resid; p.lam = l.lam; p.info = info;
-    p.seg = seg;
+    p.seg = seg; p.order = nullptr;
     p.L = make_layout(r, l, n_rows);
     p.tm = make_tile_map(l, n_rows);
+    if (order_ws && r.length <= 32 && order_applies(p.tm)) {
+        // workspace: count keys (float), then count slot numbers (uint32)
+        float *key = reinterpret_cast<float *>(order_ws);
+        uint32_t *order = order_ws + p.tm.count;
+        hipLaunchKernelGGL(slot_cost_kernel, dim3(p.tm.count), dim3(64), 0, s, y, addend, l.lam, p.L,
+                           p.tm, key);
+        hipLaunchKernelGGL(slot_rank_kernel, dim3(1), dim3((p.tm.count + 63u) / 64u * 64u), 0, s, key,
+                           p.tm.count, order);
+        if (launch_status() != TV_OK) return TV_ERR_HIP;
+        p.order = order;
+    }
     const bool packed = rows_packed(r) && aligned16(y) && aligned16(x) &&
                         (!addend || aligned16(addend)) && (!resid || aligned16(resid));
     if (r.length <= 8) return launch_fwd_short<8>(p, packed, s);
@@ -279,8 +371,15 @@ int zero_floats(float *p, int64_t n, hipStream_t s)
     return launch_status();
 }
 
-int fwd_entry(const float *y, float *x, int32_t *info, uint64_t *seg, bool want_seg, tv_rows rows,
-              tv_lambda lam, hipStream_t s)
+// Scratch of the forward call where the slot order applies: a float key and a uint32 per slot.
+size_t fwd_workspace_bytes(const tv_rows &rows, const tv_lambda &lam, int64_t n_rows)
+{
+    if (rows.length > 32 || !order_applies(make_tile_map(lam, n_rows))) return 0;
+    return align16((size_t)lam.count * 8);
+}
+
+int fwd_entry(const float *y, float *x, tv_rows rows, tv_lambda lam, const tv_fwd_extra &e,
+              hipStream_t s)
 {
     int st = check_lambda(lam);
     if (st != TV_OK) return st;
@@ -290,12 +389,18 @@ int fwd_entry(const float *y, float *x, int32_t *info, uint64_t *seg, bool want_
     if (n_rows == 0) return TV_OK;
     if (!y || !x || !lam.lam) return TV_ERR_NULL;
     if (rows.length > TV_MAX_LENGTH) return TV_ERR_UNSUPPORTED;
-    if (want_seg) {
-        if (!seg) return TV_ERR_NULL;
+    if (e.seg) {
         if (rows.length > TV_SEG_MAX_LENGTH) return TV_ERR_UNSUPPORTED;
-        if ((uintptr_t)seg % 8 != 0) return TV_ERR_STRIDE;
+        if ((uintptr_t)e.seg % 8 != 0) return TV_ERR_STRIDE;
     }
-    return run_fwd(y, nullptr, x, nullptr, info, reinterpret_cast<uint2 *>(seg), rows, lam, n_rows, s);
+    uint32_t *order_ws = nullptr;
+    if (e.ws) {
+        if (!aligned16(e.ws) || e.ws_bytes < fwd_workspace_bytes(rows, lam, n_rows))
+            return TV_ERR_WORKSPACE;
+        order_ws = (uint32_t *)e.ws;
+    }
+    return run_fwd(y, nullptr, x, nullptr, e.info, reinterpret_cast<uint2 *>(e.seg), order_ws, rows,
+                   lam, n_rows, s);
 }
 
 int bwd_entry(const float *g_up, const float *x, const uint64_t *seg, bool with_seg, float *grad_y,
@@ -346,19 +451,37 @@ const char *tv_status_str(int status)
 
 int tv1d_prox_fwd(const float *y, float *x, tv_rows rows, tv_lambda lam, hipStream_t stream)
 {
-    return fwd_entry(y, x, nullptr, nullptr, false, rows, lam, stream);
+    return fwd_entry(y, x, rows, lam, tv_fwd_extra{nullptr, nullptr, nullptr, 0}, stream);
 }
 
 int tv1d_prox_fwd_info(const float *y, float *x, int32_t *info, tv_rows rows, tv_lambda lam,
                        hipStream_t stream)
 {
-    return fwd_entry(y, x, info, nullptr, false, rows, lam, stream);
+    return fwd_entry(y, x, rows, lam, tv_fwd_extra{info, nullptr, nullptr, 0}, stream);
 }
 
 int tv1d_prox_fwd_seg(const float *y, float *x, uint64_t *seg, tv_rows rows, tv_lambda lam,
                       hipStream_t stream)
 {
-    return fwd_entry(y, x, nullptr, seg, true, rows, lam, stream);
+    if (!seg) {
+        int64_t n_rows;
+        if (check_lambda(lam) == TV_OK && check_rows(rows, &n_rows) == TV_OK && n_rows > 0)
+            return TV_ERR_NULL;
+    }
+    return fwd_entry(y, x, rows, lam, tv_fwd_extra{nullptr, seg, nullptr, 0}, stream);
+}
+
+int tv1d_prox_fwd_ex(const float *y, float *x, tv_rows rows, tv_lambda lam, tv_fwd_extra extra,
+                     hipStream_t stream)
+{
+    return fwd_entry(y, x, rows, lam, extra, stream);
+}
+
+size_t tv1d_fwd_workspace_bytes(tv_rows rows, tv_lambda lam)
+{
+    int64_t n_rows;
+    if (check_lambda(lam) != TV_OK || check_rows(rows, &n_rows) != TV_OK) return 0;
+    return fwd_workspace_bytes(rows, lam, n_rows);
 }
 
 size_t tv1d_bwd_workspace_bytes(tv_rows rows, tv_lambda lam)
@@ -429,11 +552,11 @@ int tv2d_prox_fwd(const float *y, float *x, int64_t planes, int64_t H, int64_t W
         const float *Yk = (k == 0) ? y : saved(2 * k - 1);
         float *Z = saved(2 * k), *Yn = saved(2 * k + 1);
         // Z = proxRows(Y + P);  P <- (Y + P) - Z      (P = 0 in the first sweep)
-        st = run_fwd(Yk, k == 0 ? nullptr : P, Z, last ? nullptr : P, nullptr, nullptr, rrow, lrow,
+        st = run_fwd(Yk, k == 0 ? nullptr : P, Z, last ? nullptr : P, nullptr, nullptr, nullptr, rrow, lrow,
                      planes * H, stream);
         if (st != TV_OK) return st;
         // Y' = proxCols(Z + Q);  Q <- (Z + Q) - Y'
-        st = run_fwd(Z, k == 0 ? nullptr : Q, Yn, last ? nullptr : Q, nullptr, nullptr, rcol, lcol,
+        st = run_fwd(Z, k == 0 ? nullptr : Q, Yn, last ? nullptr : Q, nullptr, nullptr, nullptr, rcol, lcol,
                      planes * W, stream);
         if (st != TV_OK) return st;
     }

@@ -4,9 +4,11 @@ from __future__ import annotations
 import numpy as np
 
 
-def run_1d(y, lam, lam_div, g=None, axis=-1, want_info=False, in_place=False, use_seg=False):
+def run_1d(y, lam, lam_div, g=None, axis=-1, want_info=False, in_place=False, use_seg=False,
+           use_ws=False):
     """Forward (+ backward when g is given) along `axis` of a contiguous array.
     use_seg: the pair tv1d_prox_fwd_seg / tv1d_prox_bwd_seg instead of the plain one.
+    use_ws: forward through tv1d_prox_fwd_ex with its workspace (cost-ordered slots).
     Returns dict with x, gy, gl, info, seg (numpy)."""
     import torch
 
@@ -20,7 +22,20 @@ def run_1d(y, lam, lam_div, g=None, axis=-1, want_info=False, in_place=False, us
     n_rows = rows.n_outer * rows.n_inner
     xt = yt if in_place else torch.full_like(yt, float("nan"))
     out = {}
-    if want_info:
+    if use_ws:
+        wsb = tv.tv1d_fwd_workspace_bytes(rows, L)
+        ws = torch.full((max(wsb, 16),), 0xff, dtype=torch.uint8, device=dev)
+        info = torch.zeros(max(n_rows, 1), dtype=torch.int32, device=dev) if want_info else None
+        seg = torch.full((max(n_rows, 1),), -1, dtype=torch.int64, device=dev) if use_seg else None
+        tv.tv1d_prox_fwd_ex(yt, xt, rows, L, info=info, seg=seg, ws=ws, ws_bytes=wsb)
+        out["ws_bytes"] = wsb
+        if want_info:
+            out["info"] = info.cpu().numpy()[:n_rows]
+        if use_seg:
+            out["seg"] = seg.cpu().numpy()[:n_rows].view(np.uint64)
+        if wsb:
+            out["order"] = ws.cpu().numpy().view(np.uint32)[lt.numel():2 * lt.numel()]
+    elif want_info:
         info = torch.zeros(max(n_rows, 1), dtype=torch.int32, device=dev)
         tv.tv1d_prox_fwd_info(yt, xt, info, rows, L)
         out["info"] = info.cpu().numpy()[:n_rows]

@@ -91,6 +91,20 @@ def test_seg_pair_validation():
     assert L.tv1d_prox_bwd_seg(None, None, None, None, tv.tv_rows(0, 32, 1, 1, 32, 1), lam, None, 0, None) == 0
 
 
+def test_forward_ex_workspace_validation():
+    L = tv.lib()
+    lam = tv.tv_lambda(FAKE, 128, 32)
+    rows = tv.rows_along((256, 128, 32, 32), -1)
+    need = tv.tv1d_fwd_workspace_bytes(rows, lam)
+    assert need == 1024                                   # a key and a slot number per slot
+    assert tv.tv1d_fwd_workspace_bytes(rows, tv.tv_lambda(FAKE, 1, 1)) == 0
+    assert tv.tv1d_fwd_workspace_bytes(tv.rows_along((256, 128, 32, 64), -1), tv.tv_lambda(FAKE, 128, 32)) == 0
+    ex = lambda ws, n: L.tv1d_prox_fwd_ex(FAKE, FAKE, rows, lam, tv.tv_fwd_extra(None, None, ws, n), None)
+    assert ex(FAKE, need - 1) == 5
+    assert ex(FAKE + 8, need) == 5                        # misaligned
+    assert L.tv1d_prox_fwd_ex(None, FAKE, rows, lam, tv.tv_fwd_extra(None, None, FAKE, need), None) == 1
+
+
 def test_2d_validation():
     L = tv.lib()
     lam = tv.tv_lambda(FAKE, 3, 1)

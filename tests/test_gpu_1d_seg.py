@@ -75,3 +75,47 @@ def test_zero_rows():
     y = np.zeros((0, 32), np.float32)
     out = run_1d(y, np.array([0.5, 0.25], np.float32), 1, y, use_seg=True)
     assert out["x"].shape == (0, 32) and np.array_equal(out["gl"], np.zeros(2, np.float32))
+
+
+# ---- tv1d_prox_fwd_ex with its workspace: slots visited in the order of decreasing predicted cost
+
+
+def _check_ordered(y, lam, lam_div, g, axis, expect_order):
+    ref = run_1d(y, lam, lam_div, g, axis=axis, use_seg=True)
+    out = run_1d(y, lam, lam_div, g, axis=axis, use_seg=True, use_ws=True, want_info=True)
+    # the order only changes which workgroup handles which rows
+    assert np.array_equal(out["x"], ref["x"])
+    assert np.array_equal(out["seg"], ref["seg"])
+    assert np.array_equal(out["gy"], ref["gy"]) and np.array_equal(out["gl"], ref["gl"])
+    if expect_order:
+        count = np.asarray(lam).size
+        assert out["ws_bytes"] >= 8 * count
+        assert np.array_equal(np.sort(out["order"]), np.arange(count))     # a permutation of the slots
+    else:
+        assert out["ws_bytes"] == 0
+    return out
+
+
+def test_ordered_config3_reduced():
+    y, lam, g = workloads.config3(B=4, C=128)
+    out = _check_ordered(y, lam, 32, g, -1, True)
+    # slots whose rows need the most Newton steps come first, the one-step slots last
+    steps = (out["info"] & 0xffff).reshape(4, 128, 32).transpose(1, 0, 2).reshape(128, -1).mean(1)
+    by_order = steps[out["order"]]
+    assert by_order[:16].mean() > 2.0 * by_order[-16:].mean()
+    assert by_order[-16:].max() <= 1.5
+    _check_ordered(y, lam, 32, g, -2, True)                                # columns: strided rows
+
+
+def test_ordered_falls_back_where_slots_do_not_group():
+    rng = np.random.default_rng(44)
+    y = rng.normal(size=(333, 32)).astype(np.float32)
+    g = rng.normal(size=y.shape).astype(np.float32)
+    _check_ordered(y, (10 ** rng.uniform(-3, 1, size=333)).astype(np.float32), 1, g, -1, False)
+    _check_ordered(y, np.array([0.3], np.float32), 1, g, -1, False)         # one slot: nothing to order
+    y = rng.normal(size=(3, 6, 16, 16)).astype(np.float32)                  # slots do not fill tiles
+    g = rng.normal(size=y.shape).astype(np.float32)
+    _check_ordered(y, (10 ** rng.uniform(-2, 0.5, size=6)).astype(np.float32), 16, g, -1, False)
+    y = rng.normal(size=(32, 6, 16, 16)).astype(np.float32)                 # now every slot fills tiles
+    g = rng.normal(size=y.shape).astype(np.float32)
+    _check_ordered(y, (10 ** rng.uniform(-2, 0.5, size=6)).astype(np.float32), 16, g, -1, True)
