@@ -157,71 +157,141 @@ int launch_bwd_short(const BwdParams &p, bool packed_ok, hipStream_t s)
 // (small lambda) or none does (large lambda), many in between.  Workgroups are dispatched in
 // grid order, and whatever runs last determines how long the chip drains with idle SIMDs, so
 // the expensive slots are dispatched first (longest processing time first).  The cost is
-// predicted from a few rows of each slot: with p the fraction of duals that the unconstrained
-// Newton step from u = 0 (the prefix sums of mean(y) - y) puts outside the box, the measured
-// step count follows p (1 - p).  One workgroup, one thread per slot; ranks by counting.
+// predicted from a few rows of each slot's first tile: with p the fraction of duals that
+// the unconstrained Newton step from u = 0 (the prefix sums of mean(y) - y) puts outside
+// the box, the measured step count follows p (1 - p).
 constexpr int kOrderMaxSlots = 1024;
 
-// Step 1, one wave per slot: lane i reads row i of the slot's first tile (a grouped tile is
-// always full) and counts its out-of-box prefix sums; key[slot] = p (1 - p).
-__global__ __launch_bounds__(64) void slot_cost_kernel(
-    const float *__restrict__ y, const float *__restrict__ addend, const float *__restrict__ lam,
-    tvk::Layout L, tvk::TileMap tm, float *__restrict__ key)
+// The value of `v` in the lane that the DPP control word names (row-local patterns only).
+template <int CTRL>
+__device__ __forceinline__ float dpp_f(float v)
 {
-    __shared__ int total;
-    const uint32_t s = blockIdx.x;
-    const float l = fmaxf(lam[s], 0.f);
-    const int n = L.n;                                    // <= 32
-    const uint32_t r = tm.row(tm.first(0u, s), threadIdx.x);
-    const int64_t off = tvk::row_offset(L, r);
-    float v[32];
-#pragma unroll
-    for (int j = 0; j < 32; ++j) {
-        v[j] = 0.f;
-        if (j < n) {
-            const int64_t a = off + j * L.elem_stride;
-            v[j] = y[a];
-            if (addend) v[j] += addend[a];
-        }
-    }
-    float sum = 0.f;
-#pragma unroll
-    for (int j = 0; j < 32; ++j) sum += v[j];             // samples past the row are 0
-    const float mean = sum / (float)n;
-    float run = 0.f;
-    int out = 0;
-#pragma unroll
-    for (int j = 0; j < 31; ++j) {
-        run += mean - v[j];
-        out += (j < n - 1 && fabsf(run) > l) ? 1 : 0;
-    }
-    if (threadIdx.x == 0) total = 0;
-    __syncthreads();
-    atomicAdd(&total, out);
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        const float p = (float)total / (float)(64 * (n > 1 ? n - 1 : 1));
-        key[s] = p * (1.f - p);
-    }
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));
 }
 
-// Step 2, one workgroup, one thread per slot: order[rank] = slot, ranks by counting the
-// slots with a larger key (ties by index), so equal inputs always give the same order.
-__global__ __launch_bounds__(kOrderMaxSlots) void slot_rank_kernel(
-    const float *__restrict__ key_in, uint32_t count, uint32_t *__restrict__ order)
+template <int CTRL>
+__device__ __forceinline__ int dpp_i(int v)
+{
+    return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, true);
+}
+
+// One workgroup of 1024 threads.
+// Step 1, key[slot] = p (1 - p) from sample rows of the slot's first tile (a grouped tile is
+// always full).  FAST (packed rows of 32 samples in groups of at least 2 consecutive rows):
+// 2 rows per slot, 8 lanes per row with 4 samples each, so one coalesced 16-byte load per
+// lane covers 4 slots; prefix sums and counts run across lanes through DPP.  Otherwise
+// thread t reads row (t % R) of slot (t / R) sample by sample, R = 1024 / (slots rounded up
+// to a power of two) rows per slot, at most 64.
+// Step 2: order[rank] = slot, ranks by counting the slots with a larger key (ties by
+// index), so equal inputs always give the same order.
+template <bool FAST>
+__global__ __launch_bounds__(kOrderMaxSlots) void slot_order_kernel(
+    const float *__restrict__ y, const float *__restrict__ addend, const float *__restrict__ lam,
+    tvk::Layout L, tvk::TileMap tm, uint32_t lgR, uint32_t *__restrict__ order)
 {
     __shared__ float key[kOrderMaxSlots];
-    const uint32_t s = threadIdx.x;
-    const float k = s < count ? key_in[s] : 0.f;
-    key[s] = k;
-    __syncthreads();
-    if (s < count) {
-        uint32_t rank = 0;
-        for (uint32_t j = 0; j < count; ++j) {
-            const float kj = key[j];
-            rank += (kj > k || (kj == k && j < s)) ? 1u : 0u;
+    const uint32_t count = tm.count;
+    if constexpr (FAST) {
+        const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+        const uint32_t sub = lane >> 4, q = lane & 7u;
+        constexpr int J = 4;                               // loads in flight per lane
+        for (uint32_t c0 = 0; c0 < count; c0 += 64u * J) {
+            float4 v[J];
+            float lv[J];
+#pragma unroll
+            for (int j = 0; j < J; ++j) {
+                const uint32_t s = c0 + (j * 16u + wave) * 4u + sub;
+                v[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+                lv[j] = 0.f;
+                if (s < count) {
+                    lv[j] = lam[s];
+                    const size_t a = (size_t)tm.first(0u, s) * 32u + (lane & 15u) * 4u;
+                    v[j] = *reinterpret_cast<const float4 *>(y + a);
+                    if (addend) {
+                        const float4 w = *reinterpret_cast<const float4 *>(addend + a);
+                        v[j].x += w.x; v[j].y += w.y; v[j].z += w.z; v[j].w += w.w;
+                    }
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < J; ++j) {
+                const uint32_t s = c0 + (j * 16u + wave) * 4u + sub;
+                float t = (v[j].x + v[j].y) + (v[j].z + v[j].w);
+                t += dpp_f<0xB1>(t);            // quad_perm [1,0,3,2]
+                t += dpp_f<0x4E>(t);            // quad_perm [2,3,0,1]
+                t += dpp_f<0x141>(t);           // row_half_mirror: the other quad of the 8 lanes
+                const float mean = t * (1.f / 32.f);
+                const float p0 = mean - v[j].x, p1 = p0 + (mean - v[j].y);
+                const float p2 = p1 + (mean - v[j].z), p3 = p2 + (mean - v[j].w);
+                float inc = p3;                 // inclusive scan over the row's 8 lanes
+                { const float up = dpp_f<0x111>(inc); if (q >= 1u) inc += up; }      // row_shr:1
+                { const float up = dpp_f<0x112>(inc); if (q >= 2u) inc += up; }      // row_shr:2
+                { const float up = dpp_f<0x114>(inc); if (q >= 4u) inc += up; }      // row_shr:4
+                const float l = fmaxf(lv[j], 0.f), e = inc - p3;
+                int out = (fabsf(e + p0) > l ? 1 : 0) + (fabsf(e + p1) > l ? 1 : 0) +
+                          (fabsf(e + p2) > l ? 1 : 0) + ((q < 7u && fabsf(e + p3) > l) ? 1 : 0);
+                out += dpp_i<0xB1>(out);
+                out += dpp_i<0x4E>(out);
+                out += dpp_i<0x141>(out);
+                out += dpp_i<0x140>(out);       // row_mirror: the other row of the slot's 16 lanes
+                if (s < count && (lane & 15u) == 0u) {
+                    const float p = (float)out * (1.f / (2.f * 31.f));
+                    key[s] = p * (1.f - p);
+                }
+            }
         }
-        order[rank] = s;
+    } else {
+    const uint32_t R = 1u << lgR;
+    const uint32_t s = threadIdx.x >> lgR, i = threadIdx.x & (R - 1u);
+    const int n = L.n;                                    // <= 32
+    int out = 0;
+    if (s < count) {
+        const float l = fmaxf(lam[s], 0.f);
+        const uint32_t r = tm.row(tm.first(0u, s), i);
+        const int64_t off = tvk::row_offset(L, r);
+        float v[32];
+#pragma unroll
+        for (int j = 0; j < 32; ++j) {
+            v[j] = 0.f;
+            if (j < n) {
+                const int64_t a = off + j * L.elem_stride;
+                v[j] = y[a];
+                if (addend) v[j] += addend[a];
+            }
+        }
+        float sum = 0.f;
+#pragma unroll
+        for (int j = 0; j < 32; ++j) sum += v[j];         // samples past the row are 0
+        const float mean = sum / (float)n;
+        float run = 0.f;
+#pragma unroll
+        for (int j = 0; j < 31; ++j) {
+            run += mean - v[j];
+            out += (j < n - 1 && fabsf(run) > l) ? 1 : 0;
+        }
+    }
+    for (uint32_t d = 1; d < R; d <<= 1) out += __shfl_xor(out, (int)d);   // R <= 64 lanes, aligned
+    if (s < count && i == 0) {
+        const float p = (float)out / (float)((int)R * (n > 1 ? n - 1 : 1));
+        key[s] = p * (1.f - p);
+    }
+    }
+    __syncthreads();
+    // ranks: the 1 << lgR lanes of a slot share the comparisons, reading keys several at a time
+    {
+        const uint32_t R = 1u << lgR;
+        const uint32_t t = threadIdx.x >> lgR, i = threadIdx.x & (R - 1u);
+        const float k = t < count ? key[t] : 0.f;
+        uint32_t rank = 0;
+        if (t < count) {
+#pragma unroll 8
+            for (uint32_t j = i; j < count; j += R) {
+                const float kj = key[j];
+                rank += (kj > k || (kj == k && j < t)) ? 1u : 0u;
+            }
+        }
+        for (uint32_t d = 1; d < R; d <<= 1) rank += __shfl_xor(rank, (int)d);
+        if (t < count && i == 0) order[rank] = t;
     }
 }
 
@@ -242,13 +312,17 @@ int run_fwd(const float *y, const float *addend, float *x, float *resid, int32_t
     p.L = make_layout(r, l, n_rows);
     p.tm = make_tile_map(l, n_rows);
     if (order_ws && r.length <= 32 && order_applies(p.tm)) {
-        // workspace: count keys (float), then count slot numbers (uint32)
-        float *key = reinterpret_cast<float *>(order_ws);
-        uint32_t *order = order_ws + p.tm.count;
-        hipLaunchKernelGGL(slot_cost_kernel, dim3(p.tm.count), dim3(64), 0, s, y, addend, l.lam, p.L,
-                           p.tm, key);
-        hipLaunchKernelGGL(slot_rank_kernel, dim3(1), dim3((p.tm.count + 63u) / 64u * 64u), 0, s, key,
-                           p.tm.count, order);
+        uint32_t lgR = 0;
+        while (lgR < 6 && ((uint64_t)p.tm.count << (lgR + 1)) <= (uint64_t)kOrderMaxSlots) ++lgR;
+        uint32_t *order = order_ws;
+        const bool fast = r.length == 32 && p.tm.lg >= 1 && rows_packed(r) && aligned16(y) &&
+                          (!addend || aligned16(addend));
+        if (fast)
+            hipLaunchKernelGGL(slot_order_kernel<true>, dim3(1), dim3(kOrderMaxSlots), 0, s, y, addend,
+                               l.lam, p.L, p.tm, lgR, order);
+        else
+            hipLaunchKernelGGL(slot_order_kernel<false>, dim3(1), dim3(kOrderMaxSlots), 0, s, y, addend,
+                               l.lam, p.L, p.tm, lgR, order);
         if (launch_status() != TV_OK) return TV_ERR_HIP;
         p.order = order;
     }
@@ -371,11 +445,11 @@ int zero_floats(float *p, int64_t n, hipStream_t s)
     return launch_status();
 }
 
-// Scratch of the forward call where the slot order applies: a float key and a uint32 per slot.
+// Scratch of the forward call where the slot order applies: a uint32 per slot.
 size_t fwd_workspace_bytes(const tv_rows &rows, const tv_lambda &lam, int64_t n_rows)
 {
     if (rows.length > 32 || !order_applies(make_tile_map(lam, n_rows))) return 0;
-    return align16((size_t)lam.count * 8);
+    return align16((size_t)lam.count * sizeof(uint32_t));
 }
 
 int fwd_entry(const float *y, float *x, tv_rows rows, tv_lambda lam, const tv_fwd_extra &e,

@@ -34,7 +34,7 @@ def run_1d(y, lam, lam_div, g=None, axis=-1, want_info=False, in_place=False, us
         if use_seg:
             out["seg"] = seg.cpu().numpy()[:n_rows].view(np.uint64)
         if wsb:
-            out["order"] = ws.cpu().numpy().view(np.uint32)[lt.numel():2 * lt.numel()]
+            out["order"] = ws.cpu().numpy().view(np.uint32)[:lt.numel()]
     elif want_info:
         info = torch.zeros(max(n_rows, 1), dtype=torch.int32, device=dev)
         tv.tv1d_prox_fwd_info(yt, xt, info, rows, L)

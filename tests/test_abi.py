@@ -96,7 +96,7 @@ def test_forward_ex_workspace_validation():
     lam = tv.tv_lambda(FAKE, 128, 32)
     rows = tv.rows_along((256, 128, 32, 32), -1)
     need = tv.tv1d_fwd_workspace_bytes(rows, lam)
-    assert need == 1024                                   # a key and a slot number per slot
+    assert need == 512                                    # a slot number per slot
     assert tv.tv1d_fwd_workspace_bytes(rows, tv.tv_lambda(FAKE, 1, 1)) == 0
     assert tv.tv1d_fwd_workspace_bytes(tv.rows_along((256, 128, 32, 64), -1), tv.tv_lambda(FAKE, 128, 32)) == 0
     ex = lambda ws, n: L.tv1d_prox_fwd_ex(FAKE, FAKE, rows, lam, tv.tv_fwd_extra(None, None, ws, n), None)

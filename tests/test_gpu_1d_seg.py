@@ -89,7 +89,7 @@ def _check_ordered(y, lam, lam_div, g, axis, expect_order):
     assert np.array_equal(out["gy"], ref["gy"]) and np.array_equal(out["gl"], ref["gl"])
     if expect_order:
         count = np.asarray(lam).size
-        assert out["ws_bytes"] >= 8 * count
+        assert out["ws_bytes"] >= 4 * count
         assert np.array_equal(np.sort(out["order"]), np.arange(count))     # a permutation of the slots
     else:
         assert out["ws_bytes"] == 0
