@@ -193,13 +193,34 @@ def main() -> int:
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    # per-call durations: K eager steps with events around the forward and the backward call
     events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
     for k in range(args.steps):
         step(events[k])
     torch.cuda.synchronize()
+    x_eager, gy_eager, gl_eager = xt.clone(), gy.clone(), gl.clone()
+
+    # the timed region: K replays of a HIP graph that holds one step (the calls launch kernels
+    # only, so a step captures as is; replays keep the launch path off the clock)
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(stream)
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            tv.tv1d_prox_fwd_ex(yt, xt, rows, L, seg=seg, ws=fws, ws_bytes=fwsb)
+            tv.tv1d_prox_bwd_seg(gt, seg, gy, gl, rows, L, ws, wsb)
+    stream.wait_stream(side)
+    for _ in range(max(3, args.warmup // 10)):
+        graph.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        graph.replay()
+    torch.cuda.synchronize()
     wall = time.perf_counter() - t0
+    if not (torch.equal(xt, x_eager) and torch.equal(gy, gy_eager) and torch.equal(gl, gl_eager)):
+        print("bench.py: graph replays and eager steps disagree", file=sys.stderr)
+        return 1
 
     fwd_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in events]))
     bwd_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in events]))   # bwd kernel + lam reduction
@@ -240,6 +261,8 @@ def main() -> int:
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
+        "timing": "value and ms_per_step: K replays of a HIP graph holding one step; per-call "
+                  "figures (roofline, plain_pair): K eager steps with events on the launch stream",
         "config": {"workload": "config 3: 2^20 rows x 32 fp32 ([256,128,32,32] ~N(0,1), per-channel "
                                "lam log-uniform [1e-3,10]), tv1d_prox_fwd_ex (seg + ws) + tv1d_prox_bwd_seg",
                    "rows": n_rows, "length": W, "lam_slots": C},

@@ -101,7 +101,8 @@ struct BwdParams {
     const float *x;        // forward output (defines the segments) ...
     const uint2 *seg;      // ... or the segment code the forward pass wrote (row-per-lane kernels)
     float       *gy;       // output
-    float       *partial;  // optional: per-row dL/dlam contribution
+    float       *partial;  // optional: dL/dlam contributions, one per group of 1 << part_lg rows
+    uint32_t     part_lg;  // row-per-lane kernels only; a group never spans two lambda slots
     Layout       L;
 };
 

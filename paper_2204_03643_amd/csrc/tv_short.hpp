@@ -641,7 +641,13 @@ __global__ __launch_bounds__(kShortBlock) void tv1d_bwd_short_kernel(BwdParams p
         }
         row_store_strided<NMAX, FULL>(p.gy, off, p.L.elem_stride, n, valid, g);
     }
-    if (p.partial && valid) p.partial[row] = glam;
+    if (p.partial) {
+        // one value per aligned group of 1 << part_lg rows (lanes), summed in a fixed order
+        float v = valid ? glam : 0.f;
+        const uint32_t gs = 1u << p.part_lg;
+        for (uint32_t d = 1; d < gs; d <<= 1) v += __shfl_xor(v, (int)d);
+        if (valid && (lane & (gs - 1u)) == 0u) p.partial[row >> p.part_lg] = v;
+    }
 }
 
 }  // namespace tvk

@@ -418,16 +418,31 @@ int run_bwd(const float *g, const float *sub, const float *x, const uint2 *seg, 
     BwdParams p;
     p.g = g; p.sub = sub; p.x = x; p.seg = seg; p.gy = gy;
     p.partial = grad_lam ? partial : nullptr;
+    p.part_lg = 0;
     p.L = make_layout(r, l, n_rows);
     const bool packed = rows_packed(r) && aligned16(g) && (!x || aligned16(x)) && aligned16(gy) &&
                         (!sub || aligned16(sub));
     int st;
+    // row-per-lane kernels add up the dL/dlam terms of neighbouring rows that share a slot
+    // before they leave the wave: groups of the largest power of two (at most 64) dividing div
+    int64_t red_rows = n_rows, red_div = l.div;
+    if (r.length <= 32 && grad_lam) {
+        uint32_t lg = 0;
+        while (lg < 6 && (l.count == 1 || l.div % ((int64_t)2 << lg) == 0)) ++lg;
+        p.part_lg = lg;
+        red_rows = (n_rows + ((int64_t)1 << lg) - 1) >> lg;
+        red_div = l.count == 1 ? 1 : l.div >> lg;
+    }
     if (r.length <= 8) st = launch_bwd_short<8>(p, packed, s);
     else if (r.length <= 16) st = launch_bwd_short<16>(p, packed, s);
     else if (r.length <= 32) st = launch_bwd_short<32>(p, packed, s);
     else st = tvk::launch_bwd_long(p, s) == hipSuccess ? TV_OK : TV_ERR_HIP;
     if (st != TV_OK) return st;
-    if (grad_lam) st = launch_reduce_lambda(partial, grad_lam, n_rows, l, accumulate, s);
+    if (grad_lam) {
+        tv_lambda lr = l;
+        lr.div = red_div;
+        st = launch_reduce_lambda(partial, grad_lam, red_rows, lr, accumulate, s);
+    }
     return st;
 }
 
