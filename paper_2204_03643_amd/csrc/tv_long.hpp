@@ -31,8 +31,32 @@ struct LongMap {
     static constexpr int NW = NT / 64;
     static constexpr int RG = COLS ? G : 1;            // rows interleaved inside a wave
     static constexpr int WPR = COLS ? NW : T / 64;     // waves holding parts of one row
+    // A row that lives in exactly one wave (which holds nothing else) never has to wait for
+    // the other waves of its workgroup: its LDS slices are its own, every barrier becomes a
+    // wave-level fence and every workgroup vote a wave vote, and the wave leaves when its
+    // row is done.
+    static constexpr bool PRIVATE = !COLS && T == 64;
+    // One row per workgroup: row-wide flags are workgroup-uniform.
+    static constexpr bool SOLO = G == 1;
     __device__ static __forceinline__ int row_of(int tid) { return COLS ? tid % G : tid / T; }
     __device__ static __forceinline__ int t_of(int tid) { return COLS ? tid / G : tid % T; }
+    // orders LDS writes before later LDS reads among the threads that share rows
+    __device__ static __forceinline__ void sync()
+    {
+        if (PRIVATE) {
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        } else {
+            __syncthreads();
+        }
+    }
+    // sync() plus: does any thread that shares rows with this one pass `pred`?
+    __device__ static __forceinline__ bool sync_any(bool pred)
+    {
+        if (PRIVATE) { sync(); return __any(pred ? 1 : 0) != 0; }
+        return __syncthreads_or(pred ? 1 : 0) != 0;
+    }
 };
 
 // Sums NV values over the T threads of each row; every thread of the row gets the totals.
@@ -63,6 +87,34 @@ __device__ __forceinline__ void row_sum(float (&v)[NV], float *red, int j, int t
     }
 }
 
+// The same with ONE barrier: consecutive calls alternate between two halves of `red`
+// (par = 0, 1, 0, ...), so the writes of a call cannot overtake the reads of the one before.
+template <int T, int G, bool COLS, int NV>
+__device__ __forceinline__ void row_sum_alt(float (&v)[NV], float *red, int j, int tid, int par)
+{
+    using Mp = LongMap<T, G, COLS>;
+#pragma unroll
+    for (int off = 32; off >= Mp::RG; off >>= 1) {
+#pragma unroll
+        for (int q = 0; q < NV; ++q) v[q] += __shfl_xor(v[q], off);
+    }
+    if (Mp::WPR == 1) return;
+    float *r = red + par * (4 * Mp::NW * Mp::RG);
+    const int wave = tid >> 6, lane = tid & 63;
+    if (lane < Mp::RG) {
+#pragma unroll
+        for (int q = 0; q < NV; ++q) r[(q * Mp::NW + wave) * Mp::RG + (COLS ? j : 0)] = v[q];
+    }
+    __syncthreads();
+    const int w0 = COLS ? 0 : j * Mp::WPR;
+#pragma unroll
+    for (int q = 0; q < NV; ++q) {
+        float s = 0.f;
+        for (int w = 0; w < Mp::WPR; ++w) s += r[(q * Mp::NW + w0 + w) * Mp::RG + (COLS ? j : 0)];
+        v[q] = s;
+    }
+}
+
 // Maximum of one non-negative value over the T threads of each row.
 template <int T, int G, bool COLS>
 __device__ __forceinline__ void row_max(float (&v)[1], float *red, int j, int tid)
@@ -88,16 +140,17 @@ __device__ __forceinline__ void row_max(float (&v)[1], float *red, int j, int ti
 // ADD: open parts accumulate (sums and counts).  !ADD: the value of the nearest closed
 // chunk is copied forward.  Returns what arrives at this thread from the scan's origin
 // side; zero at the origin.  buf: [2][3][G][T] floats.
-template <int T, int G, int DIR, bool ADD>
+template <int T, int G, bool COLS, int DIR, bool ADD>
 __device__ __forceinline__ void seg_scan(bool closed, float s, float n, float *buf, int j, int t,
                                          float &cs, float &cn)
 {
+    using Mp = LongMap<T, G, COLS>;
 #define TV_B(c, q, tt) buf[(((c) * 3 + (q)) * G + j) * T + (tt)]
     float f = closed ? 1.f : 0.f;
     int cur = 0;
     for (int d = 1; d < T; d <<= 1) {
         TV_B(cur, 0, t) = f; TV_B(cur, 1, t) = s; TV_B(cur, 2, t) = n;
-        __syncthreads();
+        Mp::sync();
         const int o = t - DIR * d;
         if (o >= 0 && o < T && f == 0.f) {
             const float of = TV_B(cur, 0, o), os = TV_B(cur, 1, o), on = TV_B(cur, 2, o);
@@ -107,11 +160,11 @@ __device__ __forceinline__ void seg_scan(bool closed, float s, float n, float *b
         cur ^= 1;
     }
     TV_B(cur, 1, t) = s; TV_B(cur, 2, t) = n;
-    __syncthreads();
+    Mp::sync();
     const int o = t - DIR;
     cs = 0.f; cn = 0.f;
     if (o >= 0 && o < T) { cs = TV_B(cur, 1, o); cn = TV_B(cur, 2, o); }
-    __syncthreads();
+    Mp::sync();
 #undef TV_B
 }
 
@@ -122,17 +175,28 @@ struct LongSmem {
     float gtab[C + 2];
     float ex[5][G][TP];
     float buf[2 * 3 * G * T];
-    float red[4 * Mp::NW * Mp::RG];
+    float red[2 * 4 * Mp::NW * Mp::RG];
 };
 
 // ---------------------------------------------------------------------------------
 // Forward: projected Newton on the dual (paper Eq. 3-4), one row per T threads.
 // ---------------------------------------------------------------------------------
-template <int T, int C, int G, bool COLS>
+//
+// XPOSE (strided samples, T = 64): global memory is accessed as in the COLS mapping (adjacent
+// lanes <-> adjacent rows, so that the accesses coalesce), but the G rows of the workgroup
+// are transposed through an LDS tile on the way in and out, and the solve itself runs in the
+// ROWS mapping with one row per wave, i.e. without any workgroup barrier.
+template <int T, int C, int G, bool COLS, bool XPOSE = false>
 __global__ __launch_bounds__(T *G) void tv1d_fwd_long_kernel(FwdParams p)
 {
-    using Mp = LongMap<T, G, COLS>;
-    __shared__ LongSmem<T, C, G, COLS> sm;
+    static_assert(!XPOSE || (COLS && T == 64), "the transposing variant is for strided rows on one wave");
+    constexpr bool MCOLS = COLS && !XPOSE;             // mapping used by the solve
+    using Mp = LongMap<T, G, MCOLS>;
+    __shared__ LongSmem<T, C, G, MCOLS> sm;
+    // tile[row][k + k / C]: the pad after every chunk makes a wave's chunk reads conflict-free,
+    // the odd pitch does the same for the transposing accesses
+    constexpr int TILE_PITCH = T * (C + 1) + 1;
+    __shared__ float tile[XPOSE ? G * TILE_PITCH : 1];
     const int tid = threadIdx.x;
     const int j = Mp::row_of(tid), t = Mp::t_of(tid);
 #define TV_EX(q, tt) sm.ex[q][j][(tt) + 1]
@@ -148,41 +212,61 @@ __global__ __launch_bounds__(T *G) void tv1d_fwd_long_kernel(FwdParams p)
 #pragma unroll
         for (int q = 0; q < 5; ++q) { sm.ex[q][j][0] = 0.f; sm.ex[q][j][T + 1] = 0.f; }
     }
+    if (Mp::PRIVATE) __syncthreads();       // the pivot table is the one thing the waves share
 
     const int64_t off = rvalid ? row_offset(p.L, row) : 0;
     const int64_t es = p.L.elem_stride;
     const float lam = rvalid ? load_lambda(p.lam, p.L, row) : 0.f;
     float y[C];
-#pragma unroll
-    for (int i = 0; i < C; ++i) {
-        float v = 0.f;
-        if (rvalid && k0 + i < n) {
-            v = p.y[off + (int64_t)(k0 + i) * es];
-            if (p.addend) v += p.addend[off + (int64_t)(k0 + i) * es];
+    // transposing variant: thread tid moves samples k = tid / G, tid / G + T, ... of row tid % G
+    const int xj = tid % G, xk0 = tid / G;
+    const uint32_t xrow = blockIdx.x * G + xj;
+    const int64_t xoff = (XPOSE && xrow < p.L.n_rows) ? row_offset(p.L, xrow) : 0;
+    if constexpr (XPOSE) {
+        for (int k = xk0; k < T * C; k += T) {
+            float v = 0.f;
+            if (xrow < p.L.n_rows && k < n) {
+                v = p.y[xoff + (int64_t)k * es];
+                if (p.addend) v += p.addend[xoff + (int64_t)k * es];
+            }
+            tile[xj * TILE_PITCH + k + k / C] = v;
         }
-        y[i] = v;
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < C; ++i) y[i] = tile[j * TILE_PITCH + t * (C + 1) + i];
+    } else {
+#pragma unroll
+        for (int i = 0; i < C; ++i) {
+            float v = 0.f;
+            if (rvalid && k0 + i < n) {
+                v = p.y[off + (int64_t)(k0 + i) * es];
+                if (p.addend) v += p.addend[off + (int64_t)(k0 + i) * es];
+            }
+            y[i] = v;
+        }
     }
     // duals past the end of the row get an empty box and never move
 #define TV_LK(i) ((k0 + (i) < M) ? lam : 0.0f)
 
     TV_EX(0, t) = y[0];
-    __syncthreads();
+    Mp::sync();
     const float ynext0 = TV_EX(0, t + 1);
-    __syncthreads();
+    Mp::sync();
     // rounding floor of a difference of two x values (|x| <= max|y|, |u| <= lam)
     float gtol;
     {
         float ym[1] = {0.f};
 #pragma unroll
         for (int i = 0; i < C; ++i) ym[0] = fmaxf(ym[0], fabsf(y[i]));
-        row_max<T, G, COLS>(ym, sm.red, j, tid);
+        row_max<T, G, MCOLS>(ym, sm.red, j, tid);
         gtol = kGradNoise * (ym[0] + lam);
-        __syncthreads();
+        Mp::sync();
     }
 
     // ---- starting point: every dual at the bound its local difference points to
     float u[C];
     float fcur;
+    float edge_l, edge_r;     // the neighbours' duals next to this chunk, carried between steps
     {
 #pragma unroll
         for (int i = 0; i < C; ++i) {
@@ -191,30 +275,31 @@ __global__ __launch_bounds__(T *G) void tv1d_fwd_long_kernel(FwdParams p)
             u[i] = __builtin_amdgcn_fmed3f(dy * 1e30f, -l, l);
         }
         TV_EX(0, t) = u[C - 1];
-        __syncthreads();
+        TV_EX(1, t) = u[0];
+        Mp::sync();
         const float uleft = TV_EX(0, t - 1);
+        edge_l = uleft;
+        edge_r = TV_EX(1, t + 1);
         float acc[1] = {0.f};
 #pragma unroll
         for (int i = 0; i < C; ++i) {
             const float xi = y[i] + u[i] - (i > 0 ? u[i - 1] : uleft);
             acc[0] = fmaf(xi, xi, acc[0]);
         }
-        row_sum<T, G, COLS, 1>(acc, sm.red, j, tid);
+        row_sum<T, G, MCOLS, 1>(acc, sm.red, j, tid);
         fcur = 0.5f * acc[0];
-        __syncthreads();
+        Mp::sync();
     }
 
     bool active = rvalid;
     bool prev_unclipped = false;
     int steps = 0, flags = 0;
+    int par = 0;
 
     for (int it = 0;; ++it) {
-        // ---- chunk edges of the dual
-        TV_EX(0, t) = u[C - 1];
-        TV_EX(1, t) = u[0];
-        __syncthreads();
-        const float uleft = TV_EX(0, t - 1);
-        const float unext0 = TV_EX(1, t + 1);
+        // ---- chunk edges of the dual: exchanged by the accepted trial of the step before
+        const float uleft = edge_l;
+        const float unext0 = edge_r;
 
         // ---- gradient, bound set, optimality test, interior elimination (Thomas, pass 1)
         float g[C], gam[C], w[C];
@@ -264,13 +349,20 @@ __global__ __launch_bounds__(T *G) void tv1d_fwd_long_kernel(FwdParams p)
         TV_EX(2, t) = p0;
         TV_EX(3, t) = c_alpha;
         TV_EX(4, t) = c_beta;
-        row_sum<T, G, COLS, 1>(viof, sm.red, j, tid);
-        __syncthreads();
+        bool vio;
+        if (Mp::SOLO) {
+            vio = Mp::sync_any(viof[0] != 0.f);             // one row: the vote is the row's
+        } else {
+            row_sum<T, G, MCOLS, 1>(viof, sm.red, j, tid);
+            vio = viof[0] != 0.f;
+            Mp::sync();
+        }
         const float p0n = TV_EX(2, t + 1), alphan = TV_EX(3, t + 1), betan = TV_EX(4, t + 1);
 
-        if (active && prev_unclipped && viof[0] == 0.f) { active = false; flags = kInfoConverged; }
+        if (active && prev_unclipped && !vio) { active = false; flags = kInfoConverged; }
         if (active && it >= kMaxNewtonSteps) { active = false; flags = kInfoCapped; }
-        if (!__syncthreads_or(active ? 1 : 0)) break;
+        if (Mp::SOLO) { if (!active) break; }               // row-wide flags are uniform here
+        else if (!Mp::sync_any(active)) break;
         steps += active ? 1 : 0;
 
         // ---- separator system (normalised to unit diagonal) and PCR
@@ -281,11 +373,14 @@ __global__ __launch_bounds__(T *G) void tv1d_fwd_long_kernel(FwdParams p)
             ec = -betan * inv;
             er = (g[C - 1] + pl + p0n) * inv;
         }
+        float sleft;
         {
             int cur = 0;
+            bool published = false;
             for (int s = 1; s < T; s <<= 1) {
                 TV_PB(cur, 0, t) = ea; TV_PB(cur, 1, t) = ec; TV_PB(cur, 2, t) = er;
-                if (!__syncthreads_or((ea != 0.f || ec != 0.f) ? 1 : 0)) break;
+                // every equation decoupled: the right-hand sides just published are the solution
+                if (!Mp::sync_any(ea != 0.f || ec != 0.f)) { published = true; break; }
                 float la = 0.f, lc = 0.f, lr = 0.f, ra = 0.f, rc = 0.f, rr = 0.f;
                 if (t - s >= 0) { la = TV_PB(cur, 0, t - s); lc = TV_PB(cur, 1, t - s); lr = TV_PB(cur, 2, t - s); }
                 if (t + s < T) { ra = TV_PB(cur, 0, t + s); rc = TV_PB(cur, 1, t + s); rr = TV_PB(cur, 2, t + s); }
@@ -295,11 +390,13 @@ __global__ __launch_bounds__(T *G) void tv1d_fwd_long_kernel(FwdParams p)
                 ea = na; ec = nc;
                 cur ^= 1;
             }
+            if (!published) {
+                TV_PB(cur, 2, t) = er;
+                Mp::sync();
+            }
+            sleft = t > 0 ? TV_PB(cur, 2, t - 1) : 0.f;
         }
         const float sigma = er;
-        TV_EX(0, t) = sigma;
-        __syncthreads();
-        const float sleft = TV_EX(0, t - 1);
 
         // ---- interior back-substitution with the separators as boundary terms (pass 2);
         //      w becomes the Newton direction d
@@ -341,19 +438,24 @@ __global__ __launch_bounds__(T *G) void tv1d_fwd_long_kernel(FwdParams p)
                 if (cc != u[i]) v[3] += 1.f;
                 uc[i] = cc;
             }
-            TV_EX(1, t) = uc[C - 1];
-            __syncthreads();
-            const float ucleft = TV_EX(1, t - 1);
+            TV_EX(0, t) = uc[C - 1];
+            TV_EX(1, t) = uc[0];
+            Mp::sync();
+            const float ucleft = TV_EX(0, t - 1);
+            edge_l = ucleft;
+            edge_r = TV_EX(1, t + 1);
 #pragma unroll
             for (int i = 0; i < C; ++i) {
                 const float xc = y[i] + uc[i] - (i > 0 ? uc[i - 1] : ucleft);
                 v[0] = fmaf(xc, xc, v[0]);
             }
-            row_sum<T, G, COLS, 4>(v, sm.red, j, tid);
+            row_sum_alt<T, G, MCOLS, 4>(v, sm.red, j, tid, par);
+            par ^= 1;
             fc = 0.5f * v[0]; dec = v[1]; clipped = v[2] > 0.f; changed = v[3] > 0.f;
             const bool ok = !active || alpha == 0.f || (alpha == 1.f && !clipped) ||
                             (fc <= fcur - kArmijoSigma * alpha * dec + kArmijoSlackEps * fabsf(fcur));
-            if (!__syncthreads_or(ok ? 0 : 1)) break;
+            if (Mp::SOLO) { if (ok) break; }                // uniform: every thread sees the row's sums
+            else if (!Mp::sync_any(!ok)) break;
             if (!ok) {
                 if (ls >= kMaxBacktracks) {
                     alpha = 0.f;
@@ -369,7 +471,8 @@ __global__ __launch_bounds__(T *G) void tv1d_fwd_long_kernel(FwdParams p)
         prev_unclipped = (alpha == 1.f) && !clipped;
         if (active) fcur = fc;
         if (active && !changed) { active = false; flags = kInfoStalled; }
-        if (!__syncthreads_or(active ? 1 : 0)) break;
+        if (Mp::SOLO) { if (!active) break; }
+        else if (!Mp::sync_any(active)) break;
     }
 
     // ---- primal recovery x = y - D^T u, then every block between two bound duals takes
@@ -378,7 +481,7 @@ __global__ __launch_bounds__(T *G) void tv1d_fwd_long_kernel(FwdParams p)
     {
         TV_EX(0, t) = u[C - 1];
         TV_EX(1, t) = u[0];
-        __syncthreads();
+        Mp::sync();
         const float uleft = TV_EX(0, t - 1);
         const float unext0 = TV_EX(1, t + 1);
         bool bnd[C];
@@ -393,7 +496,7 @@ __global__ __launch_bounds__(T *G) void tv1d_fwd_long_kernel(FwdParams p)
         }
         // a sample starts a block when the dual on its left is bound; chunk-local pass first
         TV_EX(2, t) = bnd[C - 1] ? 1.f : 0.f;
-        __syncthreads();
+        Mp::sync();
         const bool start0 = (t == 0) || (TV_EX(2, t - 1) != 0.f);
         bool closed = start0;
         float last = xs[0];
@@ -402,7 +505,7 @@ __global__ __launch_bounds__(T *G) void tv1d_fwd_long_kernel(FwdParams p)
             if (bnd[i - 1]) { closed = true; last = xs[i]; }
         // `last` = first sample of the chunk's last block (valid when closed)
         float cv, cdummy;
-        seg_scan<T, G, +1, false>(closed, last, 0.f, sm.buf, j, t, cv, cdummy);
+        seg_scan<T, G, MCOLS, +1, false>(closed, last, 0.f, sm.buf, j, t, cv, cdummy);
         float val = start0 ? xs[0] : cv;
         float dev[1] = {0.f};
 #pragma unroll
@@ -411,7 +514,7 @@ __global__ __launch_bounds__(T *G) void tv1d_fwd_long_kernel(FwdParams p)
             if (fabsf(val - xs[i]) > 2e-5f * (1.f + fabsf(y[i]) + lam)) dev[0] += 1.f;
             u[i] = val;       // u is dead from here on: reuse it for the block values
         }
-        row_sum<T, G, COLS, 1>(dev, sm.red, j, tid);
+        row_sum<T, G, MCOLS, 1>(dev, sm.red, j, tid);
         const bool use_blocks = !(flags & kInfoCapped) && dev[0] == 0.f;
         if (use_blocks) {
 #pragma unroll
@@ -421,11 +524,29 @@ __global__ __launch_bounds__(T *G) void tv1d_fwd_long_kernel(FwdParams p)
         }
     }
 
+    if constexpr (XPOSE) {
+        // a wave writes only its own row of the tile; the barrier then hands the tile over
 #pragma unroll
-    for (int i = 0; i < C; ++i) {
-        if (rvalid && k0 + i < n) {
-            p.x[off + (int64_t)(k0 + i) * es] = xs[i];
-            if (p.resid) p.resid[off + (int64_t)(k0 + i) * es] = y[i] - xs[i];
+        for (int i = 0; i < C; ++i) tile[j * TILE_PITCH + t * (C + 1) + i] = xs[i];
+        __syncthreads();
+        for (int k = xk0; k < T * C; k += T)
+            if (xrow < p.L.n_rows && k < n) p.x[xoff + (int64_t)k * es] = tile[xj * TILE_PITCH + k + k / C];
+        if (p.resid) {
+            __syncthreads();
+#pragma unroll
+            for (int i = 0; i < C; ++i) tile[j * TILE_PITCH + t * (C + 1) + i] = y[i] - xs[i];
+            __syncthreads();
+            for (int k = xk0; k < T * C; k += T)
+                if (xrow < p.L.n_rows && k < n)
+                    p.resid[xoff + (int64_t)k * es] = tile[xj * TILE_PITCH + k + k / C];
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < C; ++i) {
+            if (rvalid && k0 + i < n) {
+                p.x[off + (int64_t)(k0 + i) * es] = xs[i];
+                if (p.resid) p.resid[off + (int64_t)(k0 + i) * es] = y[i] - xs[i];
+            }
         }
     }
     if (p.info && rvalid && t == 0) p.info[row] = steps | flags;
@@ -469,7 +590,7 @@ __global__ __launch_bounds__(T *G) void tv1d_bwd_long_kernel(BwdParams p)
         g[i] = gv; x[i] = xv; sb[i] = sv;
     }
     TV_EX(0, t) = x[0];
-    __syncthreads();
+    Mp::sync();
     const float xnext0 = TV_EX(0, t + 1);
 
     // jump after sample i (always at the end of the row; samples past the end are their
@@ -491,8 +612,8 @@ __global__ __launch_bounds__(T *G) void tv1d_bwd_long_kernel(BwdParams p)
         if (jump[i]) { any = true; tail_s = 0.f; tail_n = 0.f; }
     }
     float ls, ln, rs, rn;
-    seg_scan<T, G, +1, true>(any, tail_s, tail_n, sm.buf, j, t, ls, ln);   // open part on the left
-    seg_scan<T, G, -1, true>(any, head_s, head_n, sm.buf, j, t, rs, rn);   // open part on the right
+    seg_scan<T, G, COLS, +1, true>(any, tail_s, tail_n, sm.buf, j, t, ls, ln);   // open part on the left
+    seg_scan<T, G, COLS, -1, true>(any, head_s, head_n, sm.buf, j, t, rs, rn);   // open part on the right
 
     // per-sample means: forward pass accumulates, backward pass broadcasts
     float mean[C];
@@ -516,7 +637,7 @@ __global__ __launch_bounds__(T *G) void tv1d_bwd_long_kernel(BwdParams p)
     // a head piece that is closed inside this chunk still needs nothing from the right; a
     // head piece open to the left got (ls, ln) above.  dL/dlam needs the next chunk's first mean.
     TV_EX(1, t) = mean[0];
-    __syncthreads();
+    Mp::sync();
     const float mnext0 = TV_EX(1, t + 1);
     float gl[1] = {0.f};
 #pragma unroll
@@ -546,7 +667,10 @@ template <int T, int C, int G, bool COLS>
 inline hipError_t launch_fwd_long_t(const FwdParams &p, hipStream_t s)
 {
     const dim3 grid((p.L.n_rows + G - 1) / G), block(T * G);
-    hipLaunchKernelGGL((tv1d_fwd_long_kernel<T, C, G, COLS>), grid, block, 0, s, p);
+    if constexpr (COLS && T == 64)
+        hipLaunchKernelGGL((tv1d_fwd_long_kernel<T, C, G, COLS, true>), grid, block, 0, s, p);
+    else
+        hipLaunchKernelGGL((tv1d_fwd_long_kernel<T, C, G, COLS>), grid, block, 0, s, p);
     return hipGetLastError();
 }
 
@@ -578,7 +702,7 @@ inline hipError_t launch_bwd_long_t(const BwdParams &p, hipStream_t s)
         if (n <= 1024) return FN<64, 16, 4, false>(p, s);                                 \
         if (n <= 2048) return FN<256, 8, 1, false>(p, s);                                 \
         if (n <= 4096) return FN<256, 16, 1, false>(p, s);                                \
-        if (n <= 8192) return FN<1024, 8, 1, false>(p, s);                                \
+        if (n <= 8192) return FN<512, 16, 1, false>(p, s);                                \
         return FN<1024, 16, 1, false>(p, s);                                              \
     } while (0)
 
