@@ -60,6 +60,17 @@ def test_odd_sizes_mixed_paths():
     _check_2d(y, lam[:2], 2, g, "70x33 K=2")
 
 
+@pytest.mark.parametrize("shape,K", [((5, 19, 11), 3), ((3, 32, 16), 2), ((7, 8, 32), 2), ((2, 1, 17), 2),
+                                     ((3, 32, 32), 5), ((1, 2, 2), 1)])
+def test_small_planes(shape, K):
+    # planes of at most 32 x 32: both passes on the row-per-lane kernels, ragged in both directions
+    rng = np.random.default_rng(73 + shape[1] * 64 + shape[2])
+    y = rng.normal(size=shape).astype(np.float32)
+    g = rng.normal(size=shape).astype(np.float32)
+    lam = (10 ** rng.uniform(-2, 0.3, size=min(shape[0], 3))).astype(np.float32)
+    _check_2d(y, lam, K, g, "small %s K=%d" % (shape, K), bulk=0.8)
+
+
 def test_config4_reduced():
     y, lam, g = workloads.config4(B=1, C=3, H=512, W=512, n_poly=8)
     _check_2d(y, lam, 3, g, "cfg4 reduced K=3", bulk=0.8)
