@@ -1,0 +1,100 @@
+"""GPU: the library's calls only launch kernels (no allocation, no memset), so a forward +
+backward step captures into a HIP graph as it is.  Replays are checked against the eager
+result, several times, with eager work and synchronisations between them and with new input
+values written into the captured buffers."""
+import numpy as np
+import pytest
+
+import workloads
+
+pytestmark = pytest.mark.gpu
+
+
+def test_forward_backward_step_replays_from_a_graph():
+    import torch
+
+    import paper_2204_03643_amd as tv
+
+    dev = torch.device("cuda:0")
+    y, lam, g = workloads.config3(B=4, C=128)
+    B, C, H, W = y.shape
+    yt, lt, gt = (torch.from_numpy(a).to(dev) for a in (y, lam, g))
+    xt, gy, gl = torch.empty_like(yt), torch.empty_like(yt), torch.empty_like(lt)
+    rows = tv.rows_along(y.shape, -1)
+    L = tv.tv_lambda(lt.data_ptr(), C, H)
+    seg = torch.empty(B * C * H, dtype=torch.int64, device=dev)
+    fwsb = tv.tv1d_fwd_workspace_bytes(rows, L)
+    assert fwsb > 0
+    fws = torch.empty(fwsb, dtype=torch.uint8, device=dev)
+    bwsb = tv.tv1d_bwd_workspace_bytes(rows, L)
+    bws = torch.empty(bwsb, dtype=torch.uint8, device=dev)
+
+    def step():
+        tv.tv1d_prox_fwd_ex(yt, xt, rows, L, seg=seg, ws=fws, ws_bytes=fwsb)
+        tv.tv1d_prox_bwd_seg(gt, seg, gy, gl, rows, L, bws, bwsb)
+
+    def eager():
+        step()
+        torch.cuda.synchronize()
+        return xt.clone(), gy.clone(), gl.clone()
+
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()                                           # warm-up on the capture stream
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+
+    rng = np.random.default_rng(91)
+    for rep in range(4):
+        if rep:                                          # new values in the captured buffers
+            yt.copy_(torch.from_numpy(rng.normal(size=y.shape).astype(np.float32)))
+            gt.copy_(torch.from_numpy(rng.normal(size=y.shape).astype(np.float32)))
+            lt.copy_(torch.from_numpy((10 ** rng.uniform(-3, 1, size=C)).astype(np.float32)))
+        ref = eager()
+        for t in (xt, gy, gl, seg):
+            t.zero_()                                    # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(xt, ref[0]) and torch.equal(gy, ref[1]) and torch.equal(gl, ref[2]), rep
+
+
+def test_2d_step_replays_from_a_graph():
+    import torch
+
+    import paper_2204_03643_amd as tv
+
+    dev = torch.device("cuda:0")
+    y, lam, g = workloads.config2(B=2, C=8)
+    planes, H, W, K = 16, 32, 32, 3
+    yt, lt, gt = (torch.from_numpy(a).to(dev) for a in (y, lam, g))
+    xt, gy, gl = torch.empty_like(yt), torch.empty_like(yt), torch.empty_like(lt)
+    L = tv.tv_lambda(lt.data_ptr(), lt.numel(), 1)
+    wsb = tv.tv2d_workspace_bytes(planes, H, W, K)
+    ws = torch.empty(wsb, dtype=torch.uint8, device=dev)
+
+    def step():
+        tv.tv2d_prox_fwd(yt, xt, planes, H, W, L, K, ws, wsb)
+        tv.tv2d_prox_bwd(gt, gy, gl, planes, H, W, L, K, ws, wsb)
+
+    step()
+    torch.cuda.synchronize()
+    ref = (xt.clone(), gy.clone(), gl.clone())
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.current_stream().wait_stream(side)
+    for rep in range(3):
+        for t in (xt, gy, gl):
+            t.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(xt, ref[0]) and torch.equal(gy, ref[1]) and torch.equal(gl, ref[2]), rep
