@@ -59,6 +59,60 @@ struct LongMap {
     }
 };
 
+// A thread's C contiguous samples k0 .. k0 + C - 1 of a row (zero past the end).  With unit
+// stride and 16-byte alignment they move as float4: a wave then touches every cache line of
+// its 64 * C samples C / 4 times instead of C times.
+template <int C>
+__device__ __forceinline__ bool chunk_vec_ok(const void *base, int64_t off, int64_t es, int k0)
+{
+    return C % 4 == 0 && es == 1 && (((uintptr_t)base >> 2) + (uint64_t)(off + k0)) % 4 == 0 &&
+           ((uintptr_t)base & 3u) == 0;
+}
+
+template <int C>
+__device__ __forceinline__ void chunk_load(const float *__restrict__ base, int64_t off, int64_t es,
+                                           int k0, int n, bool rvalid, float (&v)[C])
+{
+    if (rvalid && chunk_vec_ok<C>(base, off, es, k0)) {
+#pragma unroll
+        for (int i = 0; i < C; i += 4) {
+            if (k0 + i + 3 < n) {
+                const float4 q = *reinterpret_cast<const float4 *>(base + off + k0 + i);
+                v[i] = q.x; v[i + 1] = q.y; v[i + 2] = q.z; v[i + 3] = q.w;
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) v[i + e] = (k0 + i + e < n) ? base[off + k0 + i + e] : 0.f;
+            }
+        }
+        return;
+    }
+#pragma unroll
+    for (int i = 0; i < C; ++i) v[i] = (rvalid && k0 + i < n) ? base[off + (int64_t)(k0 + i) * es] : 0.f;
+}
+
+template <int C>
+__device__ __forceinline__ void chunk_store(float *__restrict__ base, int64_t off, int64_t es, int k0,
+                                            int n, bool rvalid, const float (&v)[C])
+{
+    if (!rvalid) return;
+    if (chunk_vec_ok<C>(base, off, es, k0)) {
+#pragma unroll
+        for (int i = 0; i < C; i += 4) {
+            if (k0 + i + 3 < n) {
+                *reinterpret_cast<float4 *>(base + off + k0 + i) = make_float4(v[i], v[i + 1], v[i + 2], v[i + 3]);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (k0 + i + e < n) base[off + k0 + i + e] = v[i + e];
+            }
+        }
+        return;
+    }
+#pragma unroll
+    for (int i = 0; i < C; ++i)
+        if (k0 + i < n) base[off + (int64_t)(k0 + i) * es] = v[i];
+}
+
 // Sums NV values over the T threads of each row; every thread of the row gets the totals.
 // Deterministic: fixed shuffle tree inside a wave, then a fixed-order sum over waves.
 template <int T, int G, bool COLS, int NV>
@@ -145,6 +199,57 @@ __device__ __forceinline__ void seg_scan(bool closed, float s, float n, float *b
                                          float &cs, float &cn)
 {
     using Mp = LongMap<T, G, COLS>;
+    if constexpr (!COLS) {
+        // A wave holds 64 consecutive threads of one row: scan inside the wave with lane
+        // shuffles (no LDS, no barrier), then combine the waves' totals, which takes one
+        // barrier.  combine(A earlier, B later) = B if B is closed, else A with B's open part
+        // added (ADD) or A unchanged (copy).
+        const int lane = t & 63;
+        float f = closed ? 1.f : 0.f;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const float of = DIR > 0 ? __shfl_up(f, d) : __shfl_down(f, d);
+            const float os = DIR > 0 ? __shfl_up(s, d) : __shfl_down(s, d);
+            const float on = DIR > 0 ? __shfl_up(n, d) : __shfl_down(n, d);
+            const bool has = DIR > 0 ? (lane >= d) : (lane + d < 64);
+            if (has && f == 0.f) {
+                if (ADD) { s += os; n += on; } else { s = os; n = on; }
+                f = of;
+            }
+        }
+        // what arrives at this lane from inside its wave: the inclusive value of the lane before
+        float ef = DIR > 0 ? __shfl_up(f, 1) : __shfl_down(f, 1);
+        float es = DIR > 0 ? __shfl_up(s, 1) : __shfl_down(s, 1);
+        float en = DIR > 0 ? __shfl_up(n, 1) : __shfl_down(n, 1);
+        const bool edge = DIR > 0 ? (lane == 0) : (lane == 63);
+        if (edge) { ef = 0.f; es = 0.f; en = 0.f; }
+        if constexpr (T > 64) {
+            constexpr int NWR = T / 64;                       // waves per row
+            float *tot = buf + (DIR > 0 ? 0 : 3 * G * NWR);   // the two directions never share
+            const int w = t >> 6;
+            const bool lastlane = DIR > 0 ? (lane == 63) : (lane == 0);
+            if (lastlane) {
+                tot[(0 * G + j) * NWR + w] = f; tot[(1 * G + j) * NWR + w] = s; tot[(2 * G + j) * NWR + w] = n;
+            }
+            __syncthreads();
+            float af = 0.f, as = 0.f, an = 0.f;               // waves before this one, in scan order
+            for (int q = 0; q < NWR; ++q) {
+                const int ww = DIR > 0 ? q : NWR - 1 - q;
+                const bool before = DIR > 0 ? (ww < w) : (ww > w);
+                if (!before) continue;
+                const float bf = tot[(0 * G + j) * NWR + ww], bs = tot[(1 * G + j) * NWR + ww],
+                            bn = tot[(2 * G + j) * NWR + ww];
+                if (bf != 0.f) { af = 1.f; as = bs; an = bn; }
+                else if (ADD) { as += bs; an += bn; }
+            }
+            // combine(waves before, lanes before)
+            if (ef == 0.f) {
+                if (ADD) { es += as; en += an; } else { es = as; en = an; }
+            }
+        }
+        cs = es; cn = en;
+        return;
+    } else {
 #define TV_B(c, q, tt) buf[(((c) * 3 + (q)) * G + j) * T + (tt)]
     float f = closed ? 1.f : 0.f;
     int cur = 0;
@@ -166,6 +271,7 @@ __device__ __forceinline__ void seg_scan(bool closed, float s, float n, float *b
     if (o >= 0 && o < T) { cs = TV_B(cur, 1, o); cn = TV_B(cur, 2, o); }
     Mp::sync();
 #undef TV_B
+    }
 }
 
 template <int T, int C, int G, bool COLS>
@@ -235,14 +341,12 @@ __global__ __launch_bounds__(T *G) void tv1d_fwd_long_kernel(FwdParams p)
 #pragma unroll
         for (int i = 0; i < C; ++i) y[i] = tile[j * TILE_PITCH + t * (C + 1) + i];
     } else {
+        chunk_load<C>(p.y, off, es, k0, n, rvalid, y);
+        if (p.addend) {
+            float ad[C];
+            chunk_load<C>(p.addend, off, es, k0, n, rvalid, ad);
 #pragma unroll
-        for (int i = 0; i < C; ++i) {
-            float v = 0.f;
-            if (rvalid && k0 + i < n) {
-                v = p.y[off + (int64_t)(k0 + i) * es];
-                if (p.addend) v += p.addend[off + (int64_t)(k0 + i) * es];
-            }
-            y[i] = v;
+            for (int i = 0; i < C; ++i) y[i] += ad[i];
         }
     }
     // duals past the end of the row get an empty box and never move
@@ -541,12 +645,11 @@ __global__ __launch_bounds__(T *G) void tv1d_fwd_long_kernel(FwdParams p)
                     p.resid[xoff + (int64_t)k * es] = tile[xj * TILE_PITCH + k + k / C];
         }
     } else {
+        chunk_store<C>(p.x, off, es, k0, n, rvalid, xs);
+        if (p.resid) {
 #pragma unroll
-        for (int i = 0; i < C; ++i) {
-            if (rvalid && k0 + i < n) {
-                p.x[off + (int64_t)(k0 + i) * es] = xs[i];
-                if (p.resid) p.resid[off + (int64_t)(k0 + i) * es] = y[i] - xs[i];
-            }
+            for (int i = 0; i < C; ++i) y[i] -= xs[i];
+            chunk_store<C>(p.resid, off, es, k0, n, rvalid, y);
         }
     }
     if (p.info && rvalid && t == 0) p.info[row] = steps | flags;
@@ -558,11 +661,16 @@ __global__ __launch_bounds__(T *G) void tv1d_fwd_long_kernel(FwdParams p)
 // ---------------------------------------------------------------------------------
 // Backward (paper Eq. 5-6 as segment averaging), one row per T threads.
 // ---------------------------------------------------------------------------------
-template <int T, int C, int G, bool COLS>
+// XPOSE: as in the forward kernel (strided rows through an LDS tile, one row per wave).
+template <int T, int C, int G, bool COLS, bool XPOSE = false>
 __global__ __launch_bounds__(T *G) void tv1d_bwd_long_kernel(BwdParams p)
 {
-    using Mp = LongMap<T, G, COLS>;
-    __shared__ LongSmem<T, C, G, COLS> sm;
+    static_assert(!XPOSE || (COLS && T == 64), "the transposing variant is for strided rows on one wave");
+    constexpr bool MCOLS = COLS && !XPOSE;
+    using Mp = LongMap<T, G, MCOLS>;
+    __shared__ LongSmem<T, C, G, MCOLS> sm;
+    constexpr int TILE_PITCH = T * (C + 1) + 1;
+    __shared__ float tile[XPOSE ? G * TILE_PITCH : 1];
     const int tid = threadIdx.x;
     const int j = Mp::row_of(tid), t = Mp::t_of(tid);
 #define TV_EX(q, tt) sm.ex[q][j][(tt) + 1]
@@ -577,17 +685,58 @@ __global__ __launch_bounds__(T *G) void tv1d_bwd_long_kernel(BwdParams p)
     const int64_t off = rvalid ? row_offset(p.L, row) : 0;
     const int64_t es = p.L.elem_stride;
 
-    float g[C], x[C], sb[C];
+    // transposing variant: thread tid moves samples k = tid / G, tid / G + T, ... of row tid % G
+    const int xj = tid % G, xk0 = tid / G;
+    const uint32_t xrow = blockIdx.x * G + xj;
+    const bool xvalid = XPOSE && xrow < p.L.n_rows;
+    const int64_t xoff = xvalid ? row_offset(p.L, xrow) : 0;
+    // every global load is issued before the first trip through the tile
+    auto fetch = [&](const float *__restrict__ src, float (&raw)[C]) {
 #pragma unroll
-    for (int i = 0; i < C; ++i) {
-        float gv = 0.f, xv = 0.f, sv = 0.f;
-        if (rvalid && k0 + i < n) {
-            const int64_t o = off + (int64_t)(k0 + i) * es;
-            gv = p.g[o];
-            xv = p.x[o];
-            if (p.sub) { sv = p.sub[o]; gv -= sv; }
+        for (int i = 0; i < C; ++i) {
+            const int k = xk0 + i * T;
+            raw[i] = (xvalid && k < n) ? src[xoff + (int64_t)k * es] : 0.f;
         }
-        g[i] = gv; x[i] = xv; sb[i] = sv;
+    };
+    auto turn = [&](const float (&raw)[C], float (&dst)[C]) {
+#pragma unroll
+        for (int i = 0; i < C; ++i) {
+            const int k = xk0 + i * T;
+            tile[xj * TILE_PITCH + k + k / C] = raw[i];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < C; ++i) dst[i] = tile[j * TILE_PITCH + t * (C + 1) + i];
+        __syncthreads();
+    };
+
+    float g[C], x[C], sb[C];
+    if constexpr (XPOSE) {
+        float rg[C], rx[C], rs[C];
+        fetch(p.g, rg);
+        fetch(p.x, rx);
+        if (p.sub) fetch(p.sub, rs);
+        turn(rg, g);
+        turn(rx, x);
+        if (p.sub) {
+            turn(rs, sb);
+#pragma unroll
+            for (int i = 0; i < C; ++i) g[i] -= sb[i];
+        } else {
+#pragma unroll
+            for (int i = 0; i < C; ++i) sb[i] = 0.f;
+        }
+    } else {
+        chunk_load<C>(p.g, off, es, k0, n, rvalid, g);
+        chunk_load<C>(p.x, off, es, k0, n, rvalid, x);
+        if (p.sub) {
+            chunk_load<C>(p.sub, off, es, k0, n, rvalid, sb);
+#pragma unroll
+            for (int i = 0; i < C; ++i) g[i] -= sb[i];
+        } else {
+#pragma unroll
+            for (int i = 0; i < C; ++i) sb[i] = 0.f;
+        }
     }
     TV_EX(0, t) = x[0];
     Mp::sync();
@@ -612,8 +761,8 @@ __global__ __launch_bounds__(T *G) void tv1d_bwd_long_kernel(BwdParams p)
         if (jump[i]) { any = true; tail_s = 0.f; tail_n = 0.f; }
     }
     float ls, ln, rs, rn;
-    seg_scan<T, G, COLS, +1, true>(any, tail_s, tail_n, sm.buf, j, t, ls, ln);   // open part on the left
-    seg_scan<T, G, COLS, -1, true>(any, head_s, head_n, sm.buf, j, t, rs, rn);   // open part on the right
+    seg_scan<T, G, MCOLS, +1, true>(any, tail_s, tail_n, sm.buf, j, t, ls, ln);   // open part on the left
+    seg_scan<T, G, MCOLS, -1, true>(any, head_s, head_n, sm.buf, j, t, rs, rn);   // open part on the right
 
     // per-sample means: forward pass accumulates, backward pass broadcasts
     float mean[C];
@@ -651,10 +800,18 @@ __global__ __launch_bounds__(T *G) void tv1d_bwd_long_kernel(BwdParams p)
         }
     }
 #pragma unroll
-    for (int i = 0; i < C; ++i)
-        if (rvalid && k0 + i < n) p.gy[off + (int64_t)(k0 + i) * es] = mean[i] + sb[i];
+    for (int i = 0; i < C; ++i) mean[i] += sb[i];
+    if constexpr (XPOSE) {
+#pragma unroll
+        for (int i = 0; i < C; ++i) tile[j * TILE_PITCH + t * (C + 1) + i] = mean[i];
+        __syncthreads();
+        for (int k = xk0; k < T * C; k += T)
+            if (xvalid && k < n) p.gy[xoff + (int64_t)k * es] = tile[xj * TILE_PITCH + k + k / C];
+    } else {
+        chunk_store<C>(p.gy, off, es, k0, n, rvalid, mean);
+    }
     if (p.partial) {
-        row_sum<T, G, COLS, 1>(gl, sm.red, j, tid);
+        row_sum<T, G, MCOLS, 1>(gl, sm.red, j, tid);
         if (rvalid && t == 0) p.partial[row] = gl[0];
     }
 #undef TV_EX
@@ -678,7 +835,10 @@ template <int T, int C, int G, bool COLS>
 inline hipError_t launch_bwd_long_t(const BwdParams &p, hipStream_t s)
 {
     const dim3 grid((p.L.n_rows + G - 1) / G), block(T * G);
-    hipLaunchKernelGGL((tv1d_bwd_long_kernel<T, C, G, COLS>), grid, block, 0, s, p);
+    if constexpr (COLS && T == 64)
+        hipLaunchKernelGGL((tv1d_bwd_long_kernel<T, C, G, COLS, true>), grid, block, 0, s, p);
+    else
+        hipLaunchKernelGGL((tv1d_bwd_long_kernel<T, C, G, COLS>), grid, block, 0, s, p);
     return hipGetLastError();
 }
 
