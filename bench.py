@@ -140,8 +140,8 @@ def main() -> int:
                          "exit (for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (rows are independent; see DESIGN.md for "
-              "how the path would shard); --gpus %d is not supported" % args.gpus, file=sys.stderr)
+        print("bench.py: this build runs on one GPU only (rows are independent and would shard by "
+              "row block with no exchange); --gpus %d is not supported" % args.gpus, file=sys.stderr)
         return 2
 
     import numpy as np

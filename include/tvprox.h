@@ -33,10 +33,10 @@ typedef enum {
     TV_OK = 0,
     TV_ERR_NULL = 1,        /* a required pointer is NULL                              */
     TV_ERR_SHAPE = 2,       /* negative count, length < 1, sweeps < 1, size overflow   */
-    TV_ERR_STRIDE = 3,      /* negative or zero stride where rows would overlap        */
+    TV_ERR_STRIDE = 3,      /* rows would overlap; segment-code buffer not 8-byte aligned */
     TV_ERR_LAMBDA = 4,      /* lam.count < 1 or lam.div < 1                            */
     TV_ERR_WORKSPACE = 5,   /* workspace NULL, misaligned or too small                 */
-    TV_ERR_UNSUPPORTED = 6, /* row length above TV_MAX_LENGTH                          */
+    TV_ERR_UNSUPPORTED = 6, /* row longer than TV_MAX_LENGTH (TV_SEG_MAX_LENGTH with codes) */
     TV_ERR_HIP = 7          /* a HIP runtime call (kernel launch) failed               */
 } tv_status;
 
