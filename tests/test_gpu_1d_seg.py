@@ -119,3 +119,17 @@ def test_ordered_falls_back_where_slots_do_not_group():
     y = rng.normal(size=(32, 6, 16, 16)).astype(np.float32)                 # now every slot fills tiles
     g = rng.normal(size=y.shape).astype(np.float32)
     _check_ordered(y, (10 ** rng.uniform(-2, 0.5, size=6)).astype(np.float32), 16, g, -1, True)
+
+
+@pytest.mark.parametrize("shape", [(16, 100, 8, 32), (64, 1000, 2, 16), (8, 40, 16, 32)])
+def test_ordered_many_slots_small_groups(shape):
+    # slot counts that are no power of two, groups of 8, 2 and 16 rows, up to 1000 slots
+    rng = np.random.default_rng(45 + shape[1])
+    y = rng.normal(size=shape).astype(np.float32)
+    g = rng.normal(size=shape).astype(np.float32)
+    lam = (10 ** rng.uniform(-3, 1, size=shape[1])).astype(np.float32)
+    _check_ordered(y, lam, shape[2], g, -1, True)
+    ref = run_1d(y, lam, shape[2], g, axis=-1)
+    yr, gr = rows_view(y, -1), rows_view(g, -1)
+    check_batch(yr, lam_per_row(lam, len(yr), shape[2]), gr, rows_view(ref["x"], -1), rows_view(ref["gy"], -1),
+                gl_gpu=ref["gl"], lam_count=shape[1], lam_div=shape[2], label="slots %s" % (shape,))
