@@ -255,6 +255,18 @@ def main() -> int:
         with open(tpath) as f:
             traffic = json.load(f).get("traffic_bytes_per_launch")
 
+    # vector-ALU view of the forward kernel: a SIMD retires one wave64 VALU instruction per 4
+    # cycles; 256 CUs x 4 SIMDs at 2.4 GHz.  Instruction count from the committed counter run.
+    alu = None
+    vpath = os.path.join(ROOT, "profiles", "valu_tv1d_fwd_short_config3.json")
+    if os.path.exists(vpath):
+        with open(vpath) as f:
+            valu = json.load(f).get("sq_insts_valu")
+        peak_ips = 256 * 4 * 2.4e9 / 4.0
+        alu = {"kernel": "forward call", "valu_wave_instructions_per_launch": valu,
+               "achieved_per_s": valu / (fwd_ms * 1e-3), "peak_per_s": peak_ips,
+               "frac": valu / (fwd_ms * 1e-3) / peak_ips}
+
     out = {
         "metric": "TV-prox rows/s (fwd+bwd), 2^20 rows x len 32",
         "value": value,
@@ -282,6 +294,7 @@ def main() -> int:
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": fwd_gbs / HBM_PEAK_GBS,
                      "traffic": traffic, "launch_us": fwd_ms * 1e3,
                      "algorithmic_bytes_per_launch": fwd_bytes},
+        "valu_issue": alu,
         "roofline_bwd": {"kernel": "tv1d_bwd_short_kernel<32, SEG> + reduce_lambda_kernel",
                          "bound": "hbm", "achieved": bwd_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                          "frac": bwd_gbs / HBM_PEAK_GBS, "launch_us": bwd_ms * 1e3,
