@@ -150,3 +150,20 @@ def test_full_size_config3_sampled():
     xs, gs = xr.astype(np.float64), gr.astype(np.float64)
     _, gl_ref = oracle.prox1d_bwd_batch(gs, xs, lam_count=128, lam_div=32)
     np.testing.assert_allclose(out["gl"], gl_ref, rtol=1e-4, atol=1e-2)
+
+
+@pytest.mark.parametrize("scale", [1e-4, 1e3, 1e6])
+def test_input_scale(scale):
+    # prox(c y, c lam) = c prox(y, lam): the stopping rules are relative, so parity must hold at
+    # any magnitude (the tolerance 1e-4 (1 + max|y|) is checked on the rescaled problem)
+    rng = np.random.default_rng(46)
+    y = rng.normal(size=(300, 32)).astype(np.float32)
+    g = rng.normal(size=y.shape).astype(np.float32)
+    lam = (10 ** rng.uniform(-3, 1, size=300)).astype(np.float32)
+    ys, ls = (y * np.float32(scale)).astype(np.float32), (lam * np.float32(scale)).astype(np.float32)
+    out = run_1d(ys, ls, 1, g, want_info=True)
+    assert not np.any(out["info"] >> 18 & 1)                       # no row ran into the iteration cap
+    xr = oracle.prox1d_batch(ys.astype(np.float64), ls.astype(np.float64), lam_div=1)
+    err = np.abs(out["x"] - xr).max(1) / np.abs(ys).max(1)
+    assert err.max() <= 1e-5, err.max()                            # relative to the row's own scale
+    check_batch(y, lam, g, (out["x"] / np.float32(scale)).astype(np.float32), None, label="scale %g" % scale)
