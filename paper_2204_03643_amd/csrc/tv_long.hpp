@@ -113,16 +113,42 @@ __device__ __forceinline__ void chunk_store(float *__restrict__ base, int64_t of
         if (k0 + i < n) base[off + (int64_t)(k0 + i) * es] = v[i];
 }
 
+// v of the lane that a row-local DPP pattern names (0xB1 / 0x4E: quad_perm [1,0,3,2] / [2,3,0,1];
+// 0x141 / 0x140: mirror within 8 / 16 lanes).
+template <int CTRL>
+__device__ __forceinline__ float long_dpp(float v)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));
+}
+
+// Sum over the 64 lanes of a wave, the same total in every lane, in a fixed order: four
+// exchanges inside the 16-lane rows ride on the adds themselves (DPP), two cross the rows.
+__device__ __forceinline__ float wave_sum_all(float v)
+{
+    v += long_dpp<0xB1>(v);
+    v += long_dpp<0x4E>(v);
+    v += long_dpp<0x141>(v);
+    v += long_dpp<0x140>(v);
+    v += __shfl_xor(v, 16);
+    v += __shfl_xor(v, 32);
+    return v;
+}
+
 // Sums NV values over the T threads of each row; every thread of the row gets the totals.
 // Deterministic: fixed shuffle tree inside a wave, then a fixed-order sum over waves.
 template <int T, int G, bool COLS, int NV>
 __device__ __forceinline__ void row_sum(float (&v)[NV], float *red, int j, int tid)
 {
     using Mp = LongMap<T, G, COLS>;
+    if constexpr (Mp::RG == 1) {
 #pragma unroll
-    for (int off = 32; off >= Mp::RG; off >>= 1) {
+        for (int q = 0; q < NV; ++q) v[q] = wave_sum_all(v[q]);
+    } else {
 #pragma unroll
-        for (int q = 0; q < NV; ++q) v[q] += __shfl_xor(v[q], off);
+        for (int off = 32; off >= Mp::RG; off >>= 1) {
+#pragma unroll
+            for (int q = 0; q < NV; ++q) v[q] += __shfl_xor(v[q], off);
+        }
     }
     if (Mp::WPR == 1) return;
     const int wave = tid >> 6, lane = tid & 63;
@@ -147,10 +173,15 @@ template <int T, int G, bool COLS, int NV>
 __device__ __forceinline__ void row_sum_alt(float (&v)[NV], float *red, int j, int tid, int par)
 {
     using Mp = LongMap<T, G, COLS>;
+    if constexpr (Mp::RG == 1) {
 #pragma unroll
-    for (int off = 32; off >= Mp::RG; off >>= 1) {
+        for (int q = 0; q < NV; ++q) v[q] = wave_sum_all(v[q]);
+    } else {
 #pragma unroll
-        for (int q = 0; q < NV; ++q) v[q] += __shfl_xor(v[q], off);
+        for (int off = 32; off >= Mp::RG; off >>= 1) {
+#pragma unroll
+            for (int q = 0; q < NV; ++q) v[q] += __shfl_xor(v[q], off);
+        }
     }
     if (Mp::WPR == 1) return;
     float *r = red + par * (4 * Mp::NW * Mp::RG);
@@ -472,7 +503,7 @@ __global__ __launch_bounds__(T *G) void tv1d_fwd_long_kernel(FwdParams p)
         // ---- separator system (normalised to unit diagonal) and PCR
         float ea = 0.f, ec = 0.f, er = 0.f;
         if (!bsep) {
-            const float inv = 1.0f / (2.0f - c_delta - alphan);
+            const float inv = __builtin_amdgcn_rcpf(2.0f - c_delta - alphan);
             ea = -c_beta * inv;
             ec = -betan * inv;
             er = (g[C - 1] + pl + p0n) * inv;
@@ -488,7 +519,7 @@ __global__ __launch_bounds__(T *G) void tv1d_fwd_long_kernel(FwdParams p)
                 float la = 0.f, lc = 0.f, lr = 0.f, ra = 0.f, rc = 0.f, rr = 0.f;
                 if (t - s >= 0) { la = TV_PB(cur, 0, t - s); lc = TV_PB(cur, 1, t - s); lr = TV_PB(cur, 2, t - s); }
                 if (t + s < T) { ra = TV_PB(cur, 0, t + s); rc = TV_PB(cur, 1, t + s); rr = TV_PB(cur, 2, t + s); }
-                const float inv = 1.0f / (1.0f - ea * lc - ec * ra);
+                const float inv = __builtin_amdgcn_rcpf(1.0f - ea * lc - ec * ra);
                 er = (er - ea * lr - ec * rr) * inv;
                 const float na = -ea * la * inv, nc = -ec * rc * inv;
                 ea = na; ec = nc;
@@ -533,13 +564,14 @@ __global__ __launch_bounds__(T *G) void tv1d_fwd_long_kernel(FwdParams p)
         bool clipped = false, changed = false;
         for (int ls = 0;; ++ls) {
             float v[4] = {0.f, decp, 0.f, 0.f};
+            bool cl = false, ch = false;
 #pragma unroll
             for (int i = 0; i < C; ++i) {
                 const float l = TV_LK(i);
                 const float tt = fmaf(-alpha, w[i], u[i]);
                 const float cc = __builtin_amdgcn_fmed3f(tt, -l, l);
-                if (cc != tt) v[2] += 1.f;
-                if (cc != u[i]) v[3] += 1.f;
+                cl |= (cc != tt);
+                ch |= (cc != u[i]);
                 uc[i] = cc;
             }
             TV_EX(0, t) = uc[C - 1];
@@ -553,6 +585,8 @@ __global__ __launch_bounds__(T *G) void tv1d_fwd_long_kernel(FwdParams p)
                 const float xc = y[i] + uc[i] - (i > 0 ? uc[i - 1] : ucleft);
                 v[0] = fmaf(xc, xc, v[0]);
             }
+            v[2] = cl ? 1.f : 0.f;
+            v[3] = ch ? 1.f : 0.f;
             row_sum_alt<T, G, MCOLS, 4>(v, sm.red, j, tid, par);
             par ^= 1;
             fc = 0.5f * v[0]; dec = v[1]; clipped = v[2] > 0.f; changed = v[3] > 0.f;
