@@ -1,8 +1,8 @@
 // Kernels for rows longer than 32 samples: T threads share one row, C contiguous samples
 // (and duals) per thread, G rows per workgroup.
 //
-// T = 64 keeps a row inside one wavefront (G rows per workgroup); T = 256 and T = 1024 put
-// one row on a whole workgroup.  The row, its dual and the Newton direction stay in
+// T = 32 and T = 64 keep a row inside one wavefront (G rows per workgroup, two per wave at
+// T = 32); T = 256, 512 and 1024 put one row on a whole workgroup.  The row, its dual and the Newton direction stay in
 // registers for the entire solve; only chunk edges, the interface system and row-wide
 // reductions go through LDS.
 //
@@ -30,12 +30,13 @@ struct LongMap {
     static constexpr int NT = T * G;
     static constexpr int NW = NT / 64;
     static constexpr int RG = COLS ? G : 1;            // rows interleaved inside a wave
-    static constexpr int WPR = COLS ? NW : T / 64;     // waves holding parts of one row
+    static constexpr int WPR = COLS ? NW : (T + 63) / 64;   // waves holding parts of one row
+    static constexpr int LANES = T < 64 ? T : 64;      // ROWS mapping: lanes of a wave on one row
     // A row that lives in exactly one wave (which holds nothing else) never has to wait for
     // the other waves of its workgroup: its LDS slices are its own, every barrier becomes a
     // wave-level fence and every workgroup vote a wave vote, and the wave leaves when its
     // row is done.
-    static constexpr bool PRIVATE = !COLS && T == 64;
+    static constexpr bool PRIVATE = !COLS && T <= 64;
     // One row per workgroup: row-wide flags are workgroup-uniform.
     static constexpr bool SOLO = G == 1;
     __device__ static __forceinline__ int row_of(int tid) { return COLS ? tid % G : tid / T; }
@@ -123,6 +124,7 @@ __device__ __forceinline__ float long_dpp(float v)
 
 // Sum over the 64 lanes of a wave, the same total in every lane, in a fixed order: four
 // exchanges inside the 16-lane rows ride on the adds themselves (DPP), two cross the rows.
+template <int LANES = 64>
 __device__ __forceinline__ float wave_sum_all(float v)
 {
     v += long_dpp<0xB1>(v);
@@ -130,7 +132,7 @@ __device__ __forceinline__ float wave_sum_all(float v)
     v += long_dpp<0x141>(v);
     v += long_dpp<0x140>(v);
     v += __shfl_xor(v, 16);
-    v += __shfl_xor(v, 32);
+    if (LANES > 32) v += __shfl_xor(v, 32);           // LANES = 32: two rows per wave, kept apart
     return v;
 }
 
@@ -142,7 +144,7 @@ __device__ __forceinline__ void row_sum(float (&v)[NV], float *red, int j, int t
     using Mp = LongMap<T, G, COLS>;
     if constexpr (Mp::RG == 1) {
 #pragma unroll
-        for (int q = 0; q < NV; ++q) v[q] = wave_sum_all(v[q]);
+        for (int q = 0; q < NV; ++q) v[q] = wave_sum_all<Mp::LANES>(v[q]);
     } else {
 #pragma unroll
         for (int off = 32; off >= Mp::RG; off >>= 1) {
@@ -175,7 +177,7 @@ __device__ __forceinline__ void row_sum_alt(float (&v)[NV], float *red, int j, i
     using Mp = LongMap<T, G, COLS>;
     if constexpr (Mp::RG == 1) {
 #pragma unroll
-        for (int q = 0; q < NV; ++q) v[q] = wave_sum_all(v[q]);
+        for (int q = 0; q < NV; ++q) v[q] = wave_sum_all<Mp::LANES>(v[q]);
     } else {
 #pragma unroll
         for (int off = 32; off >= Mp::RG; off >>= 1) {
@@ -206,7 +208,7 @@ __device__ __forceinline__ void row_max(float (&v)[1], float *red, int j, int ti
 {
     using Mp = LongMap<T, G, COLS>;
 #pragma unroll
-    for (int off = 32; off >= Mp::RG; off >>= 1) v[0] = fmaxf(v[0], __shfl_xor(v[0], off));
+    for (int off = (COLS ? 32 : Mp::LANES / 2); off >= Mp::RG; off >>= 1) v[0] = fmaxf(v[0], __shfl_xor(v[0], off));
     if (Mp::WPR == 1) return;
     const int wave = tid >> 6, lane = tid & 63;
     __syncthreads();
@@ -235,30 +237,31 @@ __device__ __forceinline__ void seg_scan(bool closed, float s, float n, float *b
         // shuffles (no LDS, no barrier), then combine the waves' totals, which takes one
         // barrier.  combine(A earlier, B later) = B if B is closed, else A with B's open part
         // added (ADD) or A unchanged (copy).
-        const int lane = t & 63;
+        constexpr int LN = Mp::LANES;                     // lanes of the wave that hold this row
+        const int lane = t & (LN - 1);
         float f = closed ? 1.f : 0.f;
 #pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-            const float of = DIR > 0 ? __shfl_up(f, d) : __shfl_down(f, d);
-            const float os = DIR > 0 ? __shfl_up(s, d) : __shfl_down(s, d);
-            const float on = DIR > 0 ? __shfl_up(n, d) : __shfl_down(n, d);
-            const bool has = DIR > 0 ? (lane >= d) : (lane + d < 64);
+        for (int d = 1; d < LN; d <<= 1) {
+            const float of = DIR > 0 ? __shfl_up(f, d, LN) : __shfl_down(f, d, LN);
+            const float os = DIR > 0 ? __shfl_up(s, d, LN) : __shfl_down(s, d, LN);
+            const float on = DIR > 0 ? __shfl_up(n, d, LN) : __shfl_down(n, d, LN);
+            const bool has = DIR > 0 ? (lane >= d) : (lane + d < LN);
             if (has && f == 0.f) {
                 if (ADD) { s += os; n += on; } else { s = os; n = on; }
                 f = of;
             }
         }
         // what arrives at this lane from inside its wave: the inclusive value of the lane before
-        float ef = DIR > 0 ? __shfl_up(f, 1) : __shfl_down(f, 1);
-        float es = DIR > 0 ? __shfl_up(s, 1) : __shfl_down(s, 1);
-        float en = DIR > 0 ? __shfl_up(n, 1) : __shfl_down(n, 1);
-        const bool edge = DIR > 0 ? (lane == 0) : (lane == 63);
+        float ef = DIR > 0 ? __shfl_up(f, 1, LN) : __shfl_down(f, 1, LN);
+        float es = DIR > 0 ? __shfl_up(s, 1, LN) : __shfl_down(s, 1, LN);
+        float en = DIR > 0 ? __shfl_up(n, 1, LN) : __shfl_down(n, 1, LN);
+        const bool edge = DIR > 0 ? (lane == 0) : (lane == LN - 1);
         if (edge) { ef = 0.f; es = 0.f; en = 0.f; }
         if constexpr (T > 64) {
             constexpr int NWR = T / 64;                       // waves per row
             float *tot = buf + (DIR > 0 ? 0 : 3 * G * NWR);   // the two directions never share
             const int w = t >> 6;
-            const bool lastlane = DIR > 0 ? (lane == 63) : (lane == 0);
+            const bool lastlane = DIR > 0 ? (lane == LN - 1) : (lane == 0);
             if (lastlane) {
                 tot[(0 * G + j) * NWR + w] = f; tot[(1 * G + j) * NWR + w] = s; tot[(2 * G + j) * NWR + w] = n;
             }
@@ -890,7 +893,8 @@ inline hipError_t launch_bwd_long_t(const BwdParams &p, hipStream_t s)
             if (n <= 8192) return FN<1024, 8, 1, true>(p, s);                             \
             return FN<1024, 16, 1, true>(p, s);                                           \
         }                                                                                 \
-        if (n <= 128) return FN<64, 2, 4, false>(p, s);                                   \
+        if (n <= 64) return FN<32, 2, 8, false>(p, s);                                    \
+        if (n <= 128) return FN<32, 4, 8, false>(p, s);                                   \
         if (n <= 256) return FN<64, 4, 4, false>(p, s);                                   \
         if (n <= 512) return FN<64, 8, 4, false>(p, s);                                   \
         if (n <= 1024) return FN<64, 16, 4, false>(p, s);                                 \
