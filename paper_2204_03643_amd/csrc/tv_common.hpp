@@ -86,6 +86,7 @@ struct FwdParams {
     const float *y;        // input rows
     const float *addend;   // optional: the prox input is y + addend (Dykstra correction term)
     float       *x;        // output rows
+    float       *x2;       // optional second copy of the output (same layout)
     float       *resid;    // optional: receives (y + addend) - x  (next correction term)
     const float *lam;
     int32_t     *info;     // optional per-row info word

@@ -671,7 +671,11 @@ __global__ __launch_bounds__(T *G) void tv1d_fwd_long_kernel(FwdParams p)
         for (int i = 0; i < C; ++i) tile[j * TILE_PITCH + t * (C + 1) + i] = xs[i];
         __syncthreads();
         for (int k = xk0; k < T * C; k += T)
-            if (xrow < p.L.n_rows && k < n) p.x[xoff + (int64_t)k * es] = tile[xj * TILE_PITCH + k + k / C];
+            if (xrow < p.L.n_rows && k < n) {
+                const float v = tile[xj * TILE_PITCH + k + k / C];
+                p.x[xoff + (int64_t)k * es] = v;
+                if (p.x2) p.x2[xoff + (int64_t)k * es] = v;
+            }
         if (p.resid) {
             __syncthreads();
 #pragma unroll
@@ -683,6 +687,7 @@ __global__ __launch_bounds__(T *G) void tv1d_fwd_long_kernel(FwdParams p)
         }
     } else {
         chunk_store<C>(p.x, off, es, k0, n, rvalid, xs);
+        if (p.x2) chunk_store<C>(p.x2, off, es, k0, n, rvalid, xs);
         if (p.resid) {
 #pragma unroll
             for (int i = 0; i < C; ++i) y[i] -= xs[i];

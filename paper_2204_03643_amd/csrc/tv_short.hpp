@@ -510,12 +510,14 @@ __global__ __launch_bounds__(kShortBlock) TV_FWD_ATTR void tv1d_fwd_short_kernel
         TileRegs<NMAX> t;
         rows_to_tile<NMAX>(xs, tile, lane, t);
         tile_put<NMAX>(p.x, p.tm, r0, p.L.n_rows, lane, t);
+        if (p.x2) tile_put<NMAX>(p.x2, p.tm, r0, p.L.n_rows, lane, t);
         if (want_resid) {
             rows_to_tile<NMAX>(rs, tile, lane, t);
             tile_put<NMAX>(p.resid, p.tm, r0, p.L.n_rows, lane, t);
         }
     } else {
         row_store_strided<NMAX, FULL>(p.x, off, p.L.elem_stride, n, valid, xs);
+        if (p.x2) row_store_strided<NMAX, FULL>(p.x2, off, p.L.elem_stride, n, valid, xs);
         if (want_resid) row_store_strided<NMAX, FULL>(p.resid, off, p.L.elem_stride, n, valid, rs);
     }
     if (p.info && valid) p.info[row] = sv.steps | sv.flags;

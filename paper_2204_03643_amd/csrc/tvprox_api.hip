@@ -304,10 +304,10 @@ bool order_applies(const tvk::TileMap &tm)
 
 int run_fwd(const float *y, const float *addend, float *x, float *resid, int32_t *info,
             uint2 *seg, uint32_t *order_ws, const tv_rows &r, const tv_lambda &l, int64_t n_rows,
-            hipStream_t s)
+            hipStream_t s, float *x2 = nullptr)
 {
     FwdParams p;
-    p.y = y; p.addend = addend; p.x = x; p.resid = resid; p.lam = l.lam; p.info = info;
+    p.y = y; p.addend = addend; p.x = x; p.x2 = x2; p.resid = resid; p.lam = l.lam; p.info = info;
     p.seg = seg; p.order = nullptr;
     p.L = make_layout(r, l, n_rows);
     p.tm = make_tile_map(l, n_rows);
@@ -645,13 +645,11 @@ int tv2d_prox_fwd(const float *y, float *x, int64_t planes, int64_t H, int64_t W
                      planes * H, stream);
         if (st != TV_OK) return st;
         // Y' = proxCols(Z + Q);  Q <- (Z + Q) - Y'
+        // the last pass writes its output twice: where the reverse sweep will look for it, and to x
         st = run_fwd(Z, k == 0 ? nullptr : Q, Yn, last ? nullptr : Q, nullptr, nullptr, nullptr, rcol, lcol,
-                     planes * W, stream);
+                     planes * W, stream, last ? x : nullptr);
         if (st != TV_OK) return st;
     }
-    if (hipMemcpyAsync(x, saved(2 * sweeps - 1), (size_t)(planes * H * W) * sizeof(float),
-                       hipMemcpyDeviceToDevice, stream) != hipSuccess)
-        return TV_ERR_HIP;
     return TV_OK;
 }
 
