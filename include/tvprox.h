@@ -151,7 +151,9 @@ int tv1d_prox_bwd_seg(const float *g_up, const uint64_t *seg, float *grad_y, flo
  * 2D anisotropic TV prox on `planes` images of H x W (row-major, contiguous) by
  * `sweeps` iterations of paper Alg. 1; plane p uses lam[p % count] (lam.div is
  * ignored).  ws keeps every pass's output (2*sweeps tensors) plus two scratch
- * tensors, and must be handed unchanged to tv2d_prox_bwd.  x must not alias y.
+ * tensors (and, for planes of at most 32 x 32, every pass's segment codes, which is what
+ * the backward call then reads), and must be handed unchanged to tv2d_prox_bwd.  x must
+ * not alias y.
  */
 size_t tv2d_workspace_bytes(int64_t planes, int64_t H, int64_t W, int sweeps);
 int tv2d_prox_fwd(const float *y, float *x, int64_t planes, int64_t H, int64_t W,

@@ -145,7 +145,9 @@ int launch_bwd_short(const BwdParams &p, bool packed_ok, hipStream_t s)
 template <int NMAX>
 int launch_bwd_short(const BwdParams &p, bool packed_ok, hipStream_t s)
 {
-    if (p.seg) return launch_bwd_short<NMAX, false, true>(p, packed_ok, s);   // never with sub
+    if (p.seg)
+        return p.sub ? launch_bwd_short<NMAX, true, true>(p, packed_ok, s)
+                     : launch_bwd_short<NMAX, false, true>(p, packed_ok, s);
     return p.sub ? launch_bwd_short<NMAX, true, false>(p, packed_ok, s)
                  : launch_bwd_short<NMAX, false, false>(p, packed_ok, s);
 }
@@ -595,8 +597,12 @@ int tv1d_prox_bwd_seg(const float *g_up, const uint64_t *seg, float *grad_y, flo
 
 // ---- 2D: proximal Dykstra (paper Alg. 1) ----------------------------------------------
 
+// Planes whose rows and columns both fit the row-per-lane kernels also keep every pass's
+// segment codes (8 bytes per row), which is all the reverse sweep reads of the pass outputs.
+static bool small_planes(int64_t H, int64_t W) { return H <= TV_SEG_MAX_LENGTH && W <= TV_SEG_MAX_LENGTH; }
+
 static int check_2d(int64_t planes, int64_t H, int64_t W, int sweeps, size_t *tensor_bytes,
-                    size_t *partial_bytes)
+                    size_t *partial_bytes, size_t *code_bytes)
 {
     if (planes < 0 || H < 1 || W < 1 || sweeps < 1 || sweeps > 4096) return TV_ERR_SHAPE;
     if (planes > kMaxRows || H > kMaxRows || W > kMaxRows) return TV_ERR_SHAPE;
@@ -605,32 +611,36 @@ static int check_2d(int64_t planes, int64_t H, int64_t W, int sweeps, size_t *te
     *tensor_bytes = align16((size_t)(planes * H * W) * sizeof(float));
     const int64_t mr = planes * (H > W ? H : W);
     *partial_bytes = align16((size_t)mr * sizeof(float));
+    *code_bytes = small_planes(H, W) ? align16((size_t)mr * sizeof(uint64_t)) : 0;   // per pass
     return TV_OK;
 }
 
 size_t tv2d_workspace_bytes(int64_t planes, int64_t H, int64_t W, int sweeps)
 {
-    size_t tb, pb;
-    if (check_2d(planes, H, W, sweeps, &tb, &pb) != TV_OK) return 0;
-    return tb * (size_t)(2 * sweeps + 2) + pb;
+    size_t tb, pb, cb;
+    if (check_2d(planes, H, W, sweeps, &tb, &pb, &cb) != TV_OK) return 0;
+    return tb * (size_t)(2 * sweeps + 2) + pb + cb * (size_t)(2 * sweeps);
 }
 
 int tv2d_prox_fwd(const float *y, float *x, int64_t planes, int64_t H, int64_t W, tv_lambda lam,
                   int sweeps, void *ws, size_t ws_bytes, hipStream_t stream)
 {
     if (lam.count < 1 || lam.count > kMaxRows) return TV_ERR_LAMBDA;
-    size_t tb, pb;
-    int st = check_2d(planes, H, W, sweeps, &tb, &pb);
+    size_t tb, pb, cb;
+    int st = check_2d(planes, H, W, sweeps, &tb, &pb, &cb);
     if (st != TV_OK) return st;
     if (planes == 0) return TV_OK;
     if (!y || !x || !lam.lam) return TV_ERR_NULL;
     if (H > TV_MAX_LENGTH || W > TV_MAX_LENGTH) return TV_ERR_UNSUPPORTED;
-    if (!ws || !aligned16(ws) || ws_bytes < tb * (size_t)(2 * sweeps + 2) + pb)
+    if (!ws || !aligned16(ws) || ws_bytes < tb * (size_t)(2 * sweeps + 2) + pb + cb * (size_t)(2 * sweeps))
         return TV_ERR_WORKSPACE;
 
     char *base = (char *)ws;
     auto saved = [&](int i) { return (float *)(base + tb * (size_t)i); };
     float *P = saved(2 * sweeps), *Q = saved(2 * sweeps + 1);
+    auto codes = [&](int pass) -> uint2 * {
+        return cb ? (uint2 *)(base + tb * (size_t)(2 * sweeps + 2) + pb + cb * (size_t)pass) : nullptr;
+    };
     const tv_rows rrow = {planes, H * W, H, W, W, 1};
     const tv_rows rcol = {planes, H * W, W, 1, H, W};
     const tv_lambda lrow = {lam.lam, lam.count, H};
@@ -641,13 +651,13 @@ int tv2d_prox_fwd(const float *y, float *x, int64_t planes, int64_t H, int64_t W
         const float *Yk = (k == 0) ? y : saved(2 * k - 1);
         float *Z = saved(2 * k), *Yn = saved(2 * k + 1);
         // Z = proxRows(Y + P);  P <- (Y + P) - Z      (P = 0 in the first sweep)
-        st = run_fwd(Yk, k == 0 ? nullptr : P, Z, last ? nullptr : P, nullptr, nullptr, nullptr, rrow, lrow,
-                     planes * H, stream);
+        st = run_fwd(Yk, k == 0 ? nullptr : P, Z, last ? nullptr : P, nullptr, codes(2 * k), nullptr, rrow,
+                     lrow, planes * H, stream);
         if (st != TV_OK) return st;
         // Y' = proxCols(Z + Q);  Q <- (Z + Q) - Y'
         // the last pass writes its output twice: where the reverse sweep will look for it, and to x
-        st = run_fwd(Z, k == 0 ? nullptr : Q, Yn, last ? nullptr : Q, nullptr, nullptr, nullptr, rcol, lcol,
-                     planes * W, stream, last ? x : nullptr);
+        st = run_fwd(Z, k == 0 ? nullptr : Q, Yn, last ? nullptr : Q, nullptr, codes(2 * k + 1), nullptr, rcol,
+                     lcol, planes * W, stream, last ? x : nullptr);
         if (st != TV_OK) return st;
     }
     return TV_OK;
@@ -658,21 +668,24 @@ int tv2d_prox_bwd(const float *g_up, float *grad_y, float *grad_lam, int64_t pla
                   hipStream_t stream)
 {
     if (lam.count < 1 || lam.count > kMaxRows) return TV_ERR_LAMBDA;
-    size_t tb, pb;
-    int st = check_2d(planes, H, W, sweeps, &tb, &pb);
+    size_t tb, pb, cb;
+    int st = check_2d(planes, H, W, sweeps, &tb, &pb, &cb);
     if (st != TV_OK) return st;
     if (planes == 0) {
         return grad_lam ? zero_floats(grad_lam, lam.count, stream) : TV_OK;
     }
     if (!g_up || !grad_y) return TV_ERR_NULL;
     if (H > TV_MAX_LENGTH || W > TV_MAX_LENGTH) return TV_ERR_UNSUPPORTED;
-    if (!ws || !aligned16(ws) || ws_bytes < tb * (size_t)(2 * sweeps + 2) + pb)
+    if (!ws || !aligned16(ws) || ws_bytes < tb * (size_t)(2 * sweeps + 2) + pb + cb * (size_t)(2 * sweeps))
         return TV_ERR_WORKSPACE;
 
     char *base = (char *)ws;
     auto saved = [&](int i) { return (float *)(base + tb * (size_t)i); };
     float *Ab = saved(2 * sweeps), *Bb = saved(2 * sweeps + 1);
     float *partial = (float *)(base + tb * (size_t)(2 * sweeps + 2));
+    auto codes = [&](int pass) -> const uint2 * {
+        return cb ? (const uint2 *)(base + tb * (size_t)(2 * sweeps + 2) + pb + cb * (size_t)pass) : nullptr;
+    };
     const tv_rows rrow = {planes, H * W, H, W, W, 1};
     const tv_rows rcol = {planes, H * W, W, 1, H, W};
     const tv_lambda lrow = {lam.lam, lam.count, H};
@@ -685,12 +698,12 @@ int tv2d_prox_bwd(const float *g_up, float *grad_y, float *grad_lam, int64_t pla
     int acc = 0;
     for (int k = sweeps - 1; k >= 0; --k) {
         const bool first = (k == sweeps - 1);
-        st = run_bwd(first ? g_up : Ab, first ? nullptr : Bb, saved(2 * k + 1), nullptr, Bb, grad_lam, acc,
-                     rcol, lcol, planes * W, partial, stream);
+        st = run_bwd(first ? g_up : Ab, first ? nullptr : Bb, cb ? nullptr : saved(2 * k + 1), codes(2 * k + 1),
+                     Bb, grad_lam, acc, rcol, lcol, planes * W, partial, stream);
         if (st != TV_OK) return st;
         acc = 1;
-        st = run_bwd(Bb, first ? nullptr : Ab, saved(2 * k), nullptr, k == 0 ? grad_y : Ab, grad_lam, acc,
-                     rrow, lrow, planes * H, partial, stream);
+        st = run_bwd(Bb, first ? nullptr : Ab, cb ? nullptr : saved(2 * k), codes(2 * k), k == 0 ? grad_y : Ab,
+                     grad_lam, acc, rrow, lrow, planes * H, partial, stream);
         if (st != TV_OK) return st;
     }
     return TV_OK;
