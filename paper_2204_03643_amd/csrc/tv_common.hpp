@@ -32,6 +32,7 @@ struct Layout {
     int32_t  n;            // row length
     uint32_t lam_count;
     uint32_t lam_div;
+    uint32_t stream;       // tensors too large to stay in cache: use non-temporal accesses
 };
 
 // Which 64 rows a wave of the row-per-lane forward kernel works on.  Row t of a tile is

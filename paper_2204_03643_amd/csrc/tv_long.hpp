@@ -266,14 +266,14 @@ __device__ __forceinline__ void seg_scan(bool closed, float s, float n, float *b
                 tot[(0 * G + j) * NWR + w] = f; tot[(1 * G + j) * NWR + w] = s; tot[(2 * G + j) * NWR + w] = n;
             }
             __syncthreads();
-            float af = 0.f, as = 0.f, an = 0.f;               // waves before this one, in scan order
+            float as = 0.f, an = 0.f;                         // waves before this one, in scan order
             for (int q = 0; q < NWR; ++q) {
                 const int ww = DIR > 0 ? q : NWR - 1 - q;
                 const bool before = DIR > 0 ? (ww < w) : (ww > w);
                 if (!before) continue;
                 const float bf = tot[(0 * G + j) * NWR + ww], bs = tot[(1 * G + j) * NWR + ww],
                             bn = tot[(2 * G + j) * NWR + ww];
-                if (bf != 0.f) { af = 1.f; as = bs; an = bn; }
+                if (bf != 0.f) { as = bs; an = bn; }
                 else if (ADD) { as += bs; an += bn; }
             }
             // combine(waves before, lanes before)

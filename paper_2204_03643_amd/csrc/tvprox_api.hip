@@ -73,6 +73,8 @@ Layout make_layout(const tv_rows &r, const tv_lambda &l, int64_t n_rows)
     L.n = (int32_t)r.length;
     L.lam_count = (uint32_t)l.count;
     L.lam_div = (uint32_t)l.div;
+    // a tensor of 32 MiB or more does not survive in the caches until it is touched again
+    L.stream = (n_rows * r.length >= ((int64_t)32 << 20) / 4) ? 1u : 0u;
     return L;
 }
 
