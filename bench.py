@@ -50,45 +50,76 @@ def cpu_baseline(sample_rows: int):
         oracle.prox1d_bwd_batch(g64, x, lam_count=128, axis=-1, lam_div=32)
         dt += time.perf_counter() - t0
         rows += y.size // 32
-    return {"value": rows / dt, "unit": "rows/s", "cores": oracle.num_threads(), "kind": "oracle",
+    cores = oracle.num_threads()
+    # the same oracle on one thread, on the last chunk only
+    oracle.set_num_threads(1)
+    t0 = time.perf_counter()
+    x = oracle.prox1d_batch(y64, lam64, axis=-1, lam_div=32)
+    oracle.prox1d_bwd_batch(g64, x, lam_count=128, axis=-1, lam_div=32)
+    dt1 = time.perf_counter() - t0
+    oracle.set_num_threads(cores)
+    return {"value": rows / dt, "unit": "rows/s", "cores": cores, "kind": "oracle",
             "sample": "%d rows x 32 drawn like the workload, in %d chunks (fwd+bwd, fp64, OpenMP "
-                      "over rows), %.2f s of wall time" % (rows, n_chunks, dt)}
+                      "over rows), %.2f s of wall time" % (rows, n_chunks, dt),
+            "single_thread_rows_per_s": (y.size // 32) / dt1}
 
 
-def other_workloads(dev, reps: int = 5):
-    """fwd / bwd times of the other four workloads (context beside the headline number)."""
+ROTATE_BYTES = 640 << 20        # distinct buffers cycled through so that none is still cached
+
+
+def other_workloads(dev, reps: int = 25):
+    """fwd / bwd times of the other four workloads (context beside the headline number).
+
+    Each call is timed twice: `*_us` on one set of buffers over and over (tensors of up to a few
+    tens of MiB then live in the 256 MB last-level cache), and `*_us_rotated` cycling through
+    enough copies of the buffers that every call finds its tensors in HBM only.  Median of
+    `reps` timed calls each; `*_min` is the fastest."""
+    import numpy as np
     import torch
 
     import paper_2204_03643_amd as tv
     import workloads
 
-    def timed(fn):
-        for _ in range(2):
-            fn()
+    def timed(fn, n_sets=1):
+        for k in range(max(2, min(n_sets, 4))):
+            fn(k % n_sets)
         torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(reps):
-            fn()
-        e1.record()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
+        ev[0].record()
+        for k in range(reps):
+            fn(k % n_sets)
+            ev[k + 1].record()
         torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / reps * 1e3          # microseconds
+        t = [ev[k].elapsed_time(ev[k + 1]) * 1e3 for k in range(reps)]      # microseconds
+        return float(np.median(t)), float(min(t))
+
+    def n_copies(bytes_per_set):
+        return int(max(2, min(64, -(-ROTATE_BYTES // max(1, bytes_per_set)))))
 
     def one_d(y, lam, g, axis, lam_div):
-        import numpy as np
-        yt, lt, gt = (torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(dev)
+        y0, lt, g0 = (torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(dev)
                       for a in (y, np.asarray(lam).ravel(), g))
-        xt, gy, gl = torch.empty_like(yt), torch.empty_like(yt), torch.empty_like(lt)
+        R = n_copies(4 * y0.numel() * 4)
+        yt, gt = [y0] + [y0.clone() for _ in range(R - 1)], [g0] + [g0.clone() for _ in range(R - 1)]
+        xt, gy = [torch.empty_like(y0) for _ in range(R)], [torch.empty_like(y0) for _ in range(R)]
+        gl = torch.empty_like(lt)
         rows = tv.rows_along(y.shape, axis)
         L = tv.tv_lambda(lt.data_ptr(), lt.numel(), lam_div)
         wsb = tv.tv1d_bwd_workspace_bytes(rows, L)
         ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device=dev)
-        tf = timed(lambda: tv.tv1d_prox_fwd(yt, xt, rows, L))
-        tb = timed(lambda: tv.tv1d_prox_bwd(gt, xt, gy, gl, rows, L, ws, wsb))
+        fwd = lambda k: tv.tv1d_prox_fwd(yt[k], xt[k], rows, L)
+        bwd = lambda k: tv.tv1d_prox_bwd(gt[k], xt[k], gy[k], gl, rows, L, ws, wsb)
+        for k in range(R):
+            fwd(k)                                  # every x[k] holds a solution for bwd
+        (tf, tf_min), (tb, tb_min) = timed(fwd), timed(bwd)
+        (rf, _), (rb, _) = timed(fwd, R), timed(bwd, R)
         n_rows = rows.n_outer * rows.n_inner
         return {"rows": n_rows, "length": rows.length, "fwd_us": tf, "bwd_us": tb,
+                "fwd_us_min": tf_min, "bwd_us_min": tb_min,
+                "fwd_us_rotated": rf, "bwd_us_rotated": rb, "buffer_sets": R,
                 "rows_per_s": n_rows / ((tf + tb) * 1e-6),
                 "effective_gbs": 20 * y.size / ((tf + tb) * 1e-6) / 1e9,
+                "effective_gbs_rotated": 20 * y.size / ((rf + rb) * 1e-6) / 1e9,
                 "frac_of_hbm_peak": 20 * y.size / ((tf + tb) * 1e-6) / 1e9 / HBM_PEAK_GBS}
 
     def two_d(y, lam, g, sweeps):
@@ -99,9 +130,11 @@ def other_workloads(dev, reps: int = 5):
         L = tv.tv_lambda(lt.data_ptr(), lt.numel(), 1)
         wsb = tv.tv2d_workspace_bytes(planes, H, W, sweeps)
         ws = torch.empty(wsb, dtype=torch.uint8, device=dev)
-        tf = timed(lambda: tv.tv2d_prox_fwd(yt, xt, planes, H, W, L, sweeps, ws, wsb))
-        tb = timed(lambda: tv.tv2d_prox_bwd(gt, gy, gl, planes, H, W, L, sweeps, ws, wsb))
+        # one set of buffers (the workspace of K = 10 on workload 4 alone is 0.5 GB)
+        tf, tf_min = timed(lambda k: tv.tv2d_prox_fwd(yt, xt, planes, H, W, L, sweeps, ws, wsb))
+        tb, tb_min = timed(lambda k: tv.tv2d_prox_bwd(gt, gy, gl, planes, H, W, L, sweeps, ws, wsb))
         return {"planes": planes, "H": H, "W": W, "sweeps": sweeps, "fwd_us": tf, "bwd_us": tb,
+                "fwd_us_min": tf_min, "bwd_us_min": tb_min,
                 "images_per_s": planes / ((tf + tb) * 1e-6)}
 
     out = {}
@@ -133,7 +166,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=500)
     ap.add_argument("--warmup", type=int, default=200)     # ~30 ms: lets the clocks settle
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-rows", type=int, default=1 << 23)
+    ap.add_argument("--cpu-sample-rows", type=int, default=1 << 25)
     ap.add_argument("--headline-only", action="store_true", help="skip the other four workloads")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="run fwd, bwd and a plain copy of the same tensor three times each and "
@@ -229,8 +262,9 @@ def main() -> int:
         print("bench.py: graph replays and eager steps disagree", file=sys.stderr)
         return 1
 
-    fwd_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in events]))
-    bwd_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in events]))   # bwd kernel + lam reduction
+    f_all = [e[0].elapsed_time(e[1]) for e in events]
+    b_all = [e[1].elapsed_time(e[2]) for e in events]                    # bwd kernel + lam reduction
+    fwd_ms, bwd_ms = float(np.mean(f_all)), float(np.mean(b_all))
     ms_per_step = wall * 1e3 / args.steps
     value = n_rows * args.steps / wall
 
@@ -293,11 +327,15 @@ def main() -> int:
         "roofline": {"kernel": "tv1d_fwd_short_kernel<32>", "bound": "hbm", "achieved": fwd_gbs,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": fwd_gbs / HBM_PEAK_GBS,
                      "traffic": traffic, "launch_us": fwd_ms * 1e3,
+                     "launch_us_median": float(np.median(f_all)) * 1e3,
+                     "launch_us_min": float(min(f_all)) * 1e3,
                      "algorithmic_bytes_per_launch": fwd_bytes},
         "valu_issue": alu,
         "roofline_bwd": {"kernel": "tv1d_bwd_short_kernel<32, SEG> + reduce_lambda_kernel",
                          "bound": "hbm", "achieved": bwd_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                          "frac": bwd_gbs / HBM_PEAK_GBS, "launch_us": bwd_ms * 1e3,
+                         "launch_us_median": float(np.median(b_all)) * 1e3,
+                         "launch_us_min": float(min(b_all)) * 1e3,
                          "algorithmic_bytes_per_launch": bwd_seg_bytes,
                          "note": "bytes of this variant: g_up + grad_y + 12 B/row (code, dL/dlam term)"},
         "plain_pair": {"calls": "tv1d_prox_fwd + tv1d_prox_bwd (backward reads x)",

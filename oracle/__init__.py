@@ -58,6 +58,8 @@ def _load():
         lib.tvo_prox2d_bwd.restype = None
         lib.tvo_num_threads.argtypes = []
         lib.tvo_num_threads.restype = ctypes.c_int
+        lib.tvo_set_num_threads.argtypes = [ctypes.c_int]
+        lib.tvo_set_num_threads.restype = None
         _lib = lib
     return _lib
 
@@ -72,6 +74,11 @@ def _c64(a) -> np.ndarray:
 
 def num_threads() -> int:
     return int(_load().tvo_num_threads())
+
+
+def set_num_threads(n: int) -> None:
+    """Threads the batch functions use from now on (for timing; results do not depend on it)."""
+    _load().tvo_set_num_threads(int(n))
 
 
 def prox1d(y, lam: float) -> np.ndarray:

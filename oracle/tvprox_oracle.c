@@ -256,3 +256,14 @@ int tvo_num_threads(void)
     return 1;
 #endif
 }
+
+/* Thread count of the batch loops from now on (timing only: the arithmetic per row does not
+ * depend on it).  n < 1 is ignored. */
+void tvo_set_num_threads(int n)
+{
+#ifdef _OPENMP
+    if (n >= 1) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
