@@ -83,6 +83,11 @@ __device__ __forceinline__ float load_lambda(const float *lam, const Layout &L, 
 
 // Segment code of a row of n <= 32 samples: .x bit k is set when x[k+1] != x[k] (a jump after
 // sample k), .y bit k when x[k+1] > x[k].  It carries everything the backward pass reads from x.
+// A dual that the warm start finds within this relative distance of its bound is put on the
+// bound (the prefix sums that recover it carry rounding errors, and a dual that sits a hair
+// inside the box would cost a clipped step to get back).
+constexpr float kWarmSnap = 1.0f + 1.0f / 4096.0f;
+
 struct FwdParams {
     const float *y;        // input rows
     const float *addend;   // optional: the prox input is y + addend (Dykstra correction term)
@@ -93,6 +98,7 @@ struct FwdParams {
     int32_t     *info;     // optional per-row info word
     uint2       *seg;      // optional per-row segment code (rows of up to 32 samples only)
     const uint32_t *order; // optional: grid row j of the grouped grid works on slot order[j]
+    uint32_t     warm;     // addend is D^T u of an earlier solve of nearly the same rows: start from that u
     Layout       L;
     TileMap      tm;       // row-per-lane kernels only
 };

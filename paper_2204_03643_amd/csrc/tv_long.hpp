@@ -326,7 +326,8 @@ struct LongSmem {
 // lanes <-> adjacent rows, so that the accesses coalesce), but the G rows of the workgroup
 // are transposed through an LDS tile on the way in and out, and the solve itself runs in the
 // ROWS mapping with one row per wave, i.e. without any workgroup barrier.
-template <int T, int C, int G, bool COLS, bool XPOSE = false>
+// WARM: p.addend is given and the solve starts from the dual it encodes.
+template <int T, int C, int G, bool COLS, bool XPOSE = false, bool WARM = false>
 __global__ __launch_bounds__(T *G) void tv1d_fwd_long_kernel(FwdParams p)
 {
     static_assert(!XPOSE || (COLS && T == 64), "the transposing variant is for strided rows on one wave");
@@ -362,25 +363,55 @@ __global__ __launch_bounds__(T *G) void tv1d_fwd_long_kernel(FwdParams p)
     const int xj = tid % G, xk0 = tid / G;
     const uint32_t xrow = blockIdx.x * G + xj;
     const int64_t xoff = (XPOSE && xrow < p.L.n_rows) ? row_offset(p.L, xrow) : 0;
+    // Warm start: the addend is D^T u of an earlier solve of nearly the same rows, so
+    // u_k = -(addend_0 + .. + addend_k).  u first takes the negated running sums inside the
+    // chunk; the chunks before this one are added further down.
+    constexpr bool warm = WARM;
+    float u[C];
+    float wsum = 0.f;                                  // negated sum of the chunk's addend
     if constexpr (XPOSE) {
+        if (warm) {
+            // the addend alone goes through the tile first
+            for (int k = xk0; k < T * C; k += T) {
+                float v = 0.f;
+                if (xrow < p.L.n_rows && k < n) v = p.addend[xoff + (int64_t)k * es];
+                tile[xj * TILE_PITCH + k + k / C] = v;
+            }
+            __syncthreads();
+#pragma unroll
+            for (int i = 0; i < C; ++i) {
+                y[i] = tile[j * TILE_PITCH + t * (C + 1) + i];
+                wsum -= y[i];
+                u[i] = wsum;
+            }
+            __syncthreads();
+        }
         for (int k = xk0; k < T * C; k += T) {
             float v = 0.f;
             if (xrow < p.L.n_rows && k < n) {
                 v = p.y[xoff + (int64_t)k * es];
-                if (p.addend) v += p.addend[xoff + (int64_t)k * es];
+                if (!warm && p.addend) v += p.addend[xoff + (int64_t)k * es];
             }
             tile[xj * TILE_PITCH + k + k / C] = v;
         }
         __syncthreads();
+        if (warm) {
 #pragma unroll
-        for (int i = 0; i < C; ++i) y[i] = tile[j * TILE_PITCH + t * (C + 1) + i];
+            for (int i = 0; i < C; ++i) y[i] += tile[j * TILE_PITCH + t * (C + 1) + i];
+        } else {
+#pragma unroll
+            for (int i = 0; i < C; ++i) y[i] = tile[j * TILE_PITCH + t * (C + 1) + i];
+        }
     } else {
         chunk_load<C>(p.y, off, es, k0, n, rvalid, y);
-        if (p.addend) {
+        if (warm || p.addend) {
             float ad[C];
             chunk_load<C>(p.addend, off, es, k0, n, rvalid, ad);
 #pragma unroll
-            for (int i = 0; i < C; ++i) y[i] += ad[i];
+            for (int i = 0; i < C; ++i) {
+                y[i] += ad[i];
+                if (warm) { wsum -= ad[i]; u[i] = wsum; }
+            }
         }
     }
     // duals past the end of the row get an empty box and never move
@@ -401,16 +432,27 @@ __global__ __launch_bounds__(T *G) void tv1d_fwd_long_kernel(FwdParams p)
         Mp::sync();
     }
 
-    // ---- starting point: every dual at the bound its local difference points to
-    float u[C];
+    // ---- starting point: every dual at the bound its local difference points to, or the
+    //      dual the addend encodes, brought into the box (duals within rounding distance of a
+    //      bound onto it)
     float fcur;
     float edge_l, edge_r;     // the neighbours' duals next to this chunk, carried between steps
     {
+        if (warm) {
+            float before, unused;
+            seg_scan<T, G, MCOLS, +1, true>(false, wsum, 0.f, sm.buf, j, t, before, unused);
 #pragma unroll
-        for (int i = 0; i < C; ++i) {
-            const float l = TV_LK(i);
-            const float dy = ((i + 1 < C) ? y[i + 1] : ynext0) - y[i];
-            u[i] = __builtin_amdgcn_fmed3f(dy * 1e30f, -l, l);
+            for (int i = 0; i < C; ++i) {
+                const float l = TV_LK(i);
+                u[i] = __builtin_amdgcn_fmed3f((u[i] + before) * kWarmSnap, -l, l);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < C; ++i) {
+                const float l = TV_LK(i);
+                const float dy = ((i + 1 < C) ? y[i + 1] : ynext0) - y[i];
+                u[i] = __builtin_amdgcn_fmed3f(dy * 1e30f, -l, l);
+            }
         }
         TV_EX(0, t) = u[C - 1];
         TV_EX(1, t) = u[0];
@@ -866,10 +908,11 @@ template <int T, int C, int G, bool COLS>
 inline hipError_t launch_fwd_long_t(const FwdParams &p, hipStream_t s)
 {
     const dim3 grid((p.L.n_rows + G - 1) / G), block(T * G);
-    if constexpr (COLS && T == 64)
-        hipLaunchKernelGGL((tv1d_fwd_long_kernel<T, C, G, COLS, true>), grid, block, 0, s, p);
+    constexpr bool XP = COLS && T == 64;
+    if (p.warm)
+        hipLaunchKernelGGL((tv1d_fwd_long_kernel<T, C, G, COLS, XP, true>), grid, block, 0, s, p);
     else
-        hipLaunchKernelGGL((tv1d_fwd_long_kernel<T, C, G, COLS>), grid, block, 0, s, p);
+        hipLaunchKernelGGL((tv1d_fwd_long_kernel<T, C, G, COLS, XP, false>), grid, block, 0, s, p);
     return hipGetLastError();
 }
 

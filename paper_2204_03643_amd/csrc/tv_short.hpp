@@ -143,6 +143,28 @@ __device__ __forceinline__ void tile_to_rows(const TileRegs<NMAX> &t, float *til
     for (int k = 0; k < NMAX; ++k) v[k] = tile[lane * P + k];
 }
 
+// Registers in tile order -> per lane the negated running sums of its row: u[k] = -(a_0 + .. + a_k).
+template <int NMAX, int MA>
+__device__ __forceinline__ void tile_to_neg_prefix(const TileRegs<NMAX> &t, float *tile, int lane,
+                                                   float (&u)[MA])
+{
+    constexpr int P = NMAX + 1;
+    wave_lds_sync();
+#pragma unroll
+    for (int i = 0; i < NMAX / 4; ++i) {
+        const int e4 = i * 64 + lane;
+        float *d = tile + ((e4 * 4) / NMAX) * P + (e4 * 4) % NMAX;
+        d[0] = t.q[i].x; d[1] = t.q[i].y; d[2] = t.q[i].z; d[3] = t.q[i].w;
+    }
+    wave_lds_sync();
+    float run = 0.f;
+#pragma unroll
+    for (int k = 0; k < NMAX - 1; ++k) {
+        run -= tile[lane * P + k];
+        u[k] = run;
+    }
+}
+
 // One row per lane -> registers in tile order.
 template <int NMAX>
 __device__ __forceinline__ void rows_to_tile(const float (&v)[NMAX], float *tile, int lane,
@@ -208,6 +230,27 @@ __device__ __forceinline__ void row_load_strided(const float *__restrict__ src,
             if (add) t += add[off + k * es];
         }
         v[k] = t;
+    }
+}
+
+// The same with the negated running sums of the addend: u[k] = -(add_0 + .. + add_k).
+template <int NMAX, bool FULL, int MA>
+__device__ __forceinline__ void row_load_strided_warm(const float *__restrict__ src,
+                                                      const float *__restrict__ add, int64_t off,
+                                                      int64_t es, int n, bool valid, float (&v)[NMAX],
+                                                      float (&u)[MA])
+{
+    float run = 0.f;
+#pragma unroll
+    for (int k = 0; k < NMAX; ++k) {
+        float t = 0.f, a = 0.f;
+        if (valid && (FULL || k < n)) {
+            t = src[off + k * es];
+            a = add[off + k * es];
+        }
+        v[k] = t + a;
+        run -= a;
+        if (k < NMAX - 1) u[k] = run;
     }
 }
 
@@ -306,6 +349,12 @@ struct RowSolver {
                 u[k] = un;
             }
         }
+        primal_of_start(y);
+    }
+
+    // x(u) and the dual objective of the starting dual
+    __device__ __forceinline__ void primal_of_start(const float (&y)[NMAX])
+    {
         float acc = 0.f, prev = 0.f;
 #pragma unroll
         for (int k = 0; k < M; ++k) {
@@ -320,6 +369,24 @@ struct RowSolver {
             X[M] = xc;
         }
         fcur = 0.5f * acc;
+    }
+
+    // ---- warm start: u already holds the dual of an earlier solve of nearly the same row (in
+    //      Alg. 1 the correction term that is added to a pass's input is D^T u of the same pass
+    //      one sweep earlier, so that dual is the negated running sum of the correction term).
+    //      It is brought into the box, duals within rounding distance of a bound onto it.
+    __device__ __forceinline__ void start_warm(const float (&y)[NMAX])
+    {
+        float ymax = 0.f;
+#pragma unroll
+        for (int k = 0; k < NMAX; ++k) ymax = fmaxf(ymax, fabsf(y[k]));
+        gtol = kGradNoise * (ymax + lam);
+#pragma unroll
+        for (int k = 0; k < M; ++k) {
+            const float l = lk(k);
+            u[k] = __builtin_amdgcn_fmed3f(u[k] * kWarmSnap, -l, l);
+        }
+        primal_of_start(y);
     }
 
     // One projected-Newton iteration.  Returns true when every row of the wave has stopped;
@@ -477,7 +544,8 @@ struct RowSolver {
 // Forward kernel: one row per lane.  Grid: see TileMap; waves of a workgroup never wait
 // for each other.  With a grouped grid the slots may be visited in a given order (p.order).
 // ---------------------------------------------------------------------------------
-template <int NMAX, bool FULL, bool PACKED>
+// WARM: p.addend is given and the solve starts from the dual it encodes (see start_warm).
+template <int NMAX, bool FULL, bool PACKED, bool WARM = false>
 __global__ __launch_bounds__(kShortBlock) TV_FWD_ATTR void tv1d_fwd_short_kernel(FwdParams p)
 {
     using S = ShortSmem<NMAX>;
@@ -501,15 +569,19 @@ __global__ __launch_bounds__(kShortBlock) TV_FWD_ATTR void tv1d_fwd_short_kernel
     const int64_t off = (!PACKED && valid) ? row_offset(p.L, row) : 0;
 
     float y[NMAX], xs[NMAX];
+    RowSolver<NMAX, FULL> sv;
     if constexpr (PACKED) {
         TileRegs<NMAX> t;
         tile_fetch<NMAX>(p.y, p.tm, r0, p.L.n_rows, lane, t, p.L.stream);
-        if (p.addend) {
+        if (WARM || p.addend) {
             TileRegs<NMAX> a;
             tile_fetch<NMAX>(p.addend, p.tm, r0, p.L.n_rows, lane, a, p.L.stream);
             tile_add<NMAX>(t, a, 1.f);
+            if constexpr (WARM) tile_to_neg_prefix<NMAX>(a, tile, lane, sv.u);
         }
         tile_to_rows<NMAX>(t, tile, lane, y);
+    } else if constexpr (WARM) {
+        row_load_strided_warm<NMAX, FULL>(p.y, p.addend, off, p.L.elem_stride, n, valid, y, sv.u);
     } else {
         row_load_strided<NMAX, FULL>(p.y, p.addend, off, p.L.elem_stride, n, valid, y);
     }
@@ -519,11 +591,11 @@ __global__ __launch_bounds__(kShortBlock) TV_FWD_ATTR void tv1d_fwd_short_kernel
     for (int k = 0; k < NMAX; ++k) tile[k * 64 + lane] = y[k];
     wave_lds_sync();
 
-    RowSolver<NMAX, FULL> sv;
     sv.yl = tile + lane; sv.gtab = gtab; sv.lam = lam; sv.m = n - 1;
     sv.alpha_try = 1.f; sv.steps = 0; sv.flags = 0; sv.nfail = 0;
     sv.active = valid; sv.prev_unclipped = false;
-    sv.start(y, rtab[n]);
+    if constexpr (WARM) sv.start_warm(y);
+    else sv.start(y, rtab[n]);
     for (int it = 0; !sv.iterate(it); ++it) {}
     sv.recover(xs);
 

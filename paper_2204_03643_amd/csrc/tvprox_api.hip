@@ -121,7 +121,14 @@ int launch_fwd_short(const FwdParams &p, bool packed_ok, hipStream_t s)
     static_assert(wpb == 1, "the grouped grid below assumes one tile per workgroup");
     if (p.tm.grouped) grid = dim3(n_tiles / p.tm.count, p.tm.count);
     const bool full = p.L.n == NMAX;
-    if (full && packed_ok)
+    if (p.warm) {
+        if (full && packed_ok)
+            hipLaunchKernelGGL((tvk::tv1d_fwd_short_kernel<NMAX, true, true, true>), grid, block, 0, s, p);
+        else if (full)
+            hipLaunchKernelGGL((tvk::tv1d_fwd_short_kernel<NMAX, true, false, true>), grid, block, 0, s, p);
+        else
+            hipLaunchKernelGGL((tvk::tv1d_fwd_short_kernel<NMAX, false, false, true>), grid, block, 0, s, p);
+    } else if (full && packed_ok)
         hipLaunchKernelGGL((tvk::tv1d_fwd_short_kernel<NMAX, true, true>), grid, block, 0, s, p);
     else if (full)
         hipLaunchKernelGGL((tvk::tv1d_fwd_short_kernel<NMAX, true, false>), grid, block, 0, s, p);
@@ -308,11 +315,12 @@ bool order_applies(const tvk::TileMap &tm)
 
 int run_fwd(const float *y, const float *addend, float *x, float *resid, int32_t *info,
             uint2 *seg, uint32_t *order_ws, const tv_rows &r, const tv_lambda &l, int64_t n_rows,
-            hipStream_t s, float *x2 = nullptr)
+            hipStream_t s, float *x2 = nullptr, bool warm = false)
 {
     FwdParams p;
     p.y = y; p.addend = addend; p.x = x; p.x2 = x2; p.resid = resid; p.lam = l.lam; p.info = info;
     p.seg = seg; p.order = nullptr;
+    p.warm = (warm && addend) ? 1u : 0u;
     p.L = make_layout(r, l, n_rows);
     p.tm = make_tile_map(l, n_rows);
     if (order_ws && r.length <= 32 && order_applies(p.tm)) {
@@ -653,13 +661,15 @@ int tv2d_prox_fwd(const float *y, float *x, int64_t planes, int64_t H, int64_t W
         const float *Yk = (k == 0) ? y : saved(2 * k - 1);
         float *Z = saved(2 * k), *Yn = saved(2 * k + 1);
         // Z = proxRows(Y + P);  P <- (Y + P) - Z      (P = 0 in the first sweep)
+        // From the second sweep on, P = D^T u of the row pass one sweep earlier (x = y - D^T u),
+        // and likewise Q for the columns: each pass starts from that dual.
         st = run_fwd(Yk, k == 0 ? nullptr : P, Z, last ? nullptr : P, nullptr, codes(2 * k), nullptr, rrow,
-                     lrow, planes * H, stream);
+                     lrow, planes * H, stream, nullptr, true);
         if (st != TV_OK) return st;
         // Y' = proxCols(Z + Q);  Q <- (Z + Q) - Y'
         // the last pass writes its output twice: where the reverse sweep will look for it, and to x
         st = run_fwd(Z, k == 0 ? nullptr : Q, Yn, last ? nullptr : Q, nullptr, codes(2 * k + 1), nullptr, rcol,
-                     lcol, planes * W, stream, last ? x : nullptr);
+                     lcol, planes * W, stream, last ? x : nullptr, true);
         if (st != TV_OK) return st;
     }
     return TV_OK;
