@@ -71,6 +71,17 @@ def test_small_planes(shape, K):
     _check_2d(y, lam, K, g, "small %s K=%d" % (shape, K), bulk=0.8)
 
 
+@pytest.mark.parametrize("shape", [(1, 1100, 2100), (2, 40, 9000)])
+def test_long_rows_and_columns_k2(shape):
+    """Rows and columns beyond 1024 samples (a workgroup per row; interleaved columns), two
+    sweeps, so that the second sweep's passes start from the first sweep's duals."""
+    rng = np.random.default_rng(91 + shape[1])
+    y = (np.cumsum(rng.normal(scale=0.05, size=shape), axis=-1) + rng.normal(scale=0.2, size=shape)).astype(np.float32)
+    g = rng.normal(size=shape).astype(np.float32)
+    lam = np.array([0.3, 0.05][:shape[0]], np.float32)
+    _check_2d(y, lam, 2, g, "long %s K=2" % (shape,), bulk=0.8)
+
+
 def test_config4_reduced():
     y, lam, g = workloads.config4(B=1, C=3, H=512, W=512, n_poly=8)
     _check_2d(y, lam, 3, g, "cfg4 reduced K=3", bulk=0.8)
