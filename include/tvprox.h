@@ -151,9 +151,12 @@ int tv1d_prox_bwd_seg(const float *g_up, const uint64_t *seg, float *grad_y, flo
  * 2D anisotropic TV prox on `planes` images of H x W (row-major, contiguous) by
  * `sweeps` iterations of paper Alg. 1; plane p uses lam[p % count] (lam.div is
  * ignored).  ws keeps every pass's output (2*sweeps tensors) plus two scratch
- * tensors (and, for planes of at most 32 x 32, every pass's segment codes, which is what
- * the backward call then reads), and must be handed unchanged to tv2d_prox_bwd.  x must
- * not alias y.
+ * tensors, room for every backward pass's dL/dlam terms (one float per row and pass) and,
+ * for planes of at most 32 x 32, every pass's segment codes, which is what the backward
+ * call then reads; it must be handed unchanged to tv2d_prox_bwd.  x must not alias y.
+ * From the second sweep on, the correction term a pass adds to its input is D^T u of the
+ * same pass one sweep earlier (x = y - D^T u), and the pass starts its Newton iteration
+ * from that dual.
  */
 size_t tv2d_workspace_bytes(int64_t planes, int64_t H, int64_t W, int sweeps);
 int tv2d_prox_fwd(const float *y, float *x, int64_t planes, int64_t H, int64_t W,
@@ -163,7 +166,8 @@ int tv2d_prox_fwd(const float *y, float *x, int64_t planes, int64_t H, int64_t W
  * Reverse sweep through paper Alg. 1 (replaces autograd through the loop, paper
  * Sec. 3.2).  ws is the buffer tv2d_prox_fwd filled; its two scratch tensors are
  * overwritten, the saved pass outputs are only read.  grad_lam (lam.count floats,
- * overwritten) may be NULL.  grad_y must not alias g_up.
+ * overwritten) may be NULL; it is one fp64 sum, in a fixed order, over the terms of all
+ * passes.  grad_y must not alias g_up.
  */
 int tv2d_prox_bwd(const float *g_up, float *grad_y, float *grad_lam, int64_t planes, int64_t H,
                   int64_t W, tv_lambda lam, int sweeps, void *ws, size_t ws_bytes,

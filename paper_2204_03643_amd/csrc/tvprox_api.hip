@@ -348,35 +348,43 @@ int run_fwd(const float *y, const float *addend, float *x, float *resid, int32_t
 
 // Sums the per-row dL/dlam contributions of every slot: one workgroup per slot, fp64
 // accumulation in a fixed order (deterministic).  Four independent loads are kept in
-// flight per thread; the walk over the slot's rows needs no division.
+// flight per thread; the walk over the slot's rows needs no division.  `batches` arrays of the
+// same shape, `batch_stride` floats apart, are summed together (the passes of a 2D reverse
+// sweep).  With few slots and many batches the work of a slot is split over gridDim.y
+// workgroups (workgroup j takes batches j, j + gridDim.y, ...), each leaving its fp64 sum in
+// `split_out[slot * gridDim.y + j]` for sum_splits_kernel.
 template <int kReduceThreads>
 __global__ __launch_bounds__(kReduceThreads) void reduce_lambda_kernel(
     const float *__restrict__ partial, float *__restrict__ grad_lam, uint32_t n_rows,
-    uint32_t count, uint32_t div, int accumulate)
+    uint32_t count, uint32_t div, int accumulate, uint32_t batches, uint64_t batch_stride,
+    double *__restrict__ split_out)
 {
     __shared__ double red[kReduceThreads];
     const uint32_t slot = blockIdx.x;
     // rows of this slot: r = (q*count + slot)*div + i,  i < div,  q = 0, 1, ...
     // thread t visits the pairs (q, i) with q*div + i = t, t + T, t + 2T, ...
-    uint32_t q = threadIdx.x / div, i = threadIdx.x - q * div;
     const uint32_t dq = kReduceThreads / div, di = kReduceThreads - dq * div;
     const uint64_t stride = (uint64_t)count * div;
     const uint64_t base = (uint64_t)slot * div;
     double acc[4] = {0.0, 0.0, 0.0, 0.0};
-    bool more = true;
-    while (more) {
-        float v[4];
+    partial += blockIdx.y * batch_stride;
+    for (uint32_t b = blockIdx.y; b < batches; b += gridDim.y, partial += gridDim.y * batch_stride) {
+        uint32_t q = threadIdx.x / div, i = threadIdx.x - q * div;
+        bool more = true;
+        while (more) {
+            float v[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            // group starts grow with q: once a group starts past the end, nothing follows
-            const uint64_t g0 = q * stride + base;
-            more = more && (g0 < n_rows);
-            v[j] = (more && g0 + i < n_rows) ? partial[g0 + i] : 0.f;
-            q += dq; i += di;
-            if (i >= div) { i -= div; q += 1; }
+            for (int j = 0; j < 4; ++j) {
+                // group starts grow with q: once a group starts past the end, nothing follows
+                const uint64_t g0 = q * stride + base;
+                more = more && (g0 < n_rows);
+                v[j] = (more && g0 + i < n_rows) ? partial[g0 + i] : 0.f;
+                q += dq; i += di;
+                if (i >= div) { i -= div; q += 1; }
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc[j] += (double)v[j];
         }
-#pragma unroll
-        for (int j = 0; j < 4; ++j) acc[j] += (double)v[j];
     }
     red[threadIdx.x] = (acc[0] + acc[1]) + (acc[2] + acc[3]);
     __syncthreads();
@@ -385,72 +393,127 @@ __global__ __launch_bounds__(kReduceThreads) void reduce_lambda_kernel(
         __syncthreads();
     }
     if (threadIdx.x == 0) {
-        const float v = (float)red[0];
-        grad_lam[slot] = accumulate ? grad_lam[slot] + v : v;
+        if (split_out) {
+            split_out[slot * gridDim.y + blockIdx.y] = red[0];
+        } else {
+            const float v = (float)red[0];
+            grad_lam[slot] = accumulate ? grad_lam[slot] + v : v;
+        }
     }
+}
+
+// grad_lam[slot] = the sum, in a fixed order, of the `n` fp64 sums that the split reductions left
+// per slot (both directions of a 2D reverse sweep lie side by side: n = 2 * splits).
+__global__ __launch_bounds__(64) void sum_splits_kernel(const double *__restrict__ split,
+                                                         float *__restrict__ grad_lam, uint32_t count,
+                                                         uint32_t splits)
+{
+    const uint32_t slot = blockIdx.x * 64 + threadIdx.x;
+    if (slot >= count) return;
+    double acc = 0.0;
+    for (uint32_t d = 0; d < 2; ++d)
+        for (uint32_t j = 0; j < splits; ++j) acc += split[((uint64_t)d * count + slot) * splits + j];
+    grad_lam[slot] = (float)acc;
 }
 
 // Slots that own only a handful of rows (e.g. one lambda per row): one thread per slot.
 __global__ __launch_bounds__(256) void reduce_lambda_small_kernel(
     const float *__restrict__ partial, float *__restrict__ grad_lam, uint32_t n_rows,
-    uint32_t count, uint32_t div, int accumulate)
+    uint32_t count, uint32_t div, int accumulate, uint32_t batches, uint64_t batch_stride)
 {
     const uint32_t slot = blockIdx.x * 256 + threadIdx.x;
     if (slot >= count) return;
     const uint64_t stride = (uint64_t)count * div;
     double acc = 0.0;
-    for (uint64_t g0 = (uint64_t)slot * div; g0 < n_rows; g0 += stride)
-        for (uint32_t i = 0; i < div && g0 + i < n_rows; ++i) acc += (double)partial[g0 + i];
+    for (uint32_t b = 0; b < batches; ++b, partial += batch_stride)
+        for (uint64_t g0 = (uint64_t)slot * div; g0 < n_rows; g0 += stride)
+            for (uint32_t i = 0; i < div && g0 + i < n_rows; ++i) acc += (double)partial[g0 + i];
     const float v = (float)acc;
     grad_lam[slot] = accumulate ? grad_lam[slot] + v : v;
 }
 
+// The split reduction applies below this many slots (more slots fill the chip by themselves) ...
+constexpr uint32_t kSplitMaxSlots = 64;
+// ... and uses at most this many workgroups per slot and direction.
+constexpr uint32_t kSplitMax = 32;
+constexpr size_t kSplitScratchBytes = 2 * (size_t)kSplitMaxSlots * kSplitMax * sizeof(double);
+
+uint32_t reduce_splits(int64_t count, int sweeps)
+{
+    if (count >= (int64_t)kSplitMaxSlots || sweeps < 2) return 1;
+    return (uint32_t)sweeps < kSplitMax ? (uint32_t)sweeps : kSplitMax;
+}
+
+// splits > 1: workgroup (slot, j) leaves its fp64 sum in split_out[slot * splits + j]; the rows of
+// a slot must then be many enough for the workgroup-per-slot kernel.
 int launch_reduce_lambda(const float *partial, float *grad_lam, int64_t n_rows, const tv_lambda &l,
-                         int accumulate, hipStream_t s)
+                         int accumulate, hipStream_t s, uint32_t batches = 1, uint64_t batch_stride = 0,
+                         uint32_t splits = 1, double *split_out = nullptr)
 {
     const uint32_t count = (uint32_t)l.count, div = (uint32_t)l.div, nr = (uint32_t)n_rows;
     const uint64_t groups = ((uint64_t)nr + div - 1) / div;
-    const uint64_t rows_per_slot = ((groups + count - 1) / count) * div;
-    if (rows_per_slot <= 32)
+    const uint64_t rows_per_slot = ((groups + count - 1) / count) * div * ((batches + splits - 1) / splits);
+    if (splits > 1) {
+        if (rows_per_slot <= 2048)
+            hipLaunchKernelGGL(reduce_lambda_kernel<256>, dim3(count, splits), dim3(256), 0, s, partial,
+                               grad_lam, nr, count, div, accumulate, batches, batch_stride, split_out);
+        else
+            hipLaunchKernelGGL(reduce_lambda_kernel<1024>, dim3(count, splits), dim3(1024), 0, s, partial,
+                               grad_lam, nr, count, div, accumulate, batches, batch_stride, split_out);
+    } else if (rows_per_slot <= 32)
         hipLaunchKernelGGL(reduce_lambda_small_kernel, dim3((count + 255) / 256), dim3(256), 0, s,
-                           partial, grad_lam, nr, count, div, accumulate);
+                           partial, grad_lam, nr, count, div, accumulate, batches, batch_stride);
     else if (rows_per_slot <= 2048)
         hipLaunchKernelGGL(reduce_lambda_kernel<256>, dim3(count), dim3(256), 0, s, partial, grad_lam,
-                           nr, count, div, accumulate);
+                           nr, count, div, accumulate, batches, batch_stride, (double *)nullptr);
     else
         hipLaunchKernelGGL(reduce_lambda_kernel<1024>, dim3(count), dim3(1024), 0, s, partial,
-                           grad_lam, nr, count, div, accumulate);
+                           grad_lam, nr, count, div, accumulate, batches, batch_stride, (double *)nullptr);
     return launch_status();
 }
 
+// Row-per-lane kernels add up the dL/dlam terms of neighbouring rows that share a slot before
+// they leave the wave: groups of 1 << lg rows, the largest power of two (at most 64) dividing
+// div.  What is left for the reduction kernel: red_rows values, red_div of them per slot visit.
+struct PartialShape {
+    uint32_t lg;
+    int64_t  red_rows, red_div;
+};
+
+PartialShape partial_shape(const tv_rows &r, const tv_lambda &l, int64_t n_rows)
+{
+    PartialShape ps = {0, n_rows, l.div};
+    if (r.length <= 32) {
+        uint32_t lg = 0;
+        while (lg < 6 && (l.count == 1 || l.div % ((int64_t)2 << lg) == 0)) ++lg;
+        ps.lg = lg;
+        ps.red_rows = (n_rows + ((int64_t)1 << lg) - 1) >> lg;
+        ps.red_div = l.count == 1 ? 1 : l.div >> lg;
+    }
+    return ps;
+}
+
+// reduce_now = false: the dL/dlam terms stay in `partial` and the caller sums them later.
 int run_bwd(const float *g, const float *sub, const float *x, const uint2 *seg, float *gy,
             float *grad_lam, int accumulate, const tv_rows &r, const tv_lambda &l, int64_t n_rows,
-            float *partial, hipStream_t s)
+            float *partial, hipStream_t s, bool reduce_now = true)
 {
     BwdParams p;
     p.g = g; p.sub = sub; p.x = x; p.seg = seg; p.gy = gy;
     p.partial = grad_lam ? partial : nullptr;
-    p.part_lg = 0;
     p.L = make_layout(r, l, n_rows);
     const bool packed = rows_packed(r) && aligned16(g) && (!x || aligned16(x)) && aligned16(gy) &&
                         (!sub || aligned16(sub));
     int st;
-    // row-per-lane kernels add up the dL/dlam terms of neighbouring rows that share a slot
-    // before they leave the wave: groups of the largest power of two (at most 64) dividing div
-    int64_t red_rows = n_rows, red_div = l.div;
-    if (r.length <= 32 && grad_lam) {
-        uint32_t lg = 0;
-        while (lg < 6 && (l.count == 1 || l.div % ((int64_t)2 << lg) == 0)) ++lg;
-        p.part_lg = lg;
-        red_rows = (n_rows + ((int64_t)1 << lg) - 1) >> lg;
-        red_div = l.count == 1 ? 1 : l.div >> lg;
-    }
+    const PartialShape ps = partial_shape(r, l, n_rows);
+    p.part_lg = grad_lam ? ps.lg : 0;
+    const int64_t red_rows = ps.red_rows, red_div = ps.red_div;
     if (r.length <= 8) st = launch_bwd_short<8>(p, packed, s);
     else if (r.length <= 16) st = launch_bwd_short<16>(p, packed, s);
     else if (r.length <= 32) st = launch_bwd_short<32>(p, packed, s);
     else st = tvk::launch_bwd_long(p, s) == hipSuccess ? TV_OK : TV_ERR_HIP;
     if (st != TV_OK) return st;
-    if (grad_lam) {
+    if (grad_lam && reduce_now) {
         tv_lambda lr = l;
         lr.div = red_div;
         st = launch_reduce_lambda(partial, grad_lam, red_rows, lr, accumulate, s);
@@ -629,7 +692,7 @@ size_t tv2d_workspace_bytes(int64_t planes, int64_t H, int64_t W, int sweeps)
 {
     size_t tb, pb, cb;
     if (check_2d(planes, H, W, sweeps, &tb, &pb, &cb) != TV_OK) return 0;
-    return tb * (size_t)(2 * sweeps + 2) + pb + cb * (size_t)(2 * sweeps);
+    return tb * (size_t)(2 * sweeps + 2) + (pb + cb) * (size_t)(2 * sweeps) + kSplitScratchBytes;
 }
 
 int tv2d_prox_fwd(const float *y, float *x, int64_t planes, int64_t H, int64_t W, tv_lambda lam,
@@ -642,14 +705,15 @@ int tv2d_prox_fwd(const float *y, float *x, int64_t planes, int64_t H, int64_t W
     if (planes == 0) return TV_OK;
     if (!y || !x || !lam.lam) return TV_ERR_NULL;
     if (H > TV_MAX_LENGTH || W > TV_MAX_LENGTH) return TV_ERR_UNSUPPORTED;
-    if (!ws || !aligned16(ws) || ws_bytes < tb * (size_t)(2 * sweeps + 2) + pb + cb * (size_t)(2 * sweeps))
+    if (!ws || !aligned16(ws) || ws_bytes < tb * (size_t)(2 * sweeps + 2) + (pb + cb) * (size_t)(2 * sweeps) + kSplitScratchBytes)
         return TV_ERR_WORKSPACE;
 
     char *base = (char *)ws;
     auto saved = [&](int i) { return (float *)(base + tb * (size_t)i); };
     float *P = saved(2 * sweeps), *Q = saved(2 * sweeps + 1);
     auto codes = [&](int pass) -> uint2 * {
-        return cb ? (uint2 *)(base + tb * (size_t)(2 * sweeps + 2) + pb + cb * (size_t)pass) : nullptr;
+        return cb ? (uint2 *)(base + tb * (size_t)(2 * sweeps + 2) + pb * (size_t)(2 * sweeps) + cb * (size_t)pass)
+                  : nullptr;
     };
     const tv_rows rrow = {planes, H * W, H, W, W, 1};
     const tv_rows rcol = {planes, H * W, W, 1, H, W};
@@ -688,15 +752,18 @@ int tv2d_prox_bwd(const float *g_up, float *grad_y, float *grad_lam, int64_t pla
     }
     if (!g_up || !grad_y) return TV_ERR_NULL;
     if (H > TV_MAX_LENGTH || W > TV_MAX_LENGTH) return TV_ERR_UNSUPPORTED;
-    if (!ws || !aligned16(ws) || ws_bytes < tb * (size_t)(2 * sweeps + 2) + pb + cb * (size_t)(2 * sweeps))
+    if (!ws || !aligned16(ws) || ws_bytes < tb * (size_t)(2 * sweeps + 2) + (pb + cb) * (size_t)(2 * sweeps) + kSplitScratchBytes)
         return TV_ERR_WORKSPACE;
 
     char *base = (char *)ws;
     auto saved = [&](int i) { return (float *)(base + tb * (size_t)i); };
     float *Ab = saved(2 * sweeps), *Bb = saved(2 * sweeps + 1);
-    float *partial = (float *)(base + tb * (size_t)(2 * sweeps + 2));
+    // dL/dlam terms of pass i; summed over all passes at the end, one launch per direction
+    auto partial = [&](int pass) { return (float *)(base + tb * (size_t)(2 * sweeps + 2) + pb * (size_t)pass); };
     auto codes = [&](int pass) -> const uint2 * {
-        return cb ? (const uint2 *)(base + tb * (size_t)(2 * sweeps + 2) + pb + cb * (size_t)pass) : nullptr;
+        return cb ? (const uint2 *)(base + tb * (size_t)(2 * sweeps + 2) + pb * (size_t)(2 * sweeps) +
+                                    cb * (size_t)pass)
+                  : nullptr;
     };
     const tv_rows rrow = {planes, H * W, H, W, W, 1};
     const tv_rows rcol = {planes, H * W, W, 1, H, W};
@@ -707,16 +774,33 @@ int tv2d_prox_bwd(const float *g_up, float *grad_y, float *grad_lam, int64_t pla
     //   Bbar = Qbar' + C^T(Ybar' - Qbar'),   Qbar = Bbar,
     //   Abar = Pbar' + R^T(Bbar - Pbar'),    Ybar = Pbar = Abar.
     // Ybar and Pbar coincide from the second reverse step on, so two tensors carry the state.
-    int acc = 0;
     for (int k = sweeps - 1; k >= 0; --k) {
         const bool first = (k == sweeps - 1);
         st = run_bwd(first ? g_up : Ab, first ? nullptr : Bb, cb ? nullptr : saved(2 * k + 1), codes(2 * k + 1),
-                     Bb, grad_lam, acc, rcol, lcol, planes * W, partial, stream);
+                     Bb, grad_lam, 0, rcol, lcol, planes * W, partial(2 * k + 1), stream, false);
         if (st != TV_OK) return st;
-        acc = 1;
         st = run_bwd(Bb, first ? nullptr : Ab, cb ? nullptr : saved(2 * k), codes(2 * k), k == 0 ? grad_y : Ab,
-                     grad_lam, acc, rrow, lrow, planes * H, partial, stream);
+                     grad_lam, 0, rrow, lrow, planes * H, partial(2 * k), stream, false);
         if (st != TV_OK) return st;
+    }
+    if (grad_lam) {
+        const uint64_t two_passes = 2 * (uint64_t)(pb / sizeof(float));
+        const PartialShape pr = partial_shape(rrow, lrow, planes * H), pc = partial_shape(rcol, lcol, planes * W);
+        tv_lambda lr = lrow, lc = lcol;
+        lr.div = pr.red_div; lc.div = pc.red_div;
+        const uint32_t splits = reduce_splits(lam.count, sweeps);
+        double *split = (double *)(base + tb * (size_t)(2 * sweeps + 2) + (pb + cb) * (size_t)(2 * sweeps));
+        st = launch_reduce_lambda(partial(0), grad_lam, pr.red_rows, lr, 0, stream, (uint32_t)sweeps, two_passes,
+                                  splits, splits > 1 ? split : nullptr);
+        if (st != TV_OK) return st;
+        st = launch_reduce_lambda(partial(1), grad_lam, pc.red_rows, lc, 1, stream, (uint32_t)sweeps, two_passes,
+                                  splits, splits > 1 ? split + (size_t)lam.count * splits : nullptr);
+        if (st != TV_OK) return st;
+        if (splits > 1) {
+            hipLaunchKernelGGL(sum_splits_kernel, dim3((uint32_t)((lam.count + 63) / 64)), dim3(64), 0, stream,
+                               split, grad_lam, (uint32_t)lam.count, splits);
+            if (launch_status() != TV_OK) return TV_ERR_HIP;
+        }
     }
     return TV_OK;
 }

@@ -109,9 +109,10 @@ def test_2d_validation():
     L = tv.lib()
     lam = tv.tv_lambda(FAKE, 3, 1)
     need = tv.tv2d_workspace_bytes(6, 32, 32, 2)
-    # 2K + 2 tensors, the dL/dlam partials, and (planes of at most 32 x 32) 2K sets of segment codes
-    assert need == 6 * 32 * 32 * 4 * (2 * 2 + 2) + 6 * 32 * 4 + 2 * 2 * 6 * 32 * 8
-    assert tv.tv2d_workspace_bytes(6, 32, 64, 2) == 6 * 32 * 64 * 4 * (2 * 2 + 2) + 6 * 64 * 4
+    # 2K + 2 tensors, 2K sets of dL/dlam partials, (planes of at most 32 x 32) 2K sets of segment
+    # codes, and 32 KiB for the split dL/dlam reduction
+    assert need == 6 * 32 * 32 * 4 * (2 * 2 + 2) + 2 * 2 * 6 * 32 * 4 + 2 * 2 * 6 * 32 * 8 + 32768
+    assert tv.tv2d_workspace_bytes(6, 32, 64, 2) == 6 * 32 * 64 * 4 * (2 * 2 + 2) + 2 * 2 * 6 * 64 * 4 + 32768
     assert tv.tv2d_workspace_bytes(6, 0, 32, 2) == 0
     assert L.tv2d_prox_fwd(None, FAKE, 6, 32, 32, lam, 2, FAKE, need, None) == 1
     assert L.tv2d_prox_fwd(FAKE, FAKE, 6, 32, 32, lam, 0, FAKE, need, None) == 2
