@@ -370,38 +370,46 @@ __global__ __launch_bounds__(T *G) void tv1d_fwd_long_kernel(FwdParams p)
     float u[C];
     float wsum = 0.f;                                  // negated sum of the chunk's addend
     if constexpr (XPOSE) {
-        if (warm) {
-            // the addend alone goes through the tile first
-            for (int k = xk0; k < T * C; k += T) {
-                float v = 0.f;
-                if (xrow < p.L.n_rows && k < n) v = p.addend[xoff + (int64_t)k * es];
-                tile[xj * TILE_PITCH + k + k / C] = v;
-            }
-            __syncthreads();
+        // every global load is issued before the first trip through the tile
+        const bool xvalid = xrow < p.L.n_rows;
+        float ry[C], ra[C];
+#pragma unroll
+        for (int i = 0; i < C; ++i) {
+            const int k = xk0 + i * T;
+            ry[i] = (xvalid && k < n) ? p.y[xoff + (int64_t)k * es] : 0.f;
+        }
+        if (warm || p.addend) {
 #pragma unroll
             for (int i = 0; i < C; ++i) {
-                y[i] = tile[j * TILE_PITCH + t * (C + 1) + i];
-                wsum -= y[i];
-                u[i] = wsum;
+                const int k = xk0 + i * T;
+                ra[i] = (xvalid && k < n) ? p.addend[xoff + (int64_t)k * es] : 0.f;
             }
-            __syncthreads();
+            if constexpr (warm) {
+                // the addend alone goes through the tile first
+#pragma unroll
+                for (int i = 0; i < C; ++i) {
+                    const int k = xk0 + i * T;
+                    tile[xj * TILE_PITCH + k + k / C] = ra[i];
+                }
+                __syncthreads();
+#pragma unroll
+                for (int i = 0; i < C; ++i) {
+                    wsum -= tile[j * TILE_PITCH + t * (C + 1) + i];
+                    u[i] = wsum;
+                }
+                __syncthreads();
+            }
+#pragma unroll
+            for (int i = 0; i < C; ++i) ry[i] += ra[i];
         }
-        for (int k = xk0; k < T * C; k += T) {
-            float v = 0.f;
-            if (xrow < p.L.n_rows && k < n) {
-                v = p.y[xoff + (int64_t)k * es];
-                if (!warm && p.addend) v += p.addend[xoff + (int64_t)k * es];
-            }
-            tile[xj * TILE_PITCH + k + k / C] = v;
+#pragma unroll
+        for (int i = 0; i < C; ++i) {
+            const int k = xk0 + i * T;
+            tile[xj * TILE_PITCH + k + k / C] = ry[i];
         }
         __syncthreads();
-        if (warm) {
 #pragma unroll
-            for (int i = 0; i < C; ++i) y[i] += tile[j * TILE_PITCH + t * (C + 1) + i];
-        } else {
-#pragma unroll
-            for (int i = 0; i < C; ++i) y[i] = tile[j * TILE_PITCH + t * (C + 1) + i];
-        }
+        for (int i = 0; i < C; ++i) y[i] = tile[j * TILE_PITCH + t * (C + 1) + i];
     } else {
         chunk_load<C>(p.y, off, es, k0, n, rvalid, y);
         if (warm || p.addend) {
