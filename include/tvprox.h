@@ -99,11 +99,19 @@ int tv1d_prox_fwd_info(const float *y, float *x, int32_t *info, tv_rows rows, tv
  *   info: as in tv1d_prox_fwd_info.
  *   seg:  as in tv1d_prox_fwd_seg (below).
  *   ws:   device scratch of at least tv1d_fwd_workspace_bytes() bytes, 16-byte aligned
- *         (TV_ERR_WORKSPACE otherwise), contents undefined afterwards.  With it, rows of up to
- *         32 samples whose lambda slots form whole groups of 64 rows are processed slot by
- *         slot in the order of decreasing predicted cost, which shortens the call when the
- *         slots' lambdas differ widely; results are bit-identical with or without it.
- *         tv1d_fwd_workspace_bytes() returns 0 where this does not apply (ws is then unused).
+ *         (TV_ERR_WORKSPACE otherwise), contents undefined afterwards.  Two uses:
+ *         - rows of up to 32 samples whose lambda slots form whole groups of 64 rows are
+ *           processed slot by slot in the order of decreasing predicted cost, which shortens
+ *           the call when the slots' lambdas differ widely; results are bit-identical with or
+ *           without it;
+ *         - unit-stride rows of 2048 samples or more get a multilevel start: the row averaged
+ *           in groups of 4 samples, with lambda / 4, is solved first (recursively, down to at
+ *           most 256 samples) and its dual, prolonged, is where the Newton iteration of the
+ *           row itself starts.  The paper does not fix the starting point (Sec. 3.2); the
+ *           minimiser is the same, x agrees with the plain call to rounding, and rows whose
+ *           lambda is large against their sample-to-sample variation take 4 steps instead of
+ *           10-30.  Scratch: about two thirds of the input's size.
+ *         tv1d_fwd_workspace_bytes() returns 0 where neither applies (ws is then unused).
  */
 typedef struct {
     int32_t *info;

@@ -81,13 +81,16 @@ __device__ __forceinline__ float load_lambda(const float *lam, const Layout &L, 
     return fmaxf(lam[lam_slot(L, r)], 0.0f);
 }
 
-// Segment code of a row of n <= 32 samples: .x bit k is set when x[k+1] != x[k] (a jump after
-// sample k), .y bit k when x[k+1] > x[k].  It carries everything the backward pass reads from x.
 // A dual that the warm start finds within this relative distance of its bound is put on the
 // bound (the prefix sums that recover it carry rounding errors, and a dual that sits a hair
 // inside the box would cost a clipped step to get back).
 constexpr float kWarmSnap = 1.0f + 1.0f / 4096.0f;
 
+// Multilevel start of long rows: a level averages groups of this many samples of the level below.
+constexpr int kMlFactor = 4;
+
+// Segment code of a row of n <= 32 samples: .x bit k is set when x[k+1] != x[k] (a jump after
+// sample k), .y bit k when x[k+1] > x[k].  It carries everything the backward pass reads from x.
 struct FwdParams {
     const float *y;        // input rows
     const float *addend;   // optional: the prox input is y + addend (Dykstra correction term)
@@ -98,7 +101,15 @@ struct FwdParams {
     int32_t     *info;     // optional per-row info word
     uint2       *seg;      // optional per-row segment code (rows of up to 32 samples only)
     const uint32_t *order; // optional: grid row j of the grouped grid works on slot order[j]
-    uint32_t     warm;     // addend is D^T u of an earlier solve of nearly the same rows: start from that u
+    uint32_t     warm;     // 1: addend is D^T u of an earlier solve of nearly the same rows: start from that u
+                           // 2: start from the dual of the row averaged in groups of kMlFactor (coarse_u)
+    // long-row kernels only (multilevel start):
+    const float *coarse_u; // warm == 2: duals of the averaged rows, coarse_n per row, packed
+    int32_t      coarse_n;
+    float       *dual_out; // optional: receives the final dual, L.n per row, packed (entry n - 1 is 0)
+    const uint32_t *ml_flag; // optional, per row: 0 = this row takes no part in the multilevel start
+    uint32_t     ml_skip;  // rows with ml_flag == 0 are not solved at all (the launch is a coarse level)
+    float        lam_scale; // lambda of this launch = lam[slot] * lam_scale (1 / kMlFactor per level)
     Layout       L;
     TileMap      tm;       // row-per-lane kernels only
 };

@@ -326,8 +326,11 @@ struct LongSmem {
 // lanes <-> adjacent rows, so that the accesses coalesce), but the G rows of the workgroup
 // are transposed through an LDS tile on the way in and out, and the solve itself runs in the
 // ROWS mapping with one row per wave, i.e. without any workgroup barrier.
-// WARM: p.addend is given and the solve starts from the dual it encodes.
-template <int T, int C, int G, bool COLS, bool XPOSE = false, bool WARM = false>
+// WARM = 1: p.addend is given and the solve starts from the dual it encodes.
+// WARM = 2 (unit-stride rows, C a multiple of kMlFactor): rows flagged in p.ml_flag start from
+// the dual of the same row averaged in groups of kMlFactor samples (p.coarse_u), which a launch
+// on the averaged rows with lambda / kMlFactor left behind (p.dual_out of that launch).
+template <int T, int C, int G, bool COLS, bool XPOSE = false, int WARM = 0>
 __global__ __launch_bounds__(T *G) void tv1d_fwd_long_kernel(FwdParams p)
 {
     static_assert(!XPOSE || (COLS && T == 64), "the transposing variant is for strided rows on one wave");
@@ -344,7 +347,13 @@ __global__ __launch_bounds__(T *G) void tv1d_fwd_long_kernel(FwdParams p)
 #define TV_PB(c, q, tt) sm.buf[(((c) * 3 + (q)) * G + j) * T + (tt)]
 
     const uint32_t row = blockIdx.x * G + j;
-    const bool rvalid = row < p.L.n_rows;
+    bool rvalid = row < p.L.n_rows;
+    bool from_coarse = false;
+    if (p.ml_flag && rvalid) {
+        const bool flagged = p.ml_flag[row] != 0;
+        if (p.ml_skip) rvalid = flagged;            // a coarse level: only rows that asked for it
+        else from_coarse = WARM == 2 && flagged;
+    }
     const int n = p.L.n, M = n - 1;
     const int k0 = t * C;
 
@@ -357,7 +366,7 @@ __global__ __launch_bounds__(T *G) void tv1d_fwd_long_kernel(FwdParams p)
 
     const int64_t off = rvalid ? row_offset(p.L, row) : 0;
     const int64_t es = p.L.elem_stride;
-    const float lam = rvalid ? load_lambda(p.lam, p.L, row) : 0.f;
+    const float lam = rvalid ? load_lambda(p.lam, p.L, row) * p.lam_scale : 0.f;
     float y[C];
     // transposing variant: thread tid moves samples k = tid / G, tid / G + T, ... of row tid % G
     const int xj = tid % G, xk0 = tid / G;
@@ -366,7 +375,7 @@ __global__ __launch_bounds__(T *G) void tv1d_fwd_long_kernel(FwdParams p)
     // Warm start: the addend is D^T u of an earlier solve of nearly the same rows, so
     // u_k = -(addend_0 + .. + addend_k).  u first takes the negated running sums inside the
     // chunk; the chunks before this one are added further down.
-    constexpr bool warm = WARM;
+    constexpr bool warm = WARM == 1;
     float u[C];
     float wsum = 0.f;                                  // negated sum of the chunk's addend
     if constexpr (XPOSE) {
@@ -460,6 +469,40 @@ __global__ __launch_bounds__(T *G) void tv1d_fwd_long_kernel(FwdParams p)
                 const float l = TV_LK(i);
                 const float dy = ((i + 1 < C) ? y[i + 1] : ynext0) - y[i];
                 u[i] = __builtin_amdgcn_fmed3f(dy * 1e30f, -l, l);
+            }
+        }
+        if constexpr (WARM == 2) {
+            // Prolongation of the coarse dual.  The coarse row is this row with every group of
+            // kMlFactor samples replaced by its mean, and its dual uc solves the same problem
+            // restricted to rows that are constant on the groups (lambda / kMlFactor there).
+            // At the knot behind a group the fine dual is kMlFactor * uc (exact for a power of
+            // two, so bound coarse duals give bound fine duals); inside a group it follows
+            // u_k = u_{k-1} + (x_group - y_k) with the group's coarse x, clipped into the box.
+            static_assert(WARM != 2 || C % kMlFactor == 0, "groups must not straddle chunks");
+            if (from_coarse) {
+                constexpr int F = kMlFactor;
+                const float *cu = p.coarse_u + (size_t)row * p.coarse_n;
+                const int j0 = k0 / F;
+                float ucl = (j0 > 0 && j0 - 1 < p.coarse_n) ? cu[j0 - 1] : 0.f;
+#pragma unroll
+                for (int c = 0; c < C / F; ++c) {
+                    const float ucr = (j0 + c < p.coarse_n) ? cu[j0 + c] : 0.f;
+                    float sum = 0.f, cnt = 0.f;
+#pragma unroll
+                    for (int r = 0; r < F; ++r)
+                        if (k0 + c * F + r < n) { sum += y[c * F + r]; cnt += 1.f; }
+                    const float xg = (cnt > 0.f ? sum / cnt : 0.f) + ucr - ucl;
+                    float run = (float)F * ucl;
+#pragma unroll
+                    for (int r = 0; r < F - 1; ++r) {
+                        const float l = TV_LK(c * F + r);
+                        run += xg - y[c * F + r];
+                        u[c * F + r] = __builtin_amdgcn_fmed3f(run, -l, l);
+                    }
+                    const float l = TV_LK(c * F + F - 1);
+                    u[c * F + F - 1] = __builtin_amdgcn_fmed3f((float)F * ucr, -l, l);
+                    ucl = ucr;
+                }
             }
         }
         TV_EX(0, t) = u[C - 1];
@@ -666,6 +709,8 @@ __global__ __launch_bounds__(T *G) void tv1d_fwd_long_kernel(FwdParams p)
         else if (!Mp::sync_any(active)) break;
     }
 
+    if (p.dual_out) chunk_store<C>(p.dual_out, (int64_t)row * n, 1, k0, n, rvalid, u);
+
     // ---- primal recovery x = y - D^T u, then every block between two bound duals takes
     //      the value of its first sample, so that constant runs are bit-identical
     float xs[C];
@@ -736,7 +781,7 @@ __global__ __launch_bounds__(T *G) void tv1d_fwd_long_kernel(FwdParams p)
                     p.resid[xoff + (int64_t)k * es] = tile[xj * TILE_PITCH + k + k / C];
         }
     } else {
-        chunk_store<C>(p.x, off, es, k0, n, rvalid, xs);
+        if (p.x) chunk_store<C>(p.x, off, es, k0, n, rvalid, xs);
         if (p.x2) chunk_store<C>(p.x2, off, es, k0, n, rvalid, xs);
         if (p.resid) {
 #pragma unroll
@@ -917,10 +962,15 @@ inline hipError_t launch_fwd_long_t(const FwdParams &p, hipStream_t s)
 {
     const dim3 grid((p.L.n_rows + G - 1) / G), block(T * G);
     constexpr bool XP = COLS && T == 64;
-    if (p.warm)
-        hipLaunchKernelGGL((tv1d_fwd_long_kernel<T, C, G, COLS, XP, true>), grid, block, 0, s, p);
+    if (p.warm == 2) {
+        if constexpr (!COLS && C % kMlFactor == 0)
+            hipLaunchKernelGGL((tv1d_fwd_long_kernel<T, C, G, COLS, XP, 2>), grid, block, 0, s, p);
+        else
+            return hipErrorInvalidValue;
+    } else if (p.warm)
+        hipLaunchKernelGGL((tv1d_fwd_long_kernel<T, C, G, COLS, XP, 1>), grid, block, 0, s, p);
     else
-        hipLaunchKernelGGL((tv1d_fwd_long_kernel<T, C, G, COLS, XP, false>), grid, block, 0, s, p);
+        hipLaunchKernelGGL((tv1d_fwd_long_kernel<T, C, G, COLS, XP, 0>), grid, block, 0, s, p);
     return hipGetLastError();
 }
 

@@ -311,16 +311,150 @@ bool order_applies(const tvk::TileMap &tm)
     return tm.grouped && tm.count <= (uint32_t)kOrderMaxSlots;
 }
 
+// ---- multilevel start of long unit-stride rows ------------------------------------------
+//
+// Projected Newton from the cold start needs 8 to 25 steps on rows of thousands of samples when
+// lambda is large against the sample-to-sample variation (few, long segments: the bound set
+// changes a little with every step).  The same row averaged in groups of kMlFactor samples,
+// with lambda / kMlFactor, is the problem restricted to rows that are constant on the groups;
+// its dual, prolonged (see the WARM = 2 kernel), is a start from which the fine level needs
+// about 4 steps whatever lambda is.  Levels are stacked until a row has at most kMlCoarsest
+// samples; every level is an ordinary launch of the long-row kernel on packed scratch rows.
+// Rows whose lambda is small against their variation converge in a few steps anyway and are
+// left out (ml_flag = 0): they start cold at the fine level and are skipped at the others.
+constexpr int64_t kMlMinLength = 2048;
+constexpr int64_t kMlCoarsest = 256;
+constexpr int kMlMaxLevels = 8;
+constexpr float kMlLambdaRatio = 2.0f;     // multilevel start when lambda >= ratio * mean |y[k+1] - y[k]|
+
+struct MlPlan {
+    int levels;                       // coarse levels 1 .. levels (0 = the row itself)
+    int64_t n[kMlMaxLevels + 1];
+    size_t y_off[kMlMaxLevels + 1], u_off[kMlMaxLevels + 1], flag_off, bytes;
+};
+
+bool ml_plan(const tv_rows &r, int64_t n_rows, MlPlan *pl)
+{
+    if (r.length < kMlMinLength || r.elem_stride != 1) return false;
+    pl->levels = 0;
+    pl->n[0] = r.length;
+    size_t at = 0;
+    while (pl->n[pl->levels] > kMlCoarsest && pl->levels < kMlMaxLevels) {
+        const int l = ++pl->levels;
+        pl->n[l] = (pl->n[l - 1] + tvk::kMlFactor - 1) / tvk::kMlFactor;
+        const size_t bytes = align16((size_t)n_rows * (size_t)pl->n[l] * sizeof(float));
+        pl->y_off[l] = at; at += bytes;
+        pl->u_off[l] = at; at += bytes;
+    }
+    pl->flag_off = at;
+    pl->bytes = at + align16((size_t)n_rows * sizeof(uint32_t));
+    return pl->levels > 0;
+}
+
+// out[row][j] = mean of in[row][kMlFactor j ...] (the samples that exist); one workgroup per row.
+// FIRST: `in` is the caller's tensor (rows by L), and the row's flag is decided here from the mean
+// absolute difference of neighbouring samples inside the groups; otherwise `in` is packed,
+// n_in per row, and rows with flag 0 are skipped.
+template <bool FIRST>
+__global__ __launch_bounds__(256) void ml_average_kernel(const float *__restrict__ in,
+                                                         float *__restrict__ out,
+                                                         uint32_t *__restrict__ flag,
+                                                         const float *__restrict__ lam, tvk::Layout L,
+                                                         int32_t n_in, int32_t n_out)
+{
+    constexpr int F = tvk::kMlFactor;
+    const uint32_t row = blockIdx.x;
+    if (!FIRST && flag[row] == 0) return;
+    const float *src = in + (FIRST ? tvk::row_offset(L, row) : (int64_t)row * n_in);
+    float *dst = out + (int64_t)row * n_out;
+    const bool vec = ((uintptr_t)src % 16) == 0;
+    float var = 0.f;
+    for (int j = threadIdx.x; j < n_out; j += 256) {
+        float v[F];
+        const int k = j * F;
+        if (vec && k + F <= n_in) {
+            const float4 q = *reinterpret_cast<const float4 *>(src + k);
+            v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
+        } else {
+#pragma unroll
+            for (int r = 0; r < F; ++r) v[r] = (k + r < n_in) ? src[k + r] : 0.f;
+        }
+        float sum = 0.f, cnt = 0.f;
+#pragma unroll
+        for (int r = 0; r < F; ++r)
+            if (k + r < n_in) { sum += v[r]; cnt += 1.f; }
+        dst[j] = sum / cnt;
+        if (FIRST) {
+#pragma unroll
+            for (int r = 0; r + 1 < F; ++r)
+                if (k + r + 1 < n_in) var += fabsf(v[r + 1] - v[r]);
+        }
+    }
+    if (FIRST) {
+        __shared__ float red[256];
+        red[threadIdx.x] = var;
+        __syncthreads();
+        for (int w = 128; w > 0; w >>= 1) {
+            if ((int)threadIdx.x < w) red[threadIdx.x] += red[threadIdx.x + w];
+            __syncthreads();
+        }
+        if (threadIdx.x == 0) {
+            // differences counted: F - 1 of every F neighbouring pairs
+            const float pairs = (float)(n_in - 1) * (float)(F - 1) / (float)F;
+            const float l = tvk::load_lambda(lam, L, row);
+            flag[row] = (l * pairs >= kMlLambdaRatio * red[0]) ? 1u : 0u;
+        }
+    }
+}
+static_assert(tvk::kMlFactor == 4, "ml_average_kernel loads groups as float4");
+
+// The forward call on long rows with the multilevel start; p is the fine level, fully set up.
+int run_fwd_multilevel(FwdParams p, const tv_lambda &l, int64_t n_rows, const MlPlan &pl, char *ws,
+                       hipStream_t s)
+{
+    uint32_t *flag = (uint32_t *)(ws + pl.flag_off);
+    auto yl = [&](int lv) { return (float *)(ws + pl.y_off[lv]); };
+    auto ul = [&](int lv) { return (float *)(ws + pl.u_off[lv]); };
+    const dim3 grid((uint32_t)n_rows), block(256);
+    hipLaunchKernelGGL(ml_average_kernel<true>, grid, block, 0, s, p.y, yl(1), flag, l.lam, p.L,
+                       (int32_t)pl.n[0], (int32_t)pl.n[1]);
+    for (int lv = 2; lv <= pl.levels; ++lv)
+        hipLaunchKernelGGL(ml_average_kernel<false>, grid, block, 0, s, (const float *)yl(lv - 1), yl(lv), flag,
+                           l.lam, p.L, (int32_t)pl.n[lv - 1], (int32_t)pl.n[lv]);
+    if (launch_status() != TV_OK) return TV_ERR_HIP;
+    float scale = 1.0f;
+    for (int lv = 1; lv <= pl.levels; ++lv) scale /= (float)tvk::kMlFactor;
+    for (int lv = pl.levels; lv >= 1; --lv, scale *= (float)tvk::kMlFactor) {
+        FwdParams c = p;
+        const tv_rows rc = {1, 0, n_rows, pl.n[lv], pl.n[lv], 1};
+        c.L = make_layout(rc, l, n_rows);
+        c.y = yl(lv); c.addend = nullptr; c.x = nullptr; c.x2 = nullptr; c.resid = nullptr;
+        c.info = nullptr; c.seg = nullptr; c.order = nullptr;
+        c.dual_out = ul(lv);
+        c.ml_flag = flag; c.ml_skip = 1;
+        c.lam_scale = scale;
+        c.warm = lv == pl.levels ? 0u : 2u;
+        c.coarse_u = lv == pl.levels ? nullptr : ul(lv + 1);
+        c.coarse_n = lv == pl.levels ? 0 : (int32_t)pl.n[lv + 1];
+        if (tvk::launch_fwd_long(c, s) != hipSuccess) return TV_ERR_HIP;
+    }
+    p.warm = 2; p.coarse_u = ul(1); p.coarse_n = (int32_t)pl.n[1];
+    p.ml_flag = flag; p.ml_skip = 0;
+    return tvk::launch_fwd_long(p, s) == hipSuccess ? TV_OK : TV_ERR_HIP;
+}
+
 // ---- dispatch ---------------------------------------------------------------------
 
 int run_fwd(const float *y, const float *addend, float *x, float *resid, int32_t *info,
             uint2 *seg, uint32_t *order_ws, const tv_rows &r, const tv_lambda &l, int64_t n_rows,
-            hipStream_t s, float *x2 = nullptr, bool warm = false)
+            hipStream_t s, float *x2 = nullptr, bool warm = false, char *ml_ws = nullptr)
 {
     FwdParams p;
     p.y = y; p.addend = addend; p.x = x; p.x2 = x2; p.resid = resid; p.lam = l.lam; p.info = info;
     p.seg = seg; p.order = nullptr;
     p.warm = (warm && addend) ? 1u : 0u;
+    p.coarse_u = nullptr; p.coarse_n = 0; p.dual_out = nullptr; p.ml_flag = nullptr; p.ml_skip = 0;
+    p.lam_scale = 1.0f;
     p.L = make_layout(r, l, n_rows);
     p.tm = make_tile_map(l, n_rows);
     if (order_ws && r.length <= 32 && order_applies(p.tm)) {
@@ -343,6 +477,8 @@ int run_fwd(const float *y, const float *addend, float *x, float *resid, int32_t
     if (r.length <= 8) return launch_fwd_short<8>(p, packed, s);
     if (r.length <= 16) return launch_fwd_short<16>(p, packed, s);
     if (r.length <= 32) return launch_fwd_short<32>(p, packed, s);
+    MlPlan pl;
+    if (ml_ws && !p.warm && ml_plan(r, n_rows, &pl)) return run_fwd_multilevel(p, l, n_rows, pl, ml_ws, s);
     return tvk::launch_fwd_long(p, s) == hipSuccess ? TV_OK : TV_ERR_HIP;
 }
 
@@ -535,9 +671,12 @@ int zero_floats(float *p, int64_t n, hipStream_t s)
     return launch_status();
 }
 
-// Scratch of the forward call where the slot order applies: a uint32 per slot.
+// Scratch of the forward call: a uint32 per slot where the slot order applies (rows of up to 32
+// samples), the coarse levels where the multilevel start applies (long unit-stride rows).
 size_t fwd_workspace_bytes(const tv_rows &rows, const tv_lambda &lam, int64_t n_rows)
 {
+    MlPlan pl;
+    if (ml_plan(rows, n_rows, &pl)) return pl.bytes;
     if (rows.length > 32 || !order_applies(make_tile_map(lam, n_rows))) return 0;
     return align16((size_t)lam.count * sizeof(uint32_t));
 }
@@ -564,7 +703,7 @@ int fwd_entry(const float *y, float *x, tv_rows rows, tv_lambda lam, const tv_fw
         order_ws = (uint32_t *)e.ws;
     }
     return run_fwd(y, nullptr, x, nullptr, e.info, reinterpret_cast<uint2 *>(e.seg), order_ws, rows,
-                   lam, n_rows, s);
+                   lam, n_rows, s, nullptr, false, (char *)e.ws);
 }
 
 int bwd_entry(const float *g_up, const float *x, const uint64_t *seg, bool with_seg, float *grad_y,

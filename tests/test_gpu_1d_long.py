@@ -11,8 +11,8 @@ from parity import FWD_TOL, check_batch, forward_errors
 pytestmark = pytest.mark.gpu
 
 
-def _check(y, lam, lam_div, g, axis, label, want_info=True):
-    out = run_1d(y, lam, lam_div, g, axis=axis, want_info=want_info)
+def _check(y, lam, lam_div, g, axis, label, want_info=True, use_ws=False):
+    out = run_1d(y, lam, lam_div, g, axis=axis, want_info=want_info, use_ws=use_ws)
     yr, gr = rows_view(y, axis), rows_view(g, axis)
     lr = lam_per_row(lam, len(yr), lam_div)
     st = check_batch(yr, lr, gr, rows_view(out["x"], axis), rows_view(out["gy"], axis),
@@ -20,6 +20,8 @@ def _check(y, lam, lam_div, g, axis, label, want_info=True):
     if want_info:
         assert not np.any(out["info"] & (1 << 18)), label       # nobody hit the iteration cap
         st["max_steps"] = int((out["info"] & 0xffff).max())
+        st["steps"] = out["info"] & 0xffff
+    st["ws_bytes"] = out.get("ws_bytes", 0)
     return st
 
 
@@ -51,6 +53,50 @@ def test_every_long_length(n):
     g = rng.normal(size=y.shape).astype(np.float32)
     lam = (10 ** rng.uniform(-2.5, 1, size=rows)).astype(np.float32)
     _check(y, lam, 1, g, -1, "n=%d" % n)
+
+
+@pytest.mark.parametrize("n", [2048, 2049, 3000, 4096, 5000, 8192, 10001, 16384])
+def test_multilevel_start(n):
+    """tv1d_prox_fwd_ex with its workspace on long unit-stride rows: the solve starts from the
+    duals of the averaged rows.  Same parity bar; rows with a large lambda need far fewer steps."""
+    rng = np.random.default_rng(700 + n)
+    rows = 12 if n <= 4096 else 6
+    y = _mixed_rows(rng, rows, n)
+    g = rng.normal(size=y.shape).astype(np.float32)
+    lam = (10 ** np.linspace(-2.5, 1, rows)).astype(np.float32)        # small ones start cold
+    cold = _check(y, lam, 1, g, -1, "cold n=%d" % n)
+    ml = _check(y, lam, 1, g, -1, "multilevel n=%d" % n, use_ws=True)
+    assert ml["ws_bytes"] > 0
+    big = lam >= 1.0
+    assert ml["steps"][big].max() <= 10, (ml["steps"], cold["steps"])
+    assert ml["steps"][big].sum() < cold["steps"][big].sum(), (ml["steps"], cold["steps"])
+
+
+def test_multilevel_per_channel_lambda_and_strided_rows():
+    """Rows inside a larger buffer (row stride > length), lambda shared by groups of rows."""
+    rng = np.random.default_rng(77)
+    n, rows = 2500, 10
+    buf = np.zeros((rows, 2600), np.float32)
+    buf[:, :n] = _mixed_rows(rng, rows, n)
+    import torch
+    import paper_2204_03643_amd as tv
+    dev = torch.device("cuda:0")
+    lam = np.array([3.0, 0.02, 0.8], np.float32)
+    yt, lt = torch.from_numpy(buf).to(dev), torch.from_numpy(lam).to(dev)
+    xt = torch.full_like(yt, float("nan"))
+    r = tv.tv_rows(1, 0, rows, 2600, n, 1)
+    L = tv.tv_lambda(lt.data_ptr(), 3, 2)
+    wsb = tv.tv1d_fwd_workspace_bytes(r, L)
+    assert wsb > 0
+    ws = torch.full((wsb,), 0xff, dtype=torch.uint8, device=dev)
+    tv.tv1d_prox_fwd_ex(yt, xt, r, L, ws=ws, ws_bytes=wsb)
+    torch.cuda.synchronize()
+    x = xt.cpu().numpy()
+    assert np.isnan(x[:, n:]).all()
+    lr = lam[(np.arange(rows) // 2) % 3]
+    x_ref = oracle.prox1d_batch(buf[:, :n].astype(np.float64), lr.astype(np.float64))
+    err = forward_errors(x[:, :n], x_ref, buf[:, :n])
+    assert err.max() <= FWD_TOL, err
 
 
 @pytest.mark.parametrize("n,width", [(40, 37), (64, 16), (200, 20), (512, 48), (1500, 9), (4096, 6), (9000, 3)])
