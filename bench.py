@@ -114,7 +114,15 @@ def other_workloads(dev, reps: int = 25):
         (tf, tf_min), (tb, tb_min) = timed(fwd), timed(bwd)
         (rf, _), (rb, _) = timed(fwd, R), timed(bwd, R)
         n_rows = rows.n_outer * rows.n_inner
-        return {"rows": n_rows, "length": rows.length, "fwd_us": tf, "bwd_us": tb,
+        extra = {}
+        fwsb = tv.tv1d_fwd_workspace_bytes(rows, L)
+        if fwsb:
+            # the forward call with its workspace (slot order on short rows, multilevel start on
+            # long ones)
+            fws = torch.empty(fwsb, dtype=torch.uint8, device=dev)
+            te, te_min = timed(lambda k: tv.tv1d_prox_fwd_ex(yt[k], xt[k], rows, L, ws=fws, ws_bytes=fwsb))
+            extra = {"fwd_ex_ws_us": te, "fwd_ex_ws_us_min": te_min, "fwd_ws_bytes": fwsb}
+        return {"rows": n_rows, "length": rows.length, "fwd_us": tf, "bwd_us": tb, **extra,
                 "fwd_us_min": tf_min, "bwd_us_min": tb_min,
                 "fwd_us_rotated": rf, "bwd_us_rotated": rb, "buffer_sets": R,
                 "rows_per_s": n_rows / ((tf + tb) * 1e-6),

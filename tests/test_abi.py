@@ -137,3 +137,17 @@ def test_rows_along():
     assert (r.n_outer, r.outer_stride, r.n_inner, r.inner_stride, r.length, r.elem_stride) == (30, 7, 1, 1, 7, 1)
     r = tv.rows_along((2, 3, 5, 7), -2)
     assert (r.n_outer, r.outer_stride, r.n_inner, r.inner_stride, r.length, r.elem_stride) == (6, 35, 7, 1, 5, 7)
+
+
+def test_forward_workspace_of_long_rows():
+    lam = tv.tv_lambda(FAKE, 1, 1)
+    # unit-stride rows of 2048 samples or more: coarse levels of n/4, n/16, ... down to <= 256
+    # samples (two arrays each) plus a flag per row
+    r = tv.rows_along((10, 16384), -1)
+    assert tv.tv1d_fwd_workspace_bytes(r, lam) == 2 * 10 * (4096 + 1024 + 256) * 4 + 48
+    assert tv.tv1d_fwd_workspace_bytes(tv.rows_along((10, 2047), -1), lam) == 0
+    assert tv.tv1d_fwd_workspace_bytes(tv.rows_along((4096, 8), 0), lam) == 0          # strided rows
+    L = tv.lib()
+    need = tv.tv1d_fwd_workspace_bytes(r, lam)
+    extra = tv.tv_fwd_extra(None, None, FAKE, need - 1)
+    assert L.tv1d_prox_fwd_ex(FAKE, FAKE, r, lam, extra, None) == 5
