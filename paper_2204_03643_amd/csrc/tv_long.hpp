@@ -70,15 +70,21 @@ __device__ __forceinline__ bool chunk_vec_ok(const void *base, int64_t off, int6
            ((uintptr_t)base & 3u) == 0;
 }
 
+typedef float tv_long_v4f __attribute__((ext_vector_type(4)));
+
+// stream: the tensor is far larger than the last-level cache and touched once per call;
+// non-temporal accesses keep such streams from evicting each other.
 template <int C>
 __device__ __forceinline__ void chunk_load(const float *__restrict__ base, int64_t off, int64_t es,
-                                           int k0, int n, bool rvalid, float (&v)[C])
+                                           int k0, int n, bool rvalid, float (&v)[C], bool stream = false)
 {
     if (rvalid && chunk_vec_ok<C>(base, off, es, k0)) {
 #pragma unroll
         for (int i = 0; i < C; i += 4) {
             if (k0 + i + 3 < n) {
-                const float4 q = *reinterpret_cast<const float4 *>(base + off + k0 + i);
+                tv_long_v4f q;
+                if (stream) q = __builtin_nontemporal_load(reinterpret_cast<const tv_long_v4f *>(base + off + k0 + i));
+                else q = *reinterpret_cast<const tv_long_v4f *>(base + off + k0 + i);
                 v[i] = q.x; v[i + 1] = q.y; v[i + 2] = q.z; v[i + 3] = q.w;
             } else {
 #pragma unroll
@@ -93,14 +99,17 @@ __device__ __forceinline__ void chunk_load(const float *__restrict__ base, int64
 
 template <int C>
 __device__ __forceinline__ void chunk_store(float *__restrict__ base, int64_t off, int64_t es, int k0,
-                                            int n, bool rvalid, const float (&v)[C])
+                                            int n, bool rvalid, const float (&v)[C], bool stream = false)
 {
     if (!rvalid) return;
     if (chunk_vec_ok<C>(base, off, es, k0)) {
 #pragma unroll
         for (int i = 0; i < C; i += 4) {
             if (k0 + i + 3 < n) {
-                *reinterpret_cast<float4 *>(base + off + k0 + i) = make_float4(v[i], v[i + 1], v[i + 2], v[i + 3]);
+                tv_long_v4f q;
+                q.x = v[i]; q.y = v[i + 1]; q.z = v[i + 2]; q.w = v[i + 3];
+                if (stream) __builtin_nontemporal_store(q, reinterpret_cast<tv_long_v4f *>(base + off + k0 + i));
+                else *reinterpret_cast<tv_long_v4f *>(base + off + k0 + i) = q;
             } else {
 #pragma unroll
                 for (int e = 0; e < 4; ++e)
@@ -799,8 +808,11 @@ __global__ __launch_bounds__(T *G) void tv1d_fwd_long_kernel(FwdParams p)
 // Backward (paper Eq. 5-6 as segment averaging), one row per T threads.
 // ---------------------------------------------------------------------------------
 // XPOSE: as in the forward kernel (strided rows through an LDS tile, one row per wave).
-template <int T, int C, int G, bool COLS, bool XPOSE = false>
-__global__ __launch_bounds__(T *G) void tv1d_bwd_long_kernel(BwdParams p)
+// HAS_SUB: p.sub is given (the reverse sweep of the 2D operator).
+// Workgroups of 1024 threads ask for 8 waves per SIMD (at most 64 VGPRs), so that a CU holds two of
+// them and one's loads overlap the other's scans.
+template <int T, int C, int G, bool COLS, bool XPOSE = false, bool HAS_SUB = false>
+__global__ __launch_bounds__(T *G, (T * G == 1024 && !COLS && !HAS_SUB) ? 8 : 1) void tv1d_bwd_long_kernel(BwdParams p)
 {
     static_assert(!XPOSE || (COLS && T == 64), "the transposing variant is for strided rows on one wave");
     constexpr bool MCOLS = COLS && !XPOSE;
@@ -847,46 +859,42 @@ __global__ __launch_bounds__(T *G) void tv1d_bwd_long_kernel(BwdParams p)
         __syncthreads();
     };
 
-    float g[C], x[C], sb[C];
-    if constexpr (XPOSE) {
-        float rg[C], rx[C], rs[C];
-        fetch(p.g, rg);
-        fetch(p.x, rx);
-        if (p.sub) fetch(p.sub, rs);
-        turn(rg, g);
-        turn(rx, x);
-        if (p.sub) {
-            turn(rs, sb);
+    // g becomes the averaged quantity, then the segment means, then the output; of x only two
+    // bits per sample are kept (is there a jump behind it, and does x rise there)
+    float g[C], sb[HAS_SUB ? C : 1];
+    uint32_t jmask = 0, upmask = 0;
+    {
+        float x[C];
+        if constexpr (XPOSE) {
+            float rg[C], rx[C], rs[HAS_SUB ? C : 1];
+            fetch(p.g, rg);
+            fetch(p.x, rx);
+            if constexpr (HAS_SUB) fetch(p.sub, rs);
+            turn(rg, g);
+            turn(rx, x);
+            if constexpr (HAS_SUB) turn(rs, sb);
+        } else {
+            chunk_load<C>(p.g, off, es, k0, n, rvalid, g, p.L.stream);
+            chunk_load<C>(p.x, off, es, k0, n, rvalid, x, p.L.stream);
+            if constexpr (HAS_SUB) chunk_load<C>(p.sub, off, es, k0, n, rvalid, sb, p.L.stream);
+        }
+        if constexpr (HAS_SUB) {
 #pragma unroll
             for (int i = 0; i < C; ++i) g[i] -= sb[i];
-        } else {
-#pragma unroll
-            for (int i = 0; i < C; ++i) sb[i] = 0.f;
         }
-    } else {
-        chunk_load<C>(p.g, off, es, k0, n, rvalid, g);
-        chunk_load<C>(p.x, off, es, k0, n, rvalid, x);
-        if (p.sub) {
-            chunk_load<C>(p.sub, off, es, k0, n, rvalid, sb);
+        TV_EX(0, t) = x[0];
+        Mp::sync();
+        const float xnext0 = TV_EX(0, t + 1);
+        // jump after sample i (always at the end of the row; samples past the end are their
+        // own segments and contribute nothing)
 #pragma unroll
-            for (int i = 0; i < C; ++i) g[i] -= sb[i];
-        } else {
-#pragma unroll
-            for (int i = 0; i < C; ++i) sb[i] = 0.f;
+        for (int i = 0; i < C; ++i) {
+            const float xn = (i + 1 < C) ? x[i + 1] : xnext0;
+            if ((k0 + i >= n - 1) || (xn != x[i])) jmask |= 1u << i;
+            if (xn > x[i]) upmask |= 1u << i;
         }
     }
-    TV_EX(0, t) = x[0];
-    Mp::sync();
-    const float xnext0 = TV_EX(0, t + 1);
-
-    // jump after sample i (always at the end of the row; samples past the end are their
-    // own segments and contribute nothing)
-    bool jump[C];
-#pragma unroll
-    for (int i = 0; i < C; ++i) {
-        const float xn = (i + 1 < C) ? x[i + 1] : xnext0;
-        jump[i] = (k0 + i >= n - 1) || (xn != x[i]);
-    }
+#define TV_JUMP(i) ((jmask >> (i)) & 1u)
     // chunk-local pieces: head = samples up to and including the first jump, tail = samples
     // after the last jump; both are the whole chunk when it holds no jump
     bool any = false;
@@ -895,28 +903,28 @@ __global__ __launch_bounds__(T *G) void tv1d_bwd_long_kernel(BwdParams p)
     for (int i = 0; i < C; ++i) {
         if (!any) { head_s += g[i]; head_n += 1.f; }
         tail_s += g[i]; tail_n += 1.f;
-        if (jump[i]) { any = true; tail_s = 0.f; tail_n = 0.f; }
+        if (TV_JUMP(i)) { any = true; tail_s = 0.f; tail_n = 0.f; }
     }
     float ls, ln, rs, rn;
     seg_scan<T, G, MCOLS, +1, true>(any, tail_s, tail_n, sm.buf, j, t, ls, ln);   // open part on the left
     seg_scan<T, G, MCOLS, -1, true>(any, head_s, head_n, sm.buf, j, t, rs, rn);   // open part on the right
 
     // per-sample means: forward pass accumulates, backward pass broadcasts
-    float mean[C];
+    float (&mean)[C] = g;
     {
         float s = ls, c = ln;
 #pragma unroll
         for (int i = 0; i < C; ++i) {
             s += g[i]; c += 1.f;
             mean[i] = 0.f;
-            if (jump[i]) { mean[i] = s / c; s = 0.f; c = 0.f; }
+            if (TV_JUMP(i)) { mean[i] = s * __builtin_amdgcn_rcpf(c); s = 0.f; c = 0.f; }
         }
         // trailing open part continues into the next chunks
-        const float open_mean = (c > 0.f) ? (s + rs) / (c + rn) : 0.f;
+        const float open_mean = (c > 0.f) ? (s + rs) * __builtin_amdgcn_rcpf(c + rn) : 0.f;
         float carry = open_mean;
 #pragma unroll
         for (int i = C - 1; i >= 0; --i) {
-            if (jump[i]) carry = mean[i];
+            if (TV_JUMP(i)) carry = mean[i];
             mean[i] = carry;
         }
     }
@@ -928,16 +936,16 @@ __global__ __launch_bounds__(T *G) void tv1d_bwd_long_kernel(BwdParams p)
     float gl[1] = {0.f};
 #pragma unroll
     for (int i = 0; i < C; ++i) {
-        if (k0 + i < n - 1) {
-            const float xn = (i + 1 < C) ? x[i + 1] : xnext0;
+        if (k0 + i < n - 1 && TV_JUMP(i)) {
             const float mn = (i + 1 < C) ? mean[i + 1] : mnext0;
-            const float dx = xn - x[i];
-            const float sg = (dx > 0.f) ? 1.f : ((dx < 0.f) ? -1.f : 0.f);
+            const float sg = ((upmask >> i) & 1u) ? 1.f : -1.f;
             gl[0] = fmaf(sg, mean[i] - mn, gl[0]);
         }
     }
+    if constexpr (HAS_SUB) {
 #pragma unroll
-    for (int i = 0; i < C; ++i) mean[i] += sb[i];
+        for (int i = 0; i < C; ++i) mean[i] += sb[i];
+    }
     if constexpr (XPOSE) {
 #pragma unroll
         for (int i = 0; i < C; ++i) tile[j * TILE_PITCH + t * (C + 1) + i] = mean[i];
@@ -945,13 +953,14 @@ __global__ __launch_bounds__(T *G) void tv1d_bwd_long_kernel(BwdParams p)
         for (int k = xk0; k < T * C; k += T)
             if (xvalid && k < n) p.gy[xoff + (int64_t)k * es] = tile[xj * TILE_PITCH + k + k / C];
     } else {
-        chunk_store<C>(p.gy, off, es, k0, n, rvalid, mean);
+        chunk_store<C>(p.gy, off, es, k0, n, rvalid, mean, p.L.stream);
     }
     if (p.partial) {
         row_sum<T, G, MCOLS, 1>(gl, sm.red, j, tid);
         if (rvalid && t == 0) p.partial[row] = gl[0];
     }
 #undef TV_EX
+#undef TV_JUMP
 }
 
 // ---------------------------------------------------------------------------------
@@ -978,10 +987,11 @@ template <int T, int C, int G, bool COLS>
 inline hipError_t launch_bwd_long_t(const BwdParams &p, hipStream_t s)
 {
     const dim3 grid((p.L.n_rows + G - 1) / G), block(T * G);
-    if constexpr (COLS && T == 64)
-        hipLaunchKernelGGL((tv1d_bwd_long_kernel<T, C, G, COLS, true>), grid, block, 0, s, p);
+    constexpr bool XP = COLS && T == 64;
+    if (p.sub)
+        hipLaunchKernelGGL((tv1d_bwd_long_kernel<T, C, G, COLS, XP, true>), grid, block, 0, s, p);
     else
-        hipLaunchKernelGGL((tv1d_bwd_long_kernel<T, C, G, COLS>), grid, block, 0, s, p);
+        hipLaunchKernelGGL((tv1d_bwd_long_kernel<T, C, G, COLS, XP, false>), grid, block, 0, s, p);
     return hipGetLastError();
 }
 
