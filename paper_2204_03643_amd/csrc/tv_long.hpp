@@ -39,8 +39,8 @@ struct LongMap {
     static constexpr bool PRIVATE = !COLS && T <= 64;
     // One row per workgroup: row-wide flags are workgroup-uniform.
     static constexpr bool SOLO = G == 1;
-    __device__ static __forceinline__ int row_of(int tid) { return COLS ? tid % G : tid / T; }
-    __device__ static __forceinline__ int t_of(int tid) { return COLS ? tid / G : tid % T; }
+    __device__ static __forceinline__ int row_of(int tid) { return G == 1 ? 0 : (COLS ? tid % G : tid / T); }
+    __device__ static __forceinline__ int t_of(int tid) { return G == 1 ? tid : (COLS ? tid / G : tid % T); }
     // orders LDS writes before later LDS reads among the threads that share rows
     __device__ static __forceinline__ void sync()
     {
@@ -275,16 +275,35 @@ __device__ __forceinline__ void seg_scan(bool closed, float s, float n, float *b
                 tot[(0 * G + j) * NWR + w] = f; tot[(1 * G + j) * NWR + w] = s; tot[(2 * G + j) * NWR + w] = n;
             }
             __syncthreads();
-            float as = 0.f, an = 0.f;                         // waves before this one, in scan order
-            for (int q = 0; q < NWR; ++q) {
-                const int ww = DIR > 0 ? q : NWR - 1 - q;
-                const bool before = DIR > 0 ? (ww < w) : (ww > w);
-                if (!before) continue;
-                const float bf = tot[(0 * G + j) * NWR + ww], bs = tot[(1 * G + j) * NWR + ww],
-                            bn = tot[(2 * G + j) * NWR + ww];
-                if (bf != 0.f) { as = bs; an = bn; }
-                else if (ADD) { as += bs; an += bn; }
+            // Exclusive scan over the waves' totals, done by every wave for itself: lane q (< NWR)
+            // takes the totals of the q-th wave in scan order, a segmented inclusive scan runs
+            // over those lanes (row-shift DPP: NWR <= 16 lanes lie in one DPP row), and the wave
+            // picks the lane before its own position (a uniform index).
+            static_assert(NWR <= 16, "the waves' totals must fit one 16-lane DPP row");
+            const int wl = t & 63;
+            float bf = 0.f, bs = 0.f, bn = 0.f;
+            if (wl < NWR) {
+                const int ww = DIR > 0 ? wl : NWR - 1 - wl;
+                bf = tot[(0 * G + j) * NWR + ww]; bs = tot[(1 * G + j) * NWR + ww]; bn = tot[(2 * G + j) * NWR + ww];
             }
+#define TV_SHR(v, D) __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x110 + (D), 0xf, 0xf, true))
+#define TV_STEP(D)                                                                         \
+            if constexpr ((D) < NWR) {                                                     \
+                const float of = TV_SHR(bf, D), os = TV_SHR(bs, D), on = TV_SHR(bn, D);    \
+                if (wl >= (D) && bf == 0.f) {                                              \
+                    if (ADD) { bs += os; bn += on; } else { bs = os; bn = on; }            \
+                    bf = of;                                                               \
+                }                                                                          \
+            }
+            TV_STEP(1) TV_STEP(2) TV_STEP(4) TV_STEP(8)
+#undef TV_STEP
+#undef TV_SHR
+            const int qme = DIR > 0 ? w : NWR - 1 - w;                 // this wave's position in scan order
+            const int src = __builtin_amdgcn_readfirstlane(qme > 0 ? qme - 1 : 0);
+            float af = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(bf), src));
+            float as = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(bs), src));
+            float an = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(bn), src));
+            if (qme == 0 || (!ADD && af == 0.f)) { as = 0.f; an = 0.f; }
             // combine(waves before, lanes before)
             if (ef == 0.f) {
                 if (ADD) { es += as; en += an; } else { es = as; en = an; }
@@ -441,7 +460,8 @@ __global__ __launch_bounds__(T *G) void tv1d_fwd_long_kernel(FwdParams p)
         }
     }
     // duals past the end of the row get an empty box and never move
-#define TV_LK(i) ((k0 + (i) < M) ? lam : 0.0f)
+    const int nvd = min(max(M - k0, 0), C);            // duals of this chunk inside the row
+#define TV_LK(i) (((i) < nvd) ? lam : 0.0f)
 
     TV_EX(0, t) = y[0];
     Mp::sync();
@@ -558,7 +578,7 @@ __global__ __launch_bounds__(T *G) void tv1d_fwd_long_kernel(FwdParams p)
                 g[i] = gi;
                 const float s = copysignf(TV_LK(i), gi);
                 const bool bnd = (u[i] == -s);
-                if (k0 + i < M && u[i] == s && fabsf(gi) > gtol) viof[0] += 1.f;
+                if (i < nvd && u[i] == s && fabsf(gi) > gtol) viof[0] += 1.f;
                 if (i < C - 1) {
                     pos = bnd ? 0 : pos + 1;
                     const float gm = sm.gtab[pos];
@@ -863,6 +883,9 @@ __global__ __launch_bounds__(T *G, (T * G == 1024 && !COLS && !HAS_SUB) ? 8 : 1)
     // bits per sample are kept (is there a jump behind it, and does x rise there)
     float g[C], sb[HAS_SUB ? C : 1];
     uint32_t jmask = 0, upmask = 0;
+    // duals of this chunk that lie inside the row (dual i sits behind sample k0 + i)
+    const int nv = min(max(n - 1 - k0, 0), C);
+    const uint32_t inrow = (1u << nv) - 1u;
     {
         float x[C];
         if constexpr (XPOSE) {
@@ -874,13 +897,9 @@ __global__ __launch_bounds__(T *G, (T * G == 1024 && !COLS && !HAS_SUB) ? 8 : 1)
             turn(rx, x);
             if constexpr (HAS_SUB) turn(rs, sb);
         } else {
-            chunk_load<C>(p.g, off, es, k0, n, rvalid, g, p.L.stream);
             chunk_load<C>(p.x, off, es, k0, n, rvalid, x, p.L.stream);
+            chunk_load<C>(p.g, off, es, k0, n, rvalid, g, p.L.stream);
             if constexpr (HAS_SUB) chunk_load<C>(p.sub, off, es, k0, n, rvalid, sb, p.L.stream);
-        }
-        if constexpr (HAS_SUB) {
-#pragma unroll
-            for (int i = 0; i < C; ++i) g[i] -= sb[i];
         }
         TV_EX(0, t) = x[0];
         Mp::sync();
@@ -890,9 +909,15 @@ __global__ __launch_bounds__(T *G, (T * G == 1024 && !COLS && !HAS_SUB) ? 8 : 1)
 #pragma unroll
         for (int i = 0; i < C; ++i) {
             const float xn = (i + 1 < C) ? x[i + 1] : xnext0;
-            if ((k0 + i >= n - 1) || (xn != x[i])) jmask |= 1u << i;
+            if (xn != x[i]) jmask |= 1u << i;
             if (xn > x[i]) upmask |= 1u << i;
         }
+    }
+    const uint32_t gmask = jmask & inrow;      // jumps that count for dL/dlam
+    jmask |= ~inrow;
+    if constexpr (HAS_SUB) {
+#pragma unroll
+        for (int i = 0; i < C; ++i) g[i] -= sb[i];
     }
 #define TV_JUMP(i) ((jmask >> (i)) & 1u)
     // chunk-local pieces: head = samples up to and including the first jump, tail = samples
@@ -936,7 +961,7 @@ __global__ __launch_bounds__(T *G, (T * G == 1024 && !COLS && !HAS_SUB) ? 8 : 1)
     float gl[1] = {0.f};
 #pragma unroll
     for (int i = 0; i < C; ++i) {
-        if (k0 + i < n - 1 && TV_JUMP(i)) {
+        if ((gmask >> i) & 1u) {
             const float mn = (i + 1 < C) ? mean[i + 1] : mnext0;
             const float sg = ((upmask >> i) & 1u) ? 1.f : -1.f;
             gl[0] = fmaf(sg, mean[i] - mn, gl[0]);
