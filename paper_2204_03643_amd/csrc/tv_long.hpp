@@ -346,6 +346,17 @@ struct LongSmem {
     float red[2 * 4 * Mp::NW * Mp::RG];
 };
 
+// The backward kernel exchanges two values per thread and scans through LDS only where a row
+// spans several waves: a smaller footprint lets more workgroups share a CU.
+template <int T, int C, int G, bool COLS>
+struct LongSmemBwd {
+    using Mp = LongMap<T, G, COLS>;
+    static constexpr int TP = T + 2;
+    float ex[2][G][TP];
+    float buf[COLS ? 2 * 3 * G * T : (T > 64 ? 2 * 3 * G * (T / 64) : 1)];
+    float red[2 * 4 * Mp::NW * Mp::RG];
+};
+
 // ---------------------------------------------------------------------------------
 // Forward: projected Newton on the dual (paper Eq. 3-4), one row per T threads.
 // ---------------------------------------------------------------------------------
@@ -837,7 +848,7 @@ __global__ __launch_bounds__(T *G, (T * G == 1024 && !COLS && !HAS_SUB) ? 8 : 1)
     static_assert(!XPOSE || (COLS && T == 64), "the transposing variant is for strided rows on one wave");
     constexpr bool MCOLS = COLS && !XPOSE;
     using Mp = LongMap<T, G, MCOLS>;
-    __shared__ LongSmem<T, C, G, MCOLS> sm;
+    __shared__ LongSmemBwd<T, C, G, MCOLS> sm;
     constexpr int TILE_PITCH = T * (C + 1) + 1;
     __shared__ float tile[XPOSE ? G * TILE_PITCH : 1];
     const int tid = threadIdx.x;
@@ -849,7 +860,7 @@ __global__ __launch_bounds__(T *G, (T * G == 1024 && !COLS && !HAS_SUB) ? 8 : 1)
     const int k0 = t * C;
     if (t == 0) {
 #pragma unroll
-        for (int q = 0; q < 5; ++q) { sm.ex[q][j][0] = 0.f; sm.ex[q][j][T + 1] = 0.f; }
+        for (int q = 0; q < 2; ++q) { sm.ex[q][j][0] = 0.f; sm.ex[q][j][T + 1] = 0.f; }
     }
     const int64_t off = rvalid ? row_offset(p.L, row) : 0;
     const int64_t es = p.L.elem_stride;
