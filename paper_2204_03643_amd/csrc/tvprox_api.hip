@@ -6,6 +6,7 @@
 
 #include "tv_common.hpp"
 #include "tv_long.hpp"
+#include "tv_small2d.hpp"
 #include "tv_short.hpp"
 
 namespace {
@@ -913,6 +914,21 @@ int tv2d_prox_bwd(const float *g_up, float *grad_y, float *grad_lam, int64_t pla
     //   Bbar = Qbar' + C^T(Ybar' - Qbar'),   Qbar = Bbar,
     //   Abar = Pbar' + R^T(Bbar - Pbar'),    Ybar = Pbar = Abar.
     // Ybar and Pbar coincide from the second reverse step on, so two tensors carry the state.
+    if (cb) {
+        // planes of at most 32 x 32: the whole reverse sweep in one launch, state resident in LDS
+        tvk::Small2dBwdParams q;
+        q.g_up = g_up; q.gy = grad_y; q.codes = codes(0); q.code_stride = cb / sizeof(uint2);
+        q.partial = grad_lam ? partial(0) : nullptr;
+        q.planes = (int32_t)planes; q.H = (int32_t)H; q.W = (int32_t)W; q.sweeps = sweeps;
+        q.stream = (planes * H * W >= ((int64_t)32 << 20) / 4) ? 1u : 0u;
+        const dim3 grid((uint32_t)((planes + 1) / 2));
+        if (H == 32 && W == 32) hipLaunchKernelGGL(tvk::tv2d_bwd_small_kernel<true>, grid, dim3(64), 0, stream, q);
+        else hipLaunchKernelGGL(tvk::tv2d_bwd_small_kernel<false>, grid, dim3(64), 0, stream, q);
+        if (launch_status() != TV_OK) return TV_ERR_HIP;
+        if (!grad_lam) return TV_OK;
+        const tv_lambda lp = {lam.lam, lam.count, 1};
+        return launch_reduce_lambda(partial(0), grad_lam, planes, lp, 0, stream);
+    }
     for (int k = sweeps - 1; k >= 0; --k) {
         const bool first = (k == sweeps - 1);
         st = run_bwd(first ? g_up : Ab, first ? nullptr : Bb, cb ? nullptr : saved(2 * k + 1), codes(2 * k + 1),
