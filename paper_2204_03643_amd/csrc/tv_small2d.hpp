@@ -74,7 +74,7 @@ __global__ __launch_bounds__(64) void tv2d_bwd_small_kernel(Small2dBwdParams p)
     const bool pvalid = plane < p.planes;
     const int n_here = (plane0 + 1 < p.planes) ? 2 : 1;
 
-    // the upstream gradient of the two planes -> A (entries outside H x W are never read)
+    // the upstream gradient of the two planes -> A
     {
         const float *src = p.g_up + plane0 * HW;
         if (FULL && ((uintptr_t)src % 16) == 0) {
@@ -97,42 +97,70 @@ __global__ __launch_bounds__(64) void tv2d_bwd_small_kernel(Small2dBwdParams p)
 
     float glam = 0.f;
     float v[32];
+    // the segment code of a pass is fetched one pass ahead, so that its latency hides behind
+    // the pass before
+    const bool cvalid = pvalid && (FULL || idx < W), rvalid = pvalid && (FULL || idx < H);
+    auto fetch_code = [&](int pass) -> uint2 {
+        if (pass < 0) return make_uint2(0u, 0u);
+        const bool col = (pass & 1) != 0;
+        if (!(col ? cvalid : rvalid)) return make_uint2(0u, 0u);
+        return p.codes[(size_t)pass * p.code_stride + (size_t)plane * (col ? W : H) + idx];
+    };
+    uint2 code_next = fetch_code(2 * p.sweeps - 1);
     for (int k = p.sweeps - 1; k >= 0; --k) {
         const bool first = (k == p.sweeps - 1);
         // ---- adjoint of the column pass: B <- C^T(A - B) + B  (B = 0 in the first reverse step);
         //      a lane holds column idx of its plane
         {
-            const bool valid = pvalid && (FULL || idx < W);
-            uint2 code = make_uint2(0u, 0u);
-            if (valid) code = p.codes[(size_t)(2 * k + 1) * p.code_stride + (size_t)plane * W + idx];
+            const bool valid = cvalid;
+            const uint2 code = code_next;
+            code_next = fetch_code(2 * k);
             const float *a = A + (h * 32) * P + idx;
             float *b = B + (h * 32) * P + idx;
+            // (tile entries outside H x W, and the tile half of a plane that does not exist, hold
+            // garbage that stays where it is: a segment never extends past the row's end)
+            if (first) {
 #pragma unroll
-            for (int r = 0; r < 32; ++r)
-                v[r] = (valid && (FULL || r < H)) ? (first ? a[r * P] : a[r * P] - b[r * P]) : 0.f;
+                for (int r = 0; r < 32; ++r) v[r] = a[r * P];
+            } else {
+#pragma unroll
+                for (int r = 0; r < 32; ++r) v[r] = a[r * P] - b[r * P];
+            }
             const float t = small2d_segment_means<FULL>(v, code, H, rtab);
             if (valid) glam += t;
+            if (first) {
 #pragma unroll
-            for (int r = 0; r < 32; ++r)
-                if (valid && (FULL || r < H)) b[r * P] = first ? v[r] : v[r] + b[r * P];
+                for (int r = 0; r < 32; ++r) b[r * P] = v[r];
+            } else {
+#pragma unroll
+                for (int r = 0; r < 32; ++r) b[r * P] += v[r];
+            }
         }
         wave_lds_sync();
         // ---- adjoint of the row pass: A <- R^T(B - A) + A  (without A in the first reverse step);
         //      a lane holds row idx of its plane
         {
-            const bool valid = pvalid && (FULL || idx < H);
-            uint2 code = make_uint2(0u, 0u);
-            if (valid) code = p.codes[(size_t)(2 * k) * p.code_stride + (size_t)plane * H + idx];
+            const bool valid = rvalid;
+            const uint2 code = code_next;
+            code_next = fetch_code(2 * k - 1);
             float *a = A + (h * 32 + idx) * P;
             const float *b = B + (h * 32 + idx) * P;
+            if (first) {
 #pragma unroll
-            for (int c = 0; c < 32; ++c)
-                v[c] = (valid && (FULL || c < W)) ? (first ? b[c] : b[c] - a[c]) : 0.f;
+                for (int c = 0; c < 32; ++c) v[c] = b[c];
+            } else {
+#pragma unroll
+                for (int c = 0; c < 32; ++c) v[c] = b[c] - a[c];
+            }
             const float t = small2d_segment_means<FULL>(v, code, W, rtab);
             if (valid) glam += t;
+            if (first) {
 #pragma unroll
-            for (int c = 0; c < 32; ++c)
-                if (valid && (FULL || c < W)) a[c] = first ? v[c] : v[c] + a[c];
+                for (int c = 0; c < 32; ++c) a[c] = v[c];
+            } else {
+#pragma unroll
+                for (int c = 0; c < 32; ++c) a[c] += v[c];
+            }
         }
         wave_lds_sync();
     }
