@@ -217,6 +217,83 @@ __device__ __forceinline__ void tile_add(TileRegs<NMAX> &a, const TileRegs<NMAX>
     }
 }
 
+// ---- the rows are the columns of contiguous 32 x 32 planes (the column pass of the 2D operator
+//      on such planes): a wave's 64 rows are the columns of two planes, each plane a contiguous
+//      4 KB block.  The planes move with coalesced 16-byte accesses through the wave's tile
+//      (memory rows at pitch 33), and a lane reads or writes its column there, conflict-free.
+struct PlanePair {
+    uint32_t row[2];       // row id of column 0 of each plane; offsets are recomputed where they
+                           // are used, so that only two scalars stay live across the solve
+    __device__ __forceinline__ bool there(const Layout &L, int hh) const { return row[hh] < L.n_rows; }
+    // 32 x 32 planes: row / 32 is the plane
+    __device__ __forceinline__ int64_t base(const Layout &L, int hh) const
+    {
+        return (int64_t)(row[hh] >> 5) * L.outer_stride;
+    }
+};
+
+// global -> registers, in plane order (coalesced)
+__device__ __forceinline__ void planes_fetch(const float *__restrict__ src, const PlanePair &pp,
+                                             const Layout &L, int lane, TileRegs<32> &t)
+{
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int hh = i >> 2, e = ((i & 3) * 64 + lane) * 4;
+        t.q[i] = pp.there(L, hh) ? load16(src + pp.base(L, hh) + e, L.stream)
+                                 : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+}
+
+// registers in plane order -> the tile (memory rows at pitch 33)
+__device__ __forceinline__ void planes_into_tile(const TileRegs<32> &t, float *tile, int lane)
+{
+    wave_lds_sync();                       // earlier readers of the tile are done
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int hh = i >> 2, e = ((i & 3) * 64 + lane) * 4;
+        float *d = tile + (hh * 32 + (e >> 5)) * 33 + (e & 31);
+        d[0] = t.q[i].x; d[1] = t.q[i].y; d[2] = t.q[i].z; d[3] = t.q[i].w;
+    }
+    wave_lds_sync();
+}
+
+__device__ __forceinline__ const float *plane_column(const float *tile, int lane)
+{
+    return tile + ((lane >> 5) * 32) * 33 + (lane & 31);
+}
+
+__device__ __forceinline__ void planes_to_columns(const float *__restrict__ src, const PlanePair &pp,
+                                                  const Layout &L, float *tile, int lane, float (&v)[32])
+{
+    TileRegs<32> t;
+    planes_fetch(src, pp, L, lane, t);
+    planes_into_tile(t, tile, lane);
+    const float *col = plane_column(tile, lane);
+#pragma unroll
+    for (int k = 0; k < 32; ++k) v[k] = col[k * 33];
+}
+
+__device__ __forceinline__ void columns_to_planes(const float (&v)[32], float *tile, int lane,
+                                                  float *__restrict__ dst, float *__restrict__ dst2,
+                                                  const PlanePair &pp, const Layout &L)
+{
+    wave_lds_sync();
+    float *col = tile + ((lane >> 5) * 32) * 33 + (lane & 31);
+#pragma unroll
+    for (int k = 0; k < 32; ++k) col[k * 33] = v[k];
+    wave_lds_sync();
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int hh = i >> 2, e = ((i & 3) * 64 + lane) * 4;
+        const float *sp = tile + (hh * 32 + (e >> 5)) * 33 + (e & 31);
+        const float4 q = make_float4(sp[0], sp[1], sp[2], sp[3]);
+        if (pp.there(L, hh)) {
+            store16(dst + pp.base(L, hh) + e, q, L.stream);
+            if (dst2) store16(dst2 + pp.base(L, hh) + e, q, L.stream);
+        }
+    }
+}
+
 template <int NMAX, bool FULL>
 __device__ __forceinline__ void row_load_strided(const float *__restrict__ src,
                                                  const float *__restrict__ add, int64_t off,
@@ -545,7 +622,8 @@ struct RowSolver {
 // for each other.  With a grouped grid the slots may be visited in a given order (p.order).
 // ---------------------------------------------------------------------------------
 // WARM: p.addend is given and the solve starts from the dual it encodes (see start_warm).
-template <int NMAX, bool FULL, bool PACKED, bool WARM = false>
+// PLANE (NMAX = 32, FULL, not PACKED): the rows are the columns of contiguous 32 x 32 planes.
+template <int NMAX, bool FULL, bool PACKED, bool WARM = false, bool PLANE = false>
 __global__ __launch_bounds__(kShortBlock) TV_FWD_ATTR void tv1d_fwd_short_kernel(FwdParams p)
 {
     using S = ShortSmem<NMAX>;
@@ -567,10 +645,37 @@ __global__ __launch_bounds__(kShortBlock) TV_FWD_ATTR void tv1d_fwd_short_kernel
     if (p.tm.grouped) lam = fmaxf(p.lam[slot], 0.f);            // one slot per tile
     else if (valid) lam = load_lambda(p.lam, p.L, row);
     const int64_t off = (!PACKED && valid) ? row_offset(p.L, row) : 0;
+    static_assert(!PLANE || (NMAX == 32 && FULL && !PACKED), "plane columns: 32 x 32 planes only");
+    PlanePair pp = {{0u, 0u}};
+    if constexpr (PLANE) {
+        pp.row[0] = __builtin_amdgcn_readfirstlane(p.tm.row(r0, 0));
+        pp.row[1] = __builtin_amdgcn_readfirstlane(p.tm.row(r0, 32));
+    }
 
     float y[NMAX], xs[NMAX];
     RowSolver<NMAX, FULL> sv;
-    if constexpr (PACKED) {
+    if constexpr (PLANE) {
+        TileRegs<32> t, a;
+        planes_fetch(p.y, pp, p.L, lane, t);
+        const bool has_add = WARM || p.addend;
+        if (has_add) {
+            planes_fetch(p.addend, pp, p.L, lane, a);
+            tile_add<32>(t, a, 1.f);
+        }
+        planes_into_tile(t, tile, lane);
+        const float *col = plane_column(tile, lane);
+#pragma unroll
+        for (int k = 0; k < NMAX; ++k) y[k] = col[k * 33];
+        if constexpr (WARM) {
+            planes_into_tile(a, tile, lane);
+            float run = 0.f;
+#pragma unroll
+            for (int k = 0; k < NMAX - 1; ++k) {
+                run -= col[k * 33];
+                sv.u[k] = run;
+            }
+        }
+    } else if constexpr (PACKED) {
         TileRegs<NMAX> t;
         tile_fetch<NMAX>(p.y, p.tm, r0, p.L.n_rows, lane, t, p.L.stream);
         if (WARM || p.addend) {
@@ -605,7 +710,10 @@ __global__ __launch_bounds__(kShortBlock) TV_FWD_ATTR void tv1d_fwd_short_kernel
 #pragma unroll
         for (int k = 0; k < NMAX; ++k) rs[k] = tile[k * 64 + lane] - xs[k];
     }
-    if constexpr (PACKED) {
+    if constexpr (PLANE) {
+        columns_to_planes(xs, tile, lane, p.x, p.x2, pp, p.L);
+        if (want_resid) columns_to_planes(rs, tile, lane, p.resid, nullptr, pp, p.L);
+    } else if constexpr (PACKED) {
         TileRegs<NMAX> t;
         rows_to_tile<NMAX>(xs, tile, lane, t);
         tile_put<NMAX>(p.x, p.tm, r0, p.L.n_rows, lane, t, p.L.stream);
@@ -646,7 +754,8 @@ __global__ __launch_bounds__(kShortBlock) TV_FWD_ATTR void tv1d_fwd_short_kernel
 //   grad_y   = per-segment mean of (g - sub), plus sub;
 //   dL/dlam  = sum over jumps k of sign(x[k+1]-x[k]) * (mean_left - mean_right).
 // ---------------------------------------------------------------------------------
-template <int NMAX, bool FULL, bool PACKED, bool HAS_SUB, bool SEG>
+// PLANE: as in the forward kernel.
+template <int NMAX, bool FULL, bool PACKED, bool HAS_SUB, bool SEG, bool PLANE = false>
 __global__ __launch_bounds__(kShortBlock) void tv1d_bwd_short_kernel(BwdParams p)
 {
     using S = ShortSmem<NMAX>;
@@ -670,7 +779,20 @@ __global__ __launch_bounds__(kShortBlock) void tv1d_bwd_short_kernel(BwdParams p
     if constexpr (SEG) { if (valid) code = p.seg[row]; }
     float sb[NMAX];                   // sub per row (strided path)
     TileRegs<NMAX> st;                // sub in tile order, kept until the store (packed path)
-    if constexpr (PACKED) {
+    static_assert(!PLANE || (NMAX == 32 && FULL && !PACKED), "plane columns: 32 x 32 planes only");
+    PlanePair pp = {{0u, 0u}};
+    if constexpr (PLANE) {
+        pp.row[0] = __builtin_amdgcn_readfirstlane(r0);
+        pp.row[1] = __builtin_amdgcn_readfirstlane(r0 + 32);
+        planes_to_columns(p.g, pp, p.L, tile, lane, g);
+        if constexpr (!SEG) planes_to_columns(p.x, pp, p.L, tile, lane, x);
+        if constexpr (HAS_SUB) {
+            planes_to_columns(p.sub, pp, p.L, tile, lane, sb);
+#pragma unroll
+            for (int k = 0; k < NMAX; ++k) g[k] -= sb[k];
+        }
+        wave_lds_sync();
+    } else if constexpr (PACKED) {
         TileRegs<NMAX> tg, tx;
         tile_fetch<NMAX>(p.g, tm, r0, p.L.n_rows, lane, tg, p.L.stream);
         if constexpr (!SEG) tile_fetch<NMAX>(p.x, tm, r0, p.L.n_rows, lane, tx, p.L.stream);
@@ -730,7 +852,13 @@ __global__ __launch_bounds__(kShortBlock) void tv1d_bwd_short_kernel(BwdParams p
             if (k + 1 < NMAX && (FULL || k < n - 1)) glam += signed_by_jump(k, carry - right);
         }
     }
-    if constexpr (PACKED) {
+    if constexpr (PLANE) {
+        if constexpr (HAS_SUB) {
+#pragma unroll
+            for (int k = 0; k < NMAX; ++k) g[k] += sb[k];
+        }
+        columns_to_planes(g, tile, lane, p.gy, nullptr, pp, p.L);
+    } else if constexpr (PACKED) {
         TileRegs<NMAX> t;
         rows_to_tile<NMAX>(g, tile, lane, t);
         if constexpr (HAS_SUB) tile_add<NMAX>(t, st, 1.f);

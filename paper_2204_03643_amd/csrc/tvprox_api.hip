@@ -106,6 +106,13 @@ bool rows_packed(const tv_rows &r)
     return true;
 }
 
+// Rows that are the columns of contiguous 32 x 32 planes (row id = plane * 32 + column).
+bool rows_are_plane_columns(const tv_rows &r)
+{
+    return r.length == 32 && r.elem_stride == 32 && r.n_inner == 32 && r.inner_stride == 1 &&
+           (r.n_outer == 1 || (r.outer_stride >= 1024 && r.outer_stride % 4 == 0));
+}
+
 int launch_status()
 {
     return hipGetLastError() == hipSuccess ? TV_OK : TV_ERR_HIP;
@@ -114,7 +121,7 @@ int launch_status()
 // ---- short rows: one row per lane ---------------------------------------------------
 
 template <int NMAX>
-int launch_fwd_short(const FwdParams &p, bool packed_ok, hipStream_t s)
+int launch_fwd_short(const FwdParams &p, bool packed_ok, hipStream_t s, bool plane_ok = false)
 {
     constexpr uint32_t wpb = tvk::kShortBlock / 64;
     const uint32_t n_tiles = (p.L.n_rows + 63u) / 64u;
@@ -122,6 +129,14 @@ int launch_fwd_short(const FwdParams &p, bool packed_ok, hipStream_t s)
     static_assert(wpb == 1, "the grouped grid below assumes one tile per workgroup");
     if (p.tm.grouped) grid = dim3(n_tiles / p.tm.count, p.tm.count);
     const bool full = p.L.n == NMAX;
+    if constexpr (NMAX == 32) {
+        // (the warm-start variant of the plane mode runs out of scalar registers and loses a wave of
+        // occupancy to the spill; warm column passes keep the strided accesses)
+        if (plane_ok && full && !p.warm) {
+            hipLaunchKernelGGL((tvk::tv1d_fwd_short_kernel<32, true, false, false, true>), grid, block, 0, s, p);
+            return launch_status();
+        }
+    }
     if (p.warm) {
         if (full && packed_ok)
             hipLaunchKernelGGL((tvk::tv1d_fwd_short_kernel<NMAX, true, true, true>), grid, block, 0, s, p);
@@ -139,10 +154,16 @@ int launch_fwd_short(const FwdParams &p, bool packed_ok, hipStream_t s)
 }
 
 template <int NMAX, bool HAS_SUB, bool SEG>
-int launch_bwd_short(const BwdParams &p, bool packed_ok, hipStream_t s)
+int launch_bwd_short(const BwdParams &p, bool packed_ok, hipStream_t s, bool plane_ok)
 {
     const dim3 grid((p.L.n_rows + tvk::kShortBlock - 1) / tvk::kShortBlock), block(tvk::kShortBlock);
     const bool full = p.L.n == NMAX;
+    if constexpr (NMAX == 32) {
+        if (plane_ok && full) {
+            hipLaunchKernelGGL((tvk::tv1d_bwd_short_kernel<32, true, false, HAS_SUB, SEG, true>), grid, block, 0, s, p);
+            return launch_status();
+        }
+    }
     if (full && packed_ok)
         hipLaunchKernelGGL((tvk::tv1d_bwd_short_kernel<NMAX, true, true, HAS_SUB, SEG>), grid, block, 0, s, p);
     else if (full)
@@ -153,13 +174,13 @@ int launch_bwd_short(const BwdParams &p, bool packed_ok, hipStream_t s)
 }
 
 template <int NMAX>
-int launch_bwd_short(const BwdParams &p, bool packed_ok, hipStream_t s)
+int launch_bwd_short(const BwdParams &p, bool packed_ok, hipStream_t s, bool plane_ok = false)
 {
     if (p.seg)
-        return p.sub ? launch_bwd_short<NMAX, true, true>(p, packed_ok, s)
-                     : launch_bwd_short<NMAX, false, true>(p, packed_ok, s);
-    return p.sub ? launch_bwd_short<NMAX, true, false>(p, packed_ok, s)
-                 : launch_bwd_short<NMAX, false, false>(p, packed_ok, s);
+        return p.sub ? launch_bwd_short<NMAX, true, true>(p, packed_ok, s, plane_ok)
+                     : launch_bwd_short<NMAX, false, true>(p, packed_ok, s, plane_ok);
+    return p.sub ? launch_bwd_short<NMAX, true, false>(p, packed_ok, s, plane_ok)
+                 : launch_bwd_short<NMAX, false, false>(p, packed_ok, s, plane_ok);
 }
 
 // ---- slot order for the grouped grid -----------------------------------------------
@@ -477,7 +498,12 @@ int run_fwd(const float *y, const float *addend, float *x, float *resid, int32_t
                         (!addend || aligned16(addend)) && (!resid || aligned16(resid));
     if (r.length <= 8) return launch_fwd_short<8>(p, packed, s);
     if (r.length <= 16) return launch_fwd_short<16>(p, packed, s);
-    if (r.length <= 32) return launch_fwd_short<32>(p, packed, s);
+    if (r.length <= 32) {
+        const bool planes = rows_are_plane_columns(r) && aligned16(y) && aligned16(x) &&
+                            (!addend || aligned16(addend)) && (!resid || aligned16(resid)) &&
+                            (!x2 || aligned16(x2));
+        return launch_fwd_short<32>(p, packed, s, planes);
+    }
     MlPlan pl;
     if (ml_ws && !p.warm && ml_plan(r, n_rows, &pl)) return run_fwd_multilevel(p, l, n_rows, pl, ml_ws, s);
     return tvk::launch_fwd_long(p, s) == hipSuccess ? TV_OK : TV_ERR_HIP;
@@ -647,7 +673,11 @@ int run_bwd(const float *g, const float *sub, const float *x, const uint2 *seg, 
     const int64_t red_rows = ps.red_rows, red_div = ps.red_div;
     if (r.length <= 8) st = launch_bwd_short<8>(p, packed, s);
     else if (r.length <= 16) st = launch_bwd_short<16>(p, packed, s);
-    else if (r.length <= 32) st = launch_bwd_short<32>(p, packed, s);
+    else if (r.length <= 32) {
+        const bool planes = rows_are_plane_columns(r) && aligned16(g) && (!x || aligned16(x)) &&
+                            aligned16(gy) && (!sub || aligned16(sub));
+        st = launch_bwd_short<32>(p, packed, s, planes);
+    }
     else st = tvk::launch_bwd_long(p, s) == hipSuccess ? TV_OK : TV_ERR_HIP;
     if (st != TV_OK) return st;
     if (grad_lam && reduce_now) {
