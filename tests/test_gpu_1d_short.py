@@ -167,3 +167,35 @@ def test_input_scale(scale):
     err = np.abs(out["x"] - xr).max(1) / np.abs(ys).max(1)
     assert err.max() <= 1e-5, err.max()                            # relative to the row's own scale
     check_batch(y, lam, g, (out["x"] / np.float32(scale)).astype(np.float32), None, label="scale %g" % scale)
+
+
+@pytest.mark.parametrize("planes,pitch,count", [(5, 1024, 1), (7, 1280, 3), (8, 1024, 4)])
+def test_columns_of_32x32_planes(planes, pitch, count):
+    """The column pass on contiguous 32 x 32 planes moves whole planes through LDS: an odd number
+    of planes (half-empty last wave), planes that are not adjacent in memory, lambda per plane
+    group; forward and backward, against the oracle column by column."""
+    import torch
+
+    import paper_2204_03643_amd as tv
+
+    rng = np.random.default_rng(planes * 7 + count)
+    buf = rng.normal(size=(planes, pitch)).astype(np.float32)
+    gbuf = rng.normal(size=(planes, pitch)).astype(np.float32)
+    lam = (10 ** rng.uniform(-1.5, 0.5, size=count)).astype(np.float32)
+    dev = torch.device("cuda:0")
+    yt, gt, lt = (torch.from_numpy(a).to(dev) for a in (buf, gbuf, lam))
+    xt, gy = torch.full_like(yt, float("nan")), torch.full_like(yt, float("nan"))
+    gl = torch.full((count,), float("nan"), device=dev)
+    r = tv.tv_rows(planes, pitch, 32, 1, 32, 32)          # row id = plane * 32 + column
+    L = tv.tv_lambda(lt.data_ptr(), count, 32)
+    wsb = tv.tv1d_bwd_workspace_bytes(r, L)
+    ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device=dev)
+    tv.tv1d_prox_fwd(yt, xt, r, L)
+    tv.tv1d_prox_bwd(gt, xt, gy, gl, r, L, ws, wsb)
+    torch.cuda.synchronize()
+    x, gyn = xt.cpu().numpy(), gy.cpu().numpy()
+    assert np.isnan(x[:, 1024:]).all() and np.isnan(gyn[:, 1024:]).all()      # nothing outside the planes
+    cols = lambda a: a[:, :1024].reshape(planes, 32, 32).transpose(0, 2, 1).reshape(-1, 32)
+    lr = lam[(np.arange(planes * 32) // 32) % count]
+    check_batch(cols(buf), lr, cols(gbuf), cols(x), cols(gyn), gl_gpu=gl.cpu().numpy(), lam_count=count,
+                lam_div=32, label="plane columns %d/%d/%d" % (planes, pitch, count))
