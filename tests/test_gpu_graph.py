@@ -98,3 +98,60 @@ def test_2d_step_replays_from_a_graph():
         graph.replay()
         torch.cuda.synchronize()
         assert torch.equal(xt, ref[0]) and torch.equal(gy, ref[1]) and torch.equal(gl, ref[2]), rep
+
+
+def test_long_rows_and_large_planes_replay_from_a_graph():
+    """Long rows with the multilevel start (averaging kernels, coarse levels, fine level) and the
+    2D operator on planes beyond 32 x 32 (warm-started passes, transposing column kernels, split
+    dL/dlam reduction): every replay must reproduce the eager result bit for bit."""
+    import torch
+
+    import paper_2204_03643_amd as tv
+
+    dev = torch.device("cuda:0")
+    rng = np.random.default_rng(17)
+    n, n_rows = 2500, 9
+    y1 = np.cumsum(rng.normal(scale=0.05, size=(n_rows, n)), axis=1).astype(np.float32)
+    lam1 = (10 ** np.linspace(-2, 0.7, n_rows)).astype(np.float32)
+    y1t, l1t = torch.from_numpy(y1).to(dev), torch.from_numpy(lam1).to(dev)
+    x1t = torch.empty_like(y1t)
+    r1 = tv.rows_along(y1.shape, -1)
+    L1 = tv.tv_lambda(l1t.data_ptr(), n_rows, 1)
+    fwsb = tv.tv1d_fwd_workspace_bytes(r1, L1)
+    assert fwsb > 0
+    fws = torch.empty(fwsb, dtype=torch.uint8, device=dev)
+
+    planes, H, W, K = 3, 70, 48, 3
+    y2 = rng.normal(size=(planes, H, W)).astype(np.float32)
+    g2 = rng.normal(size=(planes, H, W)).astype(np.float32)
+    y2t, g2t = torch.from_numpy(y2).to(dev), torch.from_numpy(g2).to(dev)
+    l2t = torch.tensor([0.4], device=dev)
+    x2t, gy2, gl2 = torch.empty_like(y2t), torch.empty_like(y2t), torch.empty_like(l2t)
+    L2 = tv.tv_lambda(l2t.data_ptr(), 1, 1)
+    wsb = tv.tv2d_workspace_bytes(planes, H, W, K)
+    ws = torch.empty(wsb, dtype=torch.uint8, device=dev)
+
+    def step():
+        tv.tv1d_prox_fwd_ex(y1t, x1t, r1, L1, ws=fws, ws_bytes=fwsb)
+        tv.tv2d_prox_fwd(y2t, x2t, planes, H, W, L2, K, ws, wsb)
+        tv.tv2d_prox_bwd(g2t, gy2, gl2, planes, H, W, L2, K, ws, wsb)
+
+    step()
+    torch.cuda.synchronize()
+    ref = [t.clone() for t in (x1t, x2t, gy2, gl2)]
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.current_stream().wait_stream(side)
+    for rep in range(3):
+        for t in (x1t, x2t, gy2, gl2):
+            t.zero_()
+        fws.fill_(0xff)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for a, b in zip((x1t, x2t, gy2, gl2), ref):
+            assert torch.equal(a, b), rep
