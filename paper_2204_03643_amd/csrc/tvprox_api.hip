@@ -348,6 +348,7 @@ constexpr int64_t kMlMinLength = 2048;
 constexpr int64_t kMlCoarsest = 256;
 constexpr int kMlMaxLevels = 8;
 constexpr float kMlLambdaRatio = 2.0f;     // multilevel start when lambda >= ratio * mean |y[k+1] - y[k]|
+constexpr int kMlProbeGroups = 512;        // ... judged on the row's first 2048 samples
 
 struct MlPlan {
     int levels;                       // coarse levels 1 .. levels (0 = the row itself)
@@ -390,9 +391,7 @@ __global__ __launch_bounds__(256) void ml_average_kernel(const float *__restrict
     const float *src = in + (FIRST ? tvk::row_offset(L, row) : (int64_t)row * n_in);
     float *dst = out + (int64_t)row * n_out;
     const bool vec = ((uintptr_t)src % 16) == 0;
-    float var = 0.f;
-    for (int j = threadIdx.x; j < n_out; j += 256) {
-        float v[F];
+    auto group = [&](int j, float (&v)[F]) {
         const int k = j * F;
         if (vec && k + F <= n_in) {
             const float4 q = *reinterpret_cast<const float4 *>(src + k);
@@ -401,19 +400,21 @@ __global__ __launch_bounds__(256) void ml_average_kernel(const float *__restrict
 #pragma unroll
             for (int r = 0; r < F; ++r) v[r] = (k + r < n_in) ? src[k + r] : 0.f;
         }
-        float sum = 0.f, cnt = 0.f;
-#pragma unroll
-        for (int r = 0; r < F; ++r)
-            if (k + r < n_in) { sum += v[r]; cnt += 1.f; }
-        dst[j] = sum / cnt;
-        if (FIRST) {
+    };
+    if (FIRST) {
+        // the row's variation is judged on its first kMlProbeGroups groups; a row that stays
+        // out of the multilevel start needs no averages
+        __shared__ float red[256];
+        __shared__ uint32_t decision;
+        const int probe = n_out < kMlProbeGroups ? n_out : kMlProbeGroups;
+        float var = 0.f;
+        for (int j = threadIdx.x; j < probe; j += 256) {
+            float v[F];
+            group(j, v);
 #pragma unroll
             for (int r = 0; r + 1 < F; ++r)
-                if (k + r + 1 < n_in) var += fabsf(v[r + 1] - v[r]);
+                if (j * F + r + 1 < n_in) var += fabsf(v[r + 1] - v[r]);
         }
-    }
-    if (FIRST) {
-        __shared__ float red[256];
         red[threadIdx.x] = var;
         __syncthreads();
         for (int w = 128; w > 0; w >>= 1) {
@@ -421,11 +422,24 @@ __global__ __launch_bounds__(256) void ml_average_kernel(const float *__restrict
             __syncthreads();
         }
         if (threadIdx.x == 0) {
-            // differences counted: F - 1 of every F neighbouring pairs
-            const float pairs = (float)(n_in - 1) * (float)(F - 1) / (float)F;
+            // differences counted: F - 1 of every F neighbouring pairs of the probed samples
+            const int last = probe * F < n_in ? probe * F : n_in;
+            const float pairs = (float)(last - 1) * (float)(F - 1) / (float)F;
             const float l = tvk::load_lambda(lam, L, row);
-            flag[row] = (l * pairs >= kMlLambdaRatio * red[0]) ? 1u : 0u;
+            decision = (l * pairs >= kMlLambdaRatio * red[0]) ? 1u : 0u;
+            flag[row] = decision;
         }
+        __syncthreads();
+        if (decision == 0) return;
+    }
+    for (int j = threadIdx.x; j < n_out; j += 256) {
+        float v[F];
+        group(j, v);
+        float sum = 0.f, cnt = 0.f;
+#pragma unroll
+        for (int r = 0; r < F; ++r)
+            if (j * F + r < n_in) { sum += v[r]; cnt += 1.f; }
+        dst[j] = sum / cnt;
     }
 }
 static_assert(tvk::kMlFactor == 4, "ml_average_kernel loads groups as float4");
