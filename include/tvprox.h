@@ -157,6 +157,23 @@ int tv1d_prox_bwd_seg(const float *g_up, const uint64_t *seg, float *grad_y, flo
                       tv_rows rows, tv_lambda lam, void *ws, size_t ws_bytes, hipStream_t stream);
 
 /*
+ * The same pair with bf16 storage and fp32 arithmetic (the inputs are widened exactly, the
+ * solve and the segment averaging run as in the fp32 kernels, the outputs are rounded to
+ * nearest even): y, x, g_up and grad_y are arrays of bf16 bit patterns (uint16_t), 16-byte
+ * aligned.  The paper computes in fp32; this halves the bytes the pair moves.  x is bit for bit
+ * the rounded output of tv1d_prox_fwd_seg on the widened input, the codes are identical, and
+ * the backward pass uses the codes (segments of the unrounded x), so rounding never merges or
+ * splits a segment.  Only packed rows of exactly 32 samples (unit element stride, rows back
+ * to back): TV_ERR_UNSUPPORTED otherwise.  ws / ws_bytes of the forward call: as in
+ * tv1d_prox_fwd_ex (may be NULL / 0); grad_lam stays fp32.
+ */
+int tv1d_prox_fwd_seg_bf16(const uint16_t *y, uint16_t *x, uint64_t *seg, tv_rows rows,
+                           tv_lambda lam, void *ws, size_t ws_bytes, hipStream_t stream);
+int tv1d_prox_bwd_seg_bf16(const uint16_t *g_up, const uint64_t *seg, uint16_t *grad_y,
+                           float *grad_lam, tv_rows rows, tv_lambda lam, void *ws, size_t ws_bytes,
+                           hipStream_t stream);
+
+/*
  * 2D anisotropic TV prox on `planes` images of H x W (row-major, contiguous) by
  * `sweeps` iterations of paper Alg. 1; plane p uses lam[p % count] (lam.div is
  * ignored).  ws keeps every pass's output (2*sweeps tensors) plus two scratch

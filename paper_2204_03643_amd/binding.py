@@ -55,6 +55,10 @@ def lib() -> ctypes.CDLL:
         L.tv1d_fwd_workspace_bytes.restype = ctypes.c_size_t
         L.tv1d_prox_bwd_seg.argtypes = [_vp, _vp, _vp, _vp, tv_rows, tv_lambda, _vp, ctypes.c_size_t, _vp]
         L.tv1d_prox_bwd_seg.restype = ctypes.c_int
+        L.tv1d_prox_fwd_seg_bf16.argtypes = [_vp, _vp, _vp, tv_rows, tv_lambda, _vp, ctypes.c_size_t, _vp]
+        L.tv1d_prox_fwd_seg_bf16.restype = ctypes.c_int
+        L.tv1d_prox_bwd_seg_bf16.argtypes = [_vp, _vp, _vp, _vp, tv_rows, tv_lambda, _vp, ctypes.c_size_t, _vp]
+        L.tv1d_prox_bwd_seg_bf16.restype = ctypes.c_int
         L.tv1d_bwd_workspace_bytes.argtypes = [tv_rows, tv_lambda]
         L.tv1d_bwd_workspace_bytes.restype = ctypes.c_size_t
         L.tv2d_workspace_bytes.argtypes = [_i64, _i64, _i64, ctypes.c_int]
@@ -145,6 +149,17 @@ def tv1d_prox_bwd_seg(g_up, seg, grad_y, grad_lam, rows: tv_rows, lam: tv_lambda
                       stream=None):
     _check(lib().tv1d_prox_bwd_seg(_ptr(g_up), _ptr(seg), _ptr(grad_y), _ptr(grad_lam), rows, lam,
                                    _ptr(ws), int(ws_bytes), _stream(stream)))
+
+
+def tv1d_prox_fwd_seg_bf16(y, x, seg, rows: tv_rows, lam: tv_lambda, ws=None, ws_bytes: int = 0, stream=None):
+    _check(lib().tv1d_prox_fwd_seg_bf16(_ptr(y), _ptr(x), _ptr(seg), rows, lam, _ptr(ws), int(ws_bytes),
+                                        _stream(stream)))
+
+
+def tv1d_prox_bwd_seg_bf16(g_up, seg, grad_y, grad_lam, rows: tv_rows, lam: tv_lambda, ws, ws_bytes: int,
+                           stream=None):
+    _check(lib().tv1d_prox_bwd_seg_bf16(_ptr(g_up), _ptr(seg), _ptr(grad_y), _ptr(grad_lam), rows, lam,
+                                        _ptr(ws), int(ws_bytes), _stream(stream)))
 
 
 def tv2d_workspace_bytes(planes: int, H: int, W: int, sweeps: int) -> int:

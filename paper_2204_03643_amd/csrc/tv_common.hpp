@@ -101,6 +101,7 @@ struct FwdParams {
     int32_t     *info;     // optional per-row info word
     uint2       *seg;      // optional per-row segment code (rows of up to 32 samples only)
     const uint32_t *order; // optional: grid row j of the grouped grid works on slot order[j]
+    uint32_t     io16;     // y and x are bf16 arrays (row-per-lane kernel, packed rows of 32 only)
     uint32_t     warm;     // 1: addend is D^T u of an earlier solve of nearly the same rows: start from that u
                            // 2: start from the dual of the row averaged in groups of kMlFactor (coarse_u)
     // long-row kernels only (multilevel start):
@@ -122,6 +123,7 @@ struct BwdParams {
     float       *gy;       // output
     float       *partial;  // optional: dL/dlam contributions, one per group of 1 << part_lg rows
     uint32_t     part_lg;  // row-per-lane kernels only; a group never spans two lambda slots
+    uint32_t     io16;     // g and gy are bf16 arrays (row-per-lane kernel with codes, packed rows of 32 only)
     Layout       L;
 };
 

@@ -125,6 +125,78 @@ __device__ __forceinline__ void tile_fetch(const float *__restrict__ src, const 
     }
 }
 
+// ---- bf16 storage (fp32 arithmetic).  A wave's 64 packed rows of 32 bf16 are one contiguous
+//      4 KB block: four 16-byte accesses per lane, eight samples each, straight into or out of
+//      the wave's tile (fp32, pitch NMAX + 1).
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
+
+// two floats -> two bf16 in one word (lo in the low half), round to nearest even: the
+// conversion instruction of gfx950
+typedef float tv_f2 __attribute__((ext_vector_type(2)));
+typedef __bf16 tv_bf2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t f32x2_to_bf16x2(float lo, float hi)
+{
+    tv_f2 v;
+    v.x = lo; v.y = hi;
+    const tv_bf2 r = __builtin_convertvector(v, tv_bf2);
+    uint32_t w;
+    __builtin_memcpy(&w, &r, sizeof(w));
+    return w;
+}
+
+__device__ __forceinline__ void tile16_fetch(const uint16_t *__restrict__ src, const TileMap &tm,
+                                             uint32_t first_row, uint32_t n_rows, int lane, float *tile,
+                                             bool stream)
+{
+    const bool simple = ((1u << tm.lg) % 16u) == 0 && tm.row(first_row, 63) < n_rows;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int e = (i * 64 + lane) * 8;                 // sample index inside the tile
+        const int rt = e >> 5, c = e & 31;
+        float4 q = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (simple) {
+            const uint32_t g0 = __builtin_amdgcn_readfirstlane(tm.row(first_row, i * 16));
+            q = load16(reinterpret_cast<const float *>(src + (size_t)g0 * 32) + lane * 4, stream);
+        } else {
+            const uint32_t g = tm.row(first_row, rt);
+            if (g < n_rows) q = *reinterpret_cast<const float4 *>(src + (size_t)g * 32 + c);
+        }
+        const uint32_t w[4] = {__float_as_uint(q.x), __float_as_uint(q.y), __float_as_uint(q.z),
+                               __float_as_uint(q.w)};
+        float *d = tile + rt * 33 + c;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            d[2 * j] = __uint_as_float(w[j] << 16);
+            d[2 * j + 1] = __uint_as_float(w[j] & 0xffff0000u);
+        }
+    }
+}
+
+__device__ __forceinline__ void tile16_put(uint16_t *__restrict__ dst, const TileMap &tm,
+                                           uint32_t first_row, uint32_t n_rows, int lane,
+                                           const float *tile, bool stream)
+{
+    const bool simple = ((1u << tm.lg) % 16u) == 0 && tm.row(first_row, 63) < n_rows;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int e = (i * 64 + lane) * 8;
+        const int rt = e >> 5, c = e & 31;
+        const float *sp = tile + rt * 33 + c;
+        uint32_t w[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) w[j] = f32x2_to_bf16x2(sp[2 * j], sp[2 * j + 1]);
+        const float4 q = make_float4(__uint_as_float(w[0]), __uint_as_float(w[1]), __uint_as_float(w[2]),
+                                     __uint_as_float(w[3]));
+        if (simple) {
+            const uint32_t g0 = __builtin_amdgcn_readfirstlane(tm.row(first_row, i * 16));
+            store16(reinterpret_cast<float *>(dst + (size_t)g0 * 32) + lane * 4, q, stream);
+        } else {
+            const uint32_t g = tm.row(first_row, rt);
+            if (g < n_rows) *reinterpret_cast<float4 *>(dst + (size_t)g * 32 + c) = q;
+        }
+    }
+}
+
 // Registers in tile order -> one row per lane.
 template <int NMAX>
 __device__ __forceinline__ void tile_to_rows(const TileRegs<NMAX> &t, float *tile, int lane,
@@ -623,7 +695,8 @@ struct RowSolver {
 // ---------------------------------------------------------------------------------
 // WARM: p.addend is given and the solve starts from the dual it encodes (see start_warm).
 // PLANE (NMAX = 32, FULL, not PACKED): the rows are the columns of contiguous 32 x 32 planes.
-template <int NMAX, bool FULL, bool PACKED, bool WARM = false, bool PLANE = false>
+// IO16 (NMAX = 32, FULL, PACKED, no addend / second output / residual): y and x are bf16.
+template <int NMAX, bool FULL, bool PACKED, bool WARM = false, bool PLANE = false, bool IO16 = false>
 __global__ __launch_bounds__(kShortBlock) TV_FWD_ATTR void tv1d_fwd_short_kernel(FwdParams p)
 {
     using S = ShortSmem<NMAX>;
@@ -675,6 +748,13 @@ __global__ __launch_bounds__(kShortBlock) TV_FWD_ATTR void tv1d_fwd_short_kernel
                 sv.u[k] = run;
             }
         }
+    } else if constexpr (IO16) {
+        static_assert(!IO16 || (NMAX == 32 && FULL && PACKED && !WARM), "bf16 storage: packed rows of 32");
+        wave_lds_sync();
+        tile16_fetch(reinterpret_cast<const uint16_t *>(p.y), p.tm, r0, p.L.n_rows, lane, tile, p.L.stream);
+        wave_lds_sync();
+#pragma unroll
+        for (int k = 0; k < NMAX; ++k) y[k] = tile[lane * (NMAX + 1) + k];
     } else if constexpr (PACKED) {
         TileRegs<NMAX> t;
         tile_fetch<NMAX>(p.y, p.tm, r0, p.L.n_rows, lane, t, p.L.stream);
@@ -713,6 +793,12 @@ __global__ __launch_bounds__(kShortBlock) TV_FWD_ATTR void tv1d_fwd_short_kernel
     if constexpr (PLANE) {
         columns_to_planes(xs, tile, lane, p.x, p.x2, pp, p.L);
         if (want_resid) columns_to_planes(rs, tile, lane, p.resid, nullptr, pp, p.L);
+    } else if constexpr (IO16) {
+        wave_lds_sync();
+#pragma unroll
+        for (int k = 0; k < NMAX; ++k) tile[lane * (NMAX + 1) + k] = xs[k];
+        wave_lds_sync();
+        tile16_put(reinterpret_cast<uint16_t *>(p.x), p.tm, r0, p.L.n_rows, lane, tile, p.L.stream);
     } else if constexpr (PACKED) {
         TileRegs<NMAX> t;
         rows_to_tile<NMAX>(xs, tile, lane, t);
@@ -755,7 +841,8 @@ __global__ __launch_bounds__(kShortBlock) TV_FWD_ATTR void tv1d_fwd_short_kernel
 //   dL/dlam  = sum over jumps k of sign(x[k+1]-x[k]) * (mean_left - mean_right).
 // ---------------------------------------------------------------------------------
 // PLANE: as in the forward kernel.
-template <int NMAX, bool FULL, bool PACKED, bool HAS_SUB, bool SEG, bool PLANE = false>
+// IO16 (NMAX = 32, FULL, PACKED, SEG, no sub): g and gy are bf16.
+template <int NMAX, bool FULL, bool PACKED, bool HAS_SUB, bool SEG, bool PLANE = false, bool IO16 = false>
 __global__ __launch_bounds__(kShortBlock) void tv1d_bwd_short_kernel(BwdParams p)
 {
     using S = ShortSmem<NMAX>;
@@ -792,6 +879,13 @@ __global__ __launch_bounds__(kShortBlock) void tv1d_bwd_short_kernel(BwdParams p
             for (int k = 0; k < NMAX; ++k) g[k] -= sb[k];
         }
         wave_lds_sync();
+    } else if constexpr (IO16) {
+        static_assert(!IO16 || (NMAX == 32 && FULL && PACKED && SEG && !HAS_SUB), "bf16 storage: packed rows of 32");
+        wave_lds_sync();                  // the tables are ready
+        tile16_fetch(reinterpret_cast<const uint16_t *>(p.g), tm, r0, p.L.n_rows, lane, tile, p.L.stream);
+        wave_lds_sync();
+#pragma unroll
+        for (int k = 0; k < NMAX; ++k) g[k] = tile[lane * (NMAX + 1) + k];
     } else if constexpr (PACKED) {
         TileRegs<NMAX> tg, tx;
         tile_fetch<NMAX>(p.g, tm, r0, p.L.n_rows, lane, tg, p.L.stream);
@@ -858,6 +952,12 @@ __global__ __launch_bounds__(kShortBlock) void tv1d_bwd_short_kernel(BwdParams p
             for (int k = 0; k < NMAX; ++k) g[k] += sb[k];
         }
         columns_to_planes(g, tile, lane, p.gy, nullptr, pp, p.L);
+    } else if constexpr (IO16) {
+        wave_lds_sync();
+#pragma unroll
+        for (int k = 0; k < NMAX; ++k) tile[lane * (NMAX + 1) + k] = g[k];
+        wave_lds_sync();
+        tile16_put(reinterpret_cast<uint16_t *>(p.gy), tm, r0, p.L.n_rows, lane, tile, p.L.stream);
     } else if constexpr (PACKED) {
         TileRegs<NMAX> t;
         rows_to_tile<NMAX>(g, tile, lane, t);

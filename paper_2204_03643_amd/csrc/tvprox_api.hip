@@ -130,6 +130,12 @@ int launch_fwd_short(const FwdParams &p, bool packed_ok, hipStream_t s, bool pla
     if (p.tm.grouped) grid = dim3(n_tiles / p.tm.count, p.tm.count);
     const bool full = p.L.n == NMAX;
     if constexpr (NMAX == 32) {
+        if (p.io16) {                     // the entry point has checked: packed rows of exactly 32
+            hipLaunchKernelGGL((tvk::tv1d_fwd_short_kernel<32, true, true, false, false, true>), grid, block, 0, s, p);
+            return launch_status();
+        }
+    }
+    if constexpr (NMAX == 32) {
         // (the warm-start variant of the plane mode runs out of scalar registers and loses a wave of
         // occupancy to the spill; warm column passes keep the strided accesses)
         if (plane_ok && full && !p.warm) {
@@ -158,6 +164,13 @@ int launch_bwd_short(const BwdParams &p, bool packed_ok, hipStream_t s, bool pla
 {
     const dim3 grid((p.L.n_rows + tvk::kShortBlock - 1) / tvk::kShortBlock), block(tvk::kShortBlock);
     const bool full = p.L.n == NMAX;
+    if constexpr (NMAX == 32 && SEG && !HAS_SUB) {
+        if (p.io16) {                     // the entry point has checked: packed rows of exactly 32
+            hipLaunchKernelGGL((tvk::tv1d_bwd_short_kernel<32, true, true, false, true, false, true>), grid, block, 0,
+                               s, p);
+            return launch_status();
+        }
+    }
     if constexpr (NMAX == 32) {
         if (plane_ok && full) {
             hipLaunchKernelGGL((tvk::tv1d_bwd_short_kernel<32, true, false, HAS_SUB, SEG, true>), grid, block, 0, s, p);
@@ -220,7 +233,7 @@ __device__ __forceinline__ int dpp_i(int v)
 template <bool FAST>
 __global__ __launch_bounds__(kOrderMaxSlots) void slot_order_kernel(
     const float *__restrict__ y, const float *__restrict__ addend, const float *__restrict__ lam,
-    tvk::Layout L, tvk::TileMap tm, uint32_t lgR, uint32_t *__restrict__ order)
+    tvk::Layout L, tvk::TileMap tm, uint32_t lgR, uint32_t *__restrict__ order, uint32_t io16)
 {
     __shared__ float key[kOrderMaxSlots];
     const uint32_t count = tm.count;
@@ -239,7 +252,13 @@ __global__ __launch_bounds__(kOrderMaxSlots) void slot_order_kernel(
                 if (s < count) {
                     lv[j] = lam[s];
                     const size_t a = (size_t)tm.first(0u, s) * 32u + (lane & 15u) * 4u;
-                    v[j] = *reinterpret_cast<const float4 *>(y + a);
+                    if (io16) {
+                        const uint2 h = *reinterpret_cast<const uint2 *>(reinterpret_cast<const uint16_t *>(y) + a);
+                        v[j] = make_float4(__uint_as_float(h.x << 16), __uint_as_float(h.x & 0xffff0000u),
+                                           __uint_as_float(h.y << 16), __uint_as_float(h.y & 0xffff0000u));
+                    } else {
+                        v[j] = *reinterpret_cast<const float4 *>(y + a);
+                    }
                     if (addend) {
                         const float4 w = *reinterpret_cast<const float4 *>(addend + a);
                         v[j].x += w.x; v[j].y += w.y; v[j].z += w.z; v[j].w += w.w;
@@ -288,7 +307,7 @@ __global__ __launch_bounds__(kOrderMaxSlots) void slot_order_kernel(
             v[j] = 0.f;
             if (j < n) {
                 const int64_t a = off + j * L.elem_stride;
-                v[j] = y[a];
+                v[j] = io16 ? tvk::bf16_bits_to_f32(reinterpret_cast<const uint16_t *>(y)[a]) : y[a];
                 if (addend) v[j] += addend[a];
             }
         }
@@ -483,11 +502,12 @@ int run_fwd_multilevel(FwdParams p, const tv_lambda &l, int64_t n_rows, const Ml
 
 int run_fwd(const float *y, const float *addend, float *x, float *resid, int32_t *info,
             uint2 *seg, uint32_t *order_ws, const tv_rows &r, const tv_lambda &l, int64_t n_rows,
-            hipStream_t s, float *x2 = nullptr, bool warm = false, char *ml_ws = nullptr)
+            hipStream_t s, float *x2 = nullptr, bool warm = false, char *ml_ws = nullptr, bool io16 = false)
 {
     FwdParams p;
     p.y = y; p.addend = addend; p.x = x; p.x2 = x2; p.resid = resid; p.lam = l.lam; p.info = info;
     p.seg = seg; p.order = nullptr;
+    p.io16 = io16 ? 1u : 0u;
     p.warm = (warm && addend) ? 1u : 0u;
     p.coarse_u = nullptr; p.coarse_n = 0; p.dual_out = nullptr; p.ml_flag = nullptr; p.ml_skip = 0;
     p.lam_scale = 1.0f;
@@ -501,10 +521,10 @@ int run_fwd(const float *y, const float *addend, float *x, float *resid, int32_t
                           (!addend || aligned16(addend));
         if (fast)
             hipLaunchKernelGGL(slot_order_kernel<true>, dim3(1), dim3(kOrderMaxSlots), 0, s, y, addend,
-                               l.lam, p.L, p.tm, lgR, order);
+                               l.lam, p.L, p.tm, lgR, order, io16 ? 1u : 0u);
         else
             hipLaunchKernelGGL(slot_order_kernel<false>, dim3(1), dim3(kOrderMaxSlots), 0, s, y, addend,
-                               l.lam, p.L, p.tm, lgR, order);
+                               l.lam, p.L, p.tm, lgR, order, io16 ? 1u : 0u);
         if (launch_status() != TV_OK) return TV_ERR_HIP;
         p.order = order;
     }
@@ -673,10 +693,11 @@ PartialShape partial_shape(const tv_rows &r, const tv_lambda &l, int64_t n_rows)
 // reduce_now = false: the dL/dlam terms stay in `partial` and the caller sums them later.
 int run_bwd(const float *g, const float *sub, const float *x, const uint2 *seg, float *gy,
             float *grad_lam, int accumulate, const tv_rows &r, const tv_lambda &l, int64_t n_rows,
-            float *partial, hipStream_t s, bool reduce_now = true)
+            float *partial, hipStream_t s, bool reduce_now = true, bool io16 = false)
 {
     BwdParams p;
     p.g = g; p.sub = sub; p.x = x; p.seg = seg; p.gy = gy;
+    p.io16 = io16 ? 1u : 0u;
     p.partial = grad_lam ? partial : nullptr;
     p.L = make_layout(r, l, n_rows);
     const bool packed = rows_packed(r) && aligned16(g) && (!x || aligned16(x)) && aligned16(gy) &&
@@ -850,6 +871,48 @@ int tv1d_prox_bwd_seg(const float *g_up, const uint64_t *seg, float *grad_y, flo
                       tv_rows rows, tv_lambda lam, void *ws, size_t ws_bytes, hipStream_t stream)
 {
     return bwd_entry(g_up, nullptr, seg, true, grad_y, grad_lam, rows, lam, ws, ws_bytes, stream);
+}
+
+// ---- bf16 storage, fp32 arithmetic: packed rows of exactly 32 samples, segment-code pair only --
+
+static int check_bf16(const void *a, const void *b, const uint64_t *seg, tv_rows rows, tv_lambda lam,
+                      int64_t *n_rows)
+{
+    int st = check_lambda(lam);
+    if (st != TV_OK) return st;
+    st = check_rows(rows, n_rows);
+    if (st != TV_OK) return st;
+    if (*n_rows == 0) return TV_OK;
+    if (!a || !b || !seg || !lam.lam) return TV_ERR_NULL;
+    if (rows.length != 32 || !rows_packed(rows)) return TV_ERR_UNSUPPORTED;
+    if (!aligned16(a) || !aligned16(b) || (uintptr_t)seg % 8 != 0) return TV_ERR_STRIDE;
+    return TV_OK;
+}
+
+int tv1d_prox_fwd_seg_bf16(const uint16_t *y, uint16_t *x, uint64_t *seg, tv_rows rows, tv_lambda lam,
+                           void *ws, size_t ws_bytes, hipStream_t stream)
+{
+    int64_t n_rows = 0;
+    const int st = check_bf16(y, x, seg, rows, lam, &n_rows);
+    if (st != TV_OK || n_rows == 0) return st;
+    if (ws && (!aligned16(ws) || ws_bytes < fwd_workspace_bytes(rows, lam, n_rows))) return TV_ERR_WORKSPACE;
+    return run_fwd(reinterpret_cast<const float *>(y), nullptr, reinterpret_cast<float *>(x), nullptr, nullptr,
+                   reinterpret_cast<uint2 *>(seg), (uint32_t *)ws, rows, lam, n_rows, stream, nullptr, false,
+                   nullptr, true);
+}
+
+int tv1d_prox_bwd_seg_bf16(const uint16_t *g_up, const uint64_t *seg, uint16_t *grad_y, float *grad_lam,
+                           tv_rows rows, tv_lambda lam, void *ws, size_t ws_bytes, hipStream_t stream)
+{
+    int64_t n_rows = 0;
+    const int st = check_bf16(g_up, grad_y, seg, rows, lam, &n_rows);
+    if (st != TV_OK) return st;
+    if (n_rows == 0) return grad_lam ? zero_floats(grad_lam, lam.count, stream) : TV_OK;
+    if (grad_lam && (!ws || !aligned16(ws) || ws_bytes < align16((size_t)n_rows * sizeof(float))))
+        return TV_ERR_WORKSPACE;
+    return run_bwd(reinterpret_cast<const float *>(g_up), nullptr, nullptr, reinterpret_cast<const uint2 *>(seg),
+                   reinterpret_cast<float *>(grad_y), grad_lam, 0, rows, lam, n_rows, (float *)ws, stream, true,
+                   true);
 }
 
 // ---- 2D: proximal Dykstra (paper Alg. 1) ----------------------------------------------

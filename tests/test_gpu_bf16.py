@@ -1,0 +1,101 @@
+"""GPU: the segment-code pair with bf16 storage (fp32 arithmetic).
+
+The strongest check is against the fp32 pair on the widened input: x must be its output rounded
+to nearest even, bit for bit, the codes and grad_lam identical, grad_y its rounded grad_y.  The
+oracle is compared too, with the tolerance of a bf16 result (half an ulp: at most 2^-8
+relative with an 8-bit significand) on top of the fp32 bar."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads
+from parity import FWD_TOL
+
+pytestmark = pytest.mark.gpu
+
+
+def _to_bf16_bits(a):
+    """fp32 -> bf16 bit patterns, round to nearest even (numpy, for the expected values)."""
+    u = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    r = (u + 0x7fff + ((u >> 16) & 1)) >> 16
+    return r.astype(np.uint16)
+
+
+def _widen(bits):
+    return (bits.astype(np.uint32) << 16).view(np.float32)
+
+
+def _run(y_bits, lam, lam_div, g_bits, use_ws):
+    import torch
+
+    import paper_2204_03643_amd as tv
+
+    dev = torch.device("cuda:0")
+    shape = y_bits.shape
+    n_rows = y_bits.size // 32
+    yt = torch.from_numpy(y_bits.view(np.int16)).to(dev)
+    gt = torch.from_numpy(g_bits.view(np.int16)).to(dev)
+    lt = torch.from_numpy(lam).to(dev)
+    rows = tv.rows_along(shape, -1)
+    L = tv.tv_lambda(lt.data_ptr(), lt.numel(), lam_div)
+    seg = torch.full((n_rows,), -1, dtype=torch.int64, device=dev)
+    xt, gy = torch.full_like(yt, -1), torch.full_like(yt, -1)
+    gl = torch.full((lt.numel(),), float("nan"), device=dev)
+    wsb = tv.tv1d_fwd_workspace_bytes(rows, L) if use_ws else 0
+    ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device=dev)
+    tv.tv1d_prox_fwd_seg_bf16(yt, xt, seg, rows, L, ws if wsb else None, wsb)
+    bwsb = tv.tv1d_bwd_workspace_bytes(rows, L)
+    bws = torch.empty(max(bwsb, 16), dtype=torch.uint8, device=dev)
+    tv.tv1d_prox_bwd_seg_bf16(gt, seg, gy, gl, rows, L, bws, bwsb)
+    # the fp32 pair on the widened input
+    yf = torch.from_numpy(_widen(y_bits)).to(dev)
+    gf = torch.from_numpy(_widen(g_bits)).to(dev)
+    xf, gyf, glf = torch.empty_like(yf), torch.empty_like(yf), torch.empty_like(gl)
+    segf = torch.empty_like(seg)
+    tv.tv1d_prox_fwd_seg(yf, xf, segf, rows, L)
+    tv.tv1d_prox_bwd_seg(gf, segf, gyf, glf, rows, L, bws, bwsb)
+    torch.cuda.synchronize()
+    return dict(x=xt.cpu().numpy().view(np.uint16), gy=gy.cpu().numpy().view(np.uint16), gl=gl.cpu().numpy(),
+                seg=seg.cpu().numpy(), xf=xf.cpu().numpy(), gyf=gyf.cpu().numpy(), glf=glf.cpu().numpy(),
+                segf=segf.cpu().numpy())
+
+
+@pytest.mark.parametrize("B,C,use_ws", [(4, 128, False), (4, 128, True), (1, 3, False)])
+def test_bf16_pair_equals_rounded_fp32_pair(B, C, use_ws):
+    y, lam, g = workloads.config3(B=B, C=C)
+    yb, gb = _to_bf16_bits(y), _to_bf16_bits(g)
+    out = _run(yb, lam, 32, gb, use_ws)
+    assert np.array_equal(out["seg"], out["segf"])
+    assert np.array_equal(out["x"], _to_bf16_bits(out["xf"]))
+    assert np.array_equal(out["gy"], _to_bf16_bits(out["gyf"]))
+    assert np.array_equal(out["gl"], out["glf"])
+    # and the oracle, on the values the kernel saw
+    yw = _widen(yb).reshape(-1, 32).astype(np.float64)
+    lr = np.repeat(np.tile(lam, B), 32).astype(np.float64)
+    x_ref = oracle.prox1d_batch(yw, lr)
+    x = _widen(out["x"]).reshape(-1, 32).astype(np.float64)
+    tol = 2.0 ** -8 * np.abs(x_ref) + FWD_TOL * (1 + np.abs(yw).max(1, keepdims=True))
+    assert np.all(np.abs(x - x_ref) <= tol)
+
+
+def test_bf16_ragged_batch_and_scalar_lambda():
+    rng = np.random.default_rng(5)
+    y = rng.normal(size=(77, 32)).astype(np.float32)              # not a multiple of 64 rows
+    g = rng.normal(size=(77, 32)).astype(np.float32)
+    out = _run(_to_bf16_bits(y), np.array([0.3], np.float32), 1, _to_bf16_bits(g), False)
+    assert np.array_equal(out["seg"], out["segf"])
+    assert np.array_equal(out["x"], _to_bf16_bits(out["xf"]))
+    assert np.array_equal(out["gy"], _to_bf16_bits(out["gyf"]))
+    assert np.array_equal(out["gl"], out["glf"])
+
+
+def test_bf16_rejects_other_shapes():
+    import paper_2204_03643_amd as tv
+
+    L = tv.lib()
+    FAKE = 0x1000
+    lam = tv.tv_lambda(FAKE, 1, 1)
+    assert L.tv1d_prox_fwd_seg_bf16(FAKE, FAKE, FAKE, tv.rows_along((8, 16), -1), lam, None, 0, None) == 6
+    assert L.tv1d_prox_fwd_seg_bf16(FAKE, FAKE, FAKE, tv.rows_along((32, 8), 0), lam, None, 0, None) == 6
+    assert L.tv1d_prox_fwd_seg_bf16(FAKE, FAKE, None, tv.rows_along((8, 32), -1), lam, None, 0, None) == 1
+    assert L.tv1d_prox_fwd_seg_bf16(FAKE + 2, FAKE, FAKE, tv.rows_along((8, 32), -1), lam, None, 0, None) == 3
