@@ -694,7 +694,7 @@ struct RowSolver {
 // for each other.  With a grouped grid the slots may be visited in a given order (p.order).
 // ---------------------------------------------------------------------------------
 // WARM: p.addend is given and the solve starts from the dual it encodes (see start_warm).
-// PLANE (NMAX = 32, FULL, not PACKED): the rows are the columns of contiguous 32 x 32 planes.
+// PLANE (NMAX = 32, FULL, not PACKED, not WARM): the rows are the columns of contiguous 32 x 32 planes.
 // IO16 (NMAX = 32, FULL, PACKED, no addend / second output / residual): y and x are bf16.
 template <int NMAX, bool FULL, bool PACKED, bool WARM = false, bool PLANE = false, bool IO16 = false>
 __global__ __launch_bounds__(kShortBlock) TV_FWD_ATTR void tv1d_fwd_short_kernel(FwdParams p)
@@ -728,10 +728,13 @@ __global__ __launch_bounds__(kShortBlock) TV_FWD_ATTR void tv1d_fwd_short_kernel
     float y[NMAX], xs[NMAX];
     RowSolver<NMAX, FULL> sv;
     if constexpr (PLANE) {
-        TileRegs<32> t, a;
+        // (no warm-start variant: the solver's bound masks already fill the scalar registers, the
+        // extra pointers of a warm pass spill them, and the spill costs a wave of occupancy)
+        static_assert(!(PLANE && WARM), "plane columns: cold start only");
+        TileRegs<32> t;
         planes_fetch(p.y, pp, p.L, lane, t);
-        const bool has_add = WARM || p.addend;
-        if (has_add) {
+        if (p.addend) {
+            TileRegs<32> a;
             planes_fetch(p.addend, pp, p.L, lane, a);
             tile_add<32>(t, a, 1.f);
         }
@@ -739,15 +742,6 @@ __global__ __launch_bounds__(kShortBlock) TV_FWD_ATTR void tv1d_fwd_short_kernel
         const float *col = plane_column(tile, lane);
 #pragma unroll
         for (int k = 0; k < NMAX; ++k) y[k] = col[k * 33];
-        if constexpr (WARM) {
-            planes_into_tile(a, tile, lane);
-            float run = 0.f;
-#pragma unroll
-            for (int k = 0; k < NMAX - 1; ++k) {
-                run -= col[k * 33];
-                sv.u[k] = run;
-            }
-        }
     } else if constexpr (IO16) {
         static_assert(!IO16 || (NMAX == 32 && FULL && PACKED && !WARM), "bf16 storage: packed rows of 32");
         wave_lds_sync();
