@@ -72,6 +72,19 @@ def test_multilevel_start(n):
     assert ml["steps"][big].sum() < cold["steps"][big].sum(), (ml["steps"], cold["steps"])
 
 
+def test_multilevel_degenerate_rows():
+    """Constant rows, a row of exactly the minimum length, a single row, lambda = 0 and a lambda so
+    large that the whole row is one segment, all through the workspace path."""
+    rng = np.random.default_rng(3)
+    n = 2048
+    y = np.stack([np.full(n, 1.5, np.float32), rng.normal(size=n).astype(np.float32),
+                  np.cumsum(rng.normal(scale=0.1, size=n)).astype(np.float32),
+                  np.repeat(rng.normal(size=n // 64), 64).astype(np.float32)])
+    g = rng.normal(size=y.shape).astype(np.float32)
+    _check(y, np.array([0.7, 0.0, 1e4, 0.25], np.float32), 1, g, -1, "ml degenerate", use_ws=True)
+    _check(y[2:3], np.array([2.0], np.float32), 1, g[2:3], -1, "ml single row", use_ws=True)
+
+
 def test_multilevel_per_channel_lambda_and_strided_rows():
     """Rows inside a larger buffer (row stride > length), lambda shared by groups of rows."""
     rng = np.random.default_rng(77)

@@ -61,7 +61,8 @@ def test_odd_sizes_mixed_paths():
 
 
 @pytest.mark.parametrize("shape,K", [((5, 19, 11), 3), ((3, 32, 16), 2), ((7, 8, 32), 2), ((2, 1, 17), 2),
-                                     ((3, 32, 32), 5), ((1, 2, 2), 1)])
+                                     ((3, 32, 32), 5), ((1, 2, 2), 1), ((1, 32, 32), 20), ((2, 32, 1), 3),
+                                     ((1, 1, 32), 3), ((9, 31, 32), 4)])
 def test_small_planes(shape, K):
     # planes of at most 32 x 32: both passes on the row-per-lane kernels, ragged in both directions
     rng = np.random.default_rng(73 + shape[1] * 64 + shape[2])
