@@ -369,8 +369,9 @@ struct LongSmemBwd {
 // WARM = 2 (unit-stride rows, C a multiple of kMlFactor): rows flagged in p.ml_flag start from
 // the dual of the same row averaged in groups of kMlFactor samples (p.coarse_u), which a launch
 // on the averaged rows with lambda / kMlFactor left behind (p.dual_out of that launch).
+// (512-thread workgroups ask for 4 waves per SIMD, i.e. at most 128 VGPRs, so that a CU holds two.)
 template <int T, int C, int G, bool COLS, bool XPOSE = false, int WARM = 0>
-__global__ __launch_bounds__(T *G) void tv1d_fwd_long_kernel(FwdParams p)
+__global__ __launch_bounds__(T *G, (T * G == 512 && !COLS) ? 4 : 1) void tv1d_fwd_long_kernel(FwdParams p)
 {
     static_assert(!XPOSE || (COLS && T == 64), "the transposing variant is for strided rows on one wave");
     constexpr bool MCOLS = COLS && !XPOSE;             // mapping used by the solve
