@@ -371,7 +371,7 @@ struct LongSmemBwd {
 // on the averaged rows with lambda / kMlFactor left behind (p.dual_out of that launch).
 // (512-thread workgroups ask for 4 waves per SIMD, i.e. at most 128 VGPRs, so that a CU holds two.)
 template <int T, int C, int G, bool COLS, bool XPOSE = false, int WARM = 0>
-__global__ __launch_bounds__(T *G, (T * G == 512 && !COLS) ? 4 : 1) void tv1d_fwd_long_kernel(FwdParams p)
+__global__ __launch_bounds__(T *G, (T * G == 512 && !COLS) ? 4 : ((XPOSE && C <= 4) ? 8 : 1)) void tv1d_fwd_long_kernel(FwdParams p)
 {
     static_assert(!XPOSE || (COLS && T == 64), "the transposing variant is for strided rows on one wave");
     constexpr bool MCOLS = COLS && !XPOSE;             // mapping used by the solve
@@ -380,7 +380,15 @@ __global__ __launch_bounds__(T *G, (T * G == 512 && !COLS) ? 4 : 1) void tv1d_fw
     // tile[row][k + k / C]: the pad after every chunk makes a wave's chunk reads conflict-free,
     // the odd pitch does the same for the transposing accesses
     constexpr int TILE_PITCH = T * (C + 1) + 1;
-    __shared__ float tile[XPOSE ? G * TILE_PITCH : 1];
+    // The tile is in use before the solve and after it, the exchange and PCR buffers during it:
+    // where it fits it lies on top of them (two barriers more), which is what lets a second
+    // workgroup share the CU's LDS.
+    constexpr bool TILE_ALIAS = XPOSE && (size_t)G * TILE_PITCH * sizeof(float) <= sizeof(sm.ex) + sizeof(sm.buf);
+    using Smem = LongSmem<T, C, G, MCOLS>;
+    static_assert(__builtin_offsetof(Smem, buf) == __builtin_offsetof(Smem, ex) + sizeof(sm.ex),
+                  "ex and buf must be adjacent");
+    __shared__ float tile_own[(XPOSE && !TILE_ALIAS) ? G * TILE_PITCH : 1];
+    float *tile = TILE_ALIAS ? &sm.ex[0][0][0] : tile_own;
     const int tid = threadIdx.x;
     const int j = Mp::row_of(tid), t = Mp::t_of(tid);
 #define TV_EX(q, tt) sm.ex[q][j][(tt) + 1]
@@ -398,7 +406,7 @@ __global__ __launch_bounds__(T *G, (T * G == 512 && !COLS) ? 4 : 1) void tv1d_fw
     const int k0 = t * C;
 
     if (tid <= C) sm.gtab[tid] = (float)tid / (float)(tid + 1);
-    if (t == 0) {
+    if (!TILE_ALIAS && t == 0) {
 #pragma unroll
         for (int q = 0; q < 5; ++q) { sm.ex[q][j][0] = 0.f; sm.ex[q][j][T + 1] = 0.f; }
     }
@@ -459,6 +467,13 @@ __global__ __launch_bounds__(T *G, (T * G == 512 && !COLS) ? 4 : 1) void tv1d_fw
         __syncthreads();
 #pragma unroll
         for (int i = 0; i < C; ++i) y[i] = tile[j * TILE_PITCH + t * (C + 1) + i];
+        if constexpr (TILE_ALIAS) {
+            __syncthreads();                // everyone has left the tile: its memory turns into ex / buf
+            if (t == 0) {
+#pragma unroll
+                for (int q = 0; q < 5; ++q) { sm.ex[q][j][0] = 0.f; sm.ex[q][j][T + 1] = 0.f; }
+            }
+        }
     } else {
         chunk_load<C>(p.y, off, es, k0, n, rvalid, y);
         if (warm || p.addend) {
@@ -803,6 +818,7 @@ __global__ __launch_bounds__(T *G, (T * G == 512 && !COLS) ? 4 : 1) void tv1d_fw
 
     if constexpr (XPOSE) {
         // a wave writes only its own row of the tile; the barrier then hands the tile over
+        if constexpr (TILE_ALIAS) __syncthreads();      // every wave is done with ex / buf
 #pragma unroll
         for (int i = 0; i < C; ++i) tile[j * TILE_PITCH + t * (C + 1) + i] = xs[i];
         __syncthreads();
