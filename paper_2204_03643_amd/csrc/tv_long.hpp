@@ -361,7 +361,7 @@ struct LongSmemBwd {
 // Forward: projected Newton on the dual (paper Eq. 3-4), one row per T threads.
 // ---------------------------------------------------------------------------------
 //
-// XPOSE (strided samples, T = 64): global memory is accessed as in the COLS mapping (adjacent
+// XPOSE (strided samples, T <= 64): global memory is accessed as in the COLS mapping (adjacent
 // lanes <-> adjacent rows, so that the accesses coalesce), but the G rows of the workgroup
 // are transposed through an LDS tile on the way in and out, and the solve itself runs in the
 // ROWS mapping with one row per wave, i.e. without any workgroup barrier.
@@ -373,7 +373,7 @@ struct LongSmemBwd {
 template <int T, int C, int G, bool COLS, bool XPOSE = false, int WARM = 0>
 __global__ __launch_bounds__(T *G, (T * G == 512 && !COLS) ? 4 : ((XPOSE && C <= 4) ? 8 : 1)) void tv1d_fwd_long_kernel(FwdParams p)
 {
-    static_assert(!XPOSE || (COLS && T == 64), "the transposing variant is for strided rows on one wave");
+    static_assert(!XPOSE || (COLS && T <= 64), "the transposing variant is for strided rows inside one wave");
     constexpr bool MCOLS = COLS && !XPOSE;             // mapping used by the solve
     using Mp = LongMap<T, G, MCOLS>;
     __shared__ LongSmem<T, C, G, MCOLS> sm;
@@ -862,7 +862,7 @@ __global__ __launch_bounds__(T *G, (T * G == 512 && !COLS) ? 4 : ((XPOSE && C <=
 template <int T, int C, int G, bool COLS, bool XPOSE = false, bool HAS_SUB = false>
 __global__ __launch_bounds__(T *G, (T * G == 1024 && !COLS && !HAS_SUB) ? 8 : 1) void tv1d_bwd_long_kernel(BwdParams p)
 {
-    static_assert(!XPOSE || (COLS && T == 64), "the transposing variant is for strided rows on one wave");
+    static_assert(!XPOSE || (COLS && T <= 64), "the transposing variant is for strided rows inside one wave");
     constexpr bool MCOLS = COLS && !XPOSE;
     using Mp = LongMap<T, G, MCOLS>;
     __shared__ LongSmemBwd<T, C, G, MCOLS> sm;
@@ -1023,7 +1023,7 @@ template <int T, int C, int G, bool COLS>
 inline hipError_t launch_fwd_long_t(const FwdParams &p, hipStream_t s)
 {
     const dim3 grid((p.L.n_rows + G - 1) / G), block(T * G);
-    constexpr bool XP = COLS && T == 64;
+    constexpr bool XP = COLS && T <= 64;
     if (p.warm == 2) {
         if constexpr (!COLS && C % kMlFactor == 0)
             hipLaunchKernelGGL((tv1d_fwd_long_kernel<T, C, G, COLS, XP, 2>), grid, block, 0, s, p);
@@ -1040,7 +1040,7 @@ template <int T, int C, int G, bool COLS>
 inline hipError_t launch_bwd_long_t(const BwdParams &p, hipStream_t s)
 {
     const dim3 grid((p.L.n_rows + G - 1) / G), block(T * G);
-    constexpr bool XP = COLS && T == 64;
+    constexpr bool XP = COLS && T <= 64;
     if (p.sub)
         hipLaunchKernelGGL((tv1d_bwd_long_kernel<T, C, G, COLS, XP, true>), grid, block, 0, s, p);
     else
@@ -1053,7 +1053,8 @@ inline hipError_t launch_bwd_long_t(const BwdParams &p, hipStream_t s)
         const int n = (p).L.n;                                                            \
         const bool cols = (p).L.elem_stride != 1;                                         \
         if (cols) {                                                                       \
-            if (n <= 128) return FN<64, 2, 16, true>(p, s);                               \
+            if (n <= 64) return FN<32, 2, 16, true>(p, s);                                \
+            if (n <= 128) return FN<32, 4, 16, true>(p, s);                               \
             if (n <= 256) return FN<64, 4, 16, true>(p, s);                               \
             if (n <= 512) return FN<64, 8, 16, true>(p, s);                               \
             if (n <= 1024) return FN<64, 16, 16, true>(p, s);                             \
