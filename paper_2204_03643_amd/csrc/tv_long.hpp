@@ -1055,7 +1055,7 @@ inline hipError_t launch_bwd_long_t(const BwdParams &p, hipStream_t s)
         if (cols) {                                                                       \
             if (n <= 64) return FN<32, 2, 16, true>(p, s);                                \
             if (n <= 128) return FN<32, 4, 16, true>(p, s);                               \
-            if (n <= 256) return FN<64, 4, 16, true>(p, s);                               \
+            if (n <= 256) return FN<32, 8, 16, true>(p, s);                               \
             if (n <= 512) return FN<64, 8, 16, true>(p, s);                               \
             if (n <= 1024) return FN<64, 16, 16, true>(p, s);                             \
             if (n <= 2048) return FN<256, 8, 4, true>(p, s);                              \
@@ -1065,7 +1065,7 @@ inline hipError_t launch_bwd_long_t(const BwdParams &p, hipStream_t s)
         }                                                                                 \
         if (n <= 64) return FN<32, 2, 8, false>(p, s);                                    \
         if (n <= 128) return FN<32, 4, 8, false>(p, s);                                   \
-        if (n <= 256) return FN<64, 4, 4, false>(p, s);                                   \
+        if (n <= 256) return FN<32, 8, 8, false>(p, s);                                   \
         if (n <= 512) return FN<64, 8, 4, false>(p, s);                                   \
         if (n <= 1024) return FN<64, 16, 4, false>(p, s);                                 \
         if (n <= 2048) return FN<256, 8, 1, false>(p, s);                                 \
