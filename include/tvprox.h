@@ -1,8 +1,8 @@
 /*
  * tvprox -- batched total-variation proximal operators for AMD MI355X (gfx950).
  *
- * C ABI.  Every data pointer is a DEVICE pointer to fp32 data owned by the
- * caller; the library allocates nothing, keeps no state between calls, and only
+ * C ABI.  Every data pointer is a DEVICE pointer to fp32 data (bf16 bit patterns in the
+ * two *_bf16 entry points) owned by the caller; the library allocates nothing, keeps no state between calls, and only
  * enqueues kernels on the stream it is given (asynchronous, no implicit sync).
  * Every function returns a tv_status; argument validation happens before any
  * HIP call, so invalid calls fail the same way on a machine without a GPU.
@@ -36,7 +36,8 @@ typedef enum {
     TV_ERR_STRIDE = 3,      /* rows would overlap; segment-code buffer not 8-byte aligned */
     TV_ERR_LAMBDA = 4,      /* lam.count < 1 or lam.div < 1                            */
     TV_ERR_WORKSPACE = 5,   /* workspace NULL, misaligned or too small                 */
-    TV_ERR_UNSUPPORTED = 6, /* row longer than TV_MAX_LENGTH (TV_SEG_MAX_LENGTH with codes) */
+    TV_ERR_UNSUPPORTED = 6, /* row longer than TV_MAX_LENGTH (TV_SEG_MAX_LENGTH with codes);
+                               bf16 storage on anything but packed rows of 32 samples       */
     TV_ERR_HIP = 7          /* a HIP runtime call (kernel launch) failed               */
 } tv_status;
 

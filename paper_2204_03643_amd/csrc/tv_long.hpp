@@ -2,9 +2,9 @@
 // (and duals) per thread, G rows per workgroup.
 //
 // T = 32 and T = 64 keep a row inside one wavefront (G rows per workgroup, two per wave at
-// T = 32); T = 256, 512 and 1024 put one row on a whole workgroup.  The row, its dual and the Newton direction stay in
-// registers for the entire solve; only chunk edges, the interface system and row-wide
-// reductions go through LDS.
+// T = 32); T = 256, 512 and 1024 put one row on a whole workgroup.  The row, its dual and the
+// Newton direction stay in registers for the entire solve; only chunk edges, the interface
+// system and row-wide reductions go through LDS.
 //
 // The masked tridiagonal system of paper Eq. 4 is solved by substructuring:
 //   1. every thread eliminates the interior of its chunk with the Thomas recurrences
