@@ -7,7 +7,7 @@ namespace tvk {
 
 // Solver constants.  The paper fixes none of them (Sec. 3.2 only names the Armijo
 // rule with quadratic-interpolation backtracking); these are the values chosen here.
-constexpr int   kMaxNewtonSteps  = 64;      // iteration cap per row
+constexpr int   kMaxNewtonSteps  = 128;     // iteration cap per row
 constexpr int   kMaxBacktracks   = 24;      // line-search rounds per Newton step
 constexpr float kArmijoSigma     = 1e-4f;   // sufficient-decrease fraction
 constexpr float kArmijoSlackEps  = 4.0f * 1.1920929e-7f;  // slack = this * |f|

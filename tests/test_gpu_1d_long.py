@@ -72,6 +72,20 @@ def test_multilevel_start(n):
     assert ml["steps"][big].sum() < cold["steps"][big].sum(), (ml["steps"], cold["steps"])
 
 
+def test_noise_rows_with_lambda_near_lam_max():
+    """Noise-like long rows with lambda a third of their lam_max are the worst case of the cold
+    start (every dual on the bound its local difference points to): dozens of Newton steps.
+    Strided, so that no multilevel start helps; they must still converge below the cap."""
+    rng = np.random.default_rng(2561)
+    n, rows = 2561, 12
+    y = (0.3 * rng.normal(size=(n, rows))).astype(np.float32)
+    g = rng.normal(size=y.shape).astype(np.float32)
+    pre = np.cumsum(y.mean(0, keepdims=True) - y, axis=0)
+    lam = (np.abs(pre).max(0) / 3.2).astype(np.float32)
+    st = _check(y, lam, 1, g, 0, "noise rows, lam near lam_max")
+    assert st["max_steps"] <= 128
+
+
 def test_multilevel_degenerate_rows():
     """Constant rows, a row of exactly the minimum length, a single row, lambda = 0 and a lambda so
     large that the whole row is one segment, all through the workspace path."""
