@@ -1,6 +1,7 @@
-// Reverse sweep of the 2D operator (paper Alg. 1, Sec. 3.2) for planes of at most 32 x 32, all
-// 2K passes in one launch.
+// The 2D operator (paper Alg. 1) and its reverse sweep (Sec. 3.2) for planes of at most 32 x 32,
+// all 2K passes of a call in one launch.  Forward kernel: at the end of this file.
 //
+// Reverse sweep.
 // The backward pass of a 1D prox is segment averaging (paper Eq. 5-6) and moves 12 bytes per
 // sample for a few dozen instructions, so the pass-by-pass reverse sweep is bound by memory:
 // 2K passes read and write the two adjoint state tensors again and again.  Here a wave keeps the
@@ -188,6 +189,185 @@ __global__ __launch_bounds__(64) void tv2d_bwd_small_kernel(Small2dBwdParams p)
 #pragma unroll
         for (int d = 1; d < 32; d <<= 1) s += __shfl_xor(s, d);
         if (pvalid && idx == 0) p.partial[plane] = s;
+    }
+}
+
+// ---------------------------------------------------------------------------------
+// Forward: K sweeps of paper Alg. 1 on planes of at most 32 x 32 in one launch.
+//
+// A wave owns two planes for the whole call.  A row pass gives each lane a row of its plane, a
+// column pass a column; either way the lane solves its 1D problem exactly as the short-row
+// kernel does (same RowSolver, row in registers).  Between passes the plane changes hands
+// through one LDS tile of pitch 33, which both views read and write without bank conflicts.
+// The correction terms P (rows) and Q (columns) are only ever touched by the lane that owns
+// the row or column, so they live in a lane-private LDS column; one such column suffices,
+// because P is consumed (A = Y + P) just before the new Q has to be put away and the other way
+// round.  From the second sweep on a pass starts from the dual its correction term encodes
+// (P = D^T u of the row pass one sweep earlier, likewise Q).
+//
+// Memory traffic: y is read once; every pass writes its output (the reverse sweep's tests and
+// the caller's workspace contract want them) and one 8-byte segment code per row or column.
+// ---------------------------------------------------------------------------------
+struct Small2dFwdParams {
+    const float *y;
+    float       *x;
+    float       *saved;        // output of pass i at saved + i * saved_stride (floats)
+    size_t       saved_stride;
+    uint2       *codes;        // as in Small2dBwdParams
+    size_t       code_stride;
+    const float *lam;          // plane p uses lam[p % lam_count]
+    int64_t      lam_count;
+    int32_t      planes, H, W, sweeps;
+    uint32_t     stream;
+};
+
+template <bool FULL>
+__global__ __launch_bounds__(64, 2) void tv2d_fwd_small_kernel(Small2dFwdParams p)
+{
+    constexpr int P = 33;
+    __shared__ float T1[64 * P], T2[64 * 32], gtab[34], rtab[34];
+    const int lane = threadIdx.x;
+    fill_tables<32>(gtab, rtab);
+    const int h = lane >> 5, idx = lane & 31;
+    const int H = FULL ? 32 : p.H, W = FULL ? 32 : p.W, HW = H * W;
+    const int64_t plane0 = (int64_t)blockIdx.x * 2;
+    const int64_t plane = plane0 + h;
+    const bool pvalid = plane < p.planes;
+    const int n_here = (plane0 + 1 < p.planes) ? 2 : 1;
+    float lam = 0.f;
+    if (pvalid) lam = fmaxf(p.lam[plane % p.lam_count], 0.f);
+
+    float *rowp = T1 + (h * 32 + idx) * P;      // row idx of the lane's plane, unit step
+    float *colp = T1 + (h * 32) * P + idx;      // column idx, step P
+    float *park = T1 + lane;                    // the solver's read-only copy of its input, step 64
+    float *mine = T2 + lane;                    // lane-private: the correction term, step 64
+
+    // the two planes -> T1 (memory rows at pitch P)
+    {
+        const float *src = p.y + plane0 * HW;
+        if (FULL && ((uintptr_t)src % 16) == 0) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int e = (i * 64 + lane) * 4;
+                float4 q = make_float4(0.f, 0.f, 0.f, 0.f);
+                if ((e >> 10) < n_here) q = load16(src + e, p.stream != 0);
+                float *d = T1 + (e >> 5) * P + (e & 31);
+                d[0] = q.x; d[1] = q.y; d[2] = q.z; d[3] = q.w;
+            }
+        } else {
+            for (int e = lane; e < n_here * HW; e += 64) {
+                const int hh = e / HW, rem = e - hh * HW, r = rem / W, c = rem - r * W;
+                T1[(hh * 32 + r) * P + c] = src[e];
+            }
+        }
+    }
+    wave_lds_sync();
+
+    // a pass's output, T1 -> memory in plane order
+    auto put_planes = [&](float *dst) {
+        if (FULL && ((uintptr_t)dst % 16) == 0) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int e = (i * 64 + lane) * 4;
+                const float *s = T1 + (e >> 5) * P + (e & 31);
+                if ((e >> 10) < n_here) store16(dst + e, make_float4(s[0], s[1], s[2], s[3]), p.stream != 0);
+            }
+        } else {
+            for (int e = lane; e < n_here * HW; e += 64) {
+                const int hh = e / HW, rem = e - hh * HW, r = rem / W, c = rem - r * W;
+                dst[e] = T1[(hh * 32 + r) * P + c];
+            }
+        }
+    };
+
+    float v[32], xs[32];
+    RowSolver<32, FULL> sv;
+    bool valid = pvalid && (FULL || idx < H);   // first pass: rows, of W samples
+    int n = W;
+#pragma unroll
+    for (int k = 0; k < 32; ++k) v[k] = (valid && (FULL || k < n)) ? rowp[k] : 0.f;
+
+    const int n_pass = 2 * p.sweeps;
+    for (int i = 0; i < n_pass; ++i) {
+        const bool col = (i & 1) != 0;
+        wave_lds_sync();                        // every lane has taken its input out of T1
+#pragma unroll
+        for (int k = 0; k < 32; ++k) park[k * 64] = v[k];
+        wave_lds_sync();
+
+        sv.yl = park; sv.gtab = gtab; sv.lam = lam; sv.m = n - 1;
+        sv.alpha_try = 1.f; sv.steps = 0; sv.flags = 0; sv.nfail = 0;
+        sv.active = valid; sv.prev_unclipped = false;
+        if (i < 2) sv.start(v, rtab[n]);        // first sweep: no correction term yet
+        else sv.start_warm(v);
+        for (int it = 0; !sv.iterate(it); ++it) {}
+        sv.recover(xs);
+
+        {   // segment code of the row / column (as the short-row kernel builds it)
+            uint32_t jm = 0, up = 0;
+#pragma unroll
+            for (int k = 30; k >= 0; --k) {
+                const float d = xs[k] - xs[k + 1];
+                up = __builtin_amdgcn_alignbit(up, __float_as_uint(d), 31);
+                jm = __builtin_amdgcn_alignbit(jm, __float_as_uint(0.0f - fabsf(d)), 31);
+            }
+            if (!FULL) {
+                const uint32_t in = n > 1 ? (0xffffffffu >> (33 - n)) : 0u;
+                jm &= in; up &= in;
+            }
+            if (valid) p.codes[(size_t)i * p.code_stride + (size_t)plane * (col ? W : H) + idx] = make_uint2(jm, up);
+        }
+
+        // the pass's new correction term (input - output); needed by the same direction's pass
+        // of the next sweep
+        const bool keep = i + 2 < n_pass;
+        if (keep) {
+#pragma unroll
+            for (int k = 0; k < 32; ++k) v[k] = park[k * 64] - xs[k];
+        }
+        wave_lds_sync();                        // the parked inputs have been read
+        if (col) {
+#pragma unroll
+            for (int k = 0; k < 32; ++k) colp[k * P] = xs[k];
+        } else {
+#pragma unroll
+            for (int k = 0; k < 32; ++k) rowp[k] = xs[k];
+        }
+        wave_lds_sync();
+        put_planes(p.saved + (size_t)i * p.saved_stride + plane0 * HW);
+        if (i + 1 == n_pass) {
+            put_planes(p.x + plane0 * HW);
+            break;
+        }
+
+        // input of the next pass: this output seen the other way, plus that direction's
+        // correction term, whose negated running sum is the dual to start from
+        valid = pvalid && (FULL || idx < (col ? H : W));
+        n = col ? W : H;
+        float t[32];
+        if (col) {
+#pragma unroll
+            for (int k = 0; k < 32; ++k) t[k] = (valid && (FULL || k < n)) ? rowp[k] : 0.f;
+        } else {
+#pragma unroll
+            for (int k = 0; k < 32; ++k) t[k] = (valid && (FULL || k < n)) ? colp[k * P] : 0.f;
+        }
+        if (i >= 1) {
+            float run = 0.f;
+#pragma unroll
+            for (int k = 0; k < 32; ++k) {
+                const float c = mine[k * 64];
+                t[k] += c;
+                run -= c;
+                if (k < 31) sv.u[k] = run;
+            }
+        }
+        if (keep) {
+#pragma unroll
+            for (int k = 0; k < 32; ++k) mine[k * 64] = v[k];
+        }
+#pragma unroll
+        for (int k = 0; k < 32; ++k) v[k] = t[k];
     }
 }
 

@@ -72,6 +72,17 @@ def test_small_planes(shape, K):
     _check_2d(y, lam, K, g, "small %s K=%d" % (shape, K), bulk=0.8)
 
 
+@pytest.mark.parametrize("shape,K", [((4099, 8, 9), 2), ((4097, 32, 32), 2)])
+def test_many_small_planes(shape, K):
+    # more small planes than the one-launch forward kernel takes: pass-by-pass forward (plane
+    # columns, warm rows), segment codes for the fused reverse sweep
+    rng = np.random.default_rng(79 + shape[2])
+    y = rng.normal(size=shape).astype(np.float32)
+    g = rng.normal(size=shape).astype(np.float32)
+    lam = (10 ** rng.uniform(-2, 0.3, size=5)).astype(np.float32)
+    _check_2d(y, lam, K, g, "many small %s K=%d" % (shape, K), bulk=0.8)
+
+
 @pytest.mark.parametrize("shape", [(1, 1100, 2100), (2, 40, 9000)])
 def test_long_rows_and_columns_k2(shape):
     """Rows and columns beyond 1024 samples (a workgroup per row; interleaved columns), two
