@@ -942,12 +942,44 @@ size_t tv2d_workspace_bytes(int64_t planes, int64_t H, int64_t W, int sweeps)
     return tb * (size_t)(2 * sweeps + 2) + (pb + cb) * (size_t)(2 * sweeps) + kSplitScratchBytes;
 }
 
-// The one-launch forward kernel for small planes holds two planes per wave and, with 17 KB of LDS
-// per wave, two waves per SIMD where the pass-by-pass kernels hold three.  It wins (15-30 %: no
-// launches and no memory round trips between the passes) while all its waves fit on the chip at
-// once, 2 x 1024 SIMDs x 2 planes; beyond that the lower occupancy costs more than the fusion
-// saves (measured: 4096 planes, K = 3: 171 us against 242; 8192 planes: 311 against 304).
-constexpr int64_t kFusedFwdMaxPlanes = 4096;
+// Planes of at most 32 x 32 are padded to squares of side 8, 16 or 32; a wave holds 64 / side of them.
+static int small_side(int64_t H, int64_t W)
+{
+    const int64_t m = H > W ? H : W;
+    return m <= 8 ? 8 : (m <= 16 ? 16 : 32);
+}
+
+#define TV_SMALL2D_LAUNCH(KERNEL, q, planes, H, W, stream)                                          \
+    do {                                                                                            \
+        const int side = small_side(H, W);                                                          \
+        const bool full = (H) == side && (W) == side;                                               \
+        const dim3 grid((uint32_t)(((planes) + 64 / side - 1) / (64 / side)));                      \
+        if (side == 8) {                                                                            \
+            if (full) hipLaunchKernelGGL((KERNEL<8, true>), grid, dim3(64), 0, stream, q);          \
+            else hipLaunchKernelGGL((KERNEL<8, false>), grid, dim3(64), 0, stream, q);              \
+        } else if (side == 16) {                                                                    \
+            if (full) hipLaunchKernelGGL((KERNEL<16, true>), grid, dim3(64), 0, stream, q);         \
+            else hipLaunchKernelGGL((KERNEL<16, false>), grid, dim3(64), 0, stream, q);             \
+        } else {                                                                                    \
+            if (full) hipLaunchKernelGGL((KERNEL<32, true>), grid, dim3(64), 0, stream, q);         \
+            else hipLaunchKernelGGL((KERNEL<32, false>), grid, dim3(64), 0, stream, q);             \
+        }                                                                                           \
+    } while (0)
+
+// When the one-launch forward kernel is used.  With planes padded to 32 x 32 it holds two planes
+// per wave and, with 17 KB of LDS per wave, two waves per SIMD where the pass-by-pass kernels hold
+// three: it wins (15-30 %: no launches and no memory round trips between the passes) while all its
+// waves fit on the chip at once, 2 x 1024 SIMDs x 2 planes; beyond that the lower occupancy costs
+// more than the fusion saves (measured: 4096 planes, K = 3: 171 us against 242; 8192 planes: 311
+// against 304).  Planes of at most 16 x 16 need a quarter of the LDS and 144 registers: the one
+// launch wins except for a single sweep over many planes (32 768 planes: K = 1 69 us against 58,
+// K = 3 166 against 206); planes of at most 8 x 8 are always better off in one launch.
+static bool fused_fwd_applies(int side, int64_t planes, int sweeps)
+{
+    if (side == 32) return planes <= 4096;
+    if (side == 16) return sweeps >= 2 || planes <= 16384;
+    return true;
+}
 
 int tv2d_prox_fwd(const float *y, float *x, int64_t planes, int64_t H, int64_t W, tv_lambda lam,
                   int sweeps, void *ws, size_t ws_bytes, hipStream_t stream)
@@ -974,18 +1006,15 @@ int tv2d_prox_fwd(const float *y, float *x, int64_t planes, int64_t H, int64_t W
     const tv_lambda lrow = {lam.lam, lam.count, H};
     const tv_lambda lcol = {lam.lam, lam.count, W};
 
-    if (cb && planes <= kFusedFwdMaxPlanes) {
-        // planes of at most 32 x 32, few enough that every wave is resident at once: all passes in
-        // one launch, the planes resident in LDS
+    if (cb && fused_fwd_applies(small_side(H, W), planes, sweeps)) {
+        // planes of at most 32 x 32: all passes in one launch, the planes resident in LDS
         tvk::Small2dFwdParams q;
         q.y = y; q.x = x; q.saved = saved(0); q.saved_stride = tb / sizeof(float);
         q.codes = codes(0); q.code_stride = cb / sizeof(uint2);
         q.lam = lam.lam; q.lam_count = lam.count;
         q.planes = (int32_t)planes; q.H = (int32_t)H; q.W = (int32_t)W; q.sweeps = sweeps;
         q.stream = (planes * H * W >= ((int64_t)32 << 20) / 4) ? 1u : 0u;
-        const dim3 grid((uint32_t)((planes + 1) / 2));
-        if (H == 32 && W == 32) hipLaunchKernelGGL(tvk::tv2d_fwd_small_kernel<true>, grid, dim3(64), 0, stream, q);
-        else hipLaunchKernelGGL(tvk::tv2d_fwd_small_kernel<false>, grid, dim3(64), 0, stream, q);
+        TV_SMALL2D_LAUNCH(tvk::tv2d_fwd_small_kernel, q, planes, H, W, stream);
         return launch_status();
     }
     for (int k = 0; k < sweeps; ++k) {
@@ -1049,9 +1078,7 @@ int tv2d_prox_bwd(const float *g_up, float *grad_y, float *grad_lam, int64_t pla
         q.partial = grad_lam ? partial(0) : nullptr;
         q.planes = (int32_t)planes; q.H = (int32_t)H; q.W = (int32_t)W; q.sweeps = sweeps;
         q.stream = (planes * H * W >= ((int64_t)32 << 20) / 4) ? 1u : 0u;
-        const dim3 grid((uint32_t)((planes + 1) / 2));
-        if (H == 32 && W == 32) hipLaunchKernelGGL(tvk::tv2d_bwd_small_kernel<true>, grid, dim3(64), 0, stream, q);
-        else hipLaunchKernelGGL(tvk::tv2d_bwd_small_kernel<false>, grid, dim3(64), 0, stream, q);
+        TV_SMALL2D_LAUNCH(tvk::tv2d_bwd_small_kernel, q, planes, H, W, stream);
         if (launch_status() != TV_OK) return TV_ERR_HIP;
         if (!grad_lam) return TV_OK;
         const tv_lambda lp = {lam.lam, lam.count, 1};

@@ -62,7 +62,11 @@ def test_odd_sizes_mixed_paths():
 
 @pytest.mark.parametrize("shape,K", [((5, 19, 11), 3), ((3, 32, 16), 2), ((7, 8, 32), 2), ((2, 1, 17), 2),
                                      ((3, 32, 32), 5), ((1, 2, 2), 1), ((1, 32, 32), 20), ((2, 32, 1), 3),
-                                     ((1, 1, 32), 3), ((9, 31, 32), 4)])
+                                     ((1, 1, 32), 3), ((9, 31, 32), 4),
+                                     # planes of at most 16 x 16 and 8 x 8: four and eight to a wave
+                                     ((37, 16, 16), 3), ((11, 13, 16), 2), ((3, 16, 9), 4), ((70, 8, 8), 2),
+                                     ((9, 5, 7), 3), ((13, 8, 3), 2), ((5, 1, 8), 2), ((6, 12, 1), 2),
+                                     ((4099, 8, 8), 1), ((2050, 16, 16), 2)])
 def test_small_planes(shape, K):
     # planes of at most 32 x 32: both passes on the row-per-lane kernels, ragged in both directions
     rng = np.random.default_rng(73 + shape[1] * 64 + shape[2])
@@ -72,10 +76,11 @@ def test_small_planes(shape, K):
     _check_2d(y, lam, K, g, "small %s K=%d" % (shape, K), bulk=0.8)
 
 
-@pytest.mark.parametrize("shape,K", [((4099, 8, 9), 2), ((4097, 32, 32), 2)])
+@pytest.mark.parametrize("shape,K", [((4099, 20, 9), 2), ((4097, 32, 32), 2), ((16390, 16, 16), 1)])
 def test_many_small_planes(shape, K):
-    # more small planes than the one-launch forward kernel takes: pass-by-pass forward (plane
-    # columns, warm rows), segment codes for the fused reverse sweep
+    # more small planes than the one-launch forward kernel takes (4096 padded to 32 x 32; 16 384 of
+    # at most 16 x 16 with a single sweep): pass-by-pass forward (plane columns, warm rows), segment
+    # codes for the fused reverse sweep
     rng = np.random.default_rng(79 + shape[2])
     y = rng.normal(size=shape).astype(np.float32)
     g = rng.normal(size=shape).astype(np.float32)
