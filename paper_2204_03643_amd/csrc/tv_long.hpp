@@ -140,8 +140,8 @@ __device__ __forceinline__ float wave_sum_all(float v)
     v += long_dpp<0x4E>(v);
     v += long_dpp<0x141>(v);
     v += long_dpp<0x140>(v);
-    v += __shfl_xor(v, 16);
-    if (LANES > 32) v += __shfl_xor(v, 32);           // LANES = 32: two rows per wave, kept apart
+    if (LANES > 16) v += __shfl_xor(v, 16);           // LANES = 16: four rows per wave, kept apart
+    if (LANES > 32) v += __shfl_xor(v, 32);           // LANES = 32: two rows per wave
     return v;
 }
 
@@ -1053,8 +1053,8 @@ inline hipError_t launch_bwd_long_t(const BwdParams &p, hipStream_t s)
         const int n = (p).L.n;                                                            \
         const bool cols = (p).L.elem_stride != 1;                                         \
         if (cols) {                                                                       \
-            if (n <= 64) return FN<32, 2, 16, true>(p, s);                                \
-            if (n <= 128) return FN<32, 4, 16, true>(p, s);                               \
+            if (n <= 64) return FN<16, 4, 16, true>(p, s);                                \
+            if (n <= 128) return FN<16, 8, 16, true>(p, s);                               \
             if (n <= 256) return FN<32, 8, 16, true>(p, s);                               \
             if (n <= 512) return FN<64, 8, 16, true>(p, s);                               \
             if (n <= 1024) return FN<64, 16, 16, true>(p, s);                             \
@@ -1063,8 +1063,8 @@ inline hipError_t launch_bwd_long_t(const BwdParams &p, hipStream_t s)
             if (n <= 8192) return FN<1024, 8, 1, true>(p, s);                             \
             return FN<1024, 16, 1, true>(p, s);                                           \
         }                                                                                 \
-        if (n <= 64) return FN<32, 2, 8, false>(p, s);                                    \
-        if (n <= 128) return FN<32, 4, 8, false>(p, s);                                   \
+        if (n <= 64) return FN<16, 4, 16, false>(p, s);                                   \
+        if (n <= 128) return FN<16, 8, 16, false>(p, s);                                  \
         if (n <= 256) return FN<32, 8, 8, false>(p, s);                                   \
         if (n <= 512) return FN<64, 8, 4, false>(p, s);                                   \
         if (n <= 1024) return FN<64, 16, 4, false>(p, s);                                 \
