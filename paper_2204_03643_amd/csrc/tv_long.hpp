@@ -139,7 +139,7 @@ __device__ __forceinline__ float wave_sum_all(float v)
     v += long_dpp<0xB1>(v);
     v += long_dpp<0x4E>(v);
     v += long_dpp<0x141>(v);
-    v += long_dpp<0x140>(v);
+    if (LANES > 8) v += long_dpp<0x140>(v);
     if (LANES > 16) v += __shfl_xor(v, 16);           // LANES = 16: four rows per wave, kept apart
     if (LANES > 32) v += __shfl_xor(v, 32);           // LANES = 32: two rows per wave
     return v;
@@ -341,6 +341,7 @@ struct LongSmem {
     using Mp = LongMap<T, G, COLS>;
     static constexpr int TP = T + 2;                   // one zero sentinel on either side
     float gtab[C + 2];
+    float rtab[C + 2];                                 // rtab[m] = 1 / (m + 1) = 1 - gtab[m]
     float ex[5][G][TP];
     float buf[2 * 3 * G * T];
     float red[2 * 4 * Mp::NW * Mp::RG];
@@ -405,7 +406,10 @@ __global__ __launch_bounds__(T *G, (T * G == 512 && !COLS) ? 4 : ((XPOSE && C <=
     const int n = p.L.n, M = n - 1;
     const int k0 = t * C;
 
-    if (tid <= C) sm.gtab[tid] = (float)tid / (float)(tid + 1);
+    if (tid <= C) {
+        sm.gtab[tid] = (float)tid / (float)(tid + 1);
+        sm.rtab[tid] = 1.0f / (float)(tid + 1);
+    }
     if (!TILE_ALIAS && t == 0) {
 #pragma unroll
         for (int q = 0; q < 5; ++q) { sm.ex[q][j][0] = 0.f; sm.ex[q][j][T + 1] = 0.f; }
@@ -414,7 +418,7 @@ __global__ __launch_bounds__(T *G, (T * G == 512 && !COLS) ? 4 : ((XPOSE && C <=
 
     const int64_t off = rvalid ? row_offset(p.L, row) : 0;
     const int64_t es = p.L.elem_stride;
-    const float lam = rvalid ? load_lambda(p.lam, p.L, row) * p.lam_scale : 0.f;
+    float lam = rvalid ? load_lambda(p.lam, p.L, row) * p.lam_scale : 0.f;
     float y[C];
     // transposing variant: thread tid moves samples k = tid / G, tid / G + T, ... of row tid % G
     const int xj = tid % G, xk0 = tid / G;
@@ -501,6 +505,11 @@ __global__ __launch_bounds__(T *G, (T * G == 512 && !COLS) ? 4 : ((XPOSE && C <=
 #pragma unroll
         for (int i = 0; i < C; ++i) ym[0] = fmaxf(ym[0], fabsf(y[i]));
         row_max<T, G, MCOLS>(ym, sm.red, j, tid);
+        // lam_max = max_k |sum_{i<=k} (mean(y) - y_i)| <= 2 n max|y|, and every lambda from
+        // lam_max on gives the same minimiser (the row's mean): a lambda beyond that bound is
+        // replaced by it, which keeps the dual box, and with it the rounding errors of
+        // x = y - D^T u, at the scale of the data
+        lam = fminf(lam, 2.5f * (float)n * ym[0]);
         gtol = kGradNoise * (ym[0] + lam);
         Mp::sync();
     }
@@ -630,8 +639,13 @@ __global__ __launch_bounds__(T *G, (T * G == 512 && !COLS) ? 4 : ((XPOSE && C <=
             }
             p0 = pn;
         }
-        const float c_alpha = sm.gtab[a];                       // (A^-1)_{first,first}
-        const float c_delta = sm.gtab[pos];                     // (A^-1)_{last,last}
+        // The separator's diagonal is 2 - (A^-1)_{last,last} of this chunk's interior block -
+        // (A^-1)_{first,first} of the next one's, with (A^-1)_{first,first} = a / (a + 1) for a
+        // leading free duals (likewise at the other end).  Inside a long free run that is
+        // 2 - 2 (C - 1) / C: formed from the rounded fractions it loses all but a few bits
+        // unless C is a power of two, so the exchange carries 1 - a / (a + 1) = 1 / (a + 1).
+        const float c_alpha = sm.rtab[a];                       // 1 - (A^-1)_{first,first}
+        const float c_delta = sm.rtab[pos];                     // 1 - (A^-1)_{last,last}
         const float c_beta = (a == C - 1) ? (1.0f / (float)C) : 0.f;  // (A^-1)_{first,last}
         TV_EX(2, t) = p0;
         TV_EX(3, t) = c_alpha;
@@ -655,7 +669,7 @@ __global__ __launch_bounds__(T *G, (T * G == 512 && !COLS) ? 4 : ((XPOSE && C <=
         // ---- separator system (normalised to unit diagonal) and PCR
         float ea = 0.f, ec = 0.f, er = 0.f;
         if (!bsep) {
-            const float inv = __builtin_amdgcn_rcpf(2.0f - c_delta - alphan);
+            const float inv = __builtin_amdgcn_rcpf(c_delta + alphan);
             ea = -c_beta * inv;
             ec = -betan * inv;
             er = (g[C - 1] + pl + p0n) * inv;
@@ -1053,20 +1067,28 @@ inline hipError_t launch_bwd_long_t(const BwdParams &p, hipStream_t s)
         const int n = (p).L.n;                                                            \
         const bool cols = (p).L.elem_stride != 1;                                         \
         if (cols) {                                                                       \
-            if (n <= 64) return FN<16, 4, 16, true>(p, s);                                \
+            if (n <= 64) return FN<8, 8, 16, true>(p, s);                                 \
+            if (n <= 96) return FN<8, 12, 16, true>(p, s);                                \
             if (n <= 128) return FN<16, 8, 16, true>(p, s);                               \
+            if (n <= 192) return FN<16, 12, 16, true>(p, s);                              \
             if (n <= 256) return FN<32, 8, 16, true>(p, s);                               \
+            if (n <= 384) return FN<32, 12, 16, true>(p, s);                              \
             if (n <= 512) return FN<64, 8, 16, true>(p, s);                               \
+            if (n <= 768) return FN<64, 12, 16, true>(p, s);                              \
             if (n <= 1024) return FN<64, 16, 16, true>(p, s);                             \
             if (n <= 2048) return FN<256, 8, 4, true>(p, s);                              \
             if (n <= 4096) return FN<256, 16, 4, true>(p, s);                             \
             if (n <= 8192) return FN<1024, 8, 1, true>(p, s);                             \
             return FN<1024, 16, 1, true>(p, s);                                           \
         }                                                                                 \
-        if (n <= 64) return FN<16, 4, 16, false>(p, s);                                   \
+        if (n <= 64) return FN<8, 8, 32, false>(p, s);                                    \
+        if (n <= 96) return FN<8, 12, 32, false>(p, s);                                   \
         if (n <= 128) return FN<16, 8, 16, false>(p, s);                                  \
+        if (n <= 192) return FN<16, 12, 16, false>(p, s);                                 \
         if (n <= 256) return FN<32, 8, 8, false>(p, s);                                   \
+        if (n <= 384) return FN<32, 12, 8, false>(p, s);                                  \
         if (n <= 512) return FN<64, 8, 4, false>(p, s);                                   \
+        if (n <= 768) return FN<64, 12, 4, false>(p, s);                                  \
         if (n <= 1024) return FN<64, 16, 4, false>(p, s);                                 \
         if (n <= 2048) return FN<256, 8, 1, false>(p, s);                                 \
         if (n <= 4096) return FN<256, 16, 1, false>(p, s);                                \

@@ -72,6 +72,19 @@ def test_multilevel_start(n):
     assert ml["steps"][big].sum() < cold["steps"][big].sum(), (ml["steps"], cold["steps"])
 
 
+@pytest.mark.parametrize("n", [40, 90, 160, 300, 700, 3000])
+@pytest.mark.parametrize("lam", [1e3, 1e5])
+def test_lambda_far_beyond_lam_max(n, lam):
+    """Every lambda from lam_max on gives the row mean.  A dual box far larger than the data must
+    not cost accuracy (12 samples per thread: the separator system's diagonal is formed without
+    cancellation; lambda is capped at a bound on lam_max).  Random-walk rows of thousands of
+    samples have a lam_max above 1e3: those are ordinary parity cases."""
+    rng = np.random.default_rng(900 + n)
+    y = _mixed_rows(rng, 6, n)
+    g = rng.normal(size=y.shape).astype(np.float32)
+    _check(y, np.array([lam], np.float32), 1, g, -1, "n=%d lam=%g" % (n, lam))
+
+
 def test_noise_rows_with_lambda_near_lam_max():
     """Noise-like long rows with lambda a third of their lam_max are the worst case of the cold
     start (every dual on the bound its local difference points to): dozens of Newton steps.
