@@ -1076,9 +1076,12 @@ inline hipError_t launch_bwd_long_t(const BwdParams &p, hipStream_t s)
             if (n <= 512) return FN<64, 8, 16, true>(p, s);                               \
             if (n <= 768) return FN<64, 12, 16, true>(p, s);                              \
             if (n <= 1024) return FN<64, 16, 16, true>(p, s);                             \
-            if (n <= 2048) return FN<256, 8, 4, true>(p, s);                              \
+            if (n <= 1536) return FN<128, 12, 8, true>(p, s);                             \
+            if (n <= 2048) return FN<128, 16, 8, true>(p, s);                             \
+            if (n <= 3072) return FN<256, 12, 4, true>(p, s);                             \
             if (n <= 4096) return FN<256, 16, 4, true>(p, s);                             \
             if (n <= 8192) return FN<1024, 8, 1, true>(p, s);                             \
+            if (n <= 12288) return FN<1024, 12, 1, true>(p, s);                           \
             return FN<1024, 16, 1, true>(p, s);                                           \
         }                                                                                 \
         if (n <= 64) return FN<8, 8, 32, false>(p, s);                                    \
@@ -1090,9 +1093,13 @@ inline hipError_t launch_bwd_long_t(const BwdParams &p, hipStream_t s)
         if (n <= 512) return FN<64, 8, 4, false>(p, s);                                   \
         if (n <= 768) return FN<64, 12, 4, false>(p, s);                                  \
         if (n <= 1024) return FN<64, 16, 4, false>(p, s);                                 \
+        if (n <= 1536) return FN<128, 12, 2, false>(p, s);                                \
         if (n <= 2048) return FN<256, 8, 1, false>(p, s);                                 \
+        if (n <= 3072) return FN<256, 12, 1, false>(p, s);                                \
         if (n <= 4096) return FN<256, 16, 1, false>(p, s);                                \
+        if (n <= 6144) return FN<512, 12, 1, false>(p, s);                                \
         if (n <= 8192) return FN<512, 16, 1, false>(p, s);                                \
+        if (n <= 12288) return FN<1024, 12, 1, false>(p, s);                              \
         return FN<1024, 16, 1, false>(p, s);                                              \
     } while (0)
 

@@ -44,8 +44,8 @@ def test_config1_full():
     assert st["max_steps"] <= 40
 
 
-@pytest.mark.parametrize("n", [33, 64, 65, 100, 128, 129, 255, 256, 300, 512, 513, 1000, 1024, 1025,
-                               2048, 3000, 4096, 5000, 8192, 10000, 16384])
+@pytest.mark.parametrize("n", [33, 64, 65, 96, 100, 128, 129, 192, 255, 256, 300, 384, 512, 513, 768, 1000, 1024,
+                               1025, 1536, 2048, 3000, 4096, 5000, 6144, 8192, 10000, 12288, 16384])
 def test_every_long_length(n):
     rng = np.random.default_rng(500 + n)
     rows = 7 if n <= 4096 else 3
@@ -139,7 +139,8 @@ def test_multilevel_per_channel_lambda_and_strided_rows():
     assert err.max() <= FWD_TOL, err
 
 
-@pytest.mark.parametrize("n,width", [(40, 37), (64, 16), (200, 20), (512, 48), (1500, 9), (4096, 6), (9000, 3)])
+@pytest.mark.parametrize("n,width", [(40, 37), (64, 16), (90, 33), (130, 17), (200, 20), (300, 18), (512, 48), (700, 17),
+                                          (1500, 9), (2000, 9), (2600, 5), (4096, 6), (9000, 3), (12000, 2)])
 def test_long_columns(n, width):
     rng = np.random.default_rng(600 + n)
     y = np.stack([_mixed_rows(rng, width, n).T for _ in range(2)])        # [2, n, width]
