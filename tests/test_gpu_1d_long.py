@@ -191,3 +191,22 @@ def test_long_constant_and_tied_rows():
     x_ref = oracle.prox1d_batch(y.astype(np.float64), lam.astype(np.float64))
     assert forward_errors(out["x"], x_ref, y).max() <= FWD_TOL
     assert not np.any(out["info"] & (1 << 18))
+
+
+@pytest.mark.parametrize("n,axis", [(100, -1), (100, 0), (700, -1), (700, 0), (5000, -1)])
+def test_nan_row_stays_in_its_row(n, axis):
+    """A row with a non-finite sample gets unspecified values; its neighbours (several rows share
+    a wave or a workgroup) are solved as usual and the call terminates."""
+    rng = np.random.default_rng(45 + n)
+    rows = 21
+    y = _mixed_rows(rng, rows, n)
+    y[5, n // 3] = np.nan
+    y[17, n - 1] = np.inf
+    ya = y if axis == -1 else np.ascontiguousarray(y.T)
+    out = run_1d(ya, np.array([0.3], np.float32), 1, axis=axis)
+    x = out["x"] if axis == -1 else out["x"].T
+    assert np.isnan(x[5, n // 3]) and not np.isfinite(x[17, n - 1])
+    ok = np.delete(np.arange(rows), [5, 17])
+    x_ref = oracle.prox1d_batch(y[ok].astype(np.float64), np.array([0.3]))
+    assert forward_errors(x[ok], x_ref, y[ok]).max() <= FWD_TOL
+

@@ -112,3 +112,23 @@ def test_lambda_zero_identity_and_mass():
     assert np.array_equal(out["x"], y) and np.array_equal(out["gy"], g)
     out = run_2d(y, np.array([0.4], np.float32), 4)
     np.testing.assert_allclose(out["x"].astype(np.float64).sum((-1, -2)), y.astype(np.float64).sum((-1, -2)), atol=2e-3)
+
+
+@pytest.mark.parametrize("shape", [(5, 32, 32), (9, 16, 16), (3, 40, 70)])
+def test_nan_plane_stays_in_its_plane(shape):
+    """A non-finite sample spoils its own plane at most (fused kernels hold several planes per
+    wave); the other planes match the oracle and the call terminates."""
+    rng = np.random.default_rng(83 + shape[1])
+    y = rng.normal(size=shape).astype(np.float32)
+    bad = 1
+    y[bad, shape[1] // 2, shape[2] // 3] = np.nan
+    lam = np.array([0.2, 0.7], np.float32)
+    out = run_2d(y, lam, 3)
+    assert np.isnan(out["x"][bad]).any()
+    ok = np.delete(np.arange(shape[0]), bad)
+    lam_ok = lam[ok % 2].astype(np.float64)
+    for p, l in zip(ok, lam_ok):
+        x_ref, _ = oracle.prox2d_fwd(y[p:p + 1].astype(np.float64), np.array([l]), 3)
+        err = np.abs(out["x"][p] - x_ref[0]).max() / (1 + np.abs(y[p]).max())
+        assert err <= 1e-4, (shape, p, err)
+
