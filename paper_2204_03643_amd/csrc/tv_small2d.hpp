@@ -20,49 +20,70 @@ struct Small2dBwdParams {
     float       *gy;
     const uint2 *codes;        // pass i (row pass of sweep k: 2k, column pass: 2k + 1) at codes + i * code_stride
     size_t       code_stride;  // in uint2
+    const float *saved;        // planes of 33-64 samples a side have no codes: the output of pass i,
+    size_t       saved_stride; // at saved + i * saved_stride (floats), is read instead
     float       *partial;      // optional: one dL/dlam term per plane (all passes summed)
     int32_t      planes, H, W, sweeps;
     uint32_t     stream;       // tensors too large to stay in cache: non-temporal accesses
 };
 
+// Bit k of a row's segment code: x = jump bits 0-31, y = direction bits 0-31, z and w = the same
+// for duals 32-62 (rows of more than 32 samples).
+template <int K>
+__device__ __forceinline__ bool code_jump(const uint4 &c) { return ((K < 32 ? c.x : c.z) & (1u << (K & 31))) != 0u; }
+template <int K>
+__device__ __forceinline__ bool code_up(const uint4 &c) { return ((K < 32 ? c.y : c.w) & (1u << (K & 31))) != 0u; }
+
 // Segment means of g[0 .. n-1] in place, segments given by the code's jump bits; returns the
 // row's dL/dlam term  sum over jumps k of sign(x[k+1] - x[k]) (mean_left - mean_right).
 // FULL: n = S at compile time.
-template <int S, bool FULL>
-__device__ __forceinline__ float small2d_segment_means(float (&g)[S], uint2 code, int n, const float *rtab)
+template <int S, bool FULL, int K = 0>
+__device__ __forceinline__ void small2d_means_up(float (&g)[S], const uint4 &code, int n, const float *rtab,
+                                                 float &s, int &c4)
 {
-    {
-        float s = 0.f;
-        int c4 = 0;
-#pragma unroll
-        for (int k = 0; k < S; ++k) {
-            s += g[k];
-            c4 += 4;
-            const bool last = FULL ? (k == S - 1) : (k >= n - 1);
-            const bool end = last || (k + 1 < S && (code.x & (1u << k)) != 0u);
-            g[k] = s * *reinterpret_cast<const float *>(reinterpret_cast<const char *>(rtab) + c4);
-            if (end) { s = 0.f; c4 = 0; }
-        }
+    if constexpr (K < S) {
+        s += g[K];
+        c4 += 4;
+        const bool last = FULL ? (K == S - 1) : (K >= n - 1);
+        bool end = last;
+        if constexpr (K + 1 < S) end = end || code_jump<K>(code);
+        g[K] = s * *reinterpret_cast<const float *>(reinterpret_cast<const char *>(rtab) + c4);
+        if (end) { s = 0.f; c4 = 0; }
+        small2d_means_up<S, FULL, K + 1>(g, code, n, rtab, s, c4);
     }
-    float glam = 0.f;
-    float carry = 0.f;
-#pragma unroll
-    for (int k = S - 1; k >= 0; --k) {
+}
+template <int S, bool FULL, int K = S - 1>
+__device__ __forceinline__ void small2d_means_down(float (&g)[S], const uint4 &code, int n, float &carry,
+                                                   float &glam)
+{
+    if constexpr (K >= 0) {
         const float right = carry;
-        const bool last = FULL ? (k == S - 1) : (k >= n - 1);
-        const bool end = last || (k + 1 < S && (code.x & (1u << k)) != 0u);
-        carry = end ? g[k] : carry;
-        g[k] = carry;
-        if (k + 1 < S && (FULL || k < n - 1)) {
-            const float d = carry - right;
-            glam += (code.y & (1u << k)) != 0u ? d : -d;
+        const bool last = FULL ? (K == S - 1) : (K >= n - 1);
+        bool end = last;
+        if constexpr (K + 1 < S) end = end || code_jump<K>(code);
+        carry = end ? g[K] : carry;
+        g[K] = carry;
+        if constexpr (K + 1 < S) {
+            if (FULL || K < n - 1) {
+                const float d = carry - right;
+                glam += code_up<K>(code) ? d : -d;
+            }
         }
+        small2d_means_down<S, FULL, K - 1>(g, code, n, carry, glam);
     }
+}
+template <int S, bool FULL>
+__device__ __forceinline__ float small2d_segment_means(float (&g)[S], const uint4 &code, int n, const float *rtab)
+{
+    float s = 0.f, carry = 0.f, glam = 0.f;
+    int c4 = 0;
+    small2d_means_up<S, FULL>(g, code, n, rtab, s, c4);
+    small2d_means_down<S, FULL>(g, code, n, carry, glam);
     return glam;
 }
-
-// S = 8, 16 or 32: the side of the square a plane is padded to; a wave holds 64 / S planes, one
-// row or column per lane.  FULL: planes of exactly S x S.
+// S = 8, 16, 32 or 64: the side of the square a plane is padded to; a wave holds 64 / S planes,
+// one row or column per lane.  FULL: planes of exactly S x S.  S = 64: the segments of a pass are
+// read off its saved output (the forward kernels for rows of more than 32 samples write no codes).
 template <int S, bool FULL>
 __global__ __launch_bounds__(64) void tv2d_bwd_small_kernel(Small2dBwdParams p)
 {
@@ -70,7 +91,7 @@ __global__ __launch_bounds__(64) void tv2d_bwd_small_kernel(Small2dBwdParams p)
     constexpr int PP = 64 / S;                      // planes per wave
     __shared__ float A[64 * P], B[64 * P], rtab[S + 2];
     const int lane = threadIdx.x;
-    if (lane <= S) rtab[lane] = lane > 0 ? 1.0f / (float)lane : 0.0f;
+    for (int i = lane; i <= S; i += 64) rtab[i] = i > 0 ? 1.0f / (float)i : 0.0f;
     const int h = lane / S, idx = lane % S;         // which of the wave's planes; row or column
     const int H = FULL ? S : p.H, W = FULL ? S : p.W, HW = H * W;
     const int64_t plane0 = (int64_t)blockIdx.x * PP;
@@ -104,20 +125,57 @@ __global__ __launch_bounds__(64) void tv2d_bwd_small_kernel(Small2dBwdParams p)
     // the segment code of a pass is fetched one pass ahead, so that its latency hides behind
     // the pass before
     const bool cvalid = pvalid && (FULL || idx < W), rvalid = pvalid && (FULL || idx < H);
-    auto fetch_code = [&](int pass) -> uint2 {
-        if (pass < 0) return make_uint2(0u, 0u);
+    auto fetch_code = [&](int pass) -> uint4 {
+        if (pass < 0) return make_uint4(0u, 0u, 0u, 0u);
         const bool col = (pass & 1) != 0;
-        if (!(col ? cvalid : rvalid)) return make_uint2(0u, 0u);
-        return p.codes[(size_t)pass * p.code_stride + (size_t)plane * (col ? W : H) + idx];
+        if constexpr (S <= 32) {
+            if (!(col ? cvalid : rvalid)) return make_uint4(0u, 0u, 0u, 0u);
+            const uint2 c = p.codes[(size_t)pass * p.code_stride + (size_t)plane * (col ? W : H) + idx];
+            return make_uint4(c.x, c.y, 0u, 0u);
+        } else {
+            // the lane's row or column of the pass's output, then one bit per neighbour pair
+            const float *xs = p.saved + (size_t)pass * p.saved_stride + (size_t)plane * HW;
+            float xv[S];
+            if (col) {
+#pragma unroll
+                for (int r = 0; r < S; ++r) xv[r] = (cvalid && (FULL || r < H)) ? xs[r * W + idx] : 0.f;
+            } else if (FULL && ((uintptr_t)xs % 16) == 0) {
+#pragma unroll
+                for (int c = 0; c < S; c += 4) {
+                    float4 q = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (rvalid) q = *reinterpret_cast<const float4 *>(xs + idx * S + c);
+                    xv[c] = q.x; xv[c + 1] = q.y; xv[c + 2] = q.z; xv[c + 3] = q.w;
+                }
+            } else {
+#pragma unroll
+                for (int c = 0; c < S; ++c) xv[c] = (rvalid && (FULL || c < W)) ? xs[idx * W + c] : 0.f;
+            }
+            // built from the highest dual of each word down, one shift-in per dual, so that dual k
+            // ends up at bit k & 31; the sign of x[k] - x[k+1] says "rises", that of -|.| "differs"
+            uint4 c = make_uint4(0u, 0u, 0u, 0u);
+#pragma unroll
+            for (int k = S - 2; k >= 32; --k) {
+                const float d = xv[k] - xv[k + 1];
+                c.w = __builtin_amdgcn_alignbit(c.w, __float_as_uint(d), 31);
+                c.z = __builtin_amdgcn_alignbit(c.z, __float_as_uint(0.0f - fabsf(d)), 31);
+            }
+#pragma unroll
+            for (int k = 31; k >= 0; --k) {
+                const float d = xv[k] - xv[k + 1];
+                c.y = __builtin_amdgcn_alignbit(c.y, __float_as_uint(d), 31);
+                c.x = __builtin_amdgcn_alignbit(c.x, __float_as_uint(0.0f - fabsf(d)), 31);
+            }
+            return c;
+        }
     };
-    uint2 code_next = fetch_code(2 * p.sweeps - 1);
+    uint4 code_next = fetch_code(2 * p.sweeps - 1);
     for (int k = p.sweeps - 1; k >= 0; --k) {
         const bool first = (k == p.sweeps - 1);
         // ---- adjoint of the column pass: B <- C^T(A - B) + B  (B = 0 in the first reverse step);
         //      a lane holds column idx of its plane
         {
             const bool valid = cvalid;
-            const uint2 code = code_next;
+            const uint4 code = code_next;
             code_next = fetch_code(2 * k);
             const float *a = A + (h * S) * P + idx;
             float *b = B + (h * S) * P + idx;
@@ -145,7 +203,7 @@ __global__ __launch_bounds__(64) void tv2d_bwd_small_kernel(Small2dBwdParams p)
         //      a lane holds row idx of its plane
         {
             const bool valid = rvalid;
-            const uint2 code = code_next;
+            const uint4 code = code_next;
             code_next = fetch_code(2 * k - 1);
             float *a = A + (h * S + idx) * P;
             const float *b = B + (h * S + idx) * P;

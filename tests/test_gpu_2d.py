@@ -49,6 +49,18 @@ def test_config3_planes_k1():
     _check_2d(y, lam, 1, g, "cfg3 K=1")
 
 
+@pytest.mark.parametrize("shape,K", [((5, 64, 64), 3), ((3, 40, 64), 2), ((4, 64, 33), 2), ((7, 50, 47), 4),
+                                     ((2, 33, 1), 2), ((2, 20, 60), 3), ((1, 64, 64), 12)])
+def test_mid_planes(shape, K):
+    # planes of 33-64 samples a side: pass-by-pass forward; 64 x 64: reverse sweep in one launch
+    # with the segments read off the saved pass outputs
+    rng = np.random.default_rng(87 + shape[1] * 64 + shape[2])
+    y = rng.normal(size=shape).astype(np.float32)
+    g = rng.normal(size=shape).astype(np.float32)
+    lam = (10 ** rng.uniform(-2, 0.3, size=min(shape[0], 3))).astype(np.float32)
+    _check_2d(y, lam, K, g, "mid %s K=%d" % (shape, K), bulk=0.8)
+
+
 def test_odd_sizes_mixed_paths():
     rng = np.random.default_rng(71)
     y = rng.normal(size=(3, 19, 45)).astype(np.float32)         # rows of 45 (long path), columns of 19
