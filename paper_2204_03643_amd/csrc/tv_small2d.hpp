@@ -112,9 +112,10 @@ __global__ __launch_bounds__(64) void tv2d_bwd_small_kernel(Small2dBwdParams p)
                 d[0] = q.x; d[1] = q.y; d[2] = q.z; d[3] = q.w;
             }
         } else {
-            for (int e = lane; e < n_here * HW; e += 64) {
-                const int hh = e / HW, rem = e - hh * HW, r = rem / W, c = rem - r * W;
-                A[(hh * S + r) * P + c] = src[e];
+            // lane (h, idx) moves column idx of its plane: W contiguous floats per memory row
+            if (pvalid && idx < W) {
+                const float *col = src + h * HW + idx;
+                for (int r = 0; r < H; ++r) A[(h * S + r) * P + idx] = col[r * W];
             }
         }
     }
@@ -238,9 +239,9 @@ __global__ __launch_bounds__(64) void tv2d_bwd_small_kernel(Small2dBwdParams p)
                 if (e / (S * S) < n_here) store16(dst + e, make_float4(s[0], s[1], s[2], s[3]), p.stream != 0);
             }
         } else {
-            for (int e = lane; e < n_here * HW; e += 64) {
-                const int hh = e / HW, rem = e - hh * HW, r = rem / W, c = rem - r * W;
-                dst[e] = A[(hh * S + r) * P + c];
+            if (pvalid && idx < W) {
+                float *col = dst + h * HW + idx;
+                for (int r = 0; r < H; ++r) col[r * W] = A[(h * S + r) * P + idx];
             }
         }
     }
@@ -318,9 +319,10 @@ __global__ __launch_bounds__(64, 2) void tv2d_fwd_small_kernel(Small2dFwdParams 
                 d[0] = q.x; d[1] = q.y; d[2] = q.z; d[3] = q.w;
             }
         } else {
-            for (int e = lane; e < n_here * HW; e += 64) {
-                const int hh = e / HW, rem = e - hh * HW, r = rem / W, c = rem - r * W;
-                T1[(hh * S + r) * P + c] = src[e];
+            // lane (h, idx) moves column idx of its plane: W contiguous floats per memory row
+            if (pvalid && idx < W) {
+                const float *col = src + h * HW + idx;
+                for (int r = 0; r < H; ++r) T1[(h * S + r) * P + idx] = col[r * W];
             }
         }
     }
@@ -336,9 +338,9 @@ __global__ __launch_bounds__(64, 2) void tv2d_fwd_small_kernel(Small2dFwdParams 
                 if (e / (S * S) < n_here) store16(dst + e, make_float4(s[0], s[1], s[2], s[3]), p.stream != 0);
             }
         } else {
-            for (int e = lane; e < n_here * HW; e += 64) {
-                const int hh = e / HW, rem = e - hh * HW, r = rem / W, c = rem - r * W;
-                dst[e] = T1[(hh * S + r) * P + c];
+            if (pvalid && idx < W) {
+                float *col = dst + h * HW + idx;
+                for (int r = 0; r < H; ++r) col[r * W] = T1[(h * S + r) * P + idx];
             }
         }
     };

@@ -974,9 +974,12 @@ static int small_side(int64_t H, int64_t W)
 // against 304).  Planes of at most 16 x 16 need a quarter of the LDS and 144 registers: the one
 // launch wins except for a single sweep over many planes (32 768 planes: K = 1 69 us against 58,
 // K = 3 166 against 206); planes of at most 8 x 8 are always better off in one launch.
-static bool fused_fwd_applies(int side, int64_t planes, int sweeps)
+static bool fused_fwd_applies(int side, bool full, int64_t planes, int sweeps)
 {
-    if (side == 32) return planes <= 4096;
+    // (planes smaller than their 32 x 32 square go pass by pass through the slower general
+    // variants of the row-per-lane kernels, so there the one launch wins whenever there is more
+    // than one sweep: 28 x 28, 32 768 planes, K = 4: 1.46 ms against 1.94)
+    if (side == 32) return full ? planes <= 4096 : (sweeps >= 2 || planes <= 6144);
     if (side == 16) return sweeps >= 2 || planes <= 16384;
     return true;
 }
@@ -1006,7 +1009,7 @@ int tv2d_prox_fwd(const float *y, float *x, int64_t planes, int64_t H, int64_t W
     const tv_lambda lrow = {lam.lam, lam.count, H};
     const tv_lambda lcol = {lam.lam, lam.count, W};
 
-    if (cb && fused_fwd_applies(small_side(H, W), planes, sweeps)) {
+    if (cb && fused_fwd_applies(small_side(H, W), H == small_side(H, W) && W == H, planes, sweeps)) {
         // planes of at most 32 x 32: all passes in one launch, the planes resident in LDS
         tvk::Small2dFwdParams q;
         q.y = y; q.x = x; q.saved = saved(0); q.saved_stride = tb / sizeof(float);

@@ -88,11 +88,12 @@ def test_small_planes(shape, K):
     _check_2d(y, lam, K, g, "small %s K=%d" % (shape, K), bulk=0.8)
 
 
-@pytest.mark.parametrize("shape,K", [((4099, 20, 9), 2), ((4097, 32, 32), 2), ((16390, 16, 16), 1)])
+@pytest.mark.parametrize("shape,K", [((6200, 20, 9), 1), ((4099, 20, 9), 2), ((4097, 32, 32), 2), ((16390, 16, 16), 1)])
 def test_many_small_planes(shape, K):
-    # more small planes than the one-launch forward kernel takes (4096 padded to 32 x 32; 16 384 of
-    # at most 16 x 16 with a single sweep): pass-by-pass forward (plane columns, warm rows), segment
-    # codes for the fused reverse sweep
+    # more small planes than the one-launch forward kernel takes (4096 of 32 x 32; 6144 smaller ones
+    # padded to 32 x 32, or 16 384 of at most 16 x 16, with a single sweep): pass-by-pass forward
+    # (plane columns, warm rows), segment codes for the fused reverse sweep; (4099, 20, 9) with two
+    # sweeps is a one-launch case with many workgroups
     rng = np.random.default_rng(79 + shape[2])
     y = rng.normal(size=shape).astype(np.float32)
     g = rng.normal(size=shape).astype(np.float32)
