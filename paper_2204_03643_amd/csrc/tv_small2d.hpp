@@ -77,6 +77,9 @@ __device__ __forceinline__ float small2d_segment_means(float (&g)[S], const uint
 {
     float s = 0.f, carry = 0.f, glam = 0.f;
     int c4 = 0;
+    // the row length in a vector register: as a wave-uniform value every "k is past the end"
+    // predicate of the unrolled loops would be kept in scalar registers, 2 S pairs of them
+    if (!FULL) asm volatile("" : "+v"(n));
     small2d_means_up<S, FULL>(g, code, n, rtab, s, c4);
     small2d_means_down<S, FULL>(g, code, n, carry, glam);
     return glam;
