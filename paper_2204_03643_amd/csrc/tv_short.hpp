@@ -289,6 +289,53 @@ __device__ __forceinline__ void tile_add(TileRegs<NMAX> &a, const TileRegs<NMAX>
     }
 }
 
+// ---- packed rows shorter than NMAX (row r starts r * n floats after the base, rows in natural
+//      order): a wave's 64 rows are one contiguous block of 64 n floats.  It moves with coalesced
+//      4-byte accesses (element e = i * 64 + lane of the block in step i) through the wave's tile;
+//      a lane's (row, column) advances by 64 = dq * n + dr per step, so there is one division.
+template <int NMAX>
+__device__ __forceinline__ void ragged_fetch(const float *__restrict__ src, uint32_t first_row,
+                                             uint32_t n_rows, int n, int lane, float *tile,
+                                             float (&v)[NMAX])
+{
+    constexpr int P = NMAX + 1;
+    const int rows_here = first_row < n_rows ? (int)min(64u, n_rows - first_row) : 0;
+    const int total = rows_here * n;
+    const float *blk = src + (size_t)first_row * n;
+    const int dq = 64 / n, dr = 64 - dq * n;
+    int row = lane / n, col = lane - row * n;
+    wave_lds_sync();                       // earlier readers of the tile are done
+    for (int e = lane; e < total; e += 64) {
+        tile[row * P + col] = blk[e];
+        row += dq; col += dr;
+        if (col >= n) { col -= n; row += 1; }
+    }
+    wave_lds_sync();
+#pragma unroll
+    for (int k = 0; k < NMAX; ++k) v[k] = (k < n && lane < rows_here) ? tile[lane * P + k] : 0.f;
+}
+
+template <int NMAX>
+__device__ __forceinline__ void ragged_put(float *__restrict__ dst, uint32_t first_row, uint32_t n_rows,
+                                           int n, int lane, float *tile, const float (&v)[NMAX])
+{
+    constexpr int P = NMAX + 1;
+    const int rows_here = first_row < n_rows ? (int)min(64u, n_rows - first_row) : 0;
+    const int total = rows_here * n;
+    float *blk = dst + (size_t)first_row * n;
+    const int dq = 64 / n, dr = 64 - dq * n;
+    int row = lane / n, col = lane - row * n;
+    wave_lds_sync();
+#pragma unroll
+    for (int k = 0; k < NMAX; ++k) tile[lane * P + k] = v[k];
+    wave_lds_sync();
+    for (int e = lane; e < total; e += 64) {
+        blk[e] = tile[row * P + col];
+        row += dq; col += dr;
+        if (col >= n) { col -= n; row += 1; }
+    }
+}
+
 // ---- the rows are the columns of contiguous 32 x 32 planes (the column pass of the 2D operator
 //      on such planes): a wave's 64 rows are the columns of two planes, each plane a contiguous
 //      4 KB block.  The planes move with coalesced 16-byte accesses through the wave's tile
@@ -749,6 +796,24 @@ __global__ __launch_bounds__(kShortBlock) TV_FWD_ATTR void tv1d_fwd_short_kernel
         wave_lds_sync();
 #pragma unroll
         for (int k = 0; k < NMAX; ++k) y[k] = tile[lane * (NMAX + 1) + k];
+    } else if constexpr (PACKED && !FULL) {
+        // (rows in natural order: the host asks for this variant with the identity tile map only)
+        if (WARM || p.addend) {
+            float a[NMAX];
+            ragged_fetch<NMAX>(p.addend, r0, p.L.n_rows, n, lane, tile, a);
+            ragged_fetch<NMAX>(p.y, r0, p.L.n_rows, n, lane, tile, y);
+            float run = 0.f;
+#pragma unroll
+            for (int k = 0; k < NMAX; ++k) {
+                y[k] += a[k];
+                if constexpr (WARM) {
+                    run -= a[k];
+                    if (k < NMAX - 1) sv.u[k] = run;
+                }
+            }
+        } else {
+            ragged_fetch<NMAX>(p.y, r0, p.L.n_rows, n, lane, tile, y);
+        }
     } else if constexpr (PACKED) {
         TileRegs<NMAX> t;
         tile_fetch<NMAX>(p.y, p.tm, r0, p.L.n_rows, lane, t, p.L.stream);
@@ -793,6 +858,10 @@ __global__ __launch_bounds__(kShortBlock) TV_FWD_ATTR void tv1d_fwd_short_kernel
         for (int k = 0; k < NMAX; ++k) tile[lane * (NMAX + 1) + k] = xs[k];
         wave_lds_sync();
         tile16_put(reinterpret_cast<uint16_t *>(p.x), p.tm, r0, p.L.n_rows, lane, tile, p.L.stream);
+    } else if constexpr (PACKED && !FULL) {
+        ragged_put<NMAX>(p.x, r0, p.L.n_rows, n, lane, tile, xs);
+        if (p.x2) ragged_put<NMAX>(p.x2, r0, p.L.n_rows, n, lane, tile, xs);
+        if (want_resid) ragged_put<NMAX>(p.resid, r0, p.L.n_rows, n, lane, tile, rs);
     } else if constexpr (PACKED) {
         TileRegs<NMAX> t;
         rows_to_tile<NMAX>(xs, tile, lane, t);
@@ -880,6 +949,14 @@ __global__ __launch_bounds__(kShortBlock) void tv1d_bwd_short_kernel(BwdParams p
         wave_lds_sync();
 #pragma unroll
         for (int k = 0; k < NMAX; ++k) g[k] = tile[lane * (NMAX + 1) + k];
+    } else if constexpr (PACKED && !FULL) {
+        ragged_fetch<NMAX>(p.g, r0, p.L.n_rows, n, lane, tile, g);
+        if constexpr (!SEG) ragged_fetch<NMAX>(p.x, r0, p.L.n_rows, n, lane, tile, x);
+        if constexpr (HAS_SUB) {
+            ragged_fetch<NMAX>(p.sub, r0, p.L.n_rows, n, lane, tile, sb);
+#pragma unroll
+            for (int k = 0; k < NMAX; ++k) g[k] -= sb[k];
+        }
     } else if constexpr (PACKED) {
         TileRegs<NMAX> tg, tx;
         tile_fetch<NMAX>(p.g, tm, r0, p.L.n_rows, lane, tg, p.L.stream);
@@ -952,6 +1029,12 @@ __global__ __launch_bounds__(kShortBlock) void tv1d_bwd_short_kernel(BwdParams p
         for (int k = 0; k < NMAX; ++k) tile[lane * (NMAX + 1) + k] = g[k];
         wave_lds_sync();
         tile16_put(reinterpret_cast<uint16_t *>(p.gy), tm, r0, p.L.n_rows, lane, tile, p.L.stream);
+    } else if constexpr (PACKED && !FULL) {
+        if constexpr (HAS_SUB) {
+#pragma unroll
+            for (int k = 0; k < NMAX; ++k) g[k] += sb[k];
+        }
+        ragged_put<NMAX>(p.gy, r0, p.L.n_rows, n, lane, tile, g);
     } else if constexpr (PACKED) {
         TileRegs<NMAX> t;
         rows_to_tile<NMAX>(g, tile, lane, t);

@@ -121,8 +121,12 @@ int launch_status()
 // ---- short rows: one row per lane ---------------------------------------------------
 
 template <int NMAX>
-int launch_fwd_short(const FwdParams &p, bool packed_ok, hipStream_t s, bool plane_ok = false)
+int launch_fwd_short(const FwdParams &p, bool packed_ok, hipStream_t s, bool plane_ok = false,
+                     bool ragged_ok = false)
 {
+    // ragged_ok: packed rows shorter than NMAX in natural order (any 4-byte alignment); rows of up
+    // to 8 samples lie so close together that the plain per-lane accesses do as well
+    ragged_ok = ragged_ok && NMAX >= 16 && !p.tm.grouped && p.L.n < NMAX;
     constexpr uint32_t wpb = tvk::kShortBlock / 64;
     const uint32_t n_tiles = (p.L.n_rows + 63u) / 64u;
     dim3 grid((n_tiles + wpb - 1) / wpb), block(tvk::kShortBlock);
@@ -148,20 +152,25 @@ int launch_fwd_short(const FwdParams &p, bool packed_ok, hipStream_t s, bool pla
             hipLaunchKernelGGL((tvk::tv1d_fwd_short_kernel<NMAX, true, true, true>), grid, block, 0, s, p);
         else if (full)
             hipLaunchKernelGGL((tvk::tv1d_fwd_short_kernel<NMAX, true, false, true>), grid, block, 0, s, p);
+        else if (ragged_ok)
+            hipLaunchKernelGGL((tvk::tv1d_fwd_short_kernel<NMAX, false, true, true>), grid, block, 0, s, p);
         else
             hipLaunchKernelGGL((tvk::tv1d_fwd_short_kernel<NMAX, false, false, true>), grid, block, 0, s, p);
     } else if (full && packed_ok)
         hipLaunchKernelGGL((tvk::tv1d_fwd_short_kernel<NMAX, true, true>), grid, block, 0, s, p);
     else if (full)
         hipLaunchKernelGGL((tvk::tv1d_fwd_short_kernel<NMAX, true, false>), grid, block, 0, s, p);
+    else if (ragged_ok)
+        hipLaunchKernelGGL((tvk::tv1d_fwd_short_kernel<NMAX, false, true>), grid, block, 0, s, p);
     else
         hipLaunchKernelGGL((tvk::tv1d_fwd_short_kernel<NMAX, false, false>), grid, block, 0, s, p);
     return launch_status();
 }
 
 template <int NMAX, bool HAS_SUB, bool SEG>
-int launch_bwd_short(const BwdParams &p, bool packed_ok, hipStream_t s, bool plane_ok)
+int launch_bwd_short(const BwdParams &p, bool packed_ok, hipStream_t s, bool plane_ok, bool ragged_ok)
 {
+    ragged_ok = ragged_ok && NMAX >= 16 && p.L.n < NMAX;
     const dim3 grid((p.L.n_rows + tvk::kShortBlock - 1) / tvk::kShortBlock), block(tvk::kShortBlock);
     const bool full = p.L.n == NMAX;
     if constexpr (NMAX == 32 && SEG && !HAS_SUB) {
@@ -181,19 +190,22 @@ int launch_bwd_short(const BwdParams &p, bool packed_ok, hipStream_t s, bool pla
         hipLaunchKernelGGL((tvk::tv1d_bwd_short_kernel<NMAX, true, true, HAS_SUB, SEG>), grid, block, 0, s, p);
     else if (full)
         hipLaunchKernelGGL((tvk::tv1d_bwd_short_kernel<NMAX, true, false, HAS_SUB, SEG>), grid, block, 0, s, p);
+    else if (ragged_ok)
+        hipLaunchKernelGGL((tvk::tv1d_bwd_short_kernel<NMAX, false, true, HAS_SUB, SEG>), grid, block, 0, s, p);
     else
         hipLaunchKernelGGL((tvk::tv1d_bwd_short_kernel<NMAX, false, false, HAS_SUB, SEG>), grid, block, 0, s, p);
     return launch_status();
 }
 
 template <int NMAX>
-int launch_bwd_short(const BwdParams &p, bool packed_ok, hipStream_t s, bool plane_ok = false)
+int launch_bwd_short(const BwdParams &p, bool packed_ok, hipStream_t s, bool plane_ok = false,
+                     bool ragged_ok = false)
 {
     if (p.seg)
-        return p.sub ? launch_bwd_short<NMAX, true, true>(p, packed_ok, s, plane_ok)
-                     : launch_bwd_short<NMAX, false, true>(p, packed_ok, s, plane_ok);
-    return p.sub ? launch_bwd_short<NMAX, true, false>(p, packed_ok, s, plane_ok)
-                 : launch_bwd_short<NMAX, false, false>(p, packed_ok, s, plane_ok);
+        return p.sub ? launch_bwd_short<NMAX, true, true>(p, packed_ok, s, plane_ok, ragged_ok)
+                     : launch_bwd_short<NMAX, false, true>(p, packed_ok, s, plane_ok, ragged_ok);
+    return p.sub ? launch_bwd_short<NMAX, true, false>(p, packed_ok, s, plane_ok, ragged_ok)
+                 : launch_bwd_short<NMAX, false, false>(p, packed_ok, s, plane_ok, ragged_ok);
 }
 
 // ---- slot order for the grouped grid -----------------------------------------------
@@ -530,13 +542,14 @@ int run_fwd(const float *y, const float *addend, float *x, float *resid, int32_t
     }
     const bool packed = rows_packed(r) && aligned16(y) && aligned16(x) &&
                         (!addend || aligned16(addend)) && (!resid || aligned16(resid));
-    if (r.length <= 8) return launch_fwd_short<8>(p, packed, s);
-    if (r.length <= 16) return launch_fwd_short<16>(p, packed, s);
+    const bool ragged = rows_packed(r);
+    if (r.length <= 8) return launch_fwd_short<8>(p, packed, s, false, ragged);
+    if (r.length <= 16) return launch_fwd_short<16>(p, packed, s, false, ragged);
     if (r.length <= 32) {
         const bool planes = rows_are_plane_columns(r) && aligned16(y) && aligned16(x) &&
                             (!addend || aligned16(addend)) && (!resid || aligned16(resid)) &&
                             (!x2 || aligned16(x2));
-        return launch_fwd_short<32>(p, packed, s, planes);
+        return launch_fwd_short<32>(p, packed, s, planes, ragged);
     }
     MlPlan pl;
     if (ml_ws && !p.warm && ml_plan(r, n_rows, &pl)) return run_fwd_multilevel(p, l, n_rows, pl, ml_ws, s);
@@ -706,12 +719,13 @@ int run_bwd(const float *g, const float *sub, const float *x, const uint2 *seg, 
     const PartialShape ps = partial_shape(r, l, n_rows);
     p.part_lg = grad_lam ? ps.lg : 0;
     const int64_t red_rows = ps.red_rows, red_div = ps.red_div;
-    if (r.length <= 8) st = launch_bwd_short<8>(p, packed, s);
-    else if (r.length <= 16) st = launch_bwd_short<16>(p, packed, s);
+    const bool ragged = rows_packed(r);
+    if (r.length <= 8) st = launch_bwd_short<8>(p, packed, s, false, ragged);
+    else if (r.length <= 16) st = launch_bwd_short<16>(p, packed, s, false, ragged);
     else if (r.length <= 32) {
         const bool planes = rows_are_plane_columns(r) && aligned16(g) && (!x || aligned16(x)) &&
                             aligned16(gy) && (!sub || aligned16(sub));
-        st = launch_bwd_short<32>(p, packed, s, planes);
+        st = launch_bwd_short<32>(p, packed, s, planes, ragged);
     }
     else st = tvk::launch_bwd_long(p, s) == hipSuccess ? TV_OK : TV_ERR_HIP;
     if (st != TV_OK) return st;
