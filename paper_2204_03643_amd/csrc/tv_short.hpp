@@ -483,7 +483,17 @@ struct RowSolver {
     int m, steps, flags, nfail;
     bool active, prev_unclipped;
 
-    __device__ __forceinline__ float lk(int k) const { return (FULL || k < m) ? lam : 0.0f; }
+    // (rows shorter than 32 samples in the 32-sample variant: the comparison is redone at every
+    // use; as a loop invariant the compiler keeps all 31 selected values in registers for the
+    // whole solve, which costs a wave of occupancy.  The shorter variants have the registers to
+    // spare and are faster with the invariant.)
+    __device__ __forceinline__ float lk(int k) const
+    {
+        if (FULL) return lam;
+        int mm = m;
+        if (NMAX >= 32) asm volatile("" : "+s"(mm));
+        return k < mm ? lam : 0.0f;
+    }
     __device__ __forceinline__ float yk(int k) const { return yl[k * 64]; }
     __device__ __forceinline__ float tab(const float *t, int off4) const
     {
