@@ -309,7 +309,7 @@ __global__ __launch_bounds__(64, 2) void tv2d_fwd_small_kernel(Small2dFwdParams 
     float *park = T1 + lane;                    // the solver's read-only copy of its input, step 64
     float *mine = T2 + lane;                    // lane-private: the correction term, step 64
 
-    // the two planes -> T1 (memory rows at pitch P)
+    // the wave's planes -> T1 (memory rows at pitch P)
     {
         const float *src = p.y + plane0 * HW;
         if (FULL && ((uintptr_t)src % 16) == 0) {
