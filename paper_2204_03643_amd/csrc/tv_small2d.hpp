@@ -87,7 +87,8 @@ __device__ __forceinline__ float small2d_segment_means(float (&g)[S], const uint
 // S = 8, 16, 32 or 64: the side of the square a plane is padded to; a wave holds 64 / S planes,
 // one row or column per lane.  FULL: planes of exactly S x S.  S = 64: the segments of a pass are
 // read off its saved output (the forward kernels for rows of more than 32 samples write no codes).
-template <int S, bool FULL>
+// FROM_X: the segments of a pass are read off its saved output instead of its codes.
+template <int S, bool FULL, bool FROM_X = (S > 32)>
 __global__ __launch_bounds__(64) void tv2d_bwd_small_kernel(Small2dBwdParams p)
 {
     constexpr int P = S + 1;                        // tile pitch
@@ -132,7 +133,7 @@ __global__ __launch_bounds__(64) void tv2d_bwd_small_kernel(Small2dBwdParams p)
     auto fetch_code = [&](int pass) -> uint4 {
         if (pass < 0) return make_uint4(0u, 0u, 0u, 0u);
         const bool col = (pass & 1) != 0;
-        if constexpr (S <= 32) {
+        if constexpr (!FROM_X) {
             if (!(col ? cvalid : rvalid)) return make_uint4(0u, 0u, 0u, 0u);
             const uint2 c = p.codes[(size_t)pass * p.code_stride + (size_t)plane * (col ? W : H) + idx];
             return make_uint4(c.x, c.y, 0u, 0u);
@@ -164,7 +165,7 @@ __global__ __launch_bounds__(64) void tv2d_bwd_small_kernel(Small2dBwdParams p)
                 c.z = __builtin_amdgcn_alignbit(c.z, __float_as_uint(0.0f - fabsf(d)), 31);
             }
 #pragma unroll
-            for (int k = 31; k >= 0; --k) {
+            for (int k = (S - 2 < 31 ? S - 2 : 31); k >= 0; --k) {
                 const float d = xv[k] - xv[k + 1];
                 c.y = __builtin_amdgcn_alignbit(c.y, __float_as_uint(d), 31);
                 c.x = __builtin_amdgcn_alignbit(c.x, __float_as_uint(0.0f - fabsf(d)), 31);

@@ -514,7 +514,8 @@ int run_fwd_multilevel(FwdParams p, const tv_lambda &l, int64_t n_rows, const Ml
 
 int run_fwd(const float *y, const float *addend, float *x, float *resid, int32_t *info,
             uint2 *seg, uint32_t *order_ws, const tv_rows &r, const tv_lambda &l, int64_t n_rows,
-            hipStream_t s, float *x2 = nullptr, bool warm = false, char *ml_ws = nullptr, bool io16 = false)
+            hipStream_t s, float *x2 = nullptr, bool warm = false, char *ml_ws = nullptr, bool io16 = false,
+            bool thread_per_sample = false)
 {
     FwdParams p;
     p.y = y; p.addend = addend; p.x = x; p.x2 = x2; p.resid = resid; p.lam = l.lam; p.info = info;
@@ -542,6 +543,11 @@ int run_fwd(const float *y, const float *addend, float *x, float *resid, int32_t
     }
     const bool packed = rows_packed(r) && aligned16(y) && aligned16(x) &&
                         (!addend || aligned16(addend)) && (!resid || aligned16(resid));
+    // (a few thousand short rows at most: a thread per four samples instead of a lane per row; the
+    // 2D operator asks for it on small batches of planes, where a lone row-per-lane wave is bound
+    // by its dependency chains)
+    if (thread_per_sample && r.length >= 2 && r.length <= 32 && !seg && !io16)
+        return tvk::launch_fwd_long(p, s) == hipSuccess ? TV_OK : TV_ERR_HIP;
     const bool ragged = rows_packed(r);
     if (r.length <= 8) return launch_fwd_short<8>(p, packed, s, false, ragged);
     if (r.length <= 16) return launch_fwd_short<16>(p, packed, s, false, ragged);
@@ -980,6 +986,17 @@ static int small_side(int64_t H, int64_t W)
         }                                                                                           \
     } while (0)
 
+// Up to 1024 planes of 17-32 samples a side: the forward passes run one by one on the long-row
+// kernels (eight threads per row), and the reverse sweep reads the segments off the saved pass
+// outputs instead of codes.  With so few rows a row-per-lane wave runs alone on its SIMD and issues
+// an instruction every 9 cycles; the thread-per-four-samples mapping has 8x the waves and shorter
+// chains (256 planes of 32 x 32, K = 10: 507 -> 202 us forward; from about 2048 planes on the one
+// launch is faster again).
+static bool tiny_batch_2d(int64_t planes, int64_t H, int64_t W)
+{
+    return small_planes(H, W) && small_side(H, W) == 32 && planes <= 1024;
+}
+
 // When the one-launch forward kernel is used.  With planes padded to 32 x 32 it holds two planes
 // per wave and, with 17 KB of LDS per wave, two waves per SIMD where the pass-by-pass kernels hold
 // three: it wins (15-30 %: no launches and no memory round trips between the passes) while all its
@@ -1023,7 +1040,8 @@ int tv2d_prox_fwd(const float *y, float *x, int64_t planes, int64_t H, int64_t W
     const tv_lambda lrow = {lam.lam, lam.count, H};
     const tv_lambda lcol = {lam.lam, lam.count, W};
 
-    if (cb && fused_fwd_applies(small_side(H, W), H == small_side(H, W) && W == H, planes, sweeps)) {
+    const bool tiny = cb && tiny_batch_2d(planes, H, W);
+    if (cb && !tiny && fused_fwd_applies(small_side(H, W), H == small_side(H, W) && W == H, planes, sweeps)) {
         // planes of at most 32 x 32: all passes in one launch, the planes resident in LDS
         tvk::Small2dFwdParams q;
         q.y = y; q.x = x; q.saved = saved(0); q.saved_stride = tb / sizeof(float);
@@ -1041,13 +1059,13 @@ int tv2d_prox_fwd(const float *y, float *x, int64_t planes, int64_t H, int64_t W
         // Z = proxRows(Y + P);  P <- (Y + P) - Z      (P = 0 in the first sweep)
         // From the second sweep on, P = D^T u of the row pass one sweep earlier (x = y - D^T u),
         // and likewise Q for the columns: each pass starts from that dual.
-        st = run_fwd(Yk, k == 0 ? nullptr : P, Z, last ? nullptr : P, nullptr, codes(2 * k), nullptr, rrow,
-                     lrow, planes * H, stream, nullptr, true);
+        st = run_fwd(Yk, k == 0 ? nullptr : P, Z, last ? nullptr : P, nullptr, tiny ? nullptr : codes(2 * k), nullptr,
+                     rrow, lrow, planes * H, stream, nullptr, true, nullptr, false, tiny);
         if (st != TV_OK) return st;
         // Y' = proxCols(Z + Q);  Q <- (Z + Q) - Y'
         // the last pass writes its output twice: where the reverse sweep will look for it, and to x
-        st = run_fwd(Z, k == 0 ? nullptr : Q, Yn, last ? nullptr : Q, nullptr, codes(2 * k + 1), nullptr, rcol,
-                     lcol, planes * W, stream, last ? x : nullptr, true);
+        st = run_fwd(Z, k == 0 ? nullptr : Q, Yn, last ? nullptr : Q, nullptr, tiny ? nullptr : codes(2 * k + 1), nullptr,
+                     rcol, lcol, planes * W, stream, last ? x : nullptr, true, nullptr, false, tiny);
         if (st != TV_OK) return st;
     }
     return TV_OK;
@@ -1099,7 +1117,13 @@ int tv2d_prox_bwd(const float *g_up, float *grad_y, float *grad_lam, int64_t pla
         q.partial = grad_lam ? partial(0) : nullptr;
         q.planes = (int32_t)planes; q.H = (int32_t)H; q.W = (int32_t)W; q.sweeps = sweeps;
         q.stream = (planes * H * W >= ((int64_t)32 << 20) / 4) ? 1u : 0u;
-        if (cb) {
+        if (cb && tiny_batch_2d(planes, H, W)) {
+            const dim3 grid((uint32_t)((planes + 1) / 2));
+            if (H == 32 && W == 32)
+                hipLaunchKernelGGL((tvk::tv2d_bwd_small_kernel<32, true, true>), grid, dim3(64), 0, stream, q);
+            else
+                hipLaunchKernelGGL((tvk::tv2d_bwd_small_kernel<32, false, true>), grid, dim3(64), 0, stream, q);
+        } else if (cb) {
             TV_SMALL2D_LAUNCH(tvk::tv2d_bwd_small_kernel, q, planes, H, W, stream);
         } else {
             hipLaunchKernelGGL((tvk::tv2d_bwd_small_kernel<64, true>), dim3((uint32_t)planes), dim3(64), 0, stream, q);
