@@ -157,6 +157,9 @@ def other_workloads(dev, reps: int = 25):
     out["config2_rows"] = one_d(y, lam, g, -1, 32)
     out["config2_columns"] = one_d(y, lam, g, -2, 32)
     out["config2_2d_k1"] = two_d(y, lam, g, 1)
+    # a layer-sized call (Sec. 3.2: three or four sweeps on a few hundred 32 x 32 maps): the first
+    # 256 planes of the same tensors
+    out["feature_maps_256x32x32_2d_k4"] = two_d(y.reshape(-1, 32, 32)[:256], lam, g.reshape(-1, 32, 32)[:256], 4)
     y, lam, g = workloads.config4()
     out["config4_rows"] = one_d(y, lam, g, -1, 1)
     out["config4_columns"] = one_d(y, lam, g, -2, 1)
