@@ -1069,6 +1069,7 @@ inline hipError_t launch_bwd_long_t(const BwdParams &p, hipStream_t s)
         const int n = (p).L.n;                                                            \
         const bool cols = (p).L.elem_stride != 1;                                         \
         if (cols) {                                                                       \
+            if (n <= 32 && (p).L.n_rows <= 16384) return FN<16, 2, 16, true>(p, s);       \
             if (n <= 32) return FN<8, 4, 16, true>(p, s);                                 \
             if (n <= 64) return FN<8, 8, 16, true>(p, s);                                 \
             if (n <= 96) return FN<8, 12, 16, true>(p, s);                                \
@@ -1087,6 +1088,7 @@ inline hipError_t launch_bwd_long_t(const BwdParams &p, hipStream_t s)
             if (n <= 12288) return FN<1024, 12, 1, true>(p, s);                           \
             return FN<1024, 16, 1, true>(p, s);                                           \
         }                                                                                 \
+        if (n <= 32 && (p).L.n_rows <= 16384) return FN<16, 2, 16, false>(p, s);          \
         if (n <= 32) return FN<8, 4, 32, false>(p, s);                                    \
         if (n <= 64) return FN<8, 8, 32, false>(p, s);                                    \
         if (n <= 96) return FN<8, 12, 32, false>(p, s);                                   \
