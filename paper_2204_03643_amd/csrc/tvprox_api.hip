@@ -526,6 +526,11 @@ int run_fwd(const float *y, const float *addend, float *x, float *resid, int32_t
     p.lam_scale = 1.0f;
     p.L = make_layout(r, l, n_rows);
     p.tm = make_tile_map(l, n_rows);
+    // (a few thousand short rows at most: a few threads per row instead of a lane per row; the 2D
+    // operator asks for it on small batches of planes, where a lone row-per-lane wave is bound by
+    // its dependency chains)
+    if (thread_per_sample && r.length >= 2 && r.length <= 32 && !seg && !io16)
+        return tvk::launch_fwd_long(p, s) == hipSuccess ? TV_OK : TV_ERR_HIP;
     if (order_ws && r.length <= 32 && order_applies(p.tm)) {
         uint32_t lgR = 0;
         while (lgR < 6 && ((uint64_t)p.tm.count << (lgR + 1)) <= (uint64_t)kOrderMaxSlots) ++lgR;
@@ -543,11 +548,6 @@ int run_fwd(const float *y, const float *addend, float *x, float *resid, int32_t
     }
     const bool packed = rows_packed(r) && aligned16(y) && aligned16(x) &&
                         (!addend || aligned16(addend)) && (!resid || aligned16(resid));
-    // (a few thousand short rows at most: a thread per four samples instead of a lane per row; the
-    // 2D operator asks for it on small batches of planes, where a lone row-per-lane wave is bound
-    // by its dependency chains)
-    if (thread_per_sample && r.length >= 2 && r.length <= 32 && !seg && !io16)
-        return tvk::launch_fwd_long(p, s) == hipSuccess ? TV_OK : TV_ERR_HIP;
     const bool ragged = rows_packed(r);
     if (r.length <= 8) return launch_fwd_short<8>(p, packed, s, false, ragged);
     if (r.length <= 16) return launch_fwd_short<16>(p, packed, s, false, ragged);

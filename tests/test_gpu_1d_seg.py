@@ -40,6 +40,19 @@ def test_config3_reduced_rows_and_columns():
     _check(y, lam, 32, g, -2, "cfg3 columns (seg)")
 
 
+@pytest.mark.parametrize("n,rows,axis", [(28, 16384 + 77, -1), (32, 16384 + 64, -1), (31, 16384 + 5, 0),
+                                         (28, 500, -1), (32, 8192, -1), (17, 300, 0)])
+def test_rows_of_17_to_32_samples_small_and_large_batches(n, rows, axis):
+    # ragged rows, packed and strided, a few tiles and several hundred
+    rng = np.random.default_rng(370 + n + rows)
+    y = rng.normal(size=(rows, n)).astype(np.float32)
+    g = rng.normal(size=(rows, n)).astype(np.float32)
+    lam = (10 ** rng.uniform(-3, 1, size=3)).astype(np.float32)
+    if axis == 0:
+        y, g = np.ascontiguousarray(y.T), np.ascontiguousarray(g.T)
+    _check(y, lam, 5, g, axis, "seg n=%d rows=%d axis=%d" % (n, rows, axis))
+
+
 def test_config2_reduced_ties():
     y, lam, g = workloads.config2(B=4, C=64)
     _check(y, lam, 32, g, -1, "cfg2 rows (seg)")
@@ -97,10 +110,10 @@ def _check_ordered(y, lam, lam_div, g, axis, expect_order):
 
 
 def test_ordered_config3_reduced():
-    y, lam, g = workloads.config3(B=4, C=128)
+    y, lam, g = workloads.config3(B=6, C=128)
     out = _check_ordered(y, lam, 32, g, -1, True)
     # slots whose rows need the most Newton steps come first, the one-step slots last
-    steps = (out["info"] & 0xffff).reshape(4, 128, 32).transpose(1, 0, 2).reshape(128, -1).mean(1)
+    steps = (out["info"] & 0xffff).reshape(6, 128, 32).transpose(1, 0, 2).reshape(128, -1).mean(1)
     by_order = steps[out["order"]]
     assert by_order[:16].mean() > 2.0 * by_order[-16:].mean()
     assert by_order[-16:].max() <= 1.5
@@ -121,7 +134,7 @@ def test_ordered_falls_back_where_slots_do_not_group():
     _check_ordered(y, (10 ** rng.uniform(-2, 0.5, size=6)).astype(np.float32), 16, g, -1, True)
 
 
-@pytest.mark.parametrize("shape", [(16, 100, 8, 32), (64, 1000, 2, 16), (8, 40, 16, 32)])
+@pytest.mark.parametrize("shape", [(32, 100, 8, 32), (64, 1000, 2, 16), (32, 40, 16, 32)])
 def test_ordered_many_slots_small_groups(shape):
     # slot counts that are no power of two, groups of 8, 2 and 16 rows, up to 1000 slots
     rng = np.random.default_rng(45 + shape[1])

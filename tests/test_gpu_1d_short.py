@@ -49,6 +49,20 @@ def test_every_short_length(n):
     _check(y, lam, 1, g, -1, "n=%d" % n)
 
 
+@pytest.mark.parametrize("n,axis", [(17, -1), (20, -1), (28, -1), (31, -1), (32, -1), (20, 0), (31, 0), (32, 0)])
+def test_many_rows_of_17_to_32_samples(n, axis):
+    # several hundred tiles of rows shorter than (or exactly) 32 samples, packed and strided, with
+    # a ragged last tile
+    rng = np.random.default_rng(350 + n)
+    rows = 16384 + 77
+    y = rng.normal(size=(rows, n)).astype(np.float32)
+    g = rng.normal(size=(rows, n)).astype(np.float32)
+    lam = (10 ** rng.uniform(-3, 1, size=3)).astype(np.float32)
+    if axis == 0:
+        y, g = np.ascontiguousarray(y.T), np.ascontiguousarray(g.T)
+    _check(y, lam, 5, g, axis, "n=%d rows=%d axis=%d" % (n, rows, axis))
+
+
 def test_strided_columns_odd_shape():
     rng = np.random.default_rng(41)
     y = rng.normal(size=(5, 3, 19, 11)).astype(np.float32)
