@@ -492,8 +492,6 @@ __global__ __launch_bounds__(T *G, (T * G == 512 && !COLS) ? 4 : ((XPOSE && C <=
     }
     // rounding floor of a difference of two x values (|x| <= max|y|, |u| <= lam)
     float gtol;
-    bool is_mean = false;      // lambda is past the bound on lam_max: the row's mean is the answer
-    float row_mean = 0.f;
     {
         float ym[1] = {0.f};
 #pragma unroll
@@ -505,23 +503,8 @@ __global__ __launch_bounds__(T *G, (T * G == 512 && !COLS) ? 4 : ((XPOSE && C <=
         // x = y - D^T u, at the scale of the data.  Only the cold start needs it (it puts the
         // duals on the bounds); a pass that starts from an earlier dual is left alone, where the
         // extra dependency cost 3 % of the 2D operator's time.
-        if constexpr (WARM == 0) {
-            const float cap = 2.5f * (float)n * ym[0];
-            is_mean = lam > cap;
-            lam = fminf(lam, cap);
-        }
+        if constexpr (WARM == 0) lam = fminf(lam, 2.5f * (float)n * ym[0]);
         gtol = kGradNoise * (ym[0] + lam);
-        Mp::sync();
-    }
-    // Such a row is still solved (with the capped lambda) like its neighbours, but what is written
-    // is the mean itself, which a Newton step from duals at +-lambda reaches only to within
-    // 1e-7 lambda.  The sum is only taken where some row needs it.
-    if (WARM == 0 && Mp::sync_any(is_mean)) {
-        float ys[1] = {0.f};
-#pragma unroll
-        for (int i = 0; i < C; ++i) ys[0] += y[i];
-        row_sum<T, G, MCOLS, 1>(ys, sm.red, j, tid);
-        row_mean = ys[0] / (float)n;
         Mp::sync();
     }
 
@@ -847,10 +830,6 @@ __global__ __launch_bounds__(T *G, (T * G == 512 && !COLS) ? 4 : ((XPOSE && C <=
         } else {
             flags |= 1 << 19;
         }
-    }
-    if (is_mean) {
-#pragma unroll
-        for (int i = 0; i < C; ++i) xs[i] = row_mean;
     }
 
     if constexpr (XPOSE) {
