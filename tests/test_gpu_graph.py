@@ -63,14 +63,20 @@ def test_forward_backward_step_replays_from_a_graph():
         assert torch.equal(xt, ref[0]) and torch.equal(gy, ref[1]) and torch.equal(gl, ref[2]), rep
 
 
-def test_2d_step_replays_from_a_graph():
+@pytest.mark.parametrize("planes,H,W,K", [(16, 32, 32, 3),       # small batch: passes on the long-row kernels
+                                          (40, 16, 16, 3),       # one-launch forward and reverse sweep
+                                          (1100, 32, 32, 2),     # the same, two planes per wave
+                                          (6, 64, 64, 2)])       # pass-by-pass forward, fused reverse sweep
+def test_2d_step_replays_from_a_graph(planes, H, W, K):
     import torch
 
     import paper_2204_03643_amd as tv
 
     dev = torch.device("cuda:0")
-    y, lam, g = workloads.config2(B=2, C=8)
-    planes, H, W, K = 16, 32, 32, 3
+    rng = np.random.default_rng(planes + H)
+    y = np.maximum(rng.normal(size=(planes, H, W)), 0).astype(np.float32)
+    g = rng.normal(size=(planes, H, W)).astype(np.float32)
+    lam = (10 ** rng.uniform(-2, 0.3, size=4)).astype(np.float32)
     yt, lt, gt = (torch.from_numpy(a).to(dev) for a in (y, lam, g))
     xt, gy, gl = torch.empty_like(yt), torch.empty_like(yt), torch.empty_like(lt)
     L = tv.tv_lambda(lt.data_ptr(), lt.numel(), 1)
