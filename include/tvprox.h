@@ -184,7 +184,7 @@ int tv1d_prox_bwd_seg_bf16(const uint16_t *g_up, const uint64_t *seg, uint16_t *
  * From the second sweep on, the correction term a pass adds to its input is D^T u of the
  * same pass one sweep earlier (x = y - D^T u), and the pass starts its Newton iteration
  * from that dual.  Planes of at most 32 x 32 run all their passes in one launch where that is
- * faster (any number of planes of at most 8 x 8, 1025-4096 planes of 17-32 samples a side).
+ * faster (any number of planes of at most 8 x 8, 1537-4096 planes of 17-32 samples a side).
  */
 size_t tv2d_workspace_bytes(int64_t planes, int64_t H, int64_t W, int sweeps);
 int tv2d_prox_fwd(const float *y, float *x, int64_t planes, int64_t H, int64_t W,

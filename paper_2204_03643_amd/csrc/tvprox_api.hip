@@ -986,15 +986,15 @@ static int small_side(int64_t H, int64_t W)
         }                                                                                           \
     } while (0)
 
-// Up to 1024 planes of 17-32 samples a side: the forward passes run one by one on the long-row
+// Up to 1536 planes of 17-32 samples a side: the forward passes run one by one on the long-row
 // kernels (eight threads per row), and the reverse sweep reads the segments off the saved pass
 // outputs instead of codes.  With so few rows a row-per-lane wave runs alone on its SIMD and issues
 // an instruction every 9 cycles; the thread-per-four-samples mapping has 8x the waves and shorter
-// chains (256 planes of 32 x 32, K = 10: 507 -> 202 us forward; from about 2048 planes on the one
-// launch is faster again).
+// chains (256 planes of 32 x 32, K = 10: 507 -> 180 us forward; 1536 planes: 526 -> 347 on
+// feature-map-like data, 437 -> 361 on white noise; around 2048 planes the one launch catches up).
 static bool tiny_batch_2d(int64_t planes, int64_t H, int64_t W)
 {
-    return small_planes(H, W) && small_side(H, W) == 32 && planes <= 1024;
+    return small_planes(H, W) && small_side(H, W) == 32 && planes <= 1536;
 }
 
 // When the one-launch forward kernel is used.  With planes padded to 32 x 32 it holds two planes

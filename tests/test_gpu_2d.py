@@ -79,10 +79,10 @@ def test_odd_sizes_mixed_paths():
                                      ((37, 16, 16), 3), ((11, 13, 16), 2), ((3, 16, 9), 4), ((70, 8, 8), 2),
                                      ((9, 5, 7), 3), ((13, 8, 3), 2), ((5, 1, 8), 2), ((6, 12, 1), 2),
                                      ((4099, 8, 8), 1), ((2050, 16, 16), 2),
-                                     # more than 1024 planes of 17-32 samples a side: the one-launch forward
-                                     ((1100, 32, 32), 2), ((1030, 19, 27), 3), ((1025, 32, 20), 1)])
+                                     # more than 1536 planes of 17-32 samples a side: the one-launch forward
+                                     ((1600, 32, 32), 2), ((1540, 19, 27), 3), ((1537, 32, 20), 1)])
 def test_small_planes(shape, K):
-    # planes of at most 32 x 32, ragged in both directions: up to 1024 planes of 17-32 samples a side
+    # planes of at most 32 x 32, ragged in both directions: up to 1536 planes of 17-32 samples a side
     # pass by pass on the long-row kernels (reverse sweep from the saved outputs), otherwise the
     # one-launch kernels
     rng = np.random.default_rng(73 + shape[1] * 64 + shape[2])

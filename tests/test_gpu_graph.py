@@ -65,7 +65,7 @@ def test_forward_backward_step_replays_from_a_graph():
 
 @pytest.mark.parametrize("planes,H,W,K", [(16, 32, 32, 3),       # small batch: passes on the long-row kernels
                                           (40, 16, 16, 3),       # one-launch forward and reverse sweep
-                                          (1100, 32, 32, 2),     # the same, two planes per wave
+                                          (1600, 32, 32, 2),     # the same, two planes per wave
                                           (6, 64, 64, 2)])       # pass-by-pass forward, fused reverse sweep
 def test_2d_step_replays_from_a_graph(planes, H, W, K):
     import torch
