@@ -2,7 +2,6 @@
 from __future__ import annotations
 
 import ctypes
-import os
 
 from . import build as _build
 
@@ -33,10 +32,12 @@ _lib = None
 
 
 def lib() -> ctypes.CDLL:
-    """Loads libtvprox.so, building it first only if it is not there."""
+    """Loads libtvprox.so.  A library that is missing, or that was built from other sources than
+    the tree now holds, is built first (hipcc); if that fails this raises: an old library is
+    never loaded silently, and there is no other path."""
     global _lib
     if _lib is None:
-        if not os.path.exists(_build.LIB):
+        if _build.is_stale():
             _build.build_library()
         L = ctypes.CDLL(_build.LIB)
         L.tv_status_str.argtypes = [ctypes.c_int]

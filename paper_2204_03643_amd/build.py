@@ -1,6 +1,7 @@
 """Compiles the HIP library for gfx950 in-tree (hipcc cross-compiles without a GPU)."""
 from __future__ import annotations
 
+import hashlib
 import os
 import subprocess
 import sys
@@ -8,6 +9,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtvprox.so")
+STAMP = LIB + ".stamp"          # digest of the sources and flags the library was built from
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -21,18 +23,31 @@ def sources():
     return [os.path.join(CSRC, f) for f in sorted(os.listdir(CSRC)) if f.endswith(".hip")]
 
 
-def is_stale() -> bool:
-    if not os.path.exists(LIB):
-        return True
-    t = os.path.getmtime(LIB)
-    deps = [os.path.join(CSRC, f) for f in os.listdir(CSRC)]
+def source_digest() -> str:
+    """Digest of everything the library is compiled from (file contents, not time stamps: a
+    copy of the tree keeps the one and not necessarily the other)."""
+    deps = [os.path.join(CSRC, f) for f in sorted(os.listdir(CSRC))]
     deps.append(os.path.join(os.path.dirname(HERE), "include", "tvprox.h"))
-    return any(os.path.getmtime(d) > t for d in deps)
+    h = hashlib.sha256(" ".join(HIPCC_FLAGS).encode())
+    for d in deps:
+        h.update(os.path.basename(d).encode())
+        with open(d, "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
+
+
+def is_stale() -> bool:
+    """True when the library is missing or was built from other sources than those in the tree."""
+    if not (os.path.exists(LIB) and os.path.exists(STAMP)):
+        return True
+    with open(STAMP) as f:
+        return f.read().strip() != source_digest()
 
 
 def build_library(verbose: bool = False) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     tmp = LIB + ".tmp%d" % os.getpid()
+    digest = source_digest()
     cmd = [hipcc] + HIPCC_FLAGS + sources() + ["-o", tmp]
     if verbose:
         print(" ".join(cmd), flush=True)
@@ -41,6 +56,8 @@ def build_library(verbose: bool = False) -> str:
         sys.stderr.write(res.stdout + res.stderr)
         raise RuntimeError("hipcc failed")
     os.replace(tmp, LIB)
+    with open(STAMP, "w") as f:
+        f.write(digest + "\n")
     return LIB
 
 
