@@ -2,8 +2,9 @@
  * tvprox -- batched total-variation proximal operators for AMD MI355X (gfx950).
  *
  * C ABI.  Every data pointer is a DEVICE pointer to fp32 data (bf16 bit patterns in the
- * two *_bf16 entry points) owned by the caller; the library allocates nothing, keeps no state between calls, and only
- * enqueues kernels on the stream it is given (asynchronous, no implicit sync).
+ * two *_bf16 entry points) owned by the caller; the library allocates nothing, keeps no state
+ * between calls (tv1d_prox_bwd_noalloc alone remembers, per device, where its static scratch
+ * array lies), and only enqueues kernels on the stream it is given (asynchronous, no implicit sync).
  * Every function returns a tv_status; argument validation happens before any
  * HIP call, so invalid calls fail the same way on a machine without a GPU.
  *
@@ -38,7 +39,8 @@ typedef enum {
     TV_ERR_WORKSPACE = 5,   /* workspace NULL, misaligned or too small                 */
     TV_ERR_UNSUPPORTED = 6, /* row longer than TV_MAX_LENGTH (TV_SEG_MAX_LENGTH with codes);
                                bf16 storage on anything but packed rows of 32 samples       */
-    TV_ERR_HIP = 7          /* a HIP runtime call (kernel launch) failed               */
+    TV_ERR_HIP = 7,         /* a HIP runtime call (kernel launch) failed               */
+    TV_ERR_SCRATCH = 8      /* tv1d_prox_bwd_noalloc: more than TV_NOALLOC_MAX_ROWS rows */
 } tv_status;
 
 /* Longest row any entry point accepts. */
@@ -138,6 +140,23 @@ size_t tv1d_fwd_workspace_bytes(tv_rows rows, tv_lambda lam);
 int tv1d_prox_bwd(const float *g_up, const float *x, float *grad_y, float *grad_lam,
                   tv_rows rows, tv_lambda lam, void *ws, size_t ws_bytes, hipStream_t stream);
 size_t tv1d_bwd_workspace_bytes(tv_rows rows, tv_lambda lam);
+
+/*
+ * tv1d_prox_bwd for callers that cannot allocate device memory and have no workspace to hand
+ * over (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc):
+ * same arguments without ws / ws_bytes, same kernels, same results bit for bit.  The scratch
+ * that tv1d_prox_bwd takes from its caller (one float per row for the dL/dlam terms) lies in
+ * a static device array of the library instead: TV_NOALLOC_MAX_ROWS floats (4 MiB), which
+ * every GPU the library runs on holds until the process ends.  More rows than that:
+ * TV_ERR_SCRATCH, nothing is launched.  The call allocates and frees nothing.  Its first call
+ * on a device looks the array's address up (with that device current; make that call outside
+ * a graph capture); the stream must belong to the current device.  All calls on one GPU share
+ * the one array: two calls that may overlap there (different streams, no dependency) race on
+ * it.  Nothing has to be cleared between calls: a call overwrites every entry it reads.
+ */
+#define TV_NOALLOC_MAX_ROWS (1 << 20)
+int tv1d_prox_bwd_noalloc(const float *g_up, const float *x, float *grad_y, float *grad_lam,
+                          tv_rows rows, tv_lambda lam, hipStream_t stream);
 
 /*
  * Forward/backward pair for rows of at most TV_SEG_MAX_LENGTH samples in which the

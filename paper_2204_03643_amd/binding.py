@@ -48,6 +48,8 @@ def lib() -> ctypes.CDLL:
         L.tv1d_prox_fwd_info.restype = ctypes.c_int
         L.tv1d_prox_bwd.argtypes = [_vp, _vp, _vp, _vp, tv_rows, tv_lambda, _vp, ctypes.c_size_t, _vp]
         L.tv1d_prox_bwd.restype = ctypes.c_int
+        L.tv1d_prox_bwd_noalloc.argtypes = [_vp, _vp, _vp, _vp, tv_rows, tv_lambda, _vp]
+        L.tv1d_prox_bwd_noalloc.restype = ctypes.c_int
         L.tv1d_prox_fwd_seg.argtypes = [_vp, _vp, _vp, tv_rows, tv_lambda, _vp]
         L.tv1d_prox_fwd_seg.restype = ctypes.c_int
         L.tv1d_prox_fwd_ex.argtypes = [_vp, _vp, tv_rows, tv_lambda, tv_fwd_extra, _vp]
@@ -130,6 +132,11 @@ def tv1d_prox_bwd(g_up, x, grad_y, grad_lam, rows: tv_rows, lam: tv_lambda, ws, 
                   stream=None):
     _check(lib().tv1d_prox_bwd(_ptr(g_up), _ptr(x), _ptr(grad_y), _ptr(grad_lam), rows, lam,
                                _ptr(ws), int(ws_bytes), _stream(stream)))
+
+
+def tv1d_prox_bwd_noalloc(g_up, x, grad_y, grad_lam, rows: tv_rows, lam: tv_lambda, stream=None):
+    _check(lib().tv1d_prox_bwd_noalloc(_ptr(g_up), _ptr(x), _ptr(grad_y), _ptr(grad_lam), rows, lam,
+                                       _stream(stream)))
 
 
 def tv1d_prox_fwd_seg(y, x, seg, rows: tv_rows, lam: tv_lambda, stream=None):

@@ -1,13 +1,22 @@
 // C-ABI entry points of the TV-prox library: argument validation, path selection and
-// kernel launches.  Nothing here allocates, synchronises or keeps state.
+// kernel launches.  Nothing here allocates or synchronises; the only state is the address of
+// the static scratch array of tv1d_prox_bwd_noalloc, looked up once per device.
 #include "../../include/tvprox.h"
 
 #include <hip/hip_runtime.h>
+
+#include <mutex>
 
 #include "tv_common.hpp"
 #include "tv_long.hpp"
 #include "tv_small2d.hpp"
 #include "tv_short.hpp"
+
+// Scratch of tv1d_prox_bwd_noalloc (the per-row dL/dlam terms between the backward kernel and
+// the per-slot reduction): every GPU the library runs on holds its own copy until the process
+// ends.  In host code this name is only a handle for hipGetSymbolAddress; kernels are handed
+// the address that call returns for the current device.
+static __device__ __align__(256) float scratch[TV_NOALLOC_MAX_ROWS];
 
 namespace {
 
@@ -792,8 +801,29 @@ int fwd_entry(const float *y, float *x, tv_rows rows, tv_lambda lam, const tv_fw
                    lam, n_rows, s, nullptr, false, (char *)e.ws);
 }
 
+// Device address of `scratch` on the current device, resolved on the first call there.
+constexpr int kMaxDevices = 64;
+std::mutex scratch_mutex;
+float *scratch_ptr[kMaxDevices] = {};
+
+int scratch_of_current_device(float **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return TV_ERR_HIP;
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    if (!scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return TV_ERR_HIP;
+        scratch_ptr[dev] = static_cast<float *>(ptr);
+    }
+    *out = scratch_ptr[dev];
+    return TV_OK;
+}
+
+// ws == nullptr with static_ws: the dL/dlam terms go through the library's static scratch.
 int bwd_entry(const float *g_up, const float *x, const uint64_t *seg, bool with_seg, float *grad_y,
-              float *grad_lam, tv_rows rows, tv_lambda lam, void *ws, size_t ws_bytes, hipStream_t stream)
+              float *grad_lam, tv_rows rows, tv_lambda lam, void *ws, size_t ws_bytes, hipStream_t stream,
+              bool static_ws = false)
 {
     int st = check_lambda(lam);
     if (st != TV_OK) return st;
@@ -810,7 +840,15 @@ int bwd_entry(const float *g_up, const float *x, const uint64_t *seg, bool with_
         if (rows.length > TV_SEG_MAX_LENGTH) return TV_ERR_UNSUPPORTED;
         if ((uintptr_t)seg % 8 != 0) return TV_ERR_STRIDE;
     }
-    if (grad_lam) {
+    if (static_ws) {
+        if (n_rows > (int64_t)TV_NOALLOC_MAX_ROWS) return TV_ERR_SCRATCH;
+        if (grad_lam) {
+            float *ptr = nullptr;
+            st = scratch_of_current_device(&ptr);
+            if (st != TV_OK) return st;
+            ws = ptr;
+        }
+    } else if (grad_lam) {
         if (!ws || !aligned16(ws) || ws_bytes < align16((size_t)n_rows * sizeof(float)))
             return TV_ERR_WORKSPACE;
     }
@@ -834,6 +872,7 @@ const char *tv_status_str(int status)
     case TV_ERR_WORKSPACE: return "bad workspace";
     case TV_ERR_UNSUPPORTED: return "unsupported size";
     case TV_ERR_HIP: return "HIP runtime error";
+    case TV_ERR_SCRATCH: return "more rows than the static scratch buffer holds";
     default: return "unknown status";
     }
 }
@@ -891,6 +930,12 @@ int tv1d_prox_bwd_seg(const float *g_up, const uint64_t *seg, float *grad_y, flo
                       tv_rows rows, tv_lambda lam, void *ws, size_t ws_bytes, hipStream_t stream)
 {
     return bwd_entry(g_up, nullptr, seg, true, grad_y, grad_lam, rows, lam, ws, ws_bytes, stream);
+}
+
+int tv1d_prox_bwd_noalloc(const float *g_up, const float *x, float *grad_y, float *grad_lam,
+                          tv_rows rows, tv_lambda lam, hipStream_t stream)
+{
+    return bwd_entry(g_up, x, nullptr, false, grad_y, grad_lam, rows, lam, nullptr, 0, stream, true);
 }
 
 // ---- bf16 storage, fp32 arithmetic: packed rows of exactly 32 samples, segment-code pair only --

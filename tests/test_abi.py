@@ -29,7 +29,7 @@ def test_every_declared_symbol_is_exported():
 
 def test_status_strings():
     assert tv.status_str(0) == "ok"
-    for s in range(1, 8):
+    for s in range(1, 9):
         assert tv.status_str(s) not in ("ok", "unknown status")
     assert tv.status_str(99) == "unknown status"
 
@@ -75,6 +75,21 @@ def test_backward_validation():
     assert L.tv1d_prox_bwd(FAKE, FAKE, FAKE, FAKE, rows, lam, FAKE, 8, None) == 5    # too small
     assert L.tv1d_prox_bwd(FAKE, FAKE, FAKE, FAKE, rows, lam, FAKE + 4, 64, None) == 5  # misaligned
     assert L.tv1d_prox_bwd(FAKE, FAKE, FAKE, FAKE, tv.tv_rows(4, 32, 1, 1, 0, 1), lam, FAKE, 64, None) == 2
+
+
+def test_noalloc_backward_validation():
+    """Same checks as tv1d_prox_bwd, and the row limit of the static scratch, all before any HIP call."""
+    L = tv.lib()
+    rows = tv.tv_rows(4, 32, 1, 1, 32, 1)
+    lam = tv.tv_lambda(FAKE, 1, 1)
+    assert L.tv1d_prox_bwd_noalloc(None, FAKE, FAKE, FAKE, rows, lam, None) == 1
+    assert L.tv1d_prox_bwd_noalloc(FAKE, None, FAKE, FAKE, rows, lam, None) == 1
+    assert L.tv1d_prox_bwd_noalloc(FAKE, FAKE, FAKE, FAKE, tv.tv_rows(4, 32, 1, 1, 0, 1), lam, None) == 2
+    assert L.tv1d_prox_bwd_noalloc(FAKE, FAKE, FAKE, FAKE, rows, tv.tv_lambda(FAKE, 0, 1), None) == 4
+    too_many = tv.tv_rows((1 << 20) + 1, 32, 1, 1, 32, 1)
+    assert L.tv1d_prox_bwd_noalloc(FAKE, FAKE, FAKE, FAKE, too_many, lam, None) == 8     # TV_ERR_SCRATCH
+    assert L.tv1d_prox_bwd_noalloc(FAKE, FAKE, FAKE, None, too_many, lam, None) == 8
+    assert "scratch" in tv.status_str(8)
 
 
 def test_seg_pair_validation():
