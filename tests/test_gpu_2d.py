@@ -1,41 +1,30 @@
-"""GPU parity for the 2D operator (paper Alg. 1) and its reverse sweep.
-
-Forward: element-wise against the oracle's K-sweep result.  Backward: (a) exactly the
-oracle's reverse sweep replayed on the GPU's own saved pass outputs (same segments, so
-the arithmetic must agree to rounding); (b) against the oracle's own gradient, where one
-near-degenerate row anywhere in the 2K passes changes a gradient entry by O(1), so the
-assertion is on the bulk of the entries."""
+"""GPU parity for the 2D operator (paper Alg. 1) and its reverse sweep, under the rules of
+parity.check_2d: forward and every saved pass element-wise against the oracle's K-sweep run;
+in every pass the oracle's exact jump set and jump directions on every row that is not
+near-degenerate; grad_y and grad_lam against the oracle's reverse sweep (its own segments,
+except on near-degenerate rows)."""
 import numpy as np
 import pytest
 
 import oracle
 import workloads
 from gpuutil import run_2d
+from parity import check_2d
 
 pytestmark = pytest.mark.gpu
 
 
-def _check_2d(y, lam, K, g, label, bulk=0.9):
+def _check_2d(y, lam, K, g, label):
     out = run_2d(y, lam, K, g)
-    y64, lam64, g64 = y.astype(np.float64), lam.astype(np.float64), g.astype(np.float64)
-    x_ref, saved_ref = oracle.prox2d_fwd(y64, lam64, K)
-    scale = 1.0 + np.abs(y).max()
-    assert np.all(np.isfinite(out["x"])), label
-    err = np.abs(out["x"] - x_ref).max() / scale
-    assert err <= 1e-4, (label, "forward", err)
-    perr = np.abs(out["saved"] - saved_ref).max() / scale
-    assert perr <= 1e-4, (label, "saved passes", perr)
-    assert np.array_equal(out["saved"][-1], out["x"])
-    # (a) reverse-sweep arithmetic on the GPU's own segments
+    st = check_2d(y, lam, K, g, out, label)
+    # (kept from before: the reverse-sweep arithmetic alone, replayed by the oracle on the HIP
+    # path's own pass outputs, to ten times the gradient bar)
+    g64 = g.astype(np.float64)
     gy_rep, gl_rep = oracle.prox2d_bwd(g64, out["saved"].astype(np.float64), lam.size, K)
-    gscale = np.abs(gy_rep).max()
-    assert np.abs(out["gy"] - gy_rep).max() <= 1e-4 * gscale, (label, "grad_y replay")
+    assert np.abs(out["gy"] - gy_rep).max() <= 1e-4 * np.abs(gy_rep).max(), (label, "grad_y replay")
     assert np.all(np.abs(out["gl"] - gl_rep) <= 1e-4 * (np.abs(gl_rep) + np.sqrt(y.size))), (label, "grad_lam replay")
-    # (b) against the oracle's own gradient: the bulk must agree
-    gy_ref, gl_ref = oracle.prox2d_bwd(g64, saved_ref, lam.size, K)
-    close = np.abs(out["gy"] - gy_ref) <= 1e-3 * np.abs(gy_ref).max()
-    assert close.mean() >= bulk, (label, "grad_y bulk", close.mean())
-    return err, close.mean()
+    print("%s: %s" % (label, st))
+    return st
 
 
 def test_small_maps_k1_and_k3():
@@ -58,7 +47,7 @@ def test_mid_planes(shape, K):
     y = rng.normal(size=shape).astype(np.float32)
     g = rng.normal(size=shape).astype(np.float32)
     lam = (10 ** rng.uniform(-2, 0.3, size=min(shape[0], 3))).astype(np.float32)
-    _check_2d(y, lam, K, g, "mid %s K=%d" % (shape, K), bulk=0.8)
+    _check_2d(y, lam, K, g, "mid %s K=%d" % (shape, K))
 
 
 def test_odd_sizes_mixed_paths():
@@ -89,7 +78,7 @@ def test_small_planes(shape, K):
     y = rng.normal(size=shape).astype(np.float32)
     g = rng.normal(size=shape).astype(np.float32)
     lam = (10 ** rng.uniform(-2, 0.3, size=min(shape[0], 3))).astype(np.float32)
-    _check_2d(y, lam, K, g, "small %s K=%d" % (shape, K), bulk=0.8)
+    _check_2d(y, lam, K, g, "small %s K=%d" % (shape, K))
 
 
 @pytest.mark.parametrize("shape,K", [((6200, 20, 9), 1), ((4099, 20, 9), 2), ((4097, 32, 32), 2), ((16390, 16, 16), 1)])
@@ -102,7 +91,7 @@ def test_many_small_planes(shape, K):
     y = rng.normal(size=shape).astype(np.float32)
     g = rng.normal(size=shape).astype(np.float32)
     lam = (10 ** rng.uniform(-2, 0.3, size=5)).astype(np.float32)
-    _check_2d(y, lam, K, g, "many small %s K=%d" % (shape, K), bulk=0.8)
+    _check_2d(y, lam, K, g, "many small %s K=%d" % (shape, K))
 
 
 @pytest.mark.parametrize("shape", [(1, 1100, 2100), (2, 40, 9000)])
@@ -113,12 +102,12 @@ def test_long_rows_and_columns_k2(shape):
     y = (np.cumsum(rng.normal(scale=0.05, size=shape), axis=-1) + rng.normal(scale=0.2, size=shape)).astype(np.float32)
     g = rng.normal(size=shape).astype(np.float32)
     lam = np.array([0.3, 0.05][:shape[0]], np.float32)
-    _check_2d(y, lam, 2, g, "long %s K=2" % (shape,), bulk=0.8)
+    _check_2d(y, lam, 2, g, "long %s K=2" % (shape,))
 
 
 def test_config4_reduced():
     y, lam, g = workloads.config4(B=1, C=3, H=512, W=512, n_poly=8)
-    _check_2d(y, lam, 3, g, "cfg4 reduced K=3", bulk=0.8)
+    _check_2d(y, lam, 3, g, "cfg4 reduced K=3")
 
 
 def test_lambda_zero_identity_and_mass():

@@ -1,62 +1,93 @@
 """GPU parity at the full sizes of the benchmark workloads (the launch configurations the
-benchmark times).  Forward results are compared with the oracle on every element (the C
-oracle is fast enough); gradients on sampled rows under the parity rules of parity.py."""
+benchmark times).  Every element of the forward results and of the gradients, and every
+lambda slot, is compared with the oracle under the parity rules of parity.py (the C oracle is
+fast enough)."""
 import numpy as np
 import pytest
 
-import oracle
 import workloads
 from gpuutil import lam_per_row, rows_view, run_1d, run_2d
-from parity import FWD_TOL, check_batch, forward_errors
+from parity import check_2d, check_batch
 
 pytestmark = pytest.mark.gpu
 
 
-def _full_1d(y, lam, lam_div, g, axis, label, n_sample):
+def _full_1d(y, lam, lam_div, g, axis, label):
+    """Every row and every lambda slot against the oracle; returns check_batch's statistics."""
     out = run_1d(y, lam, lam_div, g, axis=axis, want_info=True)
     assert not np.any(out["info"] & (1 << 18)), label               # nobody hit the iteration cap
     assert np.count_nonzero(out["info"] & (1 << 19)) <= 1e-4 * out["info"].size, label
     yr, gr = rows_view(y, axis), rows_view(g, axis)
     xr, gyr = rows_view(out["x"], axis), rows_view(out["gy"], axis)
     lr = lam_per_row(lam, len(yr), lam_div)
-    x_ref = oracle.prox1d_batch(yr.astype(np.float64), lr.astype(np.float64), axis=-1, lam_div=1)
-    ferr = forward_errors(xr, x_ref, yr)
-    assert ferr.max() <= FWD_TOL, (label, float(ferr.max()))
-    rng = np.random.default_rng(len(yr))
-    idx = np.sort(rng.choice(len(yr), size=min(n_sample, len(yr)), replace=False))
-    st = check_batch(yr[idx], lr[idx], gr[idx], xr[idx], gyr[idx], label=label)
-    # grad_lam against the oracle's per-row contributions on the GPU's own segments
-    _, gl_ref = oracle.prox1d_bwd_batch(gr.astype(np.float64), xr.astype(np.float64),
-                                        lam_count=np.asarray(lam).size, axis=-1, lam_div=lam_div)
-    np.testing.assert_allclose(out["gl"], gl_ref, rtol=2e-4, atol=2e-2)
+    st = check_batch(yr, lr, gr, xr, gyr, gl_gpu=out["gl"], lam_count=np.asarray(lam).size, lam_div=lam_div,
+                     label=label)
+    print(label, st)
+    # how much of the gradient parity rests on the rounding floors of the rules
+    assert st["grad_y_rows_needing_floor"] <= 1e-3 * st["rows"] + 1, (label, st)
+    assert st["grad_lam_slots_needing_floor"] <= 0.01 * st["slots"] + 1, (label, st)
     return st
 
 
 def test_config2_full():
     y, lam, g = workloads.config2()
-    _full_1d(y, lam, 32, g, -1, "cfg2 rows", 5000)
-    _full_1d(y, lam, 32, g, -2, "cfg2 columns", 5000)
+    _full_1d(y, lam, 32, g, -1, "cfg2 rows")
+    _full_1d(y, lam, 32, g, -2, "cfg2 columns")
+
+
+def test_config2_full_as_2d_k1():
+    """Workload 2 as the layer runs it: rows, then columns of the row pass's output (one sweep of
+    Alg. 1), forward and reverse sweep, every plane."""
+    y, lam, g = workloads.config2()
+    st = check_2d(y, lam, 1, g, run_2d(y, lam, 1, g), "cfg2 2D K=1")
+    print("cfg2 2D K=1:", st)
+    assert st["planes_without_near_degenerate_rows"] > 0
+
+
+def test_config3_full_timed_pair():
+    """The pair the benchmark times, at its full size and in its launch configuration (grid
+    grouped by lambda slot, slots in cost order, non-temporal accesses, segment codes):
+    tv1d_prox_fwd_ex with codes and workspace, then tv1d_prox_bwd_seg.  Bit-identical to the plain
+    pair, codes as the header defines them, and EVERY row and slot against the oracle."""
+    y, lam, g = workloads.config3()
+    out = run_1d(y, lam, 32, g, use_seg=True, use_ws=True, want_info=True)
+    plain = run_1d(y, lam, 32, g)
+    assert np.array_equal(out["x"], plain["x"]) and np.array_equal(out["gy"], plain["gy"])
+    assert np.array_equal(out["gl"], plain["gl"])
+    del plain
+    assert out["ws_bytes"] >= 4 * lam.size and np.array_equal(np.sort(out["order"]), np.arange(lam.size))
+    assert not np.any(out["info"] & (1 << 18))
+    yr, gr, xr, gyr = (a.reshape(-1, 32) for a in (y, g, out["x"], out["gy"]))
+    code = np.zeros(len(xr), dtype=np.uint64)
+    for k in range(31):
+        code |= (xr[:, k + 1] != xr[:, k]).astype(np.uint64) << np.uint64(k)
+        code |= (xr[:, k + 1] > xr[:, k]).astype(np.uint64) << np.uint64(32 + k)
+    assert np.array_equal(out["seg"], code)
+    st = check_batch(yr, lam_per_row(lam, len(yr), 32), gr, xr, gyr, gl_gpu=out["gl"], lam_count=lam.size,
+                     lam_div=32, label="cfg3 timed pair, all rows")
+    print("cfg3 timed pair:", st)
+    # how much of the gradient parity rests on the rounding floors of the rules
+    assert st["grad_y_rows_needing_floor"] <= 1e-3 * st["rows"]
+    assert st["grad_lam_slots_needing_floor"] <= 0.01 * st["slots"] + 1
+    assert st["near_degenerate"] <= 0.02 * st["rows"]
 
 
 def test_config3_full_columns():
     y, lam, g = workloads.config3()
-    _full_1d(y, lam, 32, g, -2, "cfg3 columns", 5000)
+    _full_1d(y, lam, 32, g, -2, "cfg3 columns")
 
 
-def test_config4_full_forward_and_reduced_backward():
+def test_config4_full():
+    """All eight images, K = 10: forward, every saved pass, the segments of every pass and the
+    reverse sweep."""
     y, lam, g = workloads.config4()
-    out = run_2d(y, lam, 10)
-    x_ref, _ = oracle.prox2d_fwd(y.astype(np.float64), lam.astype(np.float64), 10)
-    err = np.abs(out["x"] - x_ref).max() / (1.0 + np.abs(y).max())
-    assert err <= FWD_TOL, err
-    # reverse sweep at full image size on two of the eight images
-    y2, g2 = y[:2], g[:2]
-    out = run_2d(y2, lam, 10, g2)
-    gy_rep, gl_rep = oracle.prox2d_bwd(g2.astype(np.float64), out["saved"].astype(np.float64), 1, 10)
-    assert np.abs(out["gy"] - gy_rep).max() <= 1e-4 * np.abs(gy_rep).max()
-    assert abs(out["gl"][0] - gl_rep[0]) <= 1e-4 * (abs(gl_rep[0]) + np.sqrt(y2.size))
+    st = check_2d(y, lam, 10, g, run_2d(y, lam, 10, g), "cfg4 K=10")
+    print("cfg4 K=10:", st)
+    # rows of 512 samples nearly always hold some dual within 1e-4 of a change of status, so
+    # here the segment rule bites dual by dual: all but a fraction of a percent of them
+    assert st["pass_duals_near_degenerate"] <= 0.01 * st["pass_duals_checked"]
 
 
 def test_config5_full():
     y, lam, g = workloads.config5()
-    _full_1d(y, lam, 1, g, -1, "cfg5", 48)
+    _full_1d(y, lam, 1, g, -1, "cfg5")
