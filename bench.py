@@ -24,6 +24,8 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0           # MI355X published HBM3E peak
+WARM_SECONDS = 0.3              # warm-up goes on at least this long, whatever --warmup says
+BATCHES = 5                     # timed regions of --steps replays each; the median is reported
 FWD_BYTES_PER_ELEM = 8          # read y, write x
 BWD_BYTES_PER_ELEM = 12         # read g_up and x, write grad_y
 BWD_SEG_BYTES_PER_ELEM = 8      # read g_up, write grad_y ...
@@ -62,6 +64,48 @@ def cpu_baseline(sample_rows: int):
             "sample": "%d rows x 32 drawn like the workload, in %d chunks (fwd+bwd, fp64, OpenMP "
                       "over rows), %.2f s of wall time" % (rows, n_chunks, dt),
             "single_thread_rows_per_s": (y.size // 32) / dt1}
+
+
+def cpu_baseline_other():
+    """The oracle on the other four workloads (bounded samples, fwd + bwd), same box, same run."""
+    import numpy as np
+
+    import oracle
+    import workloads
+
+    def t_1d(y, lam, g, axis, lam_div, reps=1):
+        y64, g64, lam64 = y.astype(np.float64), g.astype(np.float64), np.asarray(lam, dtype=np.float64)
+        best = None
+        for _ in range(reps):
+            t0 = time.perf_counter()
+            x = oracle.prox1d_batch(y64, lam64, axis=axis, lam_div=lam_div)
+            oracle.prox1d_bwd_batch(g64, x, lam_count=lam64.size, axis=axis, lam_div=lam_div)
+            dt = time.perf_counter() - t0
+            best = dt if best is None else min(best, dt)
+        return best
+
+    out = {}
+    y, lam, g = workloads.config1()
+    dt = t_1d(y, lam, g, -1, 1, reps=5)
+    out["config1_1d_64x256"] = {"rows_per_s": 64 / dt, "sample": "all 64 rows, best of 5", "seconds": dt}
+    y, lam, g = workloads.config2()
+    dt = t_1d(y, lam, g, -1, 32) + t_1d(y, lam, g, -2, 32)
+    out["config2_rows_then_columns"] = {"rows_per_s": 2 * (y.size // 32) / dt,
+                                        "sample": "the whole tensor, row pass + column pass", "seconds": dt}
+    y, lam, g = workloads.config4(B=2)
+    y64, g64, lam64 = y.astype(np.float64), g.astype(np.float64), lam.astype(np.float64)
+    t0 = time.perf_counter()
+    _, saved = oracle.prox2d_fwd(y64, lam64, 10)
+    oracle.prox2d_bwd(g64, saved, lam64.size, 10)
+    dt = time.perf_counter() - t0
+    out["config4_2d_k10"] = {"images_per_s": 6 / dt, "sample": "2 of the 8 images (6 planes of 512 x 512), K = 10",
+                             "seconds": dt}
+    del saved
+    y, lam, g = workloads.config5(rows=256)
+    dt = t_1d(y, lam, g, -1, 1)
+    out["config5_1d_4096x16384"] = {"rows_per_s": 256 / dt, "sample": "256 of the 4096 rows", "seconds": dt}
+    out["cores"] = oracle.num_threads()
+    return out
 
 
 ROTATE_BYTES = 640 << 20        # distinct buffers cycled through so that none is still cached
@@ -141,9 +185,17 @@ def other_workloads(dev, reps: int = 25):
         # one set of buffers (the workspace of K = 10 on workload 4 alone is 0.5 GB)
         tf, tf_min = timed(lambda k: tv.tv2d_prox_fwd(yt, xt, planes, H, W, L, sweeps, ws, wsb))
         tb, tb_min = timed(lambda k: tv.tv2d_prox_bwd(gt, gy, gl, planes, H, W, L, sweeps, ws, wsb))
+        # algorithmic bytes per sample of Alg. 1 pass by pass: forward 16 in the first sweep
+        # (two passes reading and writing one tensor each) and 32 in every later one (the correction
+        # terms are read and written too); reverse sweep 40 per sweep
+        fb, bb = (16 + 32 * (sweeps - 1)) * y.size, 40 * sweeps * y.size
         return {"planes": planes, "H": H, "W": W, "sweeps": sweeps, "fwd_us": tf, "bwd_us": tb,
                 "fwd_us_min": tf_min, "bwd_us_min": tb_min,
-                "images_per_s": planes / ((tf + tb) * 1e-6)}
+                "images_per_s": planes / ((tf + tb) * 1e-6),
+                "rows_per_s": planes * (H + W) * sweeps / ((tf + tb) * 1e-6),
+                "effective_gbs": (fb + bb) / ((tf + tb) * 1e-6) / 1e9,
+                "frac_of_hbm_peak": (fb + bb) / ((tf + tb) * 1e-6) / 1e9 / HBM_PEAK_GBS,
+                "effective_gbs_fwd": fb / (tf * 1e-6) / 1e9, "effective_gbs_bwd": bb / (tb * 1e-6) / 1e9}
 
     out = {}
     y, lam, g = workloads.config1()
@@ -175,7 +227,7 @@ def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=500)
-    ap.add_argument("--warmup", type=int, default=200)     # ~30 ms: lets the clocks settle
+    ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-rows", type=int, default=1 << 25)
     ap.add_argument("--headline-only", action="store_true", help="skip the other four workloads")
@@ -241,18 +293,46 @@ def main() -> int:
         torch.cuda.synchronize()
         return 0
 
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    # per-call durations: K eager steps with events around the forward and the backward call
-    events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
-    for k in range(args.steps):
-        step(events[k])
-    torch.cuda.synchronize()
-    x_eager, gy_eager, gl_eager = xt.clone(), gy.clone(), gl.clone()
+    # ---- warm-up: the W steps asked for, then on until at least WARM_SECONDS have passed.  A
+    #      cold GPU runs its first milliseconds at a lower clock, and a short timed region
+    #      (say 20 steps = 3 ms) straight after 5 warm-up steps would measure that instead.
+    t_w = time.perf_counter()
+    n_w = 0
+    while n_w < args.warmup or time.perf_counter() - t_w < WARM_SECONDS:
+        for _ in range(25):
+            step()
+        n_w += 25
+        torch.cuda.synchronize()
+    warm_s = time.perf_counter() - t_w
 
-    # the timed region: K replays of a HIP graph that holds one step (the calls launch kernels
-    # only, so a step captures as is; replays keep the launch path off the clock)
+    def timed_calls(fn_a, fn_b, reps):
+        """reps eager steps a, b with events on the launch stream around each call; (a_ms, b_ms) lists"""
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(reps)]
+        for k in range(reps):
+            ev[k][0].record(stream)
+            fn_a()
+            ev[k][1].record(stream)
+            fn_b()
+            ev[k][2].record(stream)
+        torch.cuda.synchronize()
+        return ([e[0].elapsed_time(e[1]) for e in ev], [e[1].elapsed_time(e[2]) for e in ev])
+
+    reps = max(args.steps, 100)                 # per-call figures: at least 100 samples each
+    fwd_call = lambda: tv.tv1d_prox_fwd_ex(yt, xt, rows, L, seg=seg, ws=fws, ws_bytes=fwsb, stream=stream)
+    # the forward kernel alone: the slot order of the call before is still in the workspace
+    fwd_kernel = lambda: tv.tv1d_prox_fwd_ex(yt, xt, rows, L, seg=seg, ws=fws, ws_bytes=fwsb, stream=stream,
+                                             flags=tv.TV_FWD_ORDER_READY)
+    bwd_call = lambda: tv.tv1d_prox_bwd_seg(gt, seg, gy, gl, rows, L, ws, wsb, stream)
+    f_all, b_all = timed_calls(fwd_call, bwd_call, reps)
+    x_eager, gy_eager, gl_eager = xt.clone(), gy.clone(), gl.clone()
+    k_all, _ = timed_calls(fwd_kernel, bwd_call, reps)
+    if not (torch.equal(xt, x_eager) and torch.equal(gy, gy_eager)):
+        print("bench.py: the forward call with a kept slot order changed the results", file=sys.stderr)
+        return 1
+
+    # ---- the timed region: K replays of a HIP graph that holds one step (the calls launch
+    #      kernels only, so a step captures as is; replays keep the launch path off the clock).
+    #      BATCHES such regions, each bracketed by a synchronisation; the median is reported.
     graph = torch.cuda.CUDAGraph()
     side = torch.cuda.Stream()
     side.wait_stream(stream)
@@ -261,63 +341,49 @@ def main() -> int:
             tv.tv1d_prox_fwd_ex(yt, xt, rows, L, seg=seg, ws=fws, ws_bytes=fwsb)
             tv.tv1d_prox_bwd_seg(gt, seg, gy, gl, rows, L, ws, wsb)
     stream.wait_stream(side)
-    for _ in range(max(3, args.warmup // 10)):
-        graph.replay()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for k in range(args.steps):
-        graph.replay()
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
+    t_w = time.perf_counter()
+    while time.perf_counter() - t_w < 0.1:
+        for _ in range(25):
+            graph.replay()
+        torch.cuda.synchronize()
+    batch_ms = []
+    for _ in range(BATCHES):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for k in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        batch_ms.append((time.perf_counter() - t0) * 1e3 / args.steps)
     if not (torch.equal(xt, x_eager) and torch.equal(gy, gy_eager) and torch.equal(gl, gl_eager)):
         print("bench.py: graph replays and eager steps disagree", file=sys.stderr)
         return 1
+    ms_per_step = float(np.median(batch_ms))
+    value = n_rows / (ms_per_step * 1e-3)
 
-    f_all = [e[0].elapsed_time(e[1]) for e in events]
-    b_all = [e[1].elapsed_time(e[2]) for e in events]                    # bwd kernel + lam reduction
     fwd_ms, bwd_ms = float(np.mean(f_all)), float(np.mean(b_all))
-    ms_per_step = wall * 1e3 / args.steps
-    value = n_rows * args.steps / wall
+    ker_ms = float(np.mean(k_all))
 
-    # the plain pair (backward reads x), same number of steps
-    pe = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
-    plain_step()
-    for k in range(args.steps):
-        plain_step(pe[k])
-    torch.cuda.synchronize()
-    pf_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in pe]))
-    pb_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in pe]))
+    # the plain pair (backward reads x)
+    pf, pb = timed_calls(lambda: tv.tv1d_prox_fwd(yt, xt, rows, L, stream),
+                         lambda: tv.tv1d_prox_bwd(gt, xt, gy, gl, rows, L, ws, wsb, stream), reps)
+    pf_ms, pb_ms = float(np.mean(pf)), float(np.mean(pb))
 
     # the same step with bf16 storage and fp32 arithmetic (context: the paper computes in fp32,
     # and the headline value above is the fp32 pair)
     yh, gh = yt.to(torch.bfloat16), gt.to(torch.bfloat16)
     xh, gyh = torch.empty_like(yh), torch.empty_like(yh)
-
-    def bf16_step(evs=None):
-        if evs is not None:
-            evs[0].record(stream)
-        tv.tv1d_prox_fwd_seg_bf16(yh, xh, seg, rows, L, fws, fwsb, stream)
-        if evs is not None:
-            evs[1].record(stream)
-        tv.tv1d_prox_bwd_seg_bf16(gh, seg, gyh, gl, rows, L, ws, wsb, stream)
-        if evs is not None:
-            evs[2].record(stream)
-
-    he = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
-    bf16_step()
-    for k in range(args.steps):
-        bf16_step(he[k])
-    torch.cuda.synchronize()
-    hf_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in he]))
-    hb_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in he]))
+    hf, hb = timed_calls(lambda: tv.tv1d_prox_fwd_seg_bf16(yh, xh, seg, rows, L, fws, fwsb, stream),
+                         lambda: tv.tv1d_prox_bwd_seg_bf16(gh, seg, gyh, gl, rows, L, ws, wsb, stream), reps)
+    hf_ms, hb_ms = float(np.mean(hf)), float(np.mean(hb))
     del yh, gh, xh, gyh
 
     # algorithmic bytes of the method (read y, write x; read g_up and x, write grad_y) ...
     fwd_bytes, bwd_bytes = n_elem * FWD_BYTES_PER_ELEM, n_elem * BWD_BYTES_PER_ELEM
     # ... and what the backward kernel of the timed pair has to move
     bwd_seg_bytes = n_elem * BWD_SEG_BYTES_PER_ELEM + n_rows * BWD_SEG_BYTES_PER_ROW
-    fwd_gbs = fwd_bytes / (fwd_ms * 1e-3) / 1e9
+    fwd_gbs = fwd_bytes / (ker_ms * 1e-3) / 1e9          # the forward KERNEL (see roofline.note)
     bwd_gbs = bwd_seg_bytes / (bwd_ms * 1e-3) / 1e9
+    moved_bytes = fwd_bytes + 8 * n_rows + bwd_seg_bytes  # what the timed pair moves (codes written and read)
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic_tv1d_fwd_short_config3.json")
     if os.path.exists(tpath):
@@ -332,9 +398,9 @@ def main() -> int:
         with open(vpath) as f:
             valu = json.load(f).get("sq_insts_valu")
         peak_ips = 256 * 4 * 2.4e9 / 4.0
-        alu = {"kernel": "forward call", "valu_wave_instructions_per_launch": valu,
-               "achieved_per_s": valu / (fwd_ms * 1e-3), "peak_per_s": peak_ips,
-               "frac": valu / (fwd_ms * 1e-3) / peak_ips}
+        alu = {"kernel": "tv1d_fwd_short_kernel<32>", "valu_wave_instructions_per_launch": valu,
+               "achieved_per_s": valu / (ker_ms * 1e-3), "peak_per_s": peak_ips,
+               "frac": valu / (ker_ms * 1e-3) / peak_ips}
 
     out = {
         "metric": "TV-prox rows/s (fwd+bwd), 2^20 rows x len 32",
@@ -343,28 +409,41 @@ def main() -> int:
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
+        "warmup_steps_run": n_w,
+        "warmup_seconds": warm_s,
         "ms_per_step": ms_per_step,
+        "ms_per_step_batches": batch_ms,
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "timing": "value and ms_per_step: K replays of a HIP graph holding one step; per-call "
-                  "figures (roofline, plain_pair): K eager steps with events on the launch stream",
+        "timing": "value and ms_per_step: median over %d batches of K replays of a HIP graph holding one "
+                  "step, each batch between two synchronisations; per-call figures (roofline, "
+                  "plain_pair): mean over max(K, 100) eager steps with events on the launch stream; "
+                  "warm-up: W steps and on until %.1f s have passed" % (BATCHES, WARM_SECONDS),
         "config": {"workload": "config 3: 2^20 rows x 32 fp32 ([256,128,32,32] ~N(0,1), per-channel "
                                "lam log-uniform [1e-3,10]), tv1d_prox_fwd_ex (seg + ws) + tv1d_prox_bwd_seg",
                    "rows": n_rows, "length": W, "lam_slots": C},
-        # the method's 20 bytes per element over the time of the timed pair (which moves fewer)
-        "effective_gbs_fwd_bwd": (fwd_bytes + bwd_bytes) / ((fwd_ms + bwd_ms) * 1e-3) / 1e9,
-        "effective_frac_of_hbm_peak": (fwd_bytes + bwd_bytes) / ((fwd_ms + bwd_ms) * 1e-3) / 1e9 / HBM_PEAK_GBS,
-        "moved_gbs_fwd_bwd": (fwd_bytes + 8 * n_rows + bwd_seg_bytes) / ((fwd_ms + bwd_ms) * 1e-3) / 1e9,
-        # launch_us of the forward call includes its two small slot-order kernels
+        # two conventions, both over the replayed step's time: the bytes the timed pair really
+        # moves (16.5 per sample: the backward call reads 8-byte codes instead of x), and the
+        # method's 20 bytes per sample (read y, write x; read g_up and x, write grad_y), which
+        # credits the x that the code pair does not re-read
+        "moved_gbs_fwd_bwd": moved_bytes / (ms_per_step * 1e-3) / 1e9,
+        "moved_frac_of_hbm_peak": moved_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "effective_gbs_fwd_bwd": (fwd_bytes + bwd_bytes) / (ms_per_step * 1e-3) / 1e9,
+        "effective_frac_of_hbm_peak": (fwd_bytes + bwd_bytes) / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "roofline": {"kernel": "tv1d_fwd_short_kernel<32>", "bound": "hbm", "achieved": fwd_gbs,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": fwd_gbs / HBM_PEAK_GBS,
-                     "traffic": traffic, "launch_us": fwd_ms * 1e3,
-                     "launch_us_median": float(np.median(f_all)) * 1e3,
-                     "launch_us_min": float(min(f_all)) * 1e3,
-                     "algorithmic_bytes_per_launch": fwd_bytes},
+                     "traffic": traffic, "launch_us": ker_ms * 1e3,
+                     "launch_us_median": float(np.median(k_all)) * 1e3,
+                     "launch_us_min": float(min(k_all)) * 1e3,
+                     "algorithmic_bytes_per_launch": fwd_bytes,
+                     "note": "the kernel alone: events around tv1d_prox_fwd_ex with TV_FWD_ORDER_READY "
+                             "(the slot order of the call before is kept, so the call launches this one "
+                             "kernel); the full forward call, slot-order kernel included, is forward_call_us",
+                     "forward_call_us": fwd_ms * 1e3,
+                     "forward_call_us_median": float(np.median(f_all)) * 1e3},
         "valu_issue": alu,
         "roofline_bwd": {"kernel": "tv1d_bwd_short_kernel<32, SEG> + reduce_lambda_kernel",
                          "bound": "hbm", "achieved": bwd_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -405,6 +484,8 @@ def main() -> int:
         out["other_workloads"] = other_workloads(dev)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.cpu_sample_rows)
+        if not args.headline_only:
+            out["cpu_baseline_other_workloads"] = cpu_baseline_other()
     print(json.dumps(out))
     return 0
 

@@ -19,7 +19,11 @@ class tv_lambda(ctypes.Structure):
 
 
 class tv_fwd_extra(ctypes.Structure):
-    _fields_ = [("info", _vp), ("seg", _vp), ("ws", _vp), ("ws_bytes", ctypes.c_size_t)]
+    _fields_ = [("info", _vp), ("seg", _vp), ("ws", _vp), ("ws_bytes", ctypes.c_size_t),
+                ("flags", ctypes.c_uint32)]
+
+
+TV_FWD_ORDER_READY = 1
 
 
 class TVError(RuntimeError):
@@ -148,8 +152,8 @@ def tv1d_fwd_workspace_bytes(rows: tv_rows, lam: tv_lambda) -> int:
 
 
 def tv1d_prox_fwd_ex(y, x, rows: tv_rows, lam: tv_lambda, info=None, seg=None, ws=None,
-                     ws_bytes: int = 0, stream=None):
-    extra = tv_fwd_extra(_ptr(info), _ptr(seg), _ptr(ws), int(ws_bytes))
+                     ws_bytes: int = 0, stream=None, flags: int = 0):
+    extra = tv_fwd_extra(_ptr(info), _ptr(seg), _ptr(ws), int(ws_bytes), int(flags))
     _check(lib().tv1d_prox_fwd_ex(_ptr(y), _ptr(x), rows, lam, extra, _stream(stream)))
 
 

@@ -15,20 +15,14 @@
 
 namespace tvk {
 
-#ifndef TV_FWD_ATTR
-#define TV_FWD_ATTR
-#endif
-#ifndef TV_SHORT_WAVES
-#define TV_SHORT_WAVES 1
-#endif
-constexpr int kShortBlock = 64 * TV_SHORT_WAVES;   // waves per workgroup; waves never wait for each other
+constexpr int kShortBlock = 64;    // one wave per workgroup: waves never wait for each other
 
 template <int NMAX>
 struct ShortSmem {
     static constexpr int kPitch      = NMAX + 1;
     static constexpr int kTileFloats = 64 * kPitch;
     static constexpr int kTabFloats  = NMAX + 2;
-    static constexpr int kFloats     = (kShortBlock / 64) * kTileFloats + 2 * kTabFloats;
+    static constexpr int kFloats     = kTileFloats + 2 * kTabFloats;
 };
 
 // gtab[j] = j/(j+1): reciprocal Thomas pivot at position j of a free run (gtab[0] = 0
@@ -754,20 +748,19 @@ struct RowSolver {
 // PLANE (NMAX = 32, FULL, not PACKED, not WARM): the rows are the columns of contiguous 32 x 32 planes.
 // IO16 (NMAX = 32, FULL, PACKED, no addend / second output / residual): y and x are bf16.
 template <int NMAX, bool FULL, bool PACKED, bool WARM = false, bool PLANE = false, bool IO16 = false>
-__global__ __launch_bounds__(kShortBlock) TV_FWD_ATTR void tv1d_fwd_short_kernel(FwdParams p)
+__global__ __launch_bounds__(kShortBlock) void tv1d_fwd_short_kernel(FwdParams p)
 {
     using S = ShortSmem<NMAX>;
     __shared__ float smem[S::kFloats];
     const int lane = threadIdx.x & 63;
-    float *tile = smem + (threadIdx.x >> 6) * S::kTileFloats;
-    float *gtab = smem + (kShortBlock / 64) * S::kTileFloats;
+    float *tile = smem;
+    float *gtab = smem + S::kTileFloats;
     float *rtab = gtab + S::kTabFloats;
     fill_tables<NMAX>(gtab, rtab);
-    if (kShortBlock > 64) __syncthreads();      // tables are shared by the workgroup's waves
 
-    const uint32_t slot = p.order ? p.order[blockIdx.y] : blockIdx.y;
-    const uint32_t r0 = p.tm.first(
-        __builtin_amdgcn_readfirstlane(blockIdx.x * (kShortBlock / 64) + (threadIdx.x >> 6)), slot);
+    // (clamped: an order buffer that the caller declared ready may hold anything)
+    const uint32_t slot = p.order ? min(p.order[blockIdx.y], gridDim.y - 1u) : blockIdx.y;
+    const uint32_t r0 = p.tm.first(__builtin_amdgcn_readfirstlane(blockIdx.x), slot);
     const uint32_t row = p.tm.row(r0, lane);
     const bool valid = row < p.L.n_rows;
     const int n = FULL ? NMAX : p.L.n;
@@ -921,14 +914,13 @@ __global__ __launch_bounds__(kShortBlock) void tv1d_bwd_short_kernel(BwdParams p
     using S = ShortSmem<NMAX>;
     __shared__ float smem[S::kFloats];
     const int lane = threadIdx.x & 63;
-    float *tile = smem + (threadIdx.x >> 6) * S::kTileFloats;
-    float *gtab = smem + (kShortBlock / 64) * S::kTileFloats;
+    float *tile = smem;
+    float *gtab = smem + S::kTileFloats;
     float *rtab = gtab + S::kTabFloats;
     fill_tables<NMAX>(gtab, rtab);
-    if (kShortBlock > 64) __syncthreads();      // tables are shared by the workgroup's waves
 
     const TileMap tm = {6u, 0u, 0u, 1u};
-    const uint32_t r0 = (blockIdx.x * (kShortBlock / 64) + (threadIdx.x >> 6)) * 64u;
+    const uint32_t r0 = blockIdx.x * 64u;
     const uint32_t row = r0 + lane;
     const bool valid = row < p.L.n_rows;
     const int n = FULL ? NMAX : p.L.n;

@@ -136,10 +136,9 @@ int launch_fwd_short(const FwdParams &p, bool packed_ok, hipStream_t s, bool pla
     // ragged_ok: packed rows shorter than NMAX in natural order (any 4-byte alignment); rows of up
     // to 8 samples lie so close together that the plain per-lane accesses do as well
     ragged_ok = ragged_ok && NMAX >= 16 && !p.tm.grouped && p.L.n < NMAX;
-    constexpr uint32_t wpb = tvk::kShortBlock / 64;
+    static_assert(tvk::kShortBlock == 64, "one tile of 64 rows per workgroup");
     const uint32_t n_tiles = (p.L.n_rows + 63u) / 64u;
-    dim3 grid((n_tiles + wpb - 1) / wpb), block(tvk::kShortBlock);
-    static_assert(wpb == 1, "the grouped grid below assumes one tile per workgroup");
+    dim3 grid(n_tiles), block(tvk::kShortBlock);
     if (p.tm.grouped) grid = dim3(n_tiles / p.tm.count, p.tm.count);
     const bool full = p.L.n == NMAX;
     if constexpr (NMAX == 32) {
@@ -524,7 +523,7 @@ int run_fwd_multilevel(FwdParams p, const tv_lambda &l, int64_t n_rows, const Ml
 int run_fwd(const float *y, const float *addend, float *x, float *resid, int32_t *info,
             uint2 *seg, uint32_t *order_ws, const tv_rows &r, const tv_lambda &l, int64_t n_rows,
             hipStream_t s, float *x2 = nullptr, bool warm = false, char *ml_ws = nullptr, bool io16 = false,
-            bool thread_per_sample = false)
+            bool thread_per_sample = false, bool order_ready = false)
 {
     FwdParams p;
     p.y = y; p.addend = addend; p.x = x; p.x2 = x2; p.resid = resid; p.lam = l.lam; p.info = info;
@@ -546,7 +545,9 @@ int run_fwd(const float *y, const float *addend, float *x, float *resid, int32_t
         uint32_t *order = order_ws;
         const bool fast = r.length == 32 && p.tm.lg >= 1 && rows_packed(r) && aligned16(y) &&
                           (!addend || aligned16(addend));
-        if (fast)
+        if (order_ready) {
+            // the caller vouches that `order` holds what an earlier call left there
+        } else if (fast)
             hipLaunchKernelGGL(slot_order_kernel<true>, dim3(1), dim3(kOrderMaxSlots), 0, s, y, addend,
                                l.lam, p.L, p.tm, lgR, order, io16 ? 1u : 0u);
         else
@@ -798,7 +799,8 @@ int fwd_entry(const float *y, float *x, tv_rows rows, tv_lambda lam, const tv_fw
         order_ws = (uint32_t *)e.ws;
     }
     return run_fwd(y, nullptr, x, nullptr, e.info, reinterpret_cast<uint2 *>(e.seg), order_ws, rows,
-                   lam, n_rows, s, nullptr, false, (char *)e.ws);
+                   lam, n_rows, s, nullptr, false, (char *)e.ws, false, false,
+                   (e.flags & TV_FWD_ORDER_READY) != 0);
 }
 
 // Device address of `scratch` on the current device, resolved on the first call there.
@@ -879,13 +881,13 @@ const char *tv_status_str(int status)
 
 int tv1d_prox_fwd(const float *y, float *x, tv_rows rows, tv_lambda lam, hipStream_t stream)
 {
-    return fwd_entry(y, x, rows, lam, tv_fwd_extra{nullptr, nullptr, nullptr, 0}, stream);
+    return fwd_entry(y, x, rows, lam, tv_fwd_extra{nullptr, nullptr, nullptr, 0, 0}, stream);
 }
 
 int tv1d_prox_fwd_info(const float *y, float *x, int32_t *info, tv_rows rows, tv_lambda lam,
                        hipStream_t stream)
 {
-    return fwd_entry(y, x, rows, lam, tv_fwd_extra{info, nullptr, nullptr, 0}, stream);
+    return fwd_entry(y, x, rows, lam, tv_fwd_extra{info, nullptr, nullptr, 0, 0}, stream);
 }
 
 int tv1d_prox_fwd_seg(const float *y, float *x, uint64_t *seg, tv_rows rows, tv_lambda lam,
@@ -896,7 +898,7 @@ int tv1d_prox_fwd_seg(const float *y, float *x, uint64_t *seg, tv_rows rows, tv_
         if (check_lambda(lam) == TV_OK && check_rows(rows, &n_rows) == TV_OK && n_rows > 0)
             return TV_ERR_NULL;
     }
-    return fwd_entry(y, x, rows, lam, tv_fwd_extra{nullptr, seg, nullptr, 0}, stream);
+    return fwd_entry(y, x, rows, lam, tv_fwd_extra{nullptr, seg, nullptr, 0, 0}, stream);
 }
 
 int tv1d_prox_fwd_ex(const float *y, float *x, tv_rows rows, tv_lambda lam, tv_fwd_extra extra,

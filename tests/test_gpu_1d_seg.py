@@ -146,3 +146,41 @@ def test_ordered_many_slots_small_groups(shape):
     yr, gr = rows_view(y, -1), rows_view(g, -1)
     check_batch(yr, lam_per_row(lam, len(yr), shape[2]), gr, rows_view(ref["x"], -1), rows_view(ref["gy"], -1),
                 gl_gpu=ref["gl"], lam_count=shape[1], lam_div=shape[2], label="slots %s" % (shape,))
+
+
+def test_forward_with_a_kept_slot_order():
+    """TV_FWD_ORDER_READY: the call uses whatever order its workspace holds.  The order an earlier
+    call left there, the reverse of it and a buffer of numbers that are no slots at all (clamped
+    by the kernel) all give the same bits: the order only decides who works on what when."""
+    import torch
+
+    import paper_2204_03643_amd as tv
+
+    y, lam, g = workloads.config3(B=6, C=128)
+    dev = torch.device("cuda:0")
+    yt, lt = torch.from_numpy(y).to(dev), torch.from_numpy(lam).to(dev)
+    rows, L = tv.rows_along(y.shape, -1), tv.tv_lambda(lt.data_ptr(), lt.numel(), 32)
+    wsb = tv.tv1d_fwd_workspace_bytes(rows, L)
+    assert wsb >= 4 * 128
+    ws = torch.zeros(wsb, dtype=torch.uint8, device=dev)
+    n_rows = y.size // 32
+    ref, seg_ref = torch.empty_like(yt), torch.zeros(n_rows, dtype=torch.int64, device=dev)
+    tv.tv1d_prox_fwd_ex(yt, ref, rows, L, seg=seg_ref, ws=ws, ws_bytes=wsb)
+    torch.cuda.synchronize()
+    order = ws.view(torch.int32)[:128].clone()
+    assert sorted(order.tolist()) == list(range(128))
+    for new_order in (order, order.flip(0), torch.arange(128, dtype=torch.int32, device=dev)):
+        ws.view(torch.int32)[:128] = new_order
+        x, seg = torch.full_like(yt, float("nan")), torch.zeros_like(seg_ref)
+        tv.tv1d_prox_fwd_ex(yt, x, rows, L, seg=seg, ws=ws, ws_bytes=wsb, flags=tv.TV_FWD_ORDER_READY)
+        torch.cuda.synchronize()
+        assert torch.equal(ws.view(torch.int32)[:128], new_order)        # not recomputed
+        assert torch.equal(x, ref) and torch.equal(seg, seg_ref)
+    # entries beyond the slot count are clamped: the rows of the slots left out stay untouched,
+    # the rest is as before, and nothing is read or written out of bounds
+    ws.fill_(0xff)
+    x = torch.full_like(yt, float("nan"))
+    tv.tv1d_prox_fwd_ex(yt, x, rows, L, ws=ws, ws_bytes=wsb, flags=tv.TV_FWD_ORDER_READY)
+    torch.cuda.synchronize()
+    xs, rs = x.reshape(6, 128, 32, 32), ref.reshape(6, 128, 32, 32)
+    assert torch.equal(xs[:, 127], rs[:, 127]) and bool(torch.isnan(xs[:, :127]).all())
