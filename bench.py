@@ -223,6 +223,53 @@ def other_workloads(dev, reps: int = 25):
     return out
 
 
+def long_probe(dev) -> int:
+    """Every long-row kernel of workloads 4 and 5, three launches each, for profiler runs."""
+    import numpy as np
+    import torch
+
+    import paper_2204_03643_amd as tv
+    import workloads
+
+    def one_d(y, lam, g, axis, lam_div, with_ws):
+        yt, lt, gt = (torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(dev)
+                      for a in (y, np.asarray(lam).ravel(), g))
+        xt, gy, gl = torch.empty_like(yt), torch.empty_like(yt), torch.empty_like(lt)
+        rows = tv.rows_along(y.shape, axis)
+        L = tv.tv_lambda(lt.data_ptr(), lt.numel(), lam_div)
+        wsb = tv.tv1d_bwd_workspace_bytes(rows, L)
+        ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device=dev)
+        fwsb = tv.tv1d_fwd_workspace_bytes(rows, L) if with_ws else 0
+        fws = torch.empty(max(fwsb, 16), dtype=torch.uint8, device=dev)
+        for _ in range(3):
+            tv.tv1d_prox_fwd(yt, xt, rows, L)
+            if fwsb:
+                tv.tv1d_prox_fwd_ex(yt, xt, rows, L, ws=fws, ws_bytes=fwsb)
+            tv.tv1d_prox_bwd(gt, xt, gy, gl, rows, L, ws, wsb)
+            gy.copy_(gt)                        # plain copy of known size: scale for FETCH / WRITE_SIZE
+        torch.cuda.synchronize()
+
+    y, lam, g = workloads.config4()
+    one_d(y, lam, g, -1, 1, False)
+    one_d(y, lam, g, -2, 1, False)
+    H, W = y.shape[-2:]
+    planes = y.size // (H * W)
+    yt, lt, gt = (torch.from_numpy(a).to(dev) for a in (y, lam, g))
+    xt, gy, gl = torch.empty_like(yt), torch.empty_like(yt), torch.empty_like(lt)
+    L = tv.tv_lambda(lt.data_ptr(), lt.numel(), 1)
+    wsb = tv.tv2d_workspace_bytes(planes, H, W, 10)
+    ws = torch.empty(wsb, dtype=torch.uint8, device=dev)
+    for _ in range(3):
+        tv.tv2d_prox_fwd(yt, xt, planes, H, W, L, 10, ws, wsb)
+        tv.tv2d_prox_bwd(gt, gy, gl, planes, H, W, L, 10, ws, wsb)
+    torch.cuda.synchronize()
+    del yt, gt, xt, gy, ws
+    torch.cuda.empty_cache()
+    y, lam, g = workloads.config5()
+    one_d(y, lam, g, -1, 1, True)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -234,6 +281,10 @@ def main() -> int:
     ap.add_argument("--traffic-probe", action="store_true",
                     help="run fwd, bwd and a plain copy of the same tensor three times each and "
                          "exit (for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs)")
+    ap.add_argument("--long-probe", action="store_true",
+                    help="run the long-row kernels of workloads 4 and 5 three times each (single passes, "
+                         "the forward call of workload 5 with and without its workspace, the 2D call with "
+                         "K = 10) plus a plain copy, and exit (for rocprofv3 runs)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (rows are independent and would shard by "
@@ -250,6 +301,8 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
     dev = torch.device("cuda:0")
+    if args.long_probe:
+        return long_probe(dev)
     y, lam, g = workloads.config3()
     B, C, H, W = y.shape
     n_rows, n_elem = B * C * H, y.size
