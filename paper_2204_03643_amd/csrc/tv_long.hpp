@@ -63,6 +63,24 @@ struct LongMap {
 // A thread's C contiguous samples k0 .. k0 + C - 1 of a row (zero past the end).  With unit
 // stride and 16-byte alignment they move as float4: a wave then touches every cache line of
 // its 64 * C samples C / 4 times instead of C times.
+// Which group of G rows a workgroup of a strided launch works on.  Workgroups go to the 8 XCDs
+// round-robin in launch order, and each XCD has its own L2.  The G adjacent columns of a
+// workgroup are 4 G bytes of every image row, a part of a 128-byte line (half of it for G = 16);
+// with the identity mapping the other parts belong to the next workgroups, which run on other
+// XCDs, so several L2s fetch the whole line (measured with G = 16: twice the algorithmic bytes on
+// the read side).  Here the SH = 32 / G workgroups b, b + 8, ..., which the same XCD starts one
+// after the other, take the SH neighbouring groups that share a line.
+template <int G>
+__device__ __forceinline__ uint32_t xcd_grouped(uint32_t b, uint32_t n_groups)
+{
+    constexpr uint32_t SH = G >= 32 ? 1u : 32u / (uint32_t)G;     // groups per 128-byte line
+    if (SH == 1u) return b;
+    const uint32_t base = b - b % (8u * SH);
+    if (base + 8u * SH > n_groups) return b;        // the ragged end keeps the launch order
+    const uint32_t x = b & 7u, s = (b >> 3) % SH;
+    return base + SH * x + s;
+}
+
 template <int C>
 __device__ __forceinline__ bool chunk_vec_ok(const void *base, int64_t off, int64_t es, int k0)
 {
@@ -395,7 +413,8 @@ __global__ __launch_bounds__(T *G, (T * G == 512 && !COLS) ? 4 : ((XPOSE && C <=
 #define TV_EX(q, tt) sm.ex[q][j][(tt) + 1]
 #define TV_PB(c, q, tt) sm.buf[(((c) * 3 + (q)) * G + j) * T + (tt)]
 
-    const uint32_t row = blockIdx.x * G + j;
+    const uint32_t group = COLS ? xcd_grouped<G>(blockIdx.x, gridDim.x) : blockIdx.x;
+    const uint32_t row = group * G + j;
     bool rvalid = row < p.L.n_rows;
     bool from_coarse = false;
     if (p.ml_flag && rvalid) {
@@ -422,7 +441,7 @@ __global__ __launch_bounds__(T *G, (T * G == 512 && !COLS) ? 4 : ((XPOSE && C <=
     float y[C];
     // transposing variant: thread tid moves samples k = tid / G, tid / G + T, ... of row tid % G
     const int xj = tid % G, xk0 = tid / G;
-    const uint32_t xrow = blockIdx.x * G + xj;
+    const uint32_t xrow = group * G + xj;
     const int64_t xoff = (XPOSE && xrow < p.L.n_rows) ? row_offset(p.L, xrow) : 0;
     // Warm start: the addend is D^T u of an earlier solve of nearly the same rows, so
     // u_k = -(addend_0 + .. + addend_k).  u first takes the negated running sums inside the
@@ -887,7 +906,8 @@ __global__ __launch_bounds__(T *G, (T * G == 1024 && !COLS && !HAS_SUB) ? 8 : 1)
     const int tid = threadIdx.x;
     const int j = Mp::row_of(tid), t = Mp::t_of(tid);
 #define TV_EX(q, tt) sm.ex[q][j][(tt) + 1]
-    const uint32_t row = blockIdx.x * G + j;
+    const uint32_t group = COLS ? xcd_grouped<G>(blockIdx.x, gridDim.x) : blockIdx.x;
+    const uint32_t row = group * G + j;
     const bool rvalid = row < p.L.n_rows;
     const int n = p.L.n;
     const int k0 = t * C;
@@ -900,7 +920,7 @@ __global__ __launch_bounds__(T *G, (T * G == 1024 && !COLS && !HAS_SUB) ? 8 : 1)
 
     // transposing variant: thread tid moves samples k = tid / G, tid / G + T, ... of row tid % G
     const int xj = tid % G, xk0 = tid / G;
-    const uint32_t xrow = blockIdx.x * G + xj;
+    const uint32_t xrow = group * G + xj;
     const bool xvalid = XPOSE && xrow < p.L.n_rows;
     const int64_t xoff = xvalid ? row_offset(p.L, xrow) : 0;
     // every global load is issued before the first trip through the tile
