@@ -136,6 +136,27 @@ int tv1d_prox_fwd_ex(const float *y, float *x, tv_rows rows, tv_lambda lam, tv_f
 size_t tv1d_fwd_workspace_bytes(tv_rows rows, tv_lambda lam);
 
 /*
+ * A test instrument: tv1d_prox_fwd_info from the cold start that, for the first record_rows
+ * rows, also writes a record of the projected-Newton iteration itself (paper Eq. 3-4), so that a
+ * single Newton step and the descent of the dual objective can be checked from outside:
+ * tv1d_fwd_steps_floats_per_row(length) floats per row, record r at record + r * that many,
+ *   [0] Newton steps recorded, [1] lambda as used, [2] the info word,
+ *   [8 + i], i = 0 .. [0] (at most 40 entries): the dual objective f(u) = 1/2 ||y - D^T u||^2 at
+ *        the starting point and after every accepted step,
+ *   [48 + k], k < length - 1: the dual u the first iteration starts from,
+ *   [48 + length + k]: the Newton direction d of the first iteration (the solution of
+ *        H_SS d_S = grad_S on the free set S, 0 on the bound duals; the step is clip(u - alpha d)),
+ *   [48 + 2 length + k]: 1 where the first iteration holds dual k on its bound, else 0.
+ * Rows of up to 32 samples run the general row-per-lane kernel; longer rows (unit element stride
+ * only: TV_ERR_UNSUPPORTED otherwise) one of three mappings: a wavefront per row up to 512
+ * samples, a workgroup of 256 threads up to 4096, of 1024 threads beyond.  Slower than
+ * tv1d_prox_fwd; x and info are what that call returns up to rounding order.
+ */
+size_t tv1d_fwd_steps_floats_per_row(int64_t length);
+int tv1d_prox_fwd_steps(const float *y, float *x, int32_t *info, float *record, int64_t record_rows,
+                        tv_rows rows, tv_lambda lam, hipStream_t stream);
+
+/*
  * Backward of tv1d_prox_fwd (paper Eq. 5-6, evaluated as segment averaging).
  *   g_up:     upstream gradient dL/dx, laid out like x.
  *   x:        the OUTPUT of tv1d_prox_fwd for the same rows and lam.

@@ -50,6 +50,10 @@ def lib() -> ctypes.CDLL:
         L.tv1d_prox_fwd.restype = ctypes.c_int
         L.tv1d_prox_fwd_info.argtypes = [_vp, _vp, _vp, tv_rows, tv_lambda, _vp]
         L.tv1d_prox_fwd_info.restype = ctypes.c_int
+        L.tv1d_fwd_steps_floats_per_row.argtypes = [_i64]
+        L.tv1d_fwd_steps_floats_per_row.restype = ctypes.c_size_t
+        L.tv1d_prox_fwd_steps.argtypes = [_vp, _vp, _vp, _vp, _i64, tv_rows, tv_lambda, _vp]
+        L.tv1d_prox_fwd_steps.restype = ctypes.c_int
         L.tv1d_prox_bwd.argtypes = [_vp, _vp, _vp, _vp, tv_rows, tv_lambda, _vp, ctypes.c_size_t, _vp]
         L.tv1d_prox_bwd.restype = ctypes.c_int
         L.tv1d_prox_bwd_noalloc.argtypes = [_vp, _vp, _vp, _vp, tv_rows, tv_lambda, _vp]
@@ -126,6 +130,15 @@ def tv1d_prox_fwd(y, x, rows: tv_rows, lam: tv_lambda, stream=None):
 
 def tv1d_prox_fwd_info(y, x, info, rows: tv_rows, lam: tv_lambda, stream=None):
     _check(lib().tv1d_prox_fwd_info(_ptr(y), _ptr(x), _ptr(info), rows, lam, _stream(stream)))
+
+
+def tv1d_fwd_steps_floats_per_row(length: int) -> int:
+    return int(lib().tv1d_fwd_steps_floats_per_row(int(length)))
+
+
+def tv1d_prox_fwd_steps(y, x, info, record, record_rows: int, rows: tv_rows, lam: tv_lambda, stream=None):
+    _check(lib().tv1d_prox_fwd_steps(_ptr(y), _ptr(x), _ptr(info), _ptr(record), int(record_rows), rows, lam,
+                                     _stream(stream)))
 
 
 def tv1d_bwd_workspace_bytes(rows: tv_rows, lam: tv_lambda) -> int:

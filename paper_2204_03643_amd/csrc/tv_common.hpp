@@ -89,6 +89,18 @@ constexpr float kWarmSnap = 1.0f + 1.0f / 4096.0f;
 // Multilevel start of long rows: a level averages groups of this many samples of the level below.
 constexpr int kMlFactor = 4;
 
+// Step record of one row, written by the DEBUG variants of the forward kernels for the first
+// debug_rows rows of a call (a test instrument: it lets a test check one Newton step, paper
+// Eq. 4, and the descent of the dual objective, paper Eq. 3, from outside).  Floats:
+//   [0] Newton steps recorded, [1] lambda as used, [2] the info word;
+//   [kRecF + i], i = 0 .. [0]: the dual objective f = 1/2 ||x(u)||^2 at the start and after
+//        every accepted step (at most kRecMaxF entries; later ones are dropped);
+//   [kRecU + k], k < n - 1: the dual the first iteration starts from;
+//   [kRecU + n + k]: the Newton direction d of the first iteration (u <- clip(u - alpha d));
+//   [kRecU + 2n + k]: 1 where the first iteration holds dual k on its bound, else 0.
+constexpr int kRecF = 8, kRecMaxF = 40, kRecU = 48;
+__host__ __device__ constexpr int64_t step_record_floats(int64_t n) { return kRecU + 3 * n; }
+
 // Segment code of a row of n <= 32 samples: .x bit k is set when x[k+1] != x[k] (a jump after
 // sample k), .y bit k when x[k+1] > x[k].  It carries everything the backward pass reads from x.
 struct FwdParams {
@@ -111,6 +123,9 @@ struct FwdParams {
     const uint32_t *ml_flag; // optional, per row: 0 = this row takes no part in the multilevel start
     uint32_t     ml_skip;  // rows with ml_flag == 0 are not solved at all (the launch is a coarse level)
     float        lam_scale; // lambda of this launch = lam[slot] * lam_scale (1 / kMlFactor per level)
+    // step record (kernel variants with DEBUG only; see StepRecord):
+    float       *debug;     // debug_rows records of step_record_floats(L.n) floats
+    uint32_t     debug_rows;
     Layout       L;
     TileMap      tm;       // row-per-lane kernels only
 };

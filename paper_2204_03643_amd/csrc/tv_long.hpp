@@ -389,7 +389,8 @@ struct LongSmemBwd {
 // the dual of the same row averaged in groups of kMlFactor samples (p.coarse_u), which a launch
 // on the averaged rows with lambda / kMlFactor left behind (p.dual_out of that launch).
 // (512-thread workgroups ask for 4 waves per SIMD, i.e. at most 128 VGPRs, so that a CU holds two.)
-template <int T, int C, int G, bool COLS, bool XPOSE = false, int WARM = 0>
+// DEBUG: the first p.debug_rows rows leave a step record in p.debug (see step_record_floats).
+template <int T, int C, int G, bool COLS, bool XPOSE = false, int WARM = 0, bool DEBUG = false>
 __global__ __launch_bounds__(T *G, (T * G == 512 && !COLS) ? 4 : ((XPOSE && C <= 4) ? 8 : 1)) void tv1d_fwd_long_kernel(FwdParams p)
 {
     static_assert(!XPOSE || (COLS && T <= 64), "the transposing variant is for strided rows inside one wave");
@@ -612,6 +613,13 @@ __global__ __launch_bounds__(T *G, (T * G == 512 && !COLS) ? 4 : ((XPOSE && C <=
     bool prev_unclipped = false;
     int steps = 0, flags = 0;
     int par = 0;
+    float *rec = nullptr;
+    if constexpr (DEBUG) {
+        if (rvalid && row < p.debug_rows) {
+            rec = p.debug + (size_t)row * step_record_floats(n);
+            if (t == 0) { rec[0] = 0.f; rec[1] = lam; rec[kRecF] = fcur; }
+        }
+    }
 
     for (int it = 0;; ++it) {
         // ---- chunk edges of the dual: exchanged by the accepted trial of the step before
@@ -744,6 +752,17 @@ __global__ __launch_bounds__(T *G, (T * G == 512 && !COLS) ? 4 : ((XPOSE && C <=
             decp = fmaf(g[C - 1], sigma, decp);
         }
 
+        if constexpr (DEBUG) {
+            if (rec && it == 0) {
+#pragma unroll
+                for (int i = 0; i < C; ++i)
+                    if (i < nvd) {
+                        rec[kRecU + k0 + i] = u[i];
+                        rec[kRecU + n + k0 + i] = w[i];
+                        rec[kRecU + 2 * n + k0 + i] = ((i < C - 1) ? (gam[i] == 0.f) : bsep) ? 1.f : 0.f;
+                    }
+            }
+        }
         // ---- projected step with Armijo backtracking (quadratic interpolation)
         float alpha = active ? 1.f : 0.f;
         float uc[C];
@@ -795,6 +814,12 @@ __global__ __launch_bounds__(T *G, (T * G == 512 && !COLS) ? 4 : ((XPOSE && C <=
         for (int i = 0; i < C; ++i) u[i] = uc[i];
         prev_unclipped = (alpha == 1.f) && !clipped;
         if (active) fcur = fc;
+        if constexpr (DEBUG) {
+            if (rec && t == 0 && active && alpha > 0.f) {
+                const int c = (int)rec[0] + 1;
+                if (c < kRecMaxF) { rec[kRecF + c] = fc; rec[0] = (float)c; }
+            }
+        }
         if (active && !changed) { active = false; flags = kInfoStalled; }
         if (Mp::SOLO) { if (!active) break; }
         else if (!Mp::sync_any(active)) break;
@@ -882,6 +907,9 @@ __global__ __launch_bounds__(T *G, (T * G == 512 && !COLS) ? 4 : ((XPOSE && C <=
         }
     }
     if (p.info && rvalid && t == 0) p.info[row] = steps | flags;
+    if constexpr (DEBUG) {
+        if (rec && t == 0) rec[2] = (float)(steps | flags);
+    }
 #undef TV_EX
 #undef TV_PB
 #undef TV_LK
@@ -1132,6 +1160,24 @@ inline hipError_t launch_bwd_long_t(const BwdParams &p, hipStream_t s)
 inline hipError_t launch_fwd_long(const FwdParams &p, hipStream_t s)
 {
     TV_LONG_DISPATCH(launch_fwd_long_t, p, s);
+}
+
+// The forward launch with step records (cold start, unit-stride rows): one mapping of each kind
+// -- rows inside a wave (wave-level fences, PCR over the wave's separators), and a workgroup per
+// row with 256 and with 1024 threads (workgroup barriers, PCR in LDS across waves).
+inline hipError_t launch_fwd_long_debug(const FwdParams &p, hipStream_t s)
+{
+    const int n = p.L.n;
+    if (n <= 512)
+        hipLaunchKernelGGL((tv1d_fwd_long_kernel<64, 8, 4, false, false, 0, true>), dim3((p.L.n_rows + 3) / 4),
+                           dim3(256), 0, s, p);
+    else if (n <= 4096)
+        hipLaunchKernelGGL((tv1d_fwd_long_kernel<256, 16, 1, false, false, 0, true>), dim3(p.L.n_rows), dim3(256), 0,
+                           s, p);
+    else
+        hipLaunchKernelGGL((tv1d_fwd_long_kernel<1024, 16, 1, false, false, 0, true>), dim3(p.L.n_rows), dim3(1024),
+                           0, s, p);
+    return hipGetLastError();
 }
 
 inline hipError_t launch_bwd_long(const BwdParams &p, hipStream_t s)

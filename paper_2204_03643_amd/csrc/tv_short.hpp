@@ -463,8 +463,9 @@ __device__ __forceinline__ void row_store_strided(float *__restrict__ dst, int64
 // after the start and is parked in LDS, sample-major: yl[k * 64] is sample k of this lane's
 // row (consecutive lanes -> consecutive banks).  Samples k >= n must be 0.
 // ---------------------------------------------------------------------------------
-template <int NMAX, bool FULL>
+template <int NMAX, bool FULL, bool DEBUG = false>
 struct RowSolver {
+    float *rec = nullptr;                   // DEBUG: this row's step record, or null
     static constexpr int M = NMAX - 1;
     static constexpr int MA = M > 0 ? M : 1;
 
@@ -644,6 +645,18 @@ struct RowSolver {
                 D[k] = dn;
             }
         }
+        if constexpr (DEBUG) {
+            if (rec && it == 0) {
+                rec[kRecF] = fcur;
+#pragma unroll
+                for (int k = 0; k < M; ++k)
+                    if (FULL || k < m) {
+                        rec[kRecU + k] = u[k];
+                        rec[kRecU + (m + 1) + k] = D[k];
+                        rec[kRecU + 2 * (m + 1) + k] = G[k] == 0.f ? 1.f : 0.f;
+                    }
+            }
+        }
         // ---- projected step u(alpha) = clip(u - alpha d); alpha = 1 is taken outright when
         //      nothing clips (it is the exact minimiser over the free subspace), otherwise it
         //      must pass the Armijo test (paper Sec. 3.2).  The trial moves the previous dual
@@ -692,6 +705,12 @@ struct RowSolver {
                 alpha_try = fminf(fmaxf(an, 0.1f * alpha), 0.5f * alpha);
                 prev_unclipped = false;
                 if (++nfail > kMaxBacktracks) { active = false; flags = kInfoStalled | kInfoPlain; }
+            }
+        }
+        if constexpr (DEBUG) {
+            if (rec && ok && active) {
+                const int c = (int)rec[0] + 1;
+                if (c < kRecMaxF) { rec[kRecF + c] = fc; rec[0] = (float)c; }
             }
         }
         if (ok && active) {
@@ -747,7 +766,9 @@ struct RowSolver {
 // WARM: p.addend is given and the solve starts from the dual it encodes (see start_warm).
 // PLANE (NMAX = 32, FULL, not PACKED, not WARM): the rows are the columns of contiguous 32 x 32 planes.
 // IO16 (NMAX = 32, FULL, PACKED, no addend / second output / residual): y and x are bf16.
-template <int NMAX, bool FULL, bool PACKED, bool WARM = false, bool PLANE = false, bool IO16 = false>
+// DEBUG: the first p.debug_rows rows leave a step record in p.debug (see step_record_floats).
+template <int NMAX, bool FULL, bool PACKED, bool WARM = false, bool PLANE = false, bool IO16 = false,
+          bool DEBUG = false>
 __global__ __launch_bounds__(kShortBlock) void tv1d_fwd_short_kernel(FwdParams p)
 {
     using S = ShortSmem<NMAX>;
@@ -776,7 +797,13 @@ __global__ __launch_bounds__(kShortBlock) void tv1d_fwd_short_kernel(FwdParams p
     }
 
     float y[NMAX], xs[NMAX];
-    RowSolver<NMAX, FULL> sv;
+    RowSolver<NMAX, FULL, DEBUG> sv;
+    if constexpr (DEBUG) {
+        if (valid && row < p.debug_rows) {
+            sv.rec = p.debug + (size_t)row * step_record_floats(n);
+            sv.rec[0] = 0.f; sv.rec[1] = lam;
+        }
+    }
     if constexpr (PLANE) {
         // (no warm-start variant: the solver's bound masks already fill the scalar registers, the
         // extra pointers of a warm pass spill them, and the spill costs a wave of occupancy)
@@ -880,6 +907,9 @@ __global__ __launch_bounds__(kShortBlock) void tv1d_fwd_short_kernel(FwdParams p
         if (want_resid) row_store_strided<NMAX, FULL>(p.resid, off, p.L.elem_stride, n, valid, rs);
     }
     if (p.info && valid) p.info[row] = sv.steps | sv.flags;
+    if constexpr (DEBUG) {
+        if (sv.rec) sv.rec[2] = (float)(sv.steps | sv.flags);
+    }
     if (p.seg) {
         // built from the highest dual down, one shift-in per dual, so that bit k ends up at
         // position k.  d = x[k] - x[k+1] is +0 exactly inside a segment (its samples are

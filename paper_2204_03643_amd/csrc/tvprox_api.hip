@@ -532,6 +532,7 @@ int run_fwd(const float *y, const float *addend, float *x, float *resid, int32_t
     p.warm = (warm && addend) ? 1u : 0u;
     p.coarse_u = nullptr; p.coarse_n = 0; p.dual_out = nullptr; p.ml_flag = nullptr; p.ml_skip = 0;
     p.lam_scale = 1.0f;
+    p.debug = nullptr; p.debug_rows = 0;
     p.L = make_layout(r, l, n_rows);
     p.tm = make_tile_map(l, n_rows);
     // (a few thousand short rows at most: a few threads per row instead of a lane per row; the 2D
@@ -905,6 +906,47 @@ int tv1d_prox_fwd_ex(const float *y, float *x, tv_rows rows, tv_lambda lam, tv_f
                      hipStream_t stream)
 {
     return fwd_entry(y, x, rows, lam, extra, stream);
+}
+
+size_t tv1d_fwd_steps_floats_per_row(int64_t length)
+{
+    return length >= 1 && length <= TV_MAX_LENGTH ? (size_t)tvk::step_record_floats(length) : 0;
+}
+
+int tv1d_prox_fwd_steps(const float *y, float *x, int32_t *info, float *record, int64_t record_rows,
+                        tv_rows rows, tv_lambda lam, hipStream_t stream)
+{
+    int st = check_lambda(lam);
+    if (st != TV_OK) return st;
+    int64_t n_rows;
+    st = check_rows(rows, &n_rows);
+    if (st != TV_OK) return st;
+    if (record_rows < 0) return TV_ERR_SHAPE;
+    if (n_rows == 0) return TV_OK;
+    if (!y || !x || !lam.lam || (record_rows > 0 && !record)) return TV_ERR_NULL;
+    if (rows.length > TV_MAX_LENGTH) return TV_ERR_UNSUPPORTED;
+    if (rows.length > 32 && rows.elem_stride != 1) return TV_ERR_UNSUPPORTED;
+    FwdParams p;
+    p.y = y; p.addend = nullptr; p.x = x; p.x2 = nullptr; p.resid = nullptr; p.lam = lam.lam; p.info = info;
+    p.seg = nullptr; p.order = nullptr; p.io16 = 0; p.warm = 0;
+    p.coarse_u = nullptr; p.coarse_n = 0; p.dual_out = nullptr; p.ml_flag = nullptr; p.ml_skip = 0;
+    p.lam_scale = 1.0f;
+    p.debug = record;
+    p.debug_rows = (uint32_t)(record_rows < n_rows ? record_rows : n_rows);
+    p.L = make_layout(rows, lam, n_rows);
+    p.tm = tvk::TileMap{6u, 0u, 0u, 1u};
+    if (rows.length <= 32) {
+        // the general variant of the row-per-lane kernel (any length up to 32, any strides)
+        const dim3 grid((uint32_t)((n_rows + 63) / 64)), block(tvk::kShortBlock);
+        if (rows.length == 32)
+            hipLaunchKernelGGL((tvk::tv1d_fwd_short_kernel<32, true, false, false, false, false, true>), grid, block, 0,
+                               stream, p);
+        else
+            hipLaunchKernelGGL((tvk::tv1d_fwd_short_kernel<32, false, false, false, false, false, true>), grid, block, 0,
+                               stream, p);
+        return launch_status();
+    }
+    return tvk::launch_fwd_long_debug(p, stream) == hipSuccess ? TV_OK : TV_ERR_HIP;
 }
 
 size_t tv1d_fwd_workspace_bytes(tv_rows rows, tv_lambda lam)

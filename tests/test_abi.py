@@ -92,6 +92,18 @@ def test_noalloc_backward_validation():
     assert "scratch" in tv.status_str(8)
 
 
+def test_step_record_validation():
+    L = tv.lib()
+    lam = tv.tv_lambda(FAKE, 1, 1)
+    assert tv.tv1d_fwd_steps_floats_per_row(32) == 48 + 96
+    assert tv.tv1d_fwd_steps_floats_per_row(0) == 0 and tv.tv1d_fwd_steps_floats_per_row(16385) == 0
+    rows = tv.tv_rows(4, 64, 1, 1, 64, 1)
+    assert L.tv1d_prox_fwd_steps(FAKE, FAKE, None, None, 2, rows, lam, None) == 1        # no record buffer
+    assert L.tv1d_prox_fwd_steps(FAKE, FAKE, None, FAKE, -1, rows, lam, None) == 2
+    assert L.tv1d_prox_fwd_steps(FAKE, FAKE, None, FAKE, 2, tv.rows_along((64, 4), 0), lam, None) == 6   # strided long rows
+    assert L.tv1d_prox_fwd_steps(None, None, None, None, 0, tv.tv_rows(0, 64, 1, 1, 64, 1), lam, None) == 0
+
+
 def test_seg_pair_validation():
     L = tv.lib()
     rows = tv.tv_rows(4, 32, 1, 1, 32, 1)
