@@ -510,7 +510,9 @@ struct RowSolver {
         float sum = 0.f, ymax = 0.f;
 #pragma unroll
         for (int k = 0; k < NMAX; ++k) { sum += y[k]; ymax = fmaxf(ymax, fabsf(y[k])); }
-        gtol = kGradNoise * (ymax + lam);     // rounding floor of a difference of two x values
+        // rounding floor of a difference of two x values (lambda = 0: the box is a point, every dual
+        // sits on both of its bounds, and no gradient entry may count as pointing inwards)
+        gtol = lam > 0.f ? kGradNoise * (ymax + lam) : __builtin_inff();
         const float ybar = sum * inv_n;
         float run = 0.f, rmax = 0.f;
 #pragma unroll
@@ -581,7 +583,7 @@ struct RowSolver {
         float ymax = 0.f;
 #pragma unroll
         for (int k = 0; k < NMAX; ++k) ymax = fmaxf(ymax, fabsf(y[k]));
-        gtol = kGradNoise * (ymax + lam);
+        gtol = lam > 0.f ? kGradNoise * (ymax + lam) : __builtin_inff();
 #pragma unroll
         for (int k = 0; k < M; ++k) {
             const float l = lk(k);

@@ -35,6 +35,7 @@ class _Prox1d(torch.autograd.Function):
     @staticmethod
     def forward(ctx, y, lam, axis, lam_div):
         y = _check_input(y, "tv prox 1d")
+        ctx.lam_shape = lam.shape                  # the gradient goes back in the caller's shape
         lam = _check_input(lam, "tv prox 1d (lambda)").reshape(-1)
         rows = _b.rows_along(tuple(y.shape), axis)
         L = _b.tv_lambda(lam.data_ptr(), lam.numel(), int(lam_div))
@@ -49,7 +50,6 @@ class _Prox1d(torch.autograd.Function):
             seg = torch.empty(max(n_rows, 1), dtype=torch.int64, device=y.device)
         _b.tv1d_prox_fwd_ex(y, x, rows, L, seg=seg, ws=ws if wsb else None, ws_bytes=wsb)
         ctx.rows, ctx.lam_count, ctx.lam_div = rows, lam.numel(), int(lam_div)
-        ctx.lam_shape = lam.shape
         if seg is not None:
             ctx.save_for_backward(seg, lam)
             ctx.has_seg = True
@@ -82,6 +82,7 @@ class _Prox2d(torch.autograd.Function):
     @staticmethod
     def forward(ctx, y, lam, sweeps):
         y = _check_input(y, "tv prox 2d")
+        ctx.lam_shape = lam.shape                  # the gradient goes back in the caller's shape
         lam = _check_input(lam, "tv prox 2d (lambda)").reshape(-1)
         H, W = int(y.shape[-2]), int(y.shape[-1])
         planes = y.numel() // (H * W) if H * W else 0
@@ -91,7 +92,6 @@ class _Prox2d(torch.autograd.Function):
         x = torch.empty_like(y)
         _b.tv2d_prox_fwd(y, x, planes, H, W, L, int(sweeps), ws, wsb)
         ctx.dims = (planes, H, W, int(sweeps), wsb)
-        ctx.lam_shape = lam.shape
         ctx.save_for_backward(ws, lam)
         return x
 
@@ -104,8 +104,8 @@ class _Prox2d(torch.autograd.Function):
         gy = torch.empty_like(g)
         want_lam = ctx.needs_input_grad[1]
         gl = torch.empty(lam.numel(), dtype=torch.float32, device=g.device) if want_lam else None
-        # the reverse sweep uses the two correction tensors of the workspace as its state, so a
-        # second backward through the same graph would need the forward pass again
+        # (the reverse sweep restarts from g and only reads the saved pass outputs; the two
+        # correction tensors of the workspace are its scratch, so it may run again on the same graph)
         _b.tv2d_prox_bwd(g, gy, gl, planes, H, W, L, sweeps, ws, wsb)
         return gy, (gl.reshape(ctx.lam_shape) if want_lam else None), None
 

@@ -139,6 +139,22 @@ def test_info_word_reports_convergence():
     assert (info & 0xffff).max() <= 16
 
 
+def test_info_word_of_lambda_zero_rows():
+    """lambda = 0 is the identity (Sec. 3.1): the row stops at once, and its info word must not
+    claim that it stopped short of an optimal point (bit 19)."""
+    rng = np.random.default_rng(8)
+    y = rng.normal(size=(200, 32)).astype(np.float32)
+    lam = np.where(np.arange(200) % 3 == 0, 0.0, 0.3).astype(np.float32)
+    out = run_1d(y, lam, 1, want_info=True)
+    zero = lam == 0
+    assert np.array_equal(out["x"][zero], y[zero])
+    assert not np.any(out["info"] & (1 << 19)) and not np.any(out["info"] & (1 << 18))
+    assert np.all((out["info"][zero] & 0xffff) == 1)
+    y17 = rng.normal(size=(70, 17)).astype(np.float32)
+    out = run_1d(y17, np.zeros(1, np.float32), 1, want_info=True)
+    assert np.array_equal(out["x"], y17) and not np.any(out["info"] & (1 << 19))
+
+
 def test_full_size_config3_sampled():
     """The 2^20-row workload in the launch configuration the benchmark times: sampled rows
     against the oracle, the certificate on further samples, and global properties."""

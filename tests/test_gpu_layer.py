@@ -83,3 +83,27 @@ def test_layer_2d_shared_lambda_and_identity_limit():
         y2, gx2, _ = _run_layer(ident, x, g)
         np.testing.assert_allclose(y2, x, atol=1e-6)
         np.testing.assert_allclose(gx2, g, atol=1e-6)
+
+
+def test_lambda_of_any_shape_and_a_second_backward():
+    """lambda handed over as [C, 1, 1]: its gradient comes back in that shape (1D and 2D), and the
+    2D reverse sweep may run twice on one graph (it only reads what the forward pass saved)."""
+    import torch
+
+    from paper_2204_03643_amd.layer import tv_prox_1d, tv_prox_2d
+
+    rng = np.random.default_rng(31)
+    x = torch.from_numpy(rng.normal(size=(2, 3, 20, 24)).astype(np.float32)).cuda().requires_grad_(True)
+    g = torch.from_numpy(rng.normal(size=(2, 3, 20, 24)).astype(np.float32)).cuda()
+    lam = torch.tensor([0.2, 0.5, 1.0], device="cuda").reshape(3, 1, 1).requires_grad_(True)
+    y = tv_prox_1d(x, lam, axis=-1, lam_div=20)
+    gx, gl = torch.autograd.grad(y, (x, lam), g)
+    assert gl.shape == (3, 1, 1)
+    lam_flat = lam.detach().reshape(3).requires_grad_(True)
+    gx2, gl2 = torch.autograd.grad(tv_prox_1d(x, lam_flat, axis=-1, lam_div=20), (x, lam_flat), g)
+    assert torch.equal(gx, gx2) and torch.equal(gl.reshape(3), gl2)
+    y = tv_prox_2d(x, lam, 3)
+    gx, gl = torch.autograd.grad(y, (x, lam), g, retain_graph=True)
+    assert gl.shape == (3, 1, 1)
+    gx_again, gl_again = torch.autograd.grad(y, (x, lam), g)
+    assert torch.equal(gx, gx_again) and torch.equal(gl, gl_again)
