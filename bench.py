@@ -270,6 +270,133 @@ def long_probe(dev) -> int:
     return 0
 
 
+def dispatch_probe(dev) -> int:
+    """Both sides of every dispatch threshold of the library, timed at the threshold and a
+    quarter beyond it (the crossovers are gradual: a mapping loses its lead over a round of
+    waves, not at one size), each with the library's choice and with the other mapping forced
+    (tv_dispatch_override).  Prints one JSON object."""
+    import numpy as np
+    import torch
+
+    import paper_2204_03643_amd as tv
+    import workloads
+
+    defaults = tv.tv_dispatch_thresholds()
+
+    def timed(fn, reps=15):
+        for _ in range(4):
+            fn()
+        torch.cuda.synchronize()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
+        ev[0].record()
+        for k in range(reps):
+            fn()
+            ev[k + 1].record()
+        torch.cuda.synchronize()
+        return float(np.median([ev[k].elapsed_time(ev[k + 1]) * 1e3 for k in range(reps)]))
+
+    def planes_like_feature_maps(planes, H, W, seed):
+        rng = np.random.default_rng(seed)
+        y = np.maximum(rng.normal(size=(planes, H, W)), 0).astype(np.float32)
+        lam = rng.uniform(0.01, 1.0, size=64).astype(np.float32)
+        return y, lam
+
+    def two_d(planes, H, W, K):
+        y, lam = planes_like_feature_maps(planes, H, W, 7)
+        yt, lt = torch.from_numpy(y).to(dev), torch.from_numpy(lam).to(dev)
+        gt = torch.randn_like(yt)
+        xt, gy, gl = torch.empty_like(yt), torch.empty_like(yt), torch.empty_like(lt)
+        L = tv.tv_lambda(lt.data_ptr(), lt.numel(), 1)
+        wsb = tv.tv2d_workspace_bytes(planes, H, W, K)
+        ws = torch.empty(wsb, dtype=torch.uint8, device=dev)
+        tf = timed(lambda: tv.tv2d_prox_fwd(yt, xt, planes, H, W, L, K, ws, wsb))
+        tb = timed(lambda: tv.tv2d_prox_bwd(gt, gy, gl, planes, H, W, L, K, ws, wsb))
+        return {"fwd_us": tf, "bwd_us": tb, "fwd_bwd_us": tf + tb}
+
+    def one_d(shape, lam_count, lam_div, with_ws, walk=False):
+        rng = np.random.default_rng(11)
+        y = rng.normal(size=shape).astype(np.float32)
+        if walk:
+            y = (np.cumsum(0.05 * y, axis=-1)).astype(np.float32)
+        lam = (10 ** rng.uniform(-3, 1, size=lam_count)).astype(np.float32)
+        yt, lt = torch.from_numpy(y).to(dev), torch.from_numpy(lam).to(dev)
+        gt, xt, gy, gl = torch.randn_like(yt), torch.empty_like(yt), torch.empty_like(yt), torch.empty_like(lt)
+        rows = tv.rows_along(shape, -1)
+        L = tv.tv_lambda(lt.data_ptr(), lam_count, lam_div)
+        fwsb = tv.tv1d_fwd_workspace_bytes(rows, L) if with_ws else 0
+        fws = torch.empty(max(fwsb, 16), dtype=torch.uint8, device=dev)
+        wsb = tv.tv1d_bwd_workspace_bytes(rows, L)
+        ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device=dev)
+        if fwsb:
+            tf = timed(lambda: tv.tv1d_prox_fwd_ex(yt, xt, rows, L, ws=fws, ws_bytes=fwsb))
+        else:
+            tf = timed(lambda: tv.tv1d_prox_fwd(yt, xt, rows, L))
+        tb = timed(lambda: tv.tv1d_prox_bwd(gt, xt, gy, gl, rows, L, ws, wsb))
+        return {"fwd_us": tf, "bwd_us": tb, "fwd_bwd_us": tf + tb, "fwd_ws_bytes": fwsb}
+
+    res = {}
+
+    def case(name, key, fn, flipped_value, chosen, other):
+        tv.tv_dispatch_override(name, defaults[name])
+        a = fn()
+        tv.tv_dispatch_override(name, flipped_value)
+        b = fn()
+        tv.tv_dispatch_override(name, defaults[name])
+        res.setdefault(name, {"threshold": defaults[name]})[key] = {
+            "chosen": chosen, "chosen_us": a, "other": other, "other_us": b,
+            "chosen_not_slower": a["fwd_bwd_us"] <= 1.03 * b["fwd_bwd_us"]}
+
+    big = 1 << 40
+    n = defaults["tiny_batch_planes"]
+    case("tiny_batch_planes", "at_threshold_k4", lambda: two_d(n, 32, 32, 4), 0,
+         "pass by pass on the long-row kernels", "one launch")
+    case("tiny_batch_planes", "beyond_k4", lambda: two_d(n + n // 4, 32, 32, 4), big,
+         "one launch", "pass by pass on the long-row kernels")
+    for name, K in (("fused32_full_planes", 1), ("fused32_full_planes_k2", 2), ("fused32_full_planes_k3", 4)):
+        n = defaults[name]
+        case(name, "at_threshold_k%d" % K, lambda: two_d(n, 32, 32, K), 0, "one launch", "pass by pass")
+        case(name, "beyond_k%d" % K, lambda: two_d(n + n // 4, 32, 32, K), big, "pass by pass", "one launch")
+    n = defaults["fused32_ragged_planes"]
+    case("fused32_ragged_planes", "at_threshold_k1", lambda: two_d(n, 28, 28, 1), 0, "one launch", "pass by pass")
+    case("fused32_ragged_planes", "beyond_k1", lambda: two_d(n + n // 4, 28, 28, 1), big, "pass by pass", "one launch")
+    n = defaults["fused16_one_sweep_planes"]
+    case("fused16_one_sweep_planes", "at_threshold_k1", lambda: two_d(n, 16, 16, 1), 0, "one launch", "pass by pass")
+    case("fused16_one_sweep_planes", "beyond_k1", lambda: two_d(n + n // 4, 16, 16, 1), big, "pass by pass", "one launch")
+    n = defaults["thread_per_sample_wide_rows"]
+    case("thread_per_sample_wide_rows", "at_threshold_k4", lambda: two_d(n // 32, 32, 32, 4), 0,
+         "16 threads x 2 samples per row", "8 x 4")
+    case("thread_per_sample_wide_rows", "beyond_k4", lambda: two_d(n // 32 + n // 128, 32, 32, 4), big,
+         "8 threads x 4 samples per row", "16 x 2")
+    # a tensor of exactly stream_bytes bytes: rows of 32 samples in 128 lambda slots
+    nb = max(2, defaults["stream_bytes"] // (128 * 32 * 32 * 4))
+    case("stream_bytes", "at_threshold", lambda: one_d((nb, 128, 32, 32), 128, 32, False), big,
+         "non-temporal accesses", "ordinary accesses")
+    case("stream_bytes", "just_below", lambda: one_d((nb - 1, 128, 32, 32), 128, 32, False), 0,
+         "ordinary accesses", "non-temporal accesses")
+    # the slot order: the library computes it whenever it is handed the workspace; the layer hands
+    # it over from order_min_rows rows on
+    n = defaults["order_min_rows"]
+    a = one_d((n // (128 * 32), 128, 32, 32), 128, 32, True)
+    b = one_d((n // (128 * 32), 128, 32, 32), 128, 32, False)
+    res["order_min_rows"] = {"threshold": n, "at_threshold": {
+        "chosen": "slot order (workspace passed)", "chosen_us": a, "other": "natural order", "other_us": b,
+        "chosen_not_slower": a["fwd_us"] <= 1.03 * b["fwd_us"]}}
+    a = one_d((n // (128 * 32) // 2, 128, 32, 32), 128, 32, False)
+    b = one_d((n // (128 * 32) // 2, 128, 32, 32), 128, 32, True)
+    res["order_min_rows"]["at_half"] = {
+        "chosen": "natural order", "chosen_us": a, "other": "slot order (workspace passed)", "other_us": b,
+        "chosen_not_slower": a["fwd_us"] <= 1.03 * b["fwd_us"]}
+    # multilevel start: rows of ml_min_length samples with and without the workspace
+    n = defaults["ml_min_length"]
+    a = one_d((4096, n), 4096, 1, True, walk=True)
+    b = one_d((4096, n), 4096, 1, False, walk=True)
+    res["ml_min_length"] = {"threshold": n, "at_threshold": {
+        "chosen": "multilevel start (workspace passed)", "chosen_us": a, "other": "cold start", "other_us": b,
+        "chosen_not_slower": a["fwd_us"] <= 1.03 * b["fwd_us"]}}
+    print(json.dumps({"dispatch_probe": res}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -281,6 +408,9 @@ def main() -> int:
     ap.add_argument("--traffic-probe", action="store_true",
                     help="run fwd, bwd and a plain copy of the same tensor three times each and "
                          "exit (for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs)")
+    ap.add_argument("--dispatch-probe", action="store_true",
+                    help="time both sides of every dispatch threshold of the library at the threshold "
+                         "and exit")
     ap.add_argument("--long-probe", action="store_true",
                     help="run the long-row kernels of workloads 4 and 5 three times each (single passes, "
                          "the forward call of workload 5 with and without its workspace, the 2D call with "
@@ -303,6 +433,8 @@ def main() -> int:
     dev = torch.device("cuda:0")
     if args.long_probe:
         return long_probe(dev)
+    if args.dispatch_probe:
+        return dispatch_probe(dev)
     y, lam, g = workloads.config3()
     B, C, H, W = y.shape
     n_rows, n_elem = B * C * H, y.size

@@ -232,7 +232,7 @@ int tv1d_prox_bwd_seg_bf16(const uint16_t *g_up, const uint64_t *seg, uint16_t *
  * From the second sweep on, the correction term a pass adds to its input is D^T u of the
  * same pass one sweep earlier (x = y - D^T u), and the pass starts its Newton iteration
  * from that dual.  Planes of at most 32 x 32 run all their passes in one launch where that is
- * faster (any number of planes of at most 8 x 8, 1537-4096 planes of 17-32 samples a side).
+ * faster (the plane counts at which it is: csrc/tv_dispatch.hpp).
  */
 size_t tv2d_workspace_bytes(int64_t planes, int64_t H, int64_t W, int sweeps);
 int tv2d_prox_fwd(const float *y, float *x, int64_t planes, int64_t H, int64_t W,
@@ -250,6 +250,18 @@ int tv2d_prox_bwd(const float *g_up, float *grad_y, float *grad_lam, int64_t pla
                   hipStream_t stream);
 
 const char *tv_status_str(int status);
+
+/*
+ * The sizes at which the library switches between kernel mappings (csrc/tv_dispatch.hpp lists
+ * them with the measurements behind them).  tv_dispatch_name(i) is the name of the i-th one
+ * (NULL past the end), tv_dispatch_threshold(name) its current value (-1: no such name).
+ * tv_dispatch_override sets one, for benchmarks that time both sides of a threshold at the
+ * threshold; results never depend on these values.  Not thread-safe against concurrent calls
+ * of the library; TV_ERR_UNSUPPORTED for an unknown name, TV_ERR_SHAPE for a negative value.
+ */
+const char *tv_dispatch_name(int index);
+int64_t tv_dispatch_threshold(const char *name);
+int tv_dispatch_override(const char *name, int64_t value);
 
 #ifdef __cplusplus
 }

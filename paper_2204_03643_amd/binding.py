@@ -44,6 +44,12 @@ def lib() -> ctypes.CDLL:
         if _build.is_stale():
             _build.build_library()
         L = ctypes.CDLL(_build.LIB)
+        L.tv_dispatch_name.argtypes = [ctypes.c_int]
+        L.tv_dispatch_name.restype = ctypes.c_char_p
+        L.tv_dispatch_threshold.argtypes = [ctypes.c_char_p]
+        L.tv_dispatch_threshold.restype = _i64
+        L.tv_dispatch_override.argtypes = [ctypes.c_char_p, _i64]
+        L.tv_dispatch_override.restype = ctypes.c_int
         L.tv_status_str.argtypes = [ctypes.c_int]
         L.tv_status_str.restype = ctypes.c_char_p
         L.tv1d_prox_fwd.argtypes = [_vp, _vp, tv_rows, tv_lambda, _vp]
@@ -86,6 +92,25 @@ def lib() -> ctypes.CDLL:
 
 def status_str(status: int) -> str:
     return lib().tv_status_str(int(status)).decode()
+
+
+def tv_dispatch_thresholds() -> dict:
+    """{name: value} of every dispatch threshold of the library."""
+    out, i = {}, 0
+    while True:
+        name = lib().tv_dispatch_name(i)
+        if name is None:
+            return out
+        out[name.decode()] = int(lib().tv_dispatch_threshold(name))
+        i += 1
+
+
+def tv_dispatch_threshold(name: str) -> int:
+    return int(lib().tv_dispatch_threshold(name.encode()))
+
+
+def tv_dispatch_override(name: str, value: int):
+    _check(lib().tv_dispatch_override(name.encode(), int(value)))
 
 
 def _ptr(t):

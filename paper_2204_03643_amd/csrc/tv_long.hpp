@@ -22,6 +22,7 @@
 // row_in_group, so adjacent lanes read adjacent columns and global accesses coalesce.
 #pragma once
 #include "tv_common.hpp"
+#include "tv_dispatch.hpp"
 
 namespace tvk {
 
@@ -1116,8 +1117,9 @@ inline hipError_t launch_bwd_long_t(const BwdParams &p, hipStream_t s)
     do {                                                                                  \
         const int n = (p).L.n;                                                            \
         const bool cols = (p).L.elem_stride != 1;                                         \
+        const int64_t wide = tvd::get(tvd::kThreadPerSampleWideRows);                     \
         if (cols) {                                                                       \
-            if (n <= 32 && (p).L.n_rows <= 16384) return FN<16, 2, 16, true>(p, s);       \
+            if (n <= 32 && (int64_t)(p).L.n_rows <= wide) return FN<16, 2, 16, true>(p, s);        \
             if (n <= 32) return FN<8, 4, 16, true>(p, s);                                 \
             if (n <= 64) return FN<8, 8, 16, true>(p, s);                                 \
             if (n <= 96) return FN<8, 12, 16, true>(p, s);                                \
@@ -1136,7 +1138,7 @@ inline hipError_t launch_bwd_long_t(const BwdParams &p, hipStream_t s)
             if (n <= 12288) return FN<1024, 12, 1, true>(p, s);                           \
             return FN<1024, 16, 1, true>(p, s);                                           \
         }                                                                                 \
-        if (n <= 32 && (p).L.n_rows <= 16384) return FN<16, 2, 16, false>(p, s);          \
+        if (n <= 32 && (int64_t)(p).L.n_rows <= wide) return FN<16, 2, 16, false>(p, s);           \
         if (n <= 32) return FN<8, 4, 32, false>(p, s);                                    \
         if (n <= 64) return FN<8, 8, 32, false>(p, s);                                    \
         if (n <= 96) return FN<8, 12, 32, false>(p, s);                                   \

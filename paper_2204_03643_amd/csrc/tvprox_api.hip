@@ -6,8 +6,10 @@
 #include <hip/hip_runtime.h>
 
 #include <mutex>
+#include <string.h>
 
 #include "tv_common.hpp"
+#include "tv_dispatch.hpp"
 #include "tv_long.hpp"
 #include "tv_small2d.hpp"
 #include "tv_short.hpp"
@@ -84,7 +86,7 @@ Layout make_layout(const tv_rows &r, const tv_lambda &l, int64_t n_rows)
     L.lam_count = (uint32_t)l.count;
     L.lam_div = (uint32_t)l.div;
     // a tensor of 32 MiB or more does not survive in the caches until it is touched again
-    L.stream = (n_rows * r.length >= ((int64_t)32 << 20) / 4) ? 1u : 0u;
+    L.stream = (n_rows * r.length >= tvd::get(tvd::kStreamBytes) / 4) ? 1u : 0u;
     return L;
 }
 
@@ -383,9 +385,7 @@ bool order_applies(const tvk::TileMap &tm)
 // samples; every level is an ordinary launch of the long-row kernel on packed scratch rows.
 // Rows whose lambda is small against their variation converge in a few steps anyway and are
 // left out (ml_flag = 0): they start cold at the fine level and are skipped at the others.
-constexpr int64_t kMlMinLength = 2048;
-constexpr int64_t kMlCoarsest = 256;
-constexpr int kMlMaxLevels = 8;
+constexpr int kMlMaxLevels = 8;                // (where it starts and ends: tv_dispatch.hpp)
 constexpr float kMlLambdaRatio = 2.0f;     // multilevel start when lambda >= ratio * mean |y[k+1] - y[k]|
 constexpr int kMlProbeGroups = 512;        // ... judged on the row's first 2048 samples
 
@@ -397,11 +397,11 @@ struct MlPlan {
 
 bool ml_plan(const tv_rows &r, int64_t n_rows, MlPlan *pl)
 {
-    if (r.length < kMlMinLength || r.elem_stride != 1) return false;
+    if (r.length < tvd::get(tvd::kMlMinLength) || r.elem_stride != 1) return false;
     pl->levels = 0;
     pl->n[0] = r.length;
     size_t at = 0;
-    while (pl->n[pl->levels] > kMlCoarsest && pl->levels < kMlMaxLevels) {
+    while (pl->n[pl->levels] > tvd::get(tvd::kMlCoarsest) && pl->levels < kMlMaxLevels) {
         const int l = ++pl->levels;
         pl->n[l] = (pl->n[l - 1] + tvk::kMlFactor - 1) / tvk::kMlFactor;
         const size_t bytes = align16((size_t)n_rows * (size_t)pl->n[l] * sizeof(float));
@@ -864,6 +864,30 @@ int bwd_entry(const float *g_up, const float *x, const uint64_t *seg, bool with_
 
 extern "C" {
 
+int64_t tv_dispatch_threshold(const char *name)
+{
+    if (!name) return -1;
+    for (int i = 0; i < tvd::kCount; ++i)
+        if (strcmp(name, tvd::table[i].name) == 0) return tvd::table[i].value;
+    return -1;
+}
+
+int tv_dispatch_override(const char *name, int64_t value)
+{
+    if (!name || value < 0) return TV_ERR_SHAPE;
+    for (int i = 0; i < tvd::kCount; ++i)
+        if (strcmp(name, tvd::table[i].name) == 0) {
+            tvd::table[i].value = value;
+            return TV_OK;
+        }
+    return TV_ERR_UNSUPPORTED;
+}
+
+const char *tv_dispatch_name(int index)
+{
+    return index >= 0 && index < tvd::kCount ? tvd::table[index].name : nullptr;
+}
+
 const char *tv_status_str(int status)
 {
     switch (status) {
@@ -1083,24 +1107,24 @@ static int small_side(int64_t H, int64_t W)
 // feature-map-like data, 437 -> 361 on white noise; around 2048 planes the one launch catches up).
 static bool tiny_batch_2d(int64_t planes, int64_t H, int64_t W)
 {
-    return small_planes(H, W) && small_side(H, W) == 32 && planes <= 1536;
+    return small_planes(H, W) && small_side(H, W) == 32 && planes <= tvd::get(tvd::kTinyBatchPlanes);
 }
 
-// When the one-launch forward kernel is used.  With planes padded to 32 x 32 it holds two planes
-// per wave and, with 17 KB of LDS per wave, two waves per SIMD where the pass-by-pass kernels hold
-// three: it wins (15-30 %: no launches and no memory round trips between the passes) while all its
-// waves fit on the chip at once, 2 x 1024 SIMDs x 2 planes; beyond that the lower occupancy costs
-// more than the fusion saves (measured: 4096 planes, K = 3: 171 us against 242; 8192 planes: 311
-// against 304).  Planes of at most 16 x 16 need a quarter of the LDS and 144 registers: the one
-// launch wins except for a single sweep over many planes (32 768 planes: K = 1 69 us against 58,
-// K = 3 166 against 206); planes of at most 8 x 8 are always better off in one launch.
+// When the one-launch forward kernel is used: while its lower occupancy (17 KB of LDS per wave
+// for planes padded to 32 x 32: two waves per SIMD against three) costs less than the launches and
+// memory round trips it saves.  The plane counts, and the measurements behind them, are in
+// tv_dispatch.hpp; planes of at most 8 x 8 are always better off in one launch.
 static bool fused_fwd_applies(int side, bool full, int64_t planes, int sweeps)
 {
     // (planes smaller than their 32 x 32 square go pass by pass through the slower general
     // variants of the row-per-lane kernels, so there the one launch wins whenever there is more
     // than one sweep: 28 x 28, 32 768 planes, K = 4: 1.46 ms against 1.94)
-    if (side == 32) return full ? planes <= 4096 : (sweeps >= 2 || planes <= 6144);
-    if (side == 16) return sweeps >= 2 || planes <= 16384;
+    if (side == 32) {
+        if (!full) return sweeps >= 2 || planes <= tvd::get(tvd::kFused32RaggedPlanes);
+        return planes <= tvd::get(sweeps == 1 ? tvd::kFused32FullPlanes
+                                              : (sweeps == 2 ? tvd::kFused32FullPlanesK2 : tvd::kFused32FullPlanesK3));
+    }
+    if (side == 16) return sweeps >= 2 || planes <= tvd::get(tvd::kFused16OneSweepPlanes);
     return true;
 }
 
@@ -1137,7 +1161,7 @@ int tv2d_prox_fwd(const float *y, float *x, int64_t planes, int64_t H, int64_t W
         q.codes = codes(0); q.code_stride = cb / sizeof(uint2);
         q.lam = lam.lam; q.lam_count = lam.count;
         q.planes = (int32_t)planes; q.H = (int32_t)H; q.W = (int32_t)W; q.sweeps = sweeps;
-        q.stream = (planes * H * W >= ((int64_t)32 << 20) / 4) ? 1u : 0u;
+        q.stream = (planes * H * W >= tvd::get(tvd::kStreamBytes) / 4) ? 1u : 0u;
         TV_SMALL2D_LAUNCH(tvk::tv2d_fwd_small_kernel, q, planes, H, W, stream);
         return launch_status();
     }
@@ -1205,7 +1229,7 @@ int tv2d_prox_bwd(const float *g_up, float *grad_y, float *grad_lam, int64_t pla
         q.saved = saved(0); q.saved_stride = tb / sizeof(float);
         q.partial = grad_lam ? partial(0) : nullptr;
         q.planes = (int32_t)planes; q.H = (int32_t)H; q.W = (int32_t)W; q.sweeps = sweeps;
-        q.stream = (planes * H * W >= ((int64_t)32 << 20) / 4) ? 1u : 0u;
+        q.stream = (planes * H * W >= tvd::get(tvd::kStreamBytes) / 4) ? 1u : 0u;
         if (cb && tiny_batch_2d(planes, H, W)) {
             const dim3 grid((uint32_t)((planes + 1) / 2));
             if (H == 32 && W == 32)

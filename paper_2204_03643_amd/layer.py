@@ -18,7 +18,6 @@ import torch
 from . import binding as _b
 
 _SEG_MAX = 32          # TV_SEG_MAX_LENGTH
-_ORDER_MIN_ROWS = 1 << 18
 
 
 def _check_input(x: torch.Tensor, what: str) -> torch.Tensor:
@@ -42,7 +41,7 @@ class _Prox1d(torch.autograd.Function):
         n_rows = rows.n_outer * rows.n_inner
         x = torch.empty_like(y)
         wsb = _b.tv1d_fwd_workspace_bytes(rows, L)
-        if rows.length <= _SEG_MAX and n_rows < _ORDER_MIN_ROWS:
+        if rows.length <= _SEG_MAX and n_rows < _b.tv_dispatch_threshold("order_min_rows"):
             wsb = 0        # the slot order costs a 5 us kernel: it pays off on large batches only
         ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device=y.device)
         seg = None

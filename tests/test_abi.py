@@ -104,6 +104,19 @@ def test_step_record_validation():
     assert L.tv1d_prox_fwd_steps(None, None, None, None, 0, tv.tv_rows(0, 64, 1, 1, 64, 1), lam, None) == 0
 
 
+def test_dispatch_thresholds_are_listed_and_overridable():
+    th = tv.tv_dispatch_thresholds()
+    assert {"stream_bytes", "tiny_batch_planes", "fused32_full_planes", "ml_min_length"} <= set(th)
+    assert th["ml_min_length"] == 2048 and tv.tv_dispatch_threshold("no_such_name") == -1
+    tv.tv_dispatch_override("ml_min_length", 4096)
+    assert tv.tv_dispatch_threshold("ml_min_length") == 4096
+    assert tv.tv1d_fwd_workspace_bytes(tv.rows_along((10, 2048), -1), tv.tv_lambda(FAKE, 1, 1)) == 0
+    tv.tv_dispatch_override("ml_min_length", th["ml_min_length"])
+    assert tv.tv1d_fwd_workspace_bytes(tv.rows_along((10, 2048), -1), tv.tv_lambda(FAKE, 1, 1)) > 0
+    L = tv.lib()
+    assert L.tv_dispatch_override(b"no_such_name", 1) == 6 and L.tv_dispatch_override(b"ml_min_length", -1) == 2
+
+
 def test_seg_pair_validation():
     L = tv.lib()
     rows = tv.tv_rows(4, 32, 1, 1, 32, 1)

@@ -138,3 +138,40 @@ def test_nan_plane_stays_in_its_plane(shape):
         err = np.abs(out["x"][p] - x_ref[0]).max() / (1 + np.abs(y[p]).max())
         assert err <= 1e-4, (shape, p, err)
 
+
+
+@pytest.fixture
+def dispatch_defaults():
+    import paper_2204_03643_amd as tv
+    saved = tv.tv_dispatch_thresholds()
+    yield saved
+    for k, v in saved.items():
+        tv.tv_dispatch_override(k, v)
+
+
+@pytest.mark.parametrize("shape,K", [((70, 32, 32), 2), ((37, 28, 30), 3), ((90, 16, 16), 1), ((33, 13, 16), 2)])
+def test_every_forward_mapping_of_small_planes(shape, K, dispatch_defaults):
+    """The same call through each mapping the dispatch can choose for planes of at most 32 x 32
+    (pass by pass on the thread-per-few-samples kernels, all passes in one launch, pass by pass on
+    the row-per-lane kernels with plane columns and segment codes), forced through the thresholds:
+    the choice is a matter of speed only, so each one must meet the parity rules."""
+    import paper_2204_03643_amd as tv
+    rng = np.random.default_rng(97 + shape[1])
+    y = rng.normal(size=shape).astype(np.float32)
+    g = rng.normal(size=shape).astype(np.float32)
+    lam = (10 ** rng.uniform(-2, 0.3, size=3)).astype(np.float32)
+    names = ("fused32_full_planes", "fused32_full_planes_k2", "fused32_full_planes_k3", "fused32_ragged_planes",
+             "fused16_one_sweep_planes")
+    big = 1 << 40
+    outs = []
+    for tiny, fused, wide in ((big, big, big), (big, big, 0), (0, big, big), (0, 0, big)):
+        tv.tv_dispatch_override("tiny_batch_planes", tiny)
+        tv.tv_dispatch_override("thread_per_sample_wide_rows", wide)
+        for nme in names:
+            tv.tv_dispatch_override(nme, fused)
+        out = run_2d(y, lam, K, g)
+        check_2d(y, lam, K, g, out, "forced (%d, %d, %d) %s K=%d" % (tiny > 0, fused > 0, wide > 0, shape, K))
+        outs.append(out)
+    # every mapping solves the same problems to rounding: outputs agree far inside the parity bar
+    for o in outs[1:]:
+        assert np.abs(o["x"] - outs[0]["x"]).max() <= 2e-5 * (1 + np.abs(y).max())
