@@ -562,6 +562,14 @@ def main() -> int:
     hf_ms, hb_ms = float(np.mean(hf)), float(np.mean(hb))
     del yh, gh, xh, gyh
 
+    # the forward call with the paper's other step-size rule (Sec. 3.2: a search over halving step
+    # sizes tried side by side; the paper found backtracking faster)
+    ps, _ = timed_calls(lambda: tv.tv1d_prox_fwd_ex(yt, xt, rows, L, seg=seg, ws=fws, ws_bytes=fwsb, stream=stream,
+                                                    flags=tv.TV_FWD_ORDER_READY | tv.TV_FWD_PARALLEL_SEARCH),
+                        lambda: None, reps)
+    ps_ms = float(np.mean(ps))
+    ps_diff = float((xt - x_eager).abs().max())
+
     # algorithmic bytes of the method (read y, write x; read g_up and x, write grad_y) ...
     fwd_bytes, bwd_bytes = n_elem * FWD_BYTES_PER_ELEM, n_elem * BWD_BYTES_PER_ELEM
     # ... and what the backward kernel of the timed pair has to move
@@ -642,6 +650,10 @@ def main() -> int:
                        "rows_per_s": n_rows / ((pf_ms + pb_ms) * 1e-3),
                        "effective_gbs_fwd_bwd": (fwd_bytes + bwd_bytes) / ((pf_ms + pb_ms) * 1e-3) / 1e9,
                        "bwd_achieved_gbs": bwd_bytes / (pb_ms * 1e-3) / 1e9},
+        "parallel_step_search": {"call": "forward kernel with TV_FWD_PARALLEL_SEARCH (four halving step sizes "
+                                         "side by side instead of backtracking; slot order kept)",
+                                 "fwd_us": ps_ms * 1e3, "backtracking_fwd_us": ker_ms * 1e3,
+                                 "max_abs_difference_of_x": ps_diff},
         "bf16_storage_pair": {"calls": "tv1d_prox_fwd_seg_bf16 + tv1d_prox_bwd_seg_bf16 (bf16 in memory, "
                                        "fp32 arithmetic; not the headline)",
                               "fwd_us": hf_ms * 1e3, "bwd_us": hb_ms * 1e3,

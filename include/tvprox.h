@@ -116,14 +116,21 @@ int tv1d_prox_fwd_info(const float *y, float *x, int32_t *info, tv_rows rows, tv
  *           lambda is large against their sample-to-sample variation take 4 steps instead of
  *           10-30.  Scratch: about two thirds of the input's size.
  *         tv1d_fwd_workspace_bytes() returns 0 where neither applies (ws is then unused).
- *   flags: 0, or TV_FWD_ORDER_READY: ws still holds the slot order that an earlier call with
+ *   flags: 0 or a combination of
+ *         TV_FWD_ORDER_READY: ws still holds the slot order that an earlier call with
  *         the same rows and lam descriptors left there, and it is used as it stands (the order
  *         depends on lambda and on the scale of the rows, which drift slowly from one training
  *         step to the next; recomputing it costs a 5 us kernel).  Any order gives the same
  *         results; entries that are no slot numbers are clamped, so a stale or foreign buffer
  *         costs time, not correctness of the addressing.  Ignored where no slot order applies.
+ *         TV_FWD_PARALLEL_SEARCH (rows of at most TV_SEG_MAX_LENGTH samples; TV_ERR_UNSUPPORTED
+ *         beyond): the step size of every Newton iteration comes from the paper's other rule
+ *         (Sec. 3.2), a search over four halving step sizes tried side by side, instead of
+ *         backtracking with quadratic interpolation.  Same minimiser, x agrees to rounding; the
+ *         paper found backtracking faster, and so it is here (the benchmark prints both).
  */
 #define TV_FWD_ORDER_READY 1u
+#define TV_FWD_PARALLEL_SEARCH 2u
 typedef struct {
     int32_t *info;
     uint64_t *seg;

@@ -24,6 +24,7 @@ class tv_fwd_extra(ctypes.Structure):
 
 
 TV_FWD_ORDER_READY = 1
+TV_FWD_PARALLEL_SEARCH = 2
 
 
 class TVError(RuntimeError):

@@ -114,6 +114,7 @@ struct FwdParams {
     uint2       *seg;      // optional per-row segment code (rows of up to 32 samples only)
     const uint32_t *order; // optional: grid row j of the grouped grid works on slot order[j]
     uint32_t     io16;     // y and x are bf16 arrays (row-per-lane kernel, packed rows of 32 only)
+    uint32_t     psearch;  // row-per-lane kernel, rows of up to 32 samples: parallel step-size search
     uint32_t     warm;     // 1: addend is D^T u of an earlier solve of nearly the same rows: start from that u
                            // 2: start from the dual of the row averaged in groups of kMlFactor (coarse_u)
     // long-row kernels only (multilevel start):

@@ -739,6 +739,133 @@ struct RowSolver {
         return false;
     }
 
+    // The same iteration with the paper's other step-size rule (Sec. 3.2): instead of backtracking
+    // from alpha = 1 with quadratic interpolation, the kPar step sizes alpha_0 2^-j, j = 0 .. kPar-1,
+    // are tried side by side -- one sweep over the duals carries all their trial points and
+    // objective values -- and the largest that passes the Armijo test is taken (alpha = 1 outright
+    // when nothing clips).  If none passes, the next iteration goes on from alpha_0 2^-kPar.  A
+    // second sweep then writes the chosen step, so no previous dual has to be kept.
+    static constexpr int kPar = 4;
+    __device__ __forceinline__ bool iterate_psearch(int it)
+    {
+        bool vio = false;
+        {
+            int pos4 = 0;
+#pragma unroll
+            for (int k = 0; k < M; ++k) {
+                const float g = X[k] - X[k + 1];
+                const float s = copysignf(lk(k), g);
+                const bool bnd = (u[k] == -s);
+                if (FULL || k < m) vio |= (u[k] == s) && (fabsf(g) > gtol);
+                pos4 = bnd ? 0 : pos4 + 4;
+                D[k] = g;
+                G[k] = tab(gtab, pos4);
+            }
+        }
+        float dec = 0.f;
+        {
+            float tprev = 0.f;
+#pragma unroll
+            for (int k = 0; k < M; ++k) {
+                const float w = D[k] + tprev;
+                const float t = G[k] * w;
+                dec = fmaf(t, w, dec);
+                D[k] = t;
+                tprev = t;
+            }
+        }
+        if (active && prev_unclipped && !vio) { active = false; flags = kInfoConverged; }
+        if (active && it >= kMaxNewtonSteps) { active = false; flags = kInfoCapped; }
+        if (!__any(active)) return true;
+        steps += active ? 1 : 0;
+        reread();
+#pragma unroll
+        for (int k = 0; k < NMAX; ++k) X[k] = yk(k);
+        {
+            float dn = 0.f;
+#pragma unroll
+            for (int k = M - 1; k >= 0; --k) {
+                dn = fmaf(G[k], dn, D[k]);
+                D[k] = dn;
+            }
+        }
+        // ---- all kPar trial points in one sweep
+        const float a0 = active ? alpha_try : 0.f;
+        float al[kPar], acc[kPar], pv[kPar];
+#pragma unroll
+        for (int j = 0; j < kPar; ++j) { al[j] = a0 * (1.0f / (float)(1 << j)); acc[j] = 0.f; pv[j] = 0.f; }
+        float tmax = 0.f;
+#pragma unroll
+        for (int k = 0; k < M; ++k) {
+            const float l = lk(k);
+#pragma unroll
+            for (int j = 0; j < kPar; ++j) {
+                const float t = fmaf(-al[j], D[k], u[k]);
+                const float c = __builtin_amdgcn_fmed3f(t, -l, l);
+                if (j == 0) tmax = fmaxf(tmax, fabsf(t));
+                const float xc = X[k] + c - pv[j];          // X[k] holds y_k here
+                acc[j] = fmaf(xc, xc, acc[j]);
+                pv[j] = c;
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < kPar; ++j) {
+            const float xc = X[M] - pv[j];
+            acc[j] = fmaf(xc, xc, acc[j]);
+        }
+        const bool clipped = tmax > lam;
+        // the largest step that passes
+        float alpha = 0.f, fc = fcur;
+        bool found = false;
+#pragma unroll
+        for (int j = kPar - 1; j >= 0; --j) {
+            const float fj = 0.5f * acc[j];
+            const bool okj = (j == 0 && a0 == 1.f && !clipped) ||
+                             (fj <= fcur - kArmijoSigma * al[j] * dec + kArmijoSlackEps * fabsf(fcur));
+            if (okj) { alpha = al[j]; fc = fj; found = true; }
+        }
+        if (!active) { alpha = 0.f; found = true; }
+        // ---- the chosen step (alpha = 0: the dual stays, X becomes x(u) again)
+        bool changed = false;
+        {
+            float prev = 0.f;
+#pragma unroll
+            for (int k = 0; k < M; ++k) {
+                const float l = lk(k);
+                const float uo = u[k];
+                const float c = __builtin_amdgcn_fmed3f(fmaf(-alpha, D[k], uo), -l, l);
+                changed |= (c != uo);
+                X[k] = X[k] + c - prev;
+                u[k] = c; prev = c;
+            }
+            X[M] = X[M] - prev;
+        }
+        if (active && !found) {
+            alpha_try = al[kPar - 1] * 0.5f;
+            prev_unclipped = false;
+            nfail += kPar;
+            if (nfail > kMaxBacktracks) { active = false; flags = kInfoStalled | kInfoPlain; }
+        } else if (active) {
+            fcur = fc;
+            prev_unclipped = (alpha == 1.f) && !clipped;
+            alpha_try = 1.f;
+            nfail = 0;
+            if (!changed) {
+                active = false;
+                flags = kInfoStalled | ((alpha == 1.f && !vio) ? 0 : kInfoPlain);
+            }
+        }
+        if (!__any(active)) {
+#pragma unroll
+            for (int k = 0; k < M; ++k) {
+                const float g = X[k] - X[k + 1];
+                G[k] = (u[k] == -copysignf(lk(k), g)) ? 0.f : 1.f;
+            }
+            return true;
+        }
+        return false;
+    }
+
     // ---- primal recovery.  X is x = y - D^T u at the final dual, bound duals are known; at
     //      its bound duals (flagged by G[k] == 0).  Between two bound duals x is constant up to rounding; every
     //      sample takes the value of the first sample of its block, so that constant runs are
@@ -769,8 +896,9 @@ struct RowSolver {
 // PLANE (NMAX = 32, FULL, not PACKED, not WARM): the rows are the columns of contiguous 32 x 32 planes.
 // IO16 (NMAX = 32, FULL, PACKED, no addend / second output / residual): y and x are bf16.
 // DEBUG: the first p.debug_rows rows leave a step record in p.debug (see step_record_floats).
+// PSEARCH: the step size comes from the parallel search over halving step sizes (iterate_psearch).
 template <int NMAX, bool FULL, bool PACKED, bool WARM = false, bool PLANE = false, bool IO16 = false,
-          bool DEBUG = false>
+          bool DEBUG = false, bool PSEARCH = false>
 __global__ __launch_bounds__(kShortBlock) void tv1d_fwd_short_kernel(FwdParams p)
 {
     using S = ShortSmem<NMAX>;
@@ -872,7 +1000,8 @@ __global__ __launch_bounds__(kShortBlock) void tv1d_fwd_short_kernel(FwdParams p
     sv.active = valid; sv.prev_unclipped = false;
     if constexpr (WARM) sv.start_warm(y);
     else sv.start(y, rtab[n]);
-    for (int it = 0; !sv.iterate(it); ++it) {}
+    if constexpr (PSEARCH) { for (int it = 0; !sv.iterate_psearch(it); ++it) {} }
+    else { for (int it = 0; !sv.iterate(it); ++it) {} }
     sv.recover(xs);
 
     const bool want_resid = p.resid != nullptr;

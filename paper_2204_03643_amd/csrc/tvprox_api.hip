@@ -148,6 +148,15 @@ int launch_fwd_short(const FwdParams &p, bool packed_ok, hipStream_t s, bool pla
             hipLaunchKernelGGL((tvk::tv1d_fwd_short_kernel<32, true, true, false, false, true>), grid, block, 0, s, p);
             return launch_status();
         }
+        if (p.psearch) {                  // the entry point has checked: no addend, rows of up to 32 samples
+            if (full && packed_ok)
+                hipLaunchKernelGGL((tvk::tv1d_fwd_short_kernel<32, true, true, false, false, false, false, true>), grid,
+                                   block, 0, s, p);
+            else
+                hipLaunchKernelGGL((tvk::tv1d_fwd_short_kernel<32, false, false, false, false, false, false, true>), grid,
+                                   block, 0, s, p);
+            return launch_status();
+        }
     }
     if constexpr (NMAX == 32) {
         // (the warm-start variant of the plane mode runs out of scalar registers and loses a wave of
@@ -523,12 +532,13 @@ int run_fwd_multilevel(FwdParams p, const tv_lambda &l, int64_t n_rows, const Ml
 int run_fwd(const float *y, const float *addend, float *x, float *resid, int32_t *info,
             uint2 *seg, uint32_t *order_ws, const tv_rows &r, const tv_lambda &l, int64_t n_rows,
             hipStream_t s, float *x2 = nullptr, bool warm = false, char *ml_ws = nullptr, bool io16 = false,
-            bool thread_per_sample = false, bool order_ready = false)
+            bool thread_per_sample = false, bool order_ready = false, bool psearch = false)
 {
     FwdParams p;
     p.y = y; p.addend = addend; p.x = x; p.x2 = x2; p.resid = resid; p.lam = l.lam; p.info = info;
     p.seg = seg; p.order = nullptr;
     p.io16 = io16 ? 1u : 0u;
+    p.psearch = psearch ? 1u : 0u;
     p.warm = (warm && addend) ? 1u : 0u;
     p.coarse_u = nullptr; p.coarse_n = 0; p.dual_out = nullptr; p.ml_flag = nullptr; p.ml_skip = 0;
     p.lam_scale = 1.0f;
@@ -560,6 +570,7 @@ int run_fwd(const float *y, const float *addend, float *x, float *resid, int32_t
     const bool packed = rows_packed(r) && aligned16(y) && aligned16(x) &&
                         (!addend || aligned16(addend)) && (!resid || aligned16(resid));
     const bool ragged = rows_packed(r);
+    if (psearch) return launch_fwd_short<32>(p, packed, s, false, false);   // every length up to 32
     if (r.length <= 8) return launch_fwd_short<8>(p, packed, s, false, ragged);
     if (r.length <= 16) return launch_fwd_short<16>(p, packed, s, false, ragged);
     if (r.length <= 32) {
@@ -793,6 +804,7 @@ int fwd_entry(const float *y, float *x, tv_rows rows, tv_lambda lam, const tv_fw
         if (rows.length > TV_SEG_MAX_LENGTH) return TV_ERR_UNSUPPORTED;
         if ((uintptr_t)e.seg % 8 != 0) return TV_ERR_STRIDE;
     }
+    if ((e.flags & TV_FWD_PARALLEL_SEARCH) && rows.length > TV_SEG_MAX_LENGTH) return TV_ERR_UNSUPPORTED;
     uint32_t *order_ws = nullptr;
     if (e.ws) {
         if (!aligned16(e.ws) || e.ws_bytes < fwd_workspace_bytes(rows, lam, n_rows))
@@ -801,7 +813,7 @@ int fwd_entry(const float *y, float *x, tv_rows rows, tv_lambda lam, const tv_fw
     }
     return run_fwd(y, nullptr, x, nullptr, e.info, reinterpret_cast<uint2 *>(e.seg), order_ws, rows,
                    lam, n_rows, s, nullptr, false, (char *)e.ws, false, false,
-                   (e.flags & TV_FWD_ORDER_READY) != 0);
+                   (e.flags & TV_FWD_ORDER_READY) != 0, (e.flags & TV_FWD_PARALLEL_SEARCH) != 0);
 }
 
 // Device address of `scratch` on the current device, resolved on the first call there.
@@ -952,7 +964,7 @@ int tv1d_prox_fwd_steps(const float *y, float *x, int32_t *info, float *record, 
     if (rows.length > 32 && rows.elem_stride != 1) return TV_ERR_UNSUPPORTED;
     FwdParams p;
     p.y = y; p.addend = nullptr; p.x = x; p.x2 = nullptr; p.resid = nullptr; p.lam = lam.lam; p.info = info;
-    p.seg = nullptr; p.order = nullptr; p.io16 = 0; p.warm = 0;
+    p.seg = nullptr; p.order = nullptr; p.io16 = 0; p.psearch = 0; p.warm = 0;
     p.coarse_u = nullptr; p.coarse_n = 0; p.dual_out = nullptr; p.ml_flag = nullptr; p.ml_skip = 0;
     p.lam_scale = 1.0f;
     p.debug = record;

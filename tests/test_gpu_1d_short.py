@@ -229,3 +229,46 @@ def test_columns_of_32x32_planes(planes, pitch, count):
     lr = lam[(np.arange(planes * 32) // 32) % count]
     check_batch(cols(buf), lr, cols(gbuf), cols(x), cols(gyn), gl_gpu=gl.cpu().numpy(), lam_count=count,
                 lam_div=32, label="plane columns %d/%d/%d" % (planes, pitch, count))
+
+
+@pytest.mark.parametrize("shape,axis,lam_div", [((6, 128, 32, 32), -1, 32), ((3, 7, 20, 31), -1, 20), ((5, 24, 130), -2, 130),
+                                                ((333, 9), -1, 1)])
+def test_parallel_step_size_search(shape, axis, lam_div):
+    """The forward call with the paper's other step-size rule (Sec. 3.2, search over halving step
+    sizes tried side by side): the same minimiser, so the same parity rules; and the output agrees
+    with the backtracking call far inside the forward tolerance."""
+    import torch
+
+    import paper_2204_03643_amd as tv
+
+    rng = np.random.default_rng(60 + shape[-1])
+    y = rng.normal(size=shape).astype(np.float32)
+    g = rng.normal(size=shape).astype(np.float32)
+    n_slots = shape[1] if len(shape) == 4 else 3
+    lam = (10 ** rng.uniform(-3, 1, size=n_slots)).astype(np.float32)
+    dev = torch.device("cuda:0")
+    yt, lt, gt = (torch.from_numpy(a).to(dev) for a in (y, lam, g))
+    rows, L = tv.rows_along(shape, axis), tv.tv_lambda(lt.data_ptr(), lt.numel(), lam_div)
+    n_rows = rows.n_outer * rows.n_inner
+    x, x_bt = torch.full_like(yt, float("nan")), torch.empty_like(yt)
+    info = torch.zeros(n_rows, dtype=torch.int32, device=dev)
+    seg = torch.zeros(n_rows, dtype=torch.int64, device=dev)
+    tv.tv1d_prox_fwd_ex(yt, x, rows, L, info=info, seg=seg, flags=tv.TV_FWD_PARALLEL_SEARCH)
+    tv.tv1d_prox_fwd(yt, x_bt, rows, L)
+    gy, gl = torch.empty_like(yt), torch.empty_like(lt)
+    wsb = tv.tv1d_bwd_workspace_bytes(rows, L)
+    ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device=dev)
+    tv.tv1d_prox_bwd_seg(gt, seg, gy, gl, rows, L, ws, wsb)
+    torch.cuda.synchronize()
+    assert not bool((info & (1 << 18)).any())
+    assert float((x - x_bt).abs().max()) <= 2e-5 * (1 + np.abs(y).max())
+    yr, gr = rows_view(y, axis), rows_view(g, axis)
+    check_batch(yr, lam_per_row(lam, len(yr), lam_div), gr, rows_view(x.cpu().numpy(), axis),
+                rows_view(gy.cpu().numpy(), axis), gl_gpu=gl.cpu().numpy(), lam_count=lam.size, lam_div=lam_div,
+                label="parallel search %s" % (shape,))
+    # rows longer than the row-per-lane kernels take: not offered
+    yl = torch.zeros(4, 40, device=dev)
+    with pytest.raises(tv.TVError) as e:
+        tv.tv1d_prox_fwd_ex(yl, yl, tv.rows_along((4, 40), -1), tv.tv_lambda(lt.data_ptr(), 1, 1),
+                            flags=tv.TV_FWD_PARALLEL_SEARCH)
+    assert e.value.status == 6
