@@ -33,9 +33,10 @@ enum {
 inline Threshold table[kCount] = {
     // A tensor of this many bytes or more is touched once per call and does not survive in the
     // 256 MB last-level cache until the next call; its 16-byte accesses are marked non-temporal.
-    // 128 MiB tensors, forward + backward: 147 -> 136 with the hint; 32 MiB: 72 against 74 without
-    // it; 16 MiB tensors (the 2D workloads, re-read by the next pass): 3-9 % slower with it.
-    {"stream_bytes", (int64_t)64 << 20, "non-temporal accesses from this tensor size on"},
+    // 128 MiB tensors, forward + backward: 147 -> 136 with the hint; 64 MiB: 104 with it against 100
+    // without; 32 MiB: 74 against 72; 16 MiB tensors (the 2D workloads, re-read by the next pass):
+    // 3-9 % slower with it.
+    {"stream_bytes", (int64_t)96 << 20, "non-temporal accesses from this tensor size on"},
     // The slot order of the row-per-lane forward kernel costs a 5 us kernel of one workgroup and
     // shortens the drain of the main kernel: 2^20 rows 97 -> 80 + 5; 2^17 rows 45 -> 44 + 5.  The
     // library computes the order whenever it is handed the workspace; this is where the layer
