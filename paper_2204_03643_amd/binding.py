@@ -87,6 +87,10 @@ def lib() -> ctypes.CDLL:
         L.tv2d_prox_bwd.argtypes = [_vp, _vp, _vp, _i64, _i64, _i64, tv_lambda, ctypes.c_int, _vp,
                                     ctypes.c_size_t, _vp]
         L.tv2d_prox_bwd.restype = ctypes.c_int
+        L.tv2d_prox_fwd_bf16.argtypes = L.tv2d_prox_fwd.argtypes
+        L.tv2d_prox_fwd_bf16.restype = ctypes.c_int
+        L.tv2d_prox_bwd_bf16.argtypes = L.tv2d_prox_bwd.argtypes
+        L.tv2d_prox_bwd_bf16.restype = ctypes.c_int
         _lib = L
     return _lib
 
@@ -226,3 +230,14 @@ def tv2d_prox_bwd(g_up, grad_y, grad_lam, planes, H, W, lam: tv_lambda, sweeps, 
                   stream=None):
     _check(lib().tv2d_prox_bwd(_ptr(g_up), _ptr(grad_y), _ptr(grad_lam), planes, H, W, lam,
                                int(sweeps), _ptr(ws), int(ws_bytes), _stream(stream)))
+
+
+def tv2d_prox_fwd_bf16(y, x, planes, H, W, lam: tv_lambda, sweeps, ws, ws_bytes, stream=None):
+    _check(lib().tv2d_prox_fwd_bf16(_ptr(y), _ptr(x), planes, H, W, lam, int(sweeps), _ptr(ws),
+                                    int(ws_bytes), _stream(stream)))
+
+
+def tv2d_prox_bwd_bf16(g_up, grad_y, grad_lam, planes, H, W, lam: tv_lambda, sweeps, ws, ws_bytes,
+                       stream=None):
+    _check(lib().tv2d_prox_bwd_bf16(_ptr(g_up), _ptr(grad_y), _ptr(grad_lam), planes, H, W, lam,
+                                    int(sweeps), _ptr(ws), int(ws_bytes), _stream(stream)))

@@ -15,6 +15,48 @@
 
 namespace tvk {
 
+// ---- bf16 storage of the planes (fp32 everywhere inside): the wave's planes between memory (bf16
+//      bit patterns, plane after plane) and an LDS tile of fp32 rows at pitch P.
+// FULL planes (S x S, 16-byte aligned block): eight samples per 16-byte access.
+template <int S>
+__device__ __forceinline__ void planes16_into_tile(const uint16_t *__restrict__ src, int n_here, int lane,
+                                                   float *tile, bool stream)
+{
+    constexpr int P = S + 1;
+#pragma unroll
+    for (int i = 0; i < S / 8; ++i) {
+        const int e = (i * 64 + lane) * 8;                 // sample index inside the wave's block
+        float4 q = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (e / (S * S) < n_here) q = load16(reinterpret_cast<const float *>(src + e), stream);
+        const uint32_t w[4] = {__float_as_uint(q.x), __float_as_uint(q.y), __float_as_uint(q.z), __float_as_uint(q.w)};
+        float *d = tile + (e / S) * P + (e % S);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            d[2 * j] = __uint_as_float(w[j] << 16);
+            d[2 * j + 1] = __uint_as_float(w[j] & 0xffff0000u);
+        }
+    }
+}
+template <int S>
+__device__ __forceinline__ void tile_into_planes16(const float *tile, uint16_t *__restrict__ dst, int n_here,
+                                                   int lane, bool stream)
+{
+    constexpr int P = S + 1;
+#pragma unroll
+    for (int i = 0; i < S / 8; ++i) {
+        const int e = (i * 64 + lane) * 8;
+        const float *sp = tile + (e / S) * P + (e % S);
+        uint32_t w[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) w[j] = f32x2_to_bf16x2(sp[2 * j], sp[2 * j + 1]);
+        if (e / (S * S) < n_here)
+            store16(reinterpret_cast<float *>(dst + e),
+                    make_float4(__uint_as_float(w[0]), __uint_as_float(w[1]), __uint_as_float(w[2]), __uint_as_float(w[3])),
+                    stream);
+    }
+}
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float v) { return (uint16_t)(f32x2_to_bf16x2(v, 0.f) & 0xffffu); }
+
 struct Small2dBwdParams {
     const float *g_up;
     float       *gy;
@@ -25,7 +67,7 @@ struct Small2dBwdParams {
     float       *partial;      // optional: one dL/dlam term per plane (all passes summed)
     int32_t      planes, H, W, sweeps;
     uint32_t     stream;       // tensors too large to stay in cache: non-temporal accesses
-};
+};                             // (IO16 kernels: g_up and gy point to bf16 bit patterns)
 
 // Bit k of a row's segment code: x = jump bits 0-31, y = direction bits 0-31, z and w = the same
 // for duals 32-62 (rows of more than 32 samples).
@@ -88,7 +130,8 @@ __device__ __forceinline__ float small2d_segment_means(float (&g)[S], const uint
 // one row or column per lane.  FULL: planes of exactly S x S.  S = 64: the segments of a pass are
 // read off its saved output (the forward kernels for rows of more than 32 samples write no codes).
 // FROM_X: the segments of a pass are read off its saved output instead of its codes.
-template <int S, bool FULL, bool FROM_X = (S > 32)>
+// IO16: the upstream gradient and grad_y are bf16 in memory (fp32 in the tiles and in all arithmetic).
+template <int S, bool FULL, bool FROM_X = (S > 32), bool IO16 = false>
 __global__ __launch_bounds__(64) void tv2d_bwd_small_kernel(Small2dBwdParams p)
 {
     constexpr int P = S + 1;                        // tile pitch
@@ -104,7 +147,15 @@ __global__ __launch_bounds__(64) void tv2d_bwd_small_kernel(Small2dBwdParams p)
     const int n_here = (int)((p.planes - plane0 < PP) ? (p.planes - plane0) : PP);
 
     // the upstream gradient of the wave's planes -> A
-    {
+    if constexpr (IO16) {
+        const uint16_t *src = reinterpret_cast<const uint16_t *>(p.g_up) + plane0 * HW;
+        if (FULL && ((uintptr_t)src % 16) == 0) {
+            planes16_into_tile<S>(src, n_here, lane, A, p.stream != 0);
+        } else if (pvalid && idx < W) {
+            const uint16_t *col = src + h * HW + idx;
+            for (int r = 0; r < H; ++r) A[(h * S + r) * P + idx] = bf16_bits_to_f32(col[r * W]);
+        }
+    } else {
         const float *src = p.g_up + plane0 * HW;
         if (FULL && ((uintptr_t)src % 16) == 0) {
 #pragma unroll
@@ -233,7 +284,15 @@ __global__ __launch_bounds__(64) void tv2d_bwd_small_kernel(Small2dBwdParams p)
     }
 
     // grad_y = A
-    {
+    if constexpr (IO16) {
+        uint16_t *dst = reinterpret_cast<uint16_t *>(p.gy) + plane0 * HW;
+        if (FULL && ((uintptr_t)dst % 16) == 0) {
+            tile_into_planes16<S>(A, dst, n_here, lane, p.stream != 0);
+        } else if (pvalid && idx < W) {
+            uint16_t *col = dst + h * HW + idx;
+            for (int r = 0; r < H; ++r) col[r * W] = f32_to_bf16_bits(A[(h * S + r) * P + idx]);
+        }
+    } else {
         float *dst = p.gy + plane0 * HW;
         if (FULL && ((uintptr_t)dst % 16) == 0) {
 #pragma unroll
@@ -288,7 +347,8 @@ struct Small2dFwdParams {
 };
 
 // S, FULL: as in the reverse sweep (a wave holds 64 / S planes).
-template <int S, bool FULL>
+// IO16: y and x are bf16 in memory; the saved pass outputs stay fp32.
+template <int S, bool FULL, bool IO16 = false>
 __global__ __launch_bounds__(64, 2) void tv2d_fwd_small_kernel(Small2dFwdParams p)
 {
     constexpr int P = S + 1;
@@ -311,7 +371,15 @@ __global__ __launch_bounds__(64, 2) void tv2d_fwd_small_kernel(Small2dFwdParams 
     float *mine = T2 + lane;                    // lane-private: the correction term, step 64
 
     // the wave's planes -> T1 (memory rows at pitch P)
-    {
+    if constexpr (IO16) {
+        const uint16_t *src = reinterpret_cast<const uint16_t *>(p.y) + plane0 * HW;
+        if (FULL && ((uintptr_t)src % 16) == 0) {
+            planes16_into_tile<S>(src, n_here, lane, T1, p.stream != 0);
+        } else if (pvalid && idx < W) {
+            const uint16_t *col = src + h * HW + idx;
+            for (int r = 0; r < H; ++r) T1[(h * S + r) * P + idx] = bf16_bits_to_f32(col[r * W]);
+        }
+    } else {
         const float *src = p.y + plane0 * HW;
         if (FULL && ((uintptr_t)src % 16) == 0) {
 #pragma unroll
@@ -405,7 +473,17 @@ __global__ __launch_bounds__(64, 2) void tv2d_fwd_small_kernel(Small2dFwdParams 
         wave_lds_sync();
         put_planes(p.saved + (size_t)i * p.saved_stride + plane0 * HW);
         if (i + 1 == n_pass) {
-            put_planes(p.x + plane0 * HW);
+            if constexpr (IO16) {
+                uint16_t *dst = reinterpret_cast<uint16_t *>(p.x) + plane0 * HW;
+                if (FULL && ((uintptr_t)dst % 16) == 0) {
+                    tile_into_planes16<S>(T1, dst, n_here, lane, p.stream != 0);
+                } else if (pvalid && idx < W) {
+                    uint16_t *colo = dst + h * HW + idx;
+                    for (int r = 0; r < H; ++r) colo[r * W] = f32_to_bf16_bits(T1[(h * S + r) * P + idx]);
+                }
+            } else {
+                put_planes(p.x + plane0 * HW);
+            }
             break;
         }
 

@@ -1111,6 +1111,24 @@ static int small_side(int64_t H, int64_t W)
         }                                                                                           \
     } while (0)
 
+// the same for kernels with further template arguments (bool..., after S and FULL)
+#define TV_SMALL2D_LAUNCH_X(KERNEL, q, planes, H, W, stream, ...)                                    \
+    do {                                                                                            \
+        const int side = small_side(H, W);                                                          \
+        const bool full = (H) == side && (W) == side;                                               \
+        const dim3 grid((uint32_t)(((planes) + 64 / side - 1) / (64 / side)));                      \
+        if (side == 8) {                                                                            \
+            if (full) hipLaunchKernelGGL((KERNEL<8, true, __VA_ARGS__>), grid, dim3(64), 0, stream, q);   \
+            else hipLaunchKernelGGL((KERNEL<8, false, __VA_ARGS__>), grid, dim3(64), 0, stream, q);       \
+        } else if (side == 16) {                                                                    \
+            if (full) hipLaunchKernelGGL((KERNEL<16, true, __VA_ARGS__>), grid, dim3(64), 0, stream, q);  \
+            else hipLaunchKernelGGL((KERNEL<16, false, __VA_ARGS__>), grid, dim3(64), 0, stream, q);      \
+        } else {                                                                                    \
+            if (full) hipLaunchKernelGGL((KERNEL<32, true, __VA_ARGS__>), grid, dim3(64), 0, stream, q);  \
+            else hipLaunchKernelGGL((KERNEL<32, false, __VA_ARGS__>), grid, dim3(64), 0, stream, q);      \
+        }                                                                                           \
+    } while (0)
+
 // Up to 1536 planes of 17-32 samples a side: the forward passes run one by one on the long-row
 // kernels (eight threads per row), and the reverse sweep reads the segments off the saved pass
 // outputs instead of codes.  With so few rows a row-per-lane wave runs alone on its SIMD and issues
@@ -1194,6 +1212,64 @@ int tv2d_prox_fwd(const float *y, float *x, int64_t planes, int64_t H, int64_t W
         if (st != TV_OK) return st;
     }
     return TV_OK;
+}
+
+// ---- the 2D operator with bf16 storage of y, x, g_up and grad_y (planes of at most 32 x 32): always
+//      the one-launch kernels; the workspace (saved pass outputs, segment codes) is as for fp32.
+int tv2d_prox_fwd_bf16(const uint16_t *y, uint16_t *x, int64_t planes, int64_t H, int64_t W, tv_lambda lam,
+                       int sweeps, void *ws, size_t ws_bytes, hipStream_t stream)
+{
+    if (lam.count < 1 || lam.count > kMaxRows) return TV_ERR_LAMBDA;
+    size_t tb, pb, cb;
+    int st = check_2d(planes, H, W, sweeps, &tb, &pb, &cb);
+    if (st != TV_OK) return st;
+    if (planes == 0) return TV_OK;
+    if (!y || !x || !lam.lam) return TV_ERR_NULL;
+    if (!small_planes(H, W)) return TV_ERR_UNSUPPORTED;
+    if (((uintptr_t)y | (uintptr_t)x) % 2 != 0) return TV_ERR_STRIDE;
+    if (!ws || !aligned16(ws) || ws_bytes < tb * (size_t)(2 * sweeps + 2) + (pb + cb) * (size_t)(2 * sweeps) + kSplitScratchBytes)
+        return TV_ERR_WORKSPACE;
+    char *base = (char *)ws;
+    tvk::Small2dFwdParams q;
+    q.y = reinterpret_cast<const float *>(y); q.x = reinterpret_cast<float *>(x);
+    q.saved = (float *)base; q.saved_stride = tb / sizeof(float);
+    q.codes = (uint2 *)(base + tb * (size_t)(2 * sweeps + 2) + pb * (size_t)(2 * sweeps));
+    q.code_stride = cb / sizeof(uint2);
+    q.lam = lam.lam; q.lam_count = lam.count;
+    q.planes = (int32_t)planes; q.H = (int32_t)H; q.W = (int32_t)W; q.sweeps = sweeps;
+    q.stream = (planes * H * W >= tvd::get(tvd::kStreamBytes) / 4) ? 1u : 0u;
+    TV_SMALL2D_LAUNCH_X(tvk::tv2d_fwd_small_kernel, q, planes, H, W, stream, true);
+    return launch_status();
+}
+
+int tv2d_prox_bwd_bf16(const uint16_t *g_up, uint16_t *grad_y, float *grad_lam, int64_t planes, int64_t H,
+                       int64_t W, tv_lambda lam, int sweeps, void *ws, size_t ws_bytes, hipStream_t stream)
+{
+    if (lam.count < 1 || lam.count > kMaxRows) return TV_ERR_LAMBDA;
+    size_t tb, pb, cb;
+    int st = check_2d(planes, H, W, sweeps, &tb, &pb, &cb);
+    if (st != TV_OK) return st;
+    if (planes == 0) return grad_lam ? zero_floats(grad_lam, lam.count, stream) : TV_OK;
+    if (!g_up || !grad_y) return TV_ERR_NULL;
+    if (!small_planes(H, W)) return TV_ERR_UNSUPPORTED;
+    if (((uintptr_t)g_up | (uintptr_t)grad_y) % 2 != 0) return TV_ERR_STRIDE;
+    if (!ws || !aligned16(ws) || ws_bytes < tb * (size_t)(2 * sweeps + 2) + (pb + cb) * (size_t)(2 * sweeps) + kSplitScratchBytes)
+        return TV_ERR_WORKSPACE;
+    char *base = (char *)ws;
+    float *partial = (float *)(base + tb * (size_t)(2 * sweeps + 2));
+    tvk::Small2dBwdParams q;
+    q.g_up = reinterpret_cast<const float *>(g_up); q.gy = reinterpret_cast<float *>(grad_y);
+    q.codes = (const uint2 *)(base + tb * (size_t)(2 * sweeps + 2) + pb * (size_t)(2 * sweeps));
+    q.code_stride = cb / sizeof(uint2);
+    q.saved = (const float *)base; q.saved_stride = tb / sizeof(float);
+    q.partial = grad_lam ? partial : nullptr;
+    q.planes = (int32_t)planes; q.H = (int32_t)H; q.W = (int32_t)W; q.sweeps = sweeps;
+    q.stream = (planes * H * W >= tvd::get(tvd::kStreamBytes) / 4) ? 1u : 0u;
+    TV_SMALL2D_LAUNCH_X(tvk::tv2d_bwd_small_kernel, q, planes, H, W, stream, false, true);
+    if (launch_status() != TV_OK) return TV_ERR_HIP;
+    if (!grad_lam) return TV_OK;
+    const tv_lambda lp = {lam.lam, lam.count, 1};
+    return launch_reduce_lambda(partial, grad_lam, planes, lp, 0, stream);
 }
 
 int tv2d_prox_bwd(const float *g_up, float *grad_y, float *grad_lam, int64_t planes, int64_t H,

@@ -6,8 +6,10 @@ sub-problems below Alg. 1).  Its trainable parameter passes through a SoftPlus s
 lambda handed to the operator is positive (Sec. 3.1); ``sharpen=True`` returns ``2 x - prox(x)``
 (the sharpening mode of Sec. 3.1).  Forward and backward are the library's kernels
 (``tv1d_prox_fwd_ex`` / ``tv1d_prox_bwd[_seg]`` and ``tv2d_prox_fwd`` / ``tv2d_prox_bwd``); torch
-only carries the tensors, the stream and the chain rule around them.  CUDA fp32 tensors only:
-there is no CPU path.
+only carries the tensors, the stream and the chain rule around them.  CUDA tensors only: there
+is no CPU path.  fp32 everywhere; bf16 feature maps (lambda stays fp32) where the library has
+bf16 storage: 2D on planes of at most 32 x 32 and 1D along the last axis of rows of 32 samples
+(fp32 arithmetic inside, see ``include/tvprox.h``).
 """
 from __future__ import annotations
 
@@ -20,11 +22,11 @@ from . import binding as _b
 _SEG_MAX = 32          # TV_SEG_MAX_LENGTH
 
 
-def _check_input(x: torch.Tensor, what: str) -> torch.Tensor:
+def _check_input(x: torch.Tensor, what: str, bf16_ok: bool = False) -> torch.Tensor:
     if not x.is_cuda:
         raise RuntimeError("%s: the TV layer runs on the GPU only (got a %s tensor)" % (what, x.device))
-    if x.dtype != torch.float32:
-        raise TypeError("%s: float32 expected, got %s" % (what, x.dtype))
+    if x.dtype != torch.float32 and not (bf16_ok and x.dtype == torch.bfloat16):
+        raise TypeError("%s: float32%s expected, got %s" % (what, " or bfloat16" if bf16_ok else "", x.dtype))
     return x.contiguous()
 
 
@@ -33,10 +35,13 @@ class _Prox1d(torch.autograd.Function):
 
     @staticmethod
     def forward(ctx, y, lam, axis, lam_div):
-        y = _check_input(y, "tv prox 1d")
+        y = _check_input(y, "tv prox 1d", bf16_ok=True)
         ctx.lam_shape = lam.shape                  # the gradient goes back in the caller's shape
         lam = _check_input(lam, "tv prox 1d (lambda)").reshape(-1)
         rows = _b.rows_along(tuple(y.shape), axis)
+        ctx.bf16 = y.dtype == torch.bfloat16
+        if ctx.bf16 and not (rows.length == 32 and rows.elem_stride == 1):
+            raise TypeError("tv prox 1d: bfloat16 only for rows of 32 samples along the last axis")
         L = _b.tv_lambda(lam.data_ptr(), lam.numel(), int(lam_div))
         n_rows = rows.n_outer * rows.n_inner
         x = torch.empty_like(y)
@@ -47,7 +52,10 @@ class _Prox1d(torch.autograd.Function):
         seg = None
         if rows.length <= _SEG_MAX:
             seg = torch.empty(max(n_rows, 1), dtype=torch.int64, device=y.device)
-        _b.tv1d_prox_fwd_ex(y, x, rows, L, seg=seg, ws=ws if wsb else None, ws_bytes=wsb)
+        if ctx.bf16:
+            _b.tv1d_prox_fwd_seg_bf16(y, x, seg, rows, L, ws if wsb else None, wsb)
+        else:
+            _b.tv1d_prox_fwd_ex(y, x, rows, L, seg=seg, ws=ws if wsb else None, ws_bytes=wsb)
         ctx.rows, ctx.lam_count, ctx.lam_div = rows, lam.numel(), int(lam_div)
         if seg is not None:
             ctx.save_for_backward(seg, lam)
@@ -60,7 +68,9 @@ class _Prox1d(torch.autograd.Function):
     @staticmethod
     def backward(ctx, g):
         saved, lam = ctx.saved_tensors
-        g = _check_input(g, "tv prox 1d (gradient)")
+        g = _check_input(g, "tv prox 1d (gradient)", bf16_ok=ctx.bf16)
+        if ctx.bf16 and g.dtype != torch.bfloat16:
+            g = g.to(torch.bfloat16)
         rows = ctx.rows
         L = _b.tv_lambda(lam.data_ptr(), ctx.lam_count, ctx.lam_div)
         gy = torch.empty_like(g)
@@ -68,7 +78,9 @@ class _Prox1d(torch.autograd.Function):
         gl = torch.empty(ctx.lam_count, dtype=torch.float32, device=g.device) if want_lam else None
         wsb = _b.tv1d_bwd_workspace_bytes(rows, L) if want_lam else 0
         ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device=g.device) if want_lam else None
-        if ctx.has_seg:
+        if ctx.bf16:
+            _b.tv1d_prox_bwd_seg_bf16(g, saved, gy, gl, rows, L, ws, wsb)
+        elif ctx.has_seg:
             _b.tv1d_prox_bwd_seg(g, saved, gy, gl, rows, L, ws, wsb)
         else:
             _b.tv1d_prox_bwd(g, saved, gy, gl, rows, L, ws, wsb)
@@ -80,16 +92,19 @@ class _Prox2d(torch.autograd.Function):
 
     @staticmethod
     def forward(ctx, y, lam, sweeps):
-        y = _check_input(y, "tv prox 2d")
+        y = _check_input(y, "tv prox 2d", bf16_ok=True)
         ctx.lam_shape = lam.shape                  # the gradient goes back in the caller's shape
         lam = _check_input(lam, "tv prox 2d (lambda)").reshape(-1)
         H, W = int(y.shape[-2]), int(y.shape[-1])
+        ctx.bf16 = y.dtype == torch.bfloat16
+        if ctx.bf16 and (H > _SEG_MAX or W > _SEG_MAX):
+            raise TypeError("tv prox 2d: bfloat16 only for planes of at most 32 x 32")
         planes = y.numel() // (H * W) if H * W else 0
         L = _b.tv_lambda(lam.data_ptr(), lam.numel(), 1)
         wsb = _b.tv2d_workspace_bytes(planes, H, W, int(sweeps))
         ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device=y.device)
         x = torch.empty_like(y)
-        _b.tv2d_prox_fwd(y, x, planes, H, W, L, int(sweeps), ws, wsb)
+        (_b.tv2d_prox_fwd_bf16 if ctx.bf16 else _b.tv2d_prox_fwd)(y, x, planes, H, W, L, int(sweeps), ws, wsb)
         ctx.dims = (planes, H, W, int(sweeps), wsb)
         ctx.save_for_backward(ws, lam)
         return x
@@ -98,14 +113,16 @@ class _Prox2d(torch.autograd.Function):
     def backward(ctx, g):
         ws, lam = ctx.saved_tensors
         planes, H, W, sweeps, wsb = ctx.dims
-        g = _check_input(g, "tv prox 2d (gradient)")
+        g = _check_input(g, "tv prox 2d (gradient)", bf16_ok=ctx.bf16)
+        if ctx.bf16 and g.dtype != torch.bfloat16:
+            g = g.to(torch.bfloat16)
         L = _b.tv_lambda(lam.data_ptr(), lam.numel(), 1)
         gy = torch.empty_like(g)
         want_lam = ctx.needs_input_grad[1]
         gl = torch.empty(lam.numel(), dtype=torch.float32, device=g.device) if want_lam else None
         # (the reverse sweep restarts from g and only reads the saved pass outputs; the two
         # correction tensors of the workspace are its scratch, so it may run again on the same graph)
-        _b.tv2d_prox_bwd(g, gy, gl, planes, H, W, L, sweeps, ws, wsb)
+        (_b.tv2d_prox_bwd_bf16 if ctx.bf16 else _b.tv2d_prox_bwd)(g, gy, gl, planes, H, W, L, sweeps, ws, wsb)
         return gy, (gl.reshape(ctx.lam_shape) if want_lam else None), None
 
 

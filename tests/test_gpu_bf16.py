@@ -99,3 +99,74 @@ def test_bf16_rejects_other_shapes():
     assert L.tv1d_prox_fwd_seg_bf16(FAKE, FAKE, FAKE, tv.rows_along((32, 8), 0), lam, None, 0, None) == 6
     assert L.tv1d_prox_fwd_seg_bf16(FAKE, FAKE, None, tv.rows_along((8, 32), -1), lam, None, 0, None) == 1
     assert L.tv1d_prox_fwd_seg_bf16(FAKE + 2, FAKE, FAKE, tv.rows_along((8, 32), -1), lam, None, 0, None) == 3
+
+
+# ---- the 2D pair with bf16 storage (planes of at most 32 x 32, one-launch kernels)
+
+
+@pytest.mark.parametrize("shape,K", [((70, 32, 32), 3), ((5, 32, 32), 1), ((37, 28, 30), 2), ((90, 16, 16), 4),
+                                     ((33, 13, 16), 2), ((130, 8, 8), 3), ((21, 5, 7), 2), ((3, 1, 32), 2)])
+def test_bf16_2d_pair_equals_rounded_fp32_one_launch_kernels(shape, K):
+    """x is bit for bit the rounded output of the fp32 one-launch kernel on the widened input, the
+    saved passes and segment codes are identical, grad_y is the rounded fp32 grad_y and grad_lam
+    is identical; and the oracle's K-sweep result lies within bf16 rounding of x."""
+    import torch
+
+    import paper_2204_03643_amd as tv
+
+    rng = np.random.default_rng(500 + shape[1] * 40 + shape[2])
+    y_bits = _to_bf16_bits(rng.normal(size=shape))
+    g_bits = _to_bf16_bits(rng.normal(size=shape))
+    lam = (10 ** rng.uniform(-2, 0.3, size=3)).astype(np.float32)
+    dev = torch.device("cuda:0")
+    P, H, W = shape
+    lt = torch.from_numpy(lam).to(dev)
+    L = tv.tv_lambda(lt.data_ptr(), 3, 1)
+    wsb = tv.tv2d_workspace_bytes(P, H, W, K)
+    yt, gt = (torch.from_numpy(b.view(np.int16)).to(dev) for b in (y_bits, g_bits))
+    ws = torch.zeros(wsb, dtype=torch.uint8, device=dev)
+    xt, gy = torch.full_like(yt, -1), torch.full_like(yt, -1)
+    gl = torch.full((3,), float("nan"), device=dev)
+    tv.tv2d_prox_fwd_bf16(yt, xt, P, H, W, L, K, ws, wsb)
+    tv.tv2d_prox_bwd_bf16(gt, gy, gl, P, H, W, L, K, ws, wsb)
+    # the fp32 call on the widened input, forced onto the one-launch kernels
+    saved_thr = tv.tv_dispatch_thresholds()
+    try:
+        tv.tv_dispatch_override("tiny_batch_planes", 0)
+        for name in ("fused32_full_planes", "fused32_full_planes_k2", "fused32_full_planes_k3",
+                     "fused32_ragged_planes", "fused16_one_sweep_planes"):
+            tv.tv_dispatch_override(name, 1 << 40)
+        yf, gf = (torch.from_numpy(_widen(b)).to(dev) for b in (y_bits, g_bits))
+        wsf = torch.zeros(wsb, dtype=torch.uint8, device=dev)
+        xf, gyf, glf = torch.empty_like(yf), torch.empty_like(yf), torch.empty_like(gl)
+        tv.tv2d_prox_fwd(yf, xf, P, H, W, L, K, wsf, wsb)
+        tv.tv2d_prox_bwd(gf, gyf, glf, P, H, W, L, K, wsf, wsb)
+        torch.cuda.synchronize()
+    finally:
+        for k, v in saved_thr.items():
+            tv.tv_dispatch_override(k, v)
+    x = xt.cpu().numpy().view(np.uint16)
+    assert np.array_equal(x, _to_bf16_bits(xf.cpu().numpy()))
+    assert np.array_equal(gy.cpu().numpy().view(np.uint16), _to_bf16_bits(gyf.cpu().numpy()))
+    assert np.array_equal(gl.cpu().numpy(), glf.cpu().numpy())
+    nt = P * H * W
+    tensor_bytes = (nt * 4 + 15) // 16 * 16
+    assert torch.equal(ws[:2 * K * tensor_bytes], wsf[:2 * K * tensor_bytes])          # saved passes
+    # the oracle on the widened input
+    y64 = _widen(y_bits).astype(np.float64)
+    x_ref, _ = oracle.prox2d_fwd(y64, lam.astype(np.float64), K)
+    err = np.abs(_widen(x).astype(np.float64) - x_ref)
+    assert np.all(err <= FWD_TOL * (1 + np.abs(y64).max()) + 2.0 ** -8 * np.abs(x_ref))
+
+
+def test_bf16_2d_rejects_larger_planes():
+    import torch
+
+    import paper_2204_03643_amd as tv
+    t = torch.zeros(40 * 40, dtype=torch.int16, device="cuda:0")
+    lt = torch.ones(1, device="cuda:0")
+    wsb = tv.tv2d_workspace_bytes(1, 40, 40, 1)
+    ws = torch.empty(wsb, dtype=torch.uint8, device="cuda:0")
+    with pytest.raises(tv.TVError) as e:
+        tv.tv2d_prox_fwd_bf16(t, t.clone(), 1, 40, 40, tv.tv_lambda(lt.data_ptr(), 1, 1), 1, ws, wsb)
+    assert e.value.status == 6

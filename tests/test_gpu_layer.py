@@ -107,3 +107,32 @@ def test_lambda_of_any_shape_and_a_second_backward():
     assert gl.shape == (3, 1, 1)
     gx_again, gl_again = torch.autograd.grad(y, (x, lam), g)
     assert torch.equal(gx, gx_again) and torch.equal(gl, gl_again)
+
+
+def test_bf16_feature_maps_through_the_layer():
+    """bf16 feature maps (32 x 32, lambda fp32): the layer's 2D and row modes run on the library's
+    bf16-storage kernels; outputs and input gradients are bf16 and equal the fp32 layer's on the
+    same (widened) tensors up to bf16 rounding, the lambda gradient up to fp32 rounding order."""
+    import torch
+
+    from paper_2204_03643_amd.layer import TVLayer
+
+    rng = np.random.default_rng(77)
+    x32 = torch.from_numpy(rng.normal(size=(3, 4, 32, 32)).astype(np.float32)).cuda()
+    g32 = torch.from_numpy(rng.normal(size=(3, 4, 32, 32)).astype(np.float32)).cuda()
+    xb, gb = x32.to(torch.bfloat16), g32.to(torch.bfloat16)
+    for mode in ("2d", "rows"):
+        layer = TVLayer(4, mode=mode, sweeps=3).cuda()
+        a = xb.clone().requires_grad_(True)
+        ya = layer(a)
+        assert ya.dtype == torch.bfloat16
+        ga, gla = torch.autograd.grad(ya, (a, layer.raw_lambda), gb)
+        assert ga.dtype == torch.bfloat16
+        b = xb.float().requires_grad_(True)
+        yb = layer(b)
+        gbx, glb = torch.autograd.grad(yb, (b, layer.raw_lambda), gb.float())
+        assert float((ya.float() - yb).abs().max()) <= 2.0 ** -7 * float(yb.abs().max())
+        assert float((ga.float() - gbx).abs().max()) <= 2.0 ** -7 * float(gbx.abs().max())
+        assert torch.allclose(gla, glb, rtol=1e-3, atol=1e-3)
+    with pytest.raises(TypeError):
+        TVLayer(4, mode="cols").cuda()(xb)
