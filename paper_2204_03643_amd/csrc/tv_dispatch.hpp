@@ -24,6 +24,7 @@ enum {
     kFused32FullPlanesK3,
     kFused32RaggedPlanes,
     kFused16OneSweepPlanes,
+    kFused64Planes,
     kThreadPerSampleWideRows,
     kMlMinLength,
     kMlCoarsest,
@@ -69,6 +70,13 @@ inline Threshold table[kCount] = {
     // pass by pass, 20 480: 49 / 55, 32 768: 69 / 58 (K = 3: 166 against 206, so several sweeps
     // always take the one launch).
     {"fused16_one_sweep_planes", 24576, "2D planes of at most 16 x 16, one sweep: one launch up to this many planes"},
+    // 2D, planes of 33-64 samples a side: all passes in one launch, a plane per wave and a row or
+    // column per lane (the solver then fills the register file: 256 VGPRs + 256 AGPRs, one wave per
+    // SIMD), against pass by pass with eight threads per row.  The one launch never wins: 64 x 64,
+    // K = 4: 64 planes 541 / 168, 1024 planes 616 / 324, 8192 planes 3390 / 1577; 48 x 48, K = 1:
+    // 256 planes 153 / 54.  It is kept (and tested) as the stated variant for planes of up to
+    // 64 x 64; the default of 0 planes means "never".
+    {"fused64_planes", 0, "2D planes of 33-64 samples a side: one launch up to this many planes"},
     // Rows of at most 32 samples on the long-row kernels (only the 2D operator on small batches
     // of planes asks for that): 16 threads x 2 samples up to this many rows, 8 x 4 beyond
     // (256 planes of 32 x 32, K = 10: 204 -> 180 with 16 x 2).

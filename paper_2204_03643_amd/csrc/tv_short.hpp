@@ -30,8 +30,7 @@ struct ShortSmem {
 template <int NMAX>
 __device__ __forceinline__ void fill_tables(float *gtab, float *rtab)
 {
-    const int t = threadIdx.x;
-    if (t <= NMAX) {
+    for (int t = threadIdx.x; t <= NMAX; t += kShortBlock) {
         gtab[t] = (float)t / (float)(t + 1);
         rtab[t] = t > 0 ? 1.0f / (float)t : 0.0f;
     }

@@ -348,8 +348,11 @@ struct Small2dFwdParams {
 
 // S, FULL: as in the reverse sweep (a wave holds 64 / S planes).
 // IO16: y and x are bf16 in memory; the saved pass outputs stay fp32.
+// S = 64 (planes of 33-64 samples a side, one per wave): the row-per-lane solver then holds four
+// arrays of 64 registers, the whole register file of a SIMD lane (256 VGPRs + 256 AGPRs), one wave
+// per SIMD; no segment codes are written (the reverse sweep reads the saved pass outputs).
 template <int S, bool FULL, bool IO16 = false>
-__global__ __launch_bounds__(64, 2) void tv2d_fwd_small_kernel(Small2dFwdParams p)
+__global__ __launch_bounds__(64, S <= 32 ? 2 : 1) void tv2d_fwd_small_kernel(Small2dFwdParams p)
 {
     constexpr int P = S + 1;
     constexpr int PP = 64 / S;
@@ -440,7 +443,7 @@ __global__ __launch_bounds__(64, 2) void tv2d_fwd_small_kernel(Small2dFwdParams 
         for (int it = 0; !sv.iterate(it); ++it) {}
         sv.recover(xs);
 
-        {   // segment code of the row / column (as the short-row kernel builds it)
+        if constexpr (S <= 32) {   // segment code of the row / column (as the short-row kernel builds it)
             uint32_t jm = 0, up = 0;
 #pragma unroll
             for (int k = S - 2; k >= 0; --k) {

@@ -1195,6 +1195,21 @@ int tv2d_prox_fwd(const float *y, float *x, int64_t planes, int64_t H, int64_t W
         TV_SMALL2D_LAUNCH(tvk::tv2d_fwd_small_kernel, q, planes, H, W, stream);
         return launch_status();
     }
+    if (!cb && H <= 64 && W <= 64 && planes <= tvd::get(tvd::kFused64Planes)) {
+        // planes of 33-64 samples a side: all passes in one launch, a plane per wave
+        tvk::Small2dFwdParams q;
+        q.y = y; q.x = x; q.saved = saved(0); q.saved_stride = tb / sizeof(float);
+        q.codes = nullptr; q.code_stride = 0;
+        q.lam = lam.lam; q.lam_count = lam.count;
+        q.planes = (int32_t)planes; q.H = (int32_t)H; q.W = (int32_t)W; q.sweeps = sweeps;
+        q.stream = (planes * H * W >= tvd::get(tvd::kStreamBytes) / 4) ? 1u : 0u;
+        const dim3 grid((uint32_t)planes);
+        if (H == 64 && W == 64)
+            hipLaunchKernelGGL((tvk::tv2d_fwd_small_kernel<64, true>), grid, dim3(64), 0, stream, q);
+        else
+            hipLaunchKernelGGL((tvk::tv2d_fwd_small_kernel<64, false>), grid, dim3(64), 0, stream, q);
+        return launch_status();
+    }
     for (int k = 0; k < sweeps; ++k) {
         const bool last = (k == sweeps - 1);
         const float *Yk = (k == 0) ? y : saved(2 * k - 1);

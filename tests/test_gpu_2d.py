@@ -175,3 +175,22 @@ def test_every_forward_mapping_of_small_planes(shape, K, dispatch_defaults):
     # every mapping solves the same problems to rounding: outputs agree far inside the parity bar
     for o in outs[1:]:
         assert np.abs(o["x"] - outs[0]["x"]).max() <= 2e-5 * (1 + np.abs(y).max())
+
+
+@pytest.mark.parametrize("shape,K", [((5, 64, 64), 3), ((3, 40, 56), 2), ((4, 33, 64), 2), ((2, 64, 35), 1),
+                                     ((70, 48, 48), 4), ((1, 33, 33), 1)])
+def test_one_launch_forward_for_planes_of_33_to_64(shape, K, dispatch_defaults):
+    """All 2K passes of planes of 33-64 samples a side in one launch (a plane per wave, a row or
+    column per lane): slower than pass by pass at every size measured, so the dispatch never picks
+    it by itself; forced here, it must meet the same parity rules, reverse sweep included (one
+    launch for 64 x 64, pass by pass otherwise, both from the saved pass outputs)."""
+    import paper_2204_03643_amd as tv
+    rng = np.random.default_rng(61 + shape[1] + shape[2])
+    y = rng.normal(size=shape).astype(np.float32)
+    g = rng.normal(size=shape).astype(np.float32)
+    lam = (10 ** rng.uniform(-2, 0.3, size=2)).astype(np.float32)
+    ref = run_2d(y, lam, K, g)
+    tv.tv_dispatch_override("fused64_planes", 1 << 40)
+    out = run_2d(y, lam, K, g)
+    check_2d(y, lam, K, g, out, "one launch %s K=%d" % (shape, K))
+    assert np.abs(out["x"] - ref["x"]).max() <= 2e-5 * (1 + np.abs(y).max())
