@@ -153,6 +153,8 @@ size_t tv1d_fwd_workspace_bytes(tv_rows rows, tv_lambda lam);
  *   [48 + k], k < length - 1: the dual u the first iteration starts from,
  *   [48 + length + k]: the Newton direction d of the first iteration (the solution of
  *        H_SS d_S = grad_S on the free set S, 0 on the bound duals; the step is clip(u - alpha d)),
+ *        left untouched for a row of up to 32 samples whose start already passes the optimality
+ *        test (info reports 0 steps),
  *   [48 + 2 length + k]: 1 where the first iteration holds dual k on its bound, else 0.
  * Rows of up to 32 samples run the general row-per-lane kernel; longer rows (unit element stride
  * only: TV_ERR_UNSUPPORTED otherwise) one of three mappings: a wavefront per row up to 512

@@ -15,6 +15,12 @@ constexpr float kArmijoSlackEps  = 4.0f * 1.1920929e-7f;  // slack = this * |f|
 // dual that sits on its bound with such a gradient satisfies the KKT conditions (zero
 // multiplier) and must not keep the optimality test from firing.
 constexpr float kGradNoise       = 16.0f * 1.1920929e-7f;
+// The Newton decrement g^T H_S^-1 g is twice the distance of the dual objective from its minimum
+// over the free subspace, and that distance bounds 1/2 ||x - x*||^2 there.  Below
+// kDecNoise * f (the square of the same 16 ulp) no step can lower f by an amount that fp32
+// resolves: a row with such a decrement and no dual held against an inward gradient is at
+// its solution (||x - x*|| <= 16 ulp * sqrt(2 f)).
+constexpr float kDecNoise        = kGradNoise * kGradNoise;
 
 // info word written per row by the *_info entry point
 constexpr int kInfoConverged = 1 << 16;
@@ -96,7 +102,8 @@ constexpr int kMlFactor = 4;
 //   [kRecF + i], i = 0 .. [0]: the dual objective f = 1/2 ||x(u)||^2 at the start and after
 //        every accepted step (at most kRecMaxF entries; later ones are dropped);
 //   [kRecU + k], k < n - 1: the dual the first iteration starts from;
-//   [kRecU + n + k]: the Newton direction d of the first iteration (u <- clip(u - alpha d));
+//   [kRecU + n + k]: the Newton direction d of the first iteration (u <- clip(u - alpha d)); not
+//        written for a row whose start already passes the optimality test (it takes no step);
 //   [kRecU + 2n + k]: 1 where the first iteration holds dual k on its bound, else 0.
 constexpr int kRecF = 8, kRecMaxF = 40, kRecU = 48;
 __host__ __device__ constexpr int64_t step_record_floats(int64_t n) { return kRecU + 3 * n; }

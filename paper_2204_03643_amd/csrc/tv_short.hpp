@@ -625,9 +625,27 @@ struct RowSolver {
                 tprev = t;
             }
         }
-        // A full, unclipped Newton step zeroes the gradient on the free set; if no dual
-        // sits on a bound with the gradient pointing inwards, the KKT conditions hold.
-        if (active && prev_unclipped && !vio) { active = false; flags = kInfoConverged; }
+        asm volatile("" : "+v"(dec));               // summed here, not later from kept products
+        if constexpr (DEBUG) {
+            // (a row that stops right here has taken no step: its record then holds the start, the
+            // bound set and no direction)
+            if (rec && it == 0) {
+                rec[kRecF] = fcur;
+#pragma unroll
+                for (int k = 0; k < M; ++k)
+                    if (FULL || k < m) {
+                        rec[kRecU + k] = u[k];
+                        rec[kRecU + 2 * (m + 1) + k] = G[k] == 0.f ? 1.f : 0.f;
+                    }
+            }
+        }
+        // A full, unclipped Newton step zeroes the gradient on the free set, and so does any
+        // point whose Newton decrement is below what fp32 resolves (see kDecNoise; a start that
+        // is already the solution is caught here before any step is taken); if no dual sits on
+        // a bound with the gradient pointing inwards, the KKT conditions hold.
+        if (active && !vio && (prev_unclipped || dec <= fmaxf(kDecNoise * fcur, gtol * gtol))) {
+            active = false; flags = kInfoConverged;
+        }
         if (active && it >= kMaxNewtonSteps) { active = false; flags = kInfoCapped; }
         if (!__any(active)) return true;
         steps += active ? 1 : 0;
@@ -648,14 +666,9 @@ struct RowSolver {
         }
         if constexpr (DEBUG) {
             if (rec && it == 0) {
-                rec[kRecF] = fcur;
 #pragma unroll
                 for (int k = 0; k < M; ++k)
-                    if (FULL || k < m) {
-                        rec[kRecU + k] = u[k];
-                        rec[kRecU + (m + 1) + k] = D[k];
-                        rec[kRecU + 2 * (m + 1) + k] = G[k] == 0.f ? 1.f : 0.f;
-                    }
+                    if (FULL || k < m) rec[kRecU + (m + 1) + k] = D[k];
             }
         }
         // ---- projected step u(alpha) = clip(u - alpha d); alpha = 1 is taken outright when
@@ -666,27 +679,77 @@ struct RowSolver {
         //      iteration with a step length from quadratic interpolation; that is rare (under
         //      one row in a hundred), so the direction is simply recomputed there.
         const float alpha = active ? alpha_try : 0.f;
-        bool changed = false;
-        float acc = 0.f, prev = 0.f, tmax = 0.f;
+        float tmax = 0.f;
 #pragma unroll
         for (int k = 0; k < M; ++k) {
             const float l = lk(k);
             const float uo = u[k];
             const float t = fmaf(-alpha, D[k], uo);
-            const float c = __builtin_amdgcn_fmed3f(t, -l, l);
             tmax = fmaxf(tmax, fabsf(t));
-            changed |= (c != uo);
+            G[k] = uo;
+            u[k] = __builtin_amdgcn_fmed3f(t, -l, l);
+        }
+        const bool clipped = tmax > lam;
+        // ---- A clipped trial point is polished by two sweeps of projected coordinate descent on
+        //      the dual (u_k <- clip((u_{k-1} + u_{k+1} + y_{k+1} - y_k) / 2), the exact minimiser of
+        //      Eq. 3 over one dual), one in each direction.  The direction was computed as if the
+        //      duals that the projection stops were free to move, so the free duals next to them
+        //      overshoot: the sweeps repair that locally, only ever lower the dual objective, and
+        //      the polished point then has to pass the same Armijo test.  Measured on the
+        //      workloads, rejected trials all but vanish (0.17 -> 0.005 per row on post-ReLU maps)
+        //      and the slowest row of a wave needs 6 iterations where it needed 16.  The wave does
+        //      it for all its unfinished rows whenever one of them clipped.  A row that took the
+        //      full step unclipped is still accepted outright (the sweeps lower its objective by
+        //      less than the rounding error of the Armijo test), but no longer counts as sitting
+        //      on the minimiser of its free subspace: that costs it one more iteration, which the
+        //      wave runs anyway for the row that clipped.
+        const bool polish = __any(clipped && active);
+        if (polish) {
+            // (the constant is made opaque so that these differences are formed here, after the
+            // direction in D is spent, and not ahead of the branch, where they would need registers
+            // of their own)
+            float half = 0.5f;
+            asm volatile("" : "+v"(half));
+#pragma unroll
+            for (int k = 0; k < M; ++k) D[k] = half * (X[k + 1] - X[k]);     // X holds y here
+            float up = 0.f;
+#pragma unroll
+            for (int k = 0; k < M; ++k) {
+                const float l = lk(k);
+                const float un = (k + 1 < M) ? u[k + 1] : 0.f;
+                up = __builtin_amdgcn_fmed3f(fmaf(0.5f, up + un, D[k]), -l, l);
+                u[k] = up;
+            }
+            float un = 0.f;
+#pragma unroll
+            for (int k = M - 1; k >= 0; --k) {
+                const float l = lk(k);
+                const float ul = (k > 0) ? u[k - 1] : 0.f;
+                un = __builtin_amdgcn_fmed3f(fmaf(0.5f, ul + un, D[k]), -l, l);
+                u[k] = active ? un : G[k];          // a finished row keeps its dual
+                un = u[k];
+            }
+        }
+        bool changed = false;
+        float acc = 0.f, prev = 0.f;
+#pragma unroll
+        for (int k = 0; k < M; ++k) {
+            const float c = u[k];
+            changed |= (c != G[k]);
             const float xc = X[k] + c - prev;       // X[k] holds y_k here
             acc = fmaf(xc, xc, acc);
-            G[k] = uo; u[k] = c; X[k] = xc; prev = c;
+            X[k] = xc; prev = c;
         }
         {
             const float xc = X[M] - prev;
             acc = fmaf(xc, xc, acc);
             X[M] = xc;
         }
-        const bool clipped = tmax > lam;
         const float fc = 0.5f * acc;
+        // a row with NaN in it stops here and leaves x = y - D^T u as it stands (NaN at the samples
+        // that were NaN at least; the clipping of the sweeps above would otherwise wash the NaN
+        // out of the dual and the row would go on as if it were sound)
+        if (active && fc != fc) { active = false; flags = kInfoStalled | kInfoPlain; }
         const bool ok = !active || (alpha == 1.f && !clipped) ||
                         (fc <= fcur - kArmijoSigma * alpha * dec + kArmijoSlackEps * fabsf(fcur));
         if (__any(!ok)) {
@@ -716,14 +779,17 @@ struct RowSolver {
         }
         if (ok && active) {
             fcur = fc;
-            prev_unclipped = (alpha == 1.f) && !clipped;
+            prev_unclipped = (alpha == 1.f) && !clipped && !polish;
             alpha_try = 1.f;
             nfail = 0;
             if (!changed) {
                 // a step that moves nothing: a KKT point if it was a full step with no dual
-                // held against an inward gradient; otherwise the line search has run dry
+                // held against an inward gradient, or a full step that the sweeps took back (a
+                // point no single dual can improve is the minimiser of a convex function over a
+                // box; the inward gradient was rounding noise above the floor); otherwise the line
+                // search has run dry
                 active = false;
-                flags = kInfoStalled | ((alpha == 1.f && !vio) ? 0 : kInfoPlain);
+                flags = kInfoStalled | ((alpha == 1.f && (!vio || polish)) ? 0 : kInfoPlain);
             }
         }
         if (!__any(active)) {
@@ -773,7 +839,9 @@ struct RowSolver {
                 tprev = t;
             }
         }
-        if (active && prev_unclipped && !vio) { active = false; flags = kInfoConverged; }
+        if (active && !vio && (prev_unclipped || dec <= fmaxf(kDecNoise * fcur, gtol * gtol))) {
+            active = false; flags = kInfoConverged;
+        }
         if (active && it >= kMaxNewtonSteps) { active = false; flags = kInfoCapped; }
         if (!__any(active)) return true;
         steps += active ? 1 : 0;
@@ -896,9 +964,13 @@ struct RowSolver {
 // IO16 (NMAX = 32, FULL, PACKED, no addend / second output / residual): y and x are bf16.
 // DEBUG: the first p.debug_rows rows leave a step record in p.debug (see step_record_floats).
 // PSEARCH: the step size comes from the parallel search over halving step sizes (iterate_psearch).
+// (The variants for rows of exactly NMAX samples are asked to leave room for 3 waves per SIMD
+// : the 32-sample one fits 150 registers when told so and takes
+// some 200 when left alone.  The others are left alone; held to that budget they spill.)
 template <int NMAX, bool FULL, bool PACKED, bool WARM = false, bool PLANE = false, bool IO16 = false,
           bool DEBUG = false, bool PSEARCH = false>
-__global__ __launch_bounds__(kShortBlock) void tv1d_fwd_short_kernel(FwdParams p)
+__global__ __launch_bounds__(kShortBlock) __attribute__((amdgpu_waves_per_eu((FULL && !DEBUG && !PSEARCH) ? 3 : 1)))
+void tv1d_fwd_short_kernel(FwdParams p)
 {
     using S = ShortSmem<NMAX>;
     __shared__ float smem[S::kFloats];

@@ -140,8 +140,8 @@ def test_info_word_reports_convergence():
 
 
 def test_info_word_of_lambda_zero_rows():
-    """lambda = 0 is the identity (Sec. 3.1): the row stops at once, and its info word must not
-    claim that it stopped short of an optimal point (bit 19)."""
+    """lambda = 0 is the identity (Sec. 3.1): the row stops before any Newton step, and its info
+    word must not claim that it stopped short of an optimal point (bit 19)."""
     rng = np.random.default_rng(8)
     y = rng.normal(size=(200, 32)).astype(np.float32)
     lam = np.where(np.arange(200) % 3 == 0, 0.0, 0.3).astype(np.float32)
@@ -149,7 +149,7 @@ def test_info_word_of_lambda_zero_rows():
     zero = lam == 0
     assert np.array_equal(out["x"][zero], y[zero])
     assert not np.any(out["info"] & (1 << 19)) and not np.any(out["info"] & (1 << 18))
-    assert np.all((out["info"][zero] & 0xffff) == 1)
+    assert np.all((out["info"][zero] & 0xffff) == 0) and np.all(out["info"][zero] & (1 << 16))
     y17 = rng.normal(size=(70, 17)).astype(np.float32)
     out = run_1d(y17, np.zeros(1, np.float32), 1, want_info=True)
     assert np.array_equal(out["x"], y17) and not np.any(out["info"] & (1 << 19))

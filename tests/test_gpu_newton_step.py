@@ -91,12 +91,16 @@ def test_newton_direction_objective_descent_and_gap(n, rows, noise):
     for r in range(rows):
         q = rec[r]
         steps, l = int(q[0]), float(q[1])
-        assert 1 <= steps <= (info[r] & 0xffff), (n, r, steps, info[r])
+        assert steps <= (info[r] & 0xffff), (n, r, steps, info[r])
         assert abs(l - lam[r]) <= 1e-6 * lam[r]
         u0 = q[48:48 + n - 1].astype(np.float64)
-        d_gpu = q[48 + n:48 + 2 * n - 1].astype(np.float64)
         bound = q[48 + 2 * n:48 + 3 * n - 1] != 0
-        assert not np.any(np.isnan(q[48:48 + n - 1])) and not np.any(np.isnan(d_gpu))
+        assert not np.any(np.isnan(q[48:48 + n - 1]))
+        # a row whose start already passes the optimality test takes no step and records no direction
+        took_step = (info[r] & 0xffff) >= 1
+        assert took_step or steps == 0
+        d_gpu = q[48 + n:48 + 2 * n - 1].astype(np.float64) if took_step else np.zeros(n - 1)
+        assert not np.any(np.isnan(d_gpu))
         # bound duals sit exactly on the box, and the direction vanishes there
         assert np.all(np.abs(q[48:48 + n - 1][bound]) == np.float32(l))
         assert np.all(d_gpu[bound] == 0.0)
@@ -116,7 +120,7 @@ def test_newton_direction_objective_descent_and_gap(n, rows, noise):
         assert abs(q[8] - 0.5 * np.sum(x0 ** 2)) <= 1e-5 * (1 + 0.5 * np.sum(x0 ** 2))
         # the Newton direction
         run = _longest_free_run(bound)
-        if run <= 64:
+        if run <= 64 and took_step:
             d_cf = _closed_form_direction(g, bound)
             d_dn = _dense_direction(g, bound)
             # (floor: the fp32 gradient carries rounding noise of x = y - D^T u, which a run of m
