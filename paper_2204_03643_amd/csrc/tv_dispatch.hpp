@@ -39,36 +39,37 @@ inline Threshold table[kCount] = {
     // 3-9 % slower with it.
     {"stream_bytes", (int64_t)96 << 20, "non-temporal accesses from this tensor size on"},
     // The slot order of the row-per-lane forward kernel costs a 5 us kernel of one workgroup and
-    // shortens the drain of the main kernel: 2^20 rows 97 -> 80 + 5; 2^17 rows 45 -> 44 + 5.  The
-    // library computes the order whenever it is handed the workspace; this is where the layer
-    // (layer.py) starts to hand it over.
-    {"order_min_rows", (int64_t)1 << 18, "the layer passes the slot-order workspace from this many rows on"},
+    // shortens the drain of the main kernel: 2^20 rows 87 -> 77 + 5 (forward and backward calls
+    // alternating); 2^18 rows 35 -> 35 + 5, 2^17 rows 30 -> 29 + 5.  The library computes the order
+    // whenever it is handed the workspace; this is where the layer (layer.py) starts to hand it over.
+    {"order_min_rows", (int64_t)1 << 19, "the layer passes the slot-order workspace from this many rows on"},
     // 2D, planes of 17-32 samples a side: up to this many planes the 2K forward passes run one by
     // one on the thread-per-few-samples kernels (a lone row-per-lane wave per SIMD issues an
-    // instruction every 9 cycles): 256 planes, K = 10: 507 -> 180; 1536 planes: 526 -> 347
-    // (feature-map-like data), 437 -> 361 (white noise); around 2000 planes the one-launch kernel
-    // catches up (2048 planes, K = 3: 123-151 against 135-140).
-    {"tiny_batch_planes", 1536, "2D planes of 17-32 a side: pass by pass on the long-row kernels up to this many planes"},
+    // instruction every 9 cycles).  Forward + backward, pass by pass on those kernels against the
+    // one-launch kernel, feature-map-like data: K = 1: 256 planes 52 / 61, 768: 58 / 60, 1024:
+    // 64 / 66, 1536: 69 / 66; K = 2: 512 planes 85 / 86, 768: 90 / 98, 1024: 99 / 96; K = 4: 256
+    // planes 127 / 145, 512: 148 / 145, 768: 161 / 160, 1536: 204 / 167.
+    {"tiny_batch_planes", 768, "2D planes of 17-32 a side: pass by pass on the long-row kernels up to this many planes"},
     // 2D, planes of exactly 32 x 32: the one-launch forward kernel holds two waves per SIMD (17 KB
     // of LDS per wave) where the pass-by-pass kernels hold three, but pays no launches and no
     // memory round trips between the passes, which weighs more the more sweeps there are.
-    // One launch against pass by pass, feature-map-like data (white noise within 10 %):
-    //   K = 1:  4096 planes  74 /  90,  6144: 109 /  93,  8192: 123 / 121, 16 384: 218 / 177;
-    //   K = 2:  4096 planes 123 / 182,  8192: 219 / 250, 12 288: 305 / 323 (noise 285 / 274), 16 384: 388 / 373;
-    //   K = 4:  4096 planes 204 / 359,  8192: 369 / 498, 16 384: 676 / 699, 32 768: 1244 / 1207.
-    // (4097 planes still take 72 / 84, 219 / 261 with K = 2, 16 385 planes 676 / 757 with K = 4: the
-    // one launch loses its lead gradually over its second round of waves.)
-    {"fused32_full_planes", 4608, "2D planes of 32 x 32, one sweep: all passes in one launch up to this many planes"},
-    {"fused32_full_planes_k2", 10240, "... two sweeps"},
-    {"fused32_full_planes_k3", 24576, "... three sweeps or more"},
+    // One launch against pass by pass, forward + backward, feature-map-like data:
+    //   K = 1:  4096 planes  75 /  80,  4608: 100 /  85,  6144: 115 /  95, 16 384: 235 / 188;
+    //   K = 2:  4096 planes 112 / 147,  6144: 187 / 178,  8192: 209 / 233, 16 384: 392 / 392, 24 576: 579 / 553;
+    //   K = 4:  4096 planes 190 / 291,  8192: 365 / 435, 16 384: 663 / 709, 32 768: 1226 / 1254.
+    // (The one launch holds 4096 planes at once: it loses ground over its second round of waves
+    // and wins it back when that round is full.)
+    {"fused32_full_planes", 4096, "2D planes of 32 x 32, one sweep: all passes in one launch up to this many planes"},
+    {"fused32_full_planes_k2", 16384, "... two sweeps"},
+    {"fused32_full_planes_k3", 32768, "... three sweeps or more"},
     // 2D, planes of 17-32 samples a side that do not fill 32 x 32, single sweep (with two sweeps
     // or more the one launch always wins: 28 x 28, 32 768 planes, K = 4: 1.46 ms against 1.94).
-    // 28 x 28, K = 1, one launch against pass by pass: 4096 planes 96 / 122, 5120: 134 / 125,
-    // 6144: 136 / 131, 8192: 148 / 155.
-    {"fused32_ragged_planes", 4352, "2D ragged planes padded to 32 x 32, one sweep: one launch up to this many planes"},
-    // 2D, planes of 9-16 samples a side, single sweep: 16 384 planes 47 in one launch against 47
-    // pass by pass, 20 480: 49 / 55, 32 768: 69 / 58 (K = 3: 166 against 206, so several sweeps
-    // always take the one launch).
+    // 28 x 28, K = 1, one launch against pass by pass, forward + backward: 2048 planes 91 / 98,
+    // 4096: 96 / 101, 4352: 127 / 105, 5120: 140 / 120, 6144: 154 / 122.
+    {"fused32_ragged_planes", 4096, "2D ragged planes padded to 32 x 32, one sweep: one launch up to this many planes"},
+    // 2D, planes of 9-16 samples a side, single sweep, forward + backward: 16 384 planes 58 in one
+    // launch against 58 pass by pass, 24 576: 70 / 75, 32 768: 88 / 86 (K = 3: 166 against 206
+    // forward, so several sweeps always take the one launch).
     {"fused16_one_sweep_planes", 24576, "2D planes of at most 16 x 16, one sweep: one launch up to this many planes"},
     // 2D, planes of 33-64 samples a side: all passes in one launch, a plane per wave and a row or
     // column per lane (the solver then fills the register file: 256 VGPRs + 256 AGPRs, one wave per

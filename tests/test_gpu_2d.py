@@ -68,10 +68,10 @@ def test_odd_sizes_mixed_paths():
                                      ((37, 16, 16), 3), ((11, 13, 16), 2), ((3, 16, 9), 4), ((70, 8, 8), 2),
                                      ((9, 5, 7), 3), ((13, 8, 3), 2), ((5, 1, 8), 2), ((6, 12, 1), 2),
                                      ((4099, 8, 8), 1), ((2050, 16, 16), 2),
-                                     # more than 1536 planes of 17-32 samples a side: the one-launch forward
+                                     # more than 768 planes of 17-32 samples a side: the one-launch forward
                                      ((1600, 32, 32), 2), ((1540, 19, 27), 3), ((1537, 32, 20), 1)])
 def test_small_planes(shape, K):
-    # planes of at most 32 x 32, ragged in both directions: up to 1536 planes of 17-32 samples a side
+    # planes of at most 32 x 32, ragged in both directions: up to 768 planes of 17-32 samples a side
     # pass by pass on the long-row kernels (reverse sweep from the saved outputs), otherwise the
     # one-launch kernels
     rng = np.random.default_rng(73 + shape[1] * 64 + shape[2])
@@ -83,10 +83,10 @@ def test_small_planes(shape, K):
 
 @pytest.mark.parametrize("shape,K", [((6200, 20, 9), 1), ((4099, 20, 9), 2), ((4097, 32, 32), 2), ((16390, 16, 16), 1)])
 def test_many_small_planes(shape, K):
-    # more small planes than the one-launch forward kernel takes (4096 of 32 x 32; 6144 smaller ones
-    # padded to 32 x 32, or 16 384 of at most 16 x 16, with a single sweep): pass-by-pass forward
-    # (plane columns, warm rows), segment codes for the fused reverse sweep; (4099, 20, 9) with two
-    # sweeps is a one-launch case with many workgroups
+    # many small planes: beyond 4096 planes padded to 32 x 32 with a single sweep the forward goes
+    # pass by pass (plane columns, warm rows) and leaves segment codes for the fused reverse sweep;
+    # the others are one-launch cases with many workgroups (every mapping is also forced on small
+    # batches in test_every_forward_mapping_of_small_planes)
     rng = np.random.default_rng(79 + shape[2])
     y = rng.normal(size=shape).astype(np.float32)
     g = rng.normal(size=shape).astype(np.float32)
