@@ -39,10 +39,15 @@ inline Threshold table[kCount] = {
     // 3-9 % slower with it.
     {"stream_bytes", (int64_t)96 << 20, "non-temporal accesses from this tensor size on"},
     // The slot order of the row-per-lane forward kernel costs a 5 us kernel of one workgroup and
-    // shortens the drain of the main kernel: 2^20 rows 87 -> 77 + 5 (forward and backward calls
-    // alternating); 2^18 rows 35 -> 35 + 5, 2^17 rows 30 -> 29 + 5.  The library computes the order
-    // whenever it is handed the workspace; this is where the layer (layer.py) starts to hand it over.
-    {"order_min_rows", (int64_t)1 << 19, "the layer passes the slot-order workspace from this many rows on"},
+    // shortens the drain of the main kernel.  It paid while single rows of a wave could take 16
+    // Newton iterations; since clipped trial points are polished and rows stop on their Newton
+    // decrement, the slowest wave of a slot is no longer far from the others, and the order gains
+    // about 1 us: 2^20 rows x 32, forward + backward alternating, 124 natural order / 128 with
+    // the slot order; with the lambdas sorted along the slots 121 / 126 (ascending), 119 / 130
+    // (descending); with the expensive slots last 125 / 129.  The library still computes the
+    // order whenever it is handed the workspace; the layer (layer.py) would hand it over from
+    // this many rows on, and the value means "never".
+    {"order_min_rows", (int64_t)1 << 40, "the layer passes the slot-order workspace from this many rows on"},
     // 2D, planes of 17-32 samples a side: up to this many planes the 2K forward passes run one by
     // one on the thread-per-few-samples kernels (a lone row-per-lane wave per SIMD issues an
     // instruction every 9 cycles).  Forward + backward, pass by pass on those kernels against the
