@@ -234,10 +234,13 @@ int tv1d_prox_bwd_seg_bf16(const uint16_t *g_up, const uint64_t *seg, uint16_t *
 /*
  * 2D anisotropic TV prox on `planes` images of H x W (row-major, contiguous) by
  * `sweeps` iterations of paper Alg. 1; plane p uses lam[p % count] (lam.div is
- * ignored).  ws keeps every pass's output (2*sweeps tensors) plus two scratch
- * tensors, room for every backward pass's dL/dlam terms (one float per row and pass) and,
+ * ignored).  ws has room for every pass's output (2*sweeps tensors) plus two scratch
+ * tensors, for every backward pass's dL/dlam terms (one float per row and pass) and,
  * for planes of at most 32 x 32, every pass's segment codes, which is what the backward
- * call then reads; it must be handed unchanged to tv2d_prox_bwd.  x must not alias y.
+ * call then reads; it must be handed unchanged to tv2d_prox_bwd.  The forward call leaves
+ * there what the backward call will read: the pass outputs, or, where planes of at most
+ * 32 x 32 run all their passes in one launch, the codes alone (the pass outputs as well
+ * after tv_dispatch_override("fused_keeps_passes", 1)).  x must not alias y.
  * From the second sweep on, the correction term a pass adds to its input is D^T u of the
  * same pass one sweep earlier (x = y - D^T u), and the pass starts its Newton iteration
  * from that dual.  Planes of at most 32 x 32 run all their passes in one launch where that is

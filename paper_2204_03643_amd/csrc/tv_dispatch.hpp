@@ -25,6 +25,7 @@ enum {
     kFused32RaggedPlanes,
     kFused16OneSweepPlanes,
     kFused64Planes,
+    kFusedKeepsPasses,
     kThreadPerSampleWideRows,
     kMlMinLength,
     kMlCoarsest,
@@ -83,6 +84,12 @@ inline Threshold table[kCount] = {
     // 256 planes 153 / 54.  It is kept (and tested) as the stated variant for planes of up to
     // 64 x 64; the default of 0 planes means "never".
     {"fused64_planes", 0, "2D planes of 33-64 samples a side: one launch up to this many planes"},
+    // 2D, planes of at most 32 x 32 in one launch: the reverse sweep reads the segment codes of the
+    // passes, not their outputs, so the forward kernel writes only the codes and x.  1 = it also
+    // writes every pass's output into the workspace, where the pass-by-pass forward leaves them (the
+    // tests set it to compare each pass with the oracle's).  Not writing them: 4096 planes of
+    // 32 x 32, K = 1 / 4 / 10: 56 -> 52, 156 -> 149, 403 -> 385; 16 384 planes, K = 4: 560 -> 512.
+    {"fused_keeps_passes", 0, "2D one-launch forward of planes of at most 32 x 32: 1 = also write every pass's output"},
     // Rows of at most 32 samples on the long-row kernels (only the 2D operator on small batches
     // of planes asks for that): 16 threads x 2 samples up to this many rows, 8 x 4 beyond
     // (256 planes of 32 x 32, K = 10: 204 -> 180 with 16 x 2).

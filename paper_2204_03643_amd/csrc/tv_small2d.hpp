@@ -338,6 +338,7 @@ struct Small2dFwdParams {
     float       *x;
     float       *saved;        // output of pass i at saved + i * saved_stride (floats)
     size_t       saved_stride;
+    uint32_t     keep_passes;  // planes of at most 32 x 32: 0 = write the codes only, not the pass outputs
     uint2       *codes;        // as in Small2dBwdParams
     size_t       code_stride;
     const float *lam;          // plane p uses lam[p % lam_count]
@@ -474,7 +475,8 @@ __global__ __launch_bounds__(64, S <= 32 ? 2 : 1) void tv2d_fwd_small_kernel(Sma
             for (int k = 0; k < S; ++k) rowp[k] = xs[k];
         }
         wave_lds_sync();
-        put_planes(p.saved + (size_t)i * p.saved_stride + plane0 * HW);
+        // (planes of at most 32 x 32: the reverse sweep reads the codes written above)
+        if (S > 32 || p.keep_passes) put_planes(p.saved + (size_t)i * p.saved_stride + plane0 * HW);
         if (i + 1 == n_pass) {
             if constexpr (IO16) {
                 uint16_t *dst = reinterpret_cast<uint16_t *>(p.x) + plane0 * HW;

@@ -1129,12 +1129,12 @@ static int small_side(int64_t H, int64_t W)
         }                                                                                           \
     } while (0)
 
-// Up to 1536 planes of 17-32 samples a side: the forward passes run one by one on the long-row
-// kernels (eight threads per row), and the reverse sweep reads the segments off the saved pass
-// outputs instead of codes.  With so few rows a row-per-lane wave runs alone on its SIMD and issues
-// an instruction every 9 cycles; the thread-per-four-samples mapping has 8x the waves and shorter
-// chains (256 planes of 32 x 32, K = 10: 507 -> 180 us forward; 1536 planes: 526 -> 347 on
-// feature-map-like data, 437 -> 361 on white noise; around 2048 planes the one launch catches up).
+// Small batches of planes of 17-32 samples a side (up to tiny_batch_planes of tv_dispatch.hpp): the
+// forward passes run one by one on the long-row kernels (eight or sixteen threads per row), and
+// the reverse sweep reads the segments off the saved pass outputs instead of codes.  With so few
+// rows a row-per-lane wave runs alone on its SIMD and issues an instruction every 9 cycles; the
+// thread-per-few-samples mapping has 8x the waves and shorter chains (256 planes of 32 x 32,
+// K = 10: 507 -> 180 us forward); from about a thousand planes on the one launch is as fast.
 static bool tiny_batch_2d(int64_t planes, int64_t H, int64_t W)
 {
     return small_planes(H, W) && small_side(H, W) == 32 && planes <= tvd::get(tvd::kTinyBatchPlanes);
@@ -1187,7 +1187,7 @@ int tv2d_prox_fwd(const float *y, float *x, int64_t planes, int64_t H, int64_t W
     if (cb && !tiny && fused_fwd_applies(small_side(H, W), H == small_side(H, W) && W == H, planes, sweeps)) {
         // planes of at most 32 x 32: all passes in one launch, the planes resident in LDS
         tvk::Small2dFwdParams q;
-        q.y = y; q.x = x; q.saved = saved(0); q.saved_stride = tb / sizeof(float);
+        q.y = y; q.x = x; q.saved = saved(0); q.saved_stride = tb / sizeof(float); q.keep_passes = tvd::get(tvd::kFusedKeepsPasses) != 0 ? 1u : 0u;
         q.codes = codes(0); q.code_stride = cb / sizeof(uint2);
         q.lam = lam.lam; q.lam_count = lam.count;
         q.planes = (int32_t)planes; q.H = (int32_t)H; q.W = (int32_t)W; q.sweeps = sweeps;
@@ -1198,7 +1198,7 @@ int tv2d_prox_fwd(const float *y, float *x, int64_t planes, int64_t H, int64_t W
     if (!cb && H <= 64 && W <= 64 && planes <= tvd::get(tvd::kFused64Planes)) {
         // planes of 33-64 samples a side: all passes in one launch, a plane per wave
         tvk::Small2dFwdParams q;
-        q.y = y; q.x = x; q.saved = saved(0); q.saved_stride = tb / sizeof(float);
+        q.y = y; q.x = x; q.saved = saved(0); q.saved_stride = tb / sizeof(float); q.keep_passes = tvd::get(tvd::kFusedKeepsPasses) != 0 ? 1u : 0u;
         q.codes = nullptr; q.code_stride = 0;
         q.lam = lam.lam; q.lam_count = lam.count;
         q.planes = (int32_t)planes; q.H = (int32_t)H; q.W = (int32_t)W; q.sweeps = sweeps;
@@ -1247,7 +1247,7 @@ int tv2d_prox_fwd_bf16(const uint16_t *y, uint16_t *x, int64_t planes, int64_t H
     char *base = (char *)ws;
     tvk::Small2dFwdParams q;
     q.y = reinterpret_cast<const float *>(y); q.x = reinterpret_cast<float *>(x);
-    q.saved = (float *)base; q.saved_stride = tb / sizeof(float);
+    q.saved = (float *)base; q.saved_stride = tb / sizeof(float); q.keep_passes = tvd::get(tvd::kFusedKeepsPasses) != 0 ? 1u : 0u;
     q.codes = (uint2 *)(base + tb * (size_t)(2 * sweeps + 2) + pb * (size_t)(2 * sweeps));
     q.code_stride = cb / sizeof(uint2);
     q.lam = lam.lam; q.lam_count = lam.count;

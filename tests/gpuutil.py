@@ -75,7 +75,7 @@ def lam_per_row(lam, n_rows, lam_div):
     return lam[(np.arange(n_rows) // lam_div) % lam.size]
 
 
-def run_2d(y, lam, sweeps, g=None):
+def run_2d(y, lam, sweeps, g=None, keep_passes=True):
     """2D prox on y[..., H, W] with per-plane lam (plane p uses lam[p % len(lam)])."""
     import torch
 
@@ -88,9 +88,16 @@ def run_2d(y, lam, sweeps, g=None):
     lt = torch.from_numpy(np.ascontiguousarray(lam, dtype=np.float32).ravel()).to(dev)
     L = tv.tv_lambda(lt.data_ptr(), lt.numel(), 1)
     wsb = tv.tv2d_workspace_bytes(planes, H, W, sweeps)
-    ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device=dev)
+    ws = torch.full((max(wsb, 16),), 0xff, dtype=torch.uint8, device=dev)       # floats of all-ones bits are NaN
     xt = torch.full_like(yt, float("nan"))
-    tv.tv2d_prox_fwd(yt, xt, planes, H, W, L, sweeps, ws, wsb)
+    # the tests compare every pass's output with the oracle's: the one-launch forward writes them
+    # on request only (its reverse sweep reads the codes)
+    keeps = tv.tv_dispatch_threshold("fused_keeps_passes")
+    tv.tv_dispatch_override("fused_keeps_passes", 1 if keep_passes else 0)
+    try:
+        tv.tv2d_prox_fwd(yt, xt, planes, H, W, L, sweeps, ws, wsb)
+    finally:
+        tv.tv_dispatch_override("fused_keeps_passes", keeps)
     torch.cuda.synchronize()
     out = {"x": xt.cpu().numpy()}
     if g is not None:

@@ -194,3 +194,27 @@ def test_one_launch_forward_for_planes_of_33_to_64(shape, K, dispatch_defaults):
     out = run_2d(y, lam, K, g)
     check_2d(y, lam, K, g, out, "one launch %s K=%d" % (shape, K))
     assert np.abs(out["x"] - ref["x"]).max() <= 2e-5 * (1 + np.abs(y).max())
+
+
+@pytest.mark.parametrize("shape,K", [((900, 32, 32), 3), ((1000, 20, 27), 2), ((300, 16, 16), 2)])
+def test_one_launch_forward_without_the_pass_outputs(shape, K, dispatch_defaults):
+    """By default the one-launch forward of planes of at most 32 x 32 writes the codes and x only
+    (its reverse sweep reads nothing else): the part of the workspace that would hold the pass
+    outputs stays as the caller left it, and x, grad_y and grad_lam are bit for bit what the call
+    gives when it is asked to write the pass outputs too (which is how every other test runs it)."""
+    import paper_2204_03643_amd as tv
+    rng = np.random.default_rng(131 + shape[1])
+    y = np.maximum(rng.normal(size=shape), 0).astype(np.float32)
+    g = rng.normal(size=shape).astype(np.float32)
+    lam = (10 ** rng.uniform(-2, 0.3, size=4)).astype(np.float32)
+    tv.tv_dispatch_override("tiny_batch_planes", 0)           # onto the one-launch kernel whatever the count
+    for nme in ("fused32_full_planes", "fused32_full_planes_k2", "fused32_full_planes_k3", "fused32_ragged_planes",
+                "fused16_one_sweep_planes"):
+        tv.tv_dispatch_override(nme, 1 << 40)
+    assert tv.tv_dispatch_threshold("fused_keeps_passes") == 0
+    kept = run_2d(y, lam, K, g, keep_passes=True)
+    check_2d(y, lam, K, g, kept, "kept passes %s K=%d" % (shape, K))
+    lean = run_2d(y, lam, K, g, keep_passes=False)
+    for k in ("x", "gy", "gl"):
+        assert np.array_equal(kept[k], lean[k]), k
+    assert np.all(np.isnan(lean["saved"]))                     # run_2d hands over a workspace of NaN bytes

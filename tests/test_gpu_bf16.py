@@ -127,11 +127,12 @@ def test_bf16_2d_pair_equals_rounded_fp32_one_launch_kernels(shape, K):
     ws = torch.zeros(wsb, dtype=torch.uint8, device=dev)
     xt, gy = torch.full_like(yt, -1), torch.full_like(yt, -1)
     gl = torch.full((3,), float("nan"), device=dev)
-    tv.tv2d_prox_fwd_bf16(yt, xt, P, H, W, L, K, ws, wsb)
-    tv.tv2d_prox_bwd_bf16(gt, gy, gl, P, H, W, L, K, ws, wsb)
-    # the fp32 call on the widened input, forced onto the one-launch kernels
     saved_thr = tv.tv_dispatch_thresholds()
     try:
+        tv.tv_dispatch_override("fused_keeps_passes", 1)      # both calls also leave their pass outputs
+        tv.tv2d_prox_fwd_bf16(yt, xt, P, H, W, L, K, ws, wsb)
+        tv.tv2d_prox_bwd_bf16(gt, gy, gl, P, H, W, L, K, ws, wsb)
+        # the fp32 call on the widened input, forced onto the one-launch kernels
         tv.tv_dispatch_override("tiny_batch_planes", 0)
         for name in ("fused32_full_planes", "fused32_full_planes_k2", "fused32_full_planes_k3",
                      "fused32_ragged_planes", "fused16_one_sweep_planes"):
