@@ -147,8 +147,9 @@ def check_2d(y, lam, K, g, out, label=""):
     output must jump exactly where the oracle's does, in the same direction, and be bit-constant
     where the oracle's is; rows all of whose duals are ordinary thus have exactly the oracle's
     segments.
-    Backward: grad_y within 1e-3 of the plane's largest reference gradient on every entry,
-    grad_lam per slot within 1e-3 (|ref| + l2 norm of the per-plane contributions) plus the
+    Backward: grad_y within 1e-3 of the plane's largest reference gradient on every entry (plus
+    the rounding floor of an fp32 sum, 8 eps max|g_up| of the plane; the planes that need it are
+    counted), grad_lam per slot within 1e-3 (|ref| + l2 norm of the per-plane contributions) plus the
     rounding floor of the fp32 sums.  The reference is the oracle's reverse sweep over the
     oracle's own pass outputs, except that near-degenerate rows of a pass take the HIP path's
     segments (any KKT-consistent partition is a valid generalised Jacobian there).  Planes
@@ -207,16 +208,22 @@ def check_2d(y, lam, K, g, out, label=""):
     gy_ref, gl_plane = oracle.prox2d_bwd(g64, hybrid, planes, K)       # a slot per plane
     gerr = np.abs(gy_gpu - gy_ref).max(axis=(1, 2))
     gscale = np.maximum(np.abs(gy_ref).max(axis=(1, 2)), 1e-30)
-    assert (gerr / gscale).max() <= GRAD_TOL, (label, "grad_y", float((gerr / gscale).max()),
-                                                int((gerr / gscale).argmax()))
+    # rounding floor, as in check_batch: every entry of grad_y is a chain of segment means, signed
+    # fp32 sums of entries of the size of g_up, and a plane whose x is one constant gets
+    # mean(g_up) everywhere, which can cancel to 1e-6 of max|g_up| (random testing: 232 samples,
+    # mean 2.5e-6, fp32 error 6e-9)
+    gfloor = 8 * np.finfo(np.float32).eps * np.abs(g64).max(axis=(1, 2))
+    ratio = gerr / (GRAD_TOL * gscale + gfloor)
+    assert ratio.max() <= 1.0, (label, "grad_y", float((gerr / gscale).max()), int(ratio.argmax()))
     stats["grad_max_rel"] = float((gerr / gscale).max())
+    stats["grad_y_planes_needing_floor"] = int(np.count_nonzero(gerr > GRAD_TOL * gscale))
     if (~dirty).any():
         # the oracle's own gradient, nothing of the HIP path in the reference
         gy_own, _ = oracle.prox2d_bwd(g64, saved_ref, planes, K)
         c = ~dirty
         assert np.array_equal(gy_own[c], gy_ref[c])
-        own = (np.abs(gy_gpu[c] - gy_own[c]).max(axis=(1, 2)) / gscale[c]).max()
-        assert own <= GRAD_TOL, (label, "grad_y against the oracle's own gradient", float(own))
+        own = np.abs(gy_gpu[c] - gy_own[c]).max(axis=(1, 2)) / (GRAD_TOL * gscale[c] + gfloor[c])
+        assert own.max() <= 1.0, (label, "grad_y against the oracle's own gradient", float(own.max()))
     if out.get("gl") is not None:
         slots = np.arange(planes) % lam.size
         ref = np.zeros(lam.size)

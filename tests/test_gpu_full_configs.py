@@ -42,6 +42,7 @@ def test_config2_full_as_2d_k1():
     st = check_2d(y, lam, 1, g, run_2d(y, lam, 1, g), "cfg2 2D K=1")
     print("cfg2 2D K=1:", st)
     assert st["planes_without_near_degenerate_rows"] > 0
+    assert st["grad_y_planes_needing_floor"] <= 4           # of 4096
 
 
 def test_config3_full_timed_pair():
@@ -86,6 +87,7 @@ def test_config4_full():
     # rows of 512 samples nearly always hold some dual within 1e-4 of a change of status, so
     # here the segment rule bites dual by dual: all but a fraction of a percent of them
     assert st["pass_duals_near_degenerate"] <= 0.01 * st["pass_duals_checked"]
+    assert st["grad_y_planes_needing_floor"] == 0
 
 
 def test_config5_full():

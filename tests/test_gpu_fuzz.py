@@ -61,7 +61,9 @@ def _case_2d(rng):
     return "2d %dx%dx%d K=%d lam %d" % (P, H, W, K, lam.size), (y, lam, K, g)
 
 
-@pytest.mark.parametrize("seed,cases", [(20220403, 120), (3643, 120)])
+# (seed 106 holds a plane whose x is one constant and whose mean upstream gradient cancels to 2.5e-6:
+# the case behind the rounding floor of check_2d's grad_y rule)
+@pytest.mark.parametrize("seed,cases", [(20220403, 120), (3643, 120), (106, 100)])
 def test_seeded_random_cases(seed, cases):
     rng = np.random.default_rng(seed)
     n1 = n2 = 0
