@@ -53,11 +53,21 @@ struct LongMap {
             __syncthreads();
         }
     }
-    // sync() plus: does any thread that shares rows with this one pass `pred`?
-    __device__ static __forceinline__ bool sync_any(bool pred)
+    // sync() plus: does any thread that shares rows with this one pass `pred`?  Across a workgroup
+    // the vote rides on the one barrier that the exchange of data needs anyway: every wave leaves
+    // its own vote in LDS ahead of the barrier and reads all of them behind it.  `vote` holds two
+    // sets of NW flags and `vp` says which one this call uses (it flips with every call, the same
+    // in all threads): the set written now was last read two calls ago, a barrier back.
+    __device__ static __forceinline__ bool sync_any(bool pred, int *vote, int &vp)
     {
         if (PRIVATE) { sync(); return __any(pred ? 1 : 0) != 0; }
-        return __syncthreads_or(pred ? 1 : 0) != 0;
+        const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+        const bool mine = __any(pred ? 1 : 0) != 0;
+        if (lane == 0) vote[vp * NW + wave] = mine ? 1 : 0;
+        __syncthreads();
+        const int seen = lane < NW ? vote[vp * NW + lane] : 0;
+        vp ^= 1;
+        return __any(seen) != 0;
     }
 };
 
@@ -364,6 +374,7 @@ struct LongSmem {
     float ex[5][G][TP];
     float buf[2 * 3 * G * T];
     float red[2 * 4 * Mp::NW * Mp::RG];
+    int   vote[2 * Mp::NW];                            // workgroup votes (LongMap::sync_any)
 };
 
 // The backward kernel exchanges two values per thread and scans through LDS only where a row
@@ -531,7 +542,14 @@ __global__ __launch_bounds__(T *G, (T * G == 512 && !COLS) ? 4 : ((XPOSE && C <=
 
     // duals past the end of the row get an empty box and never move
     const int nvd = min(max(M - k0, 0), C);            // duals of this chunk inside the row
-#define TV_LK(i) (((i) < nvd) ? lam : 0.0f)
+    // (where a row spans several waves the comparison is redone from an opaque copy of nvd in
+    // every phase: as a loop invariant the compiler keeps all C results in scalar register pairs
+    // for the whole solve, and those kernels then spill scalar registers by the hundred; the
+    // wave-per-row kernels have the registers to spare and are 3-5 % faster with the invariant)
+    int nv = nvd;
+#define TV_NV_REFRESH() do { if constexpr (!Mp::PRIVATE) { nv = nvd; asm volatile("" : "+v"(nv)); } } while (0)
+#define TV_LK(i) (((i) < nv) ? lam : 0.0f)
+    TV_NV_REFRESH();
 
     TV_EX(0, t) = y[0];
     Mp::sync();
@@ -613,7 +631,7 @@ __global__ __launch_bounds__(T *G, (T * G == 512 && !COLS) ? 4 : ((XPOSE && C <=
     bool active = rvalid;
     bool prev_unclipped = false;
     int steps = 0, flags = 0;
-    int par = 0;
+    int par = 0, vp = 0;
     float *rec = nullptr;
     if constexpr (DEBUG) {
         if (rvalid && row < p.debug_rows) {
@@ -623,6 +641,7 @@ __global__ __launch_bounds__(T *G, (T * G == 512 && !COLS) ? 4 : ((XPOSE && C <=
     }
 
     for (int it = 0;; ++it) {
+        TV_NV_REFRESH();
         // ---- chunk edges of the dual: exchanged by the accepted trial of the step before
         const float uleft = edge_l;
         const float unext0 = edge_r;
@@ -644,7 +663,7 @@ __global__ __launch_bounds__(T *G, (T * G == 512 && !COLS) ? 4 : ((XPOSE && C <=
                 g[i] = gi;
                 const float s = copysignf(TV_LK(i), gi);
                 const bool bnd = (u[i] == -s);
-                if (i < nvd && u[i] == s && fabsf(gi) > gtol) viof[0] += 1.f;
+                if (i < nv && u[i] == s && fabsf(gi) > gtol) viof[0] += 1.f;
                 if (i < C - 1) {
                     pos = bnd ? 0 : pos + 1;
                     const float gm = sm.gtab[pos];
@@ -682,7 +701,7 @@ __global__ __launch_bounds__(T *G, (T * G == 512 && !COLS) ? 4 : ((XPOSE && C <=
         TV_EX(4, t) = c_beta;
         bool vio;
         if (Mp::SOLO) {
-            vio = Mp::sync_any(viof[0] != 0.f);             // one row: the vote is the row's
+            vio = Mp::sync_any(viof[0] != 0.f, sm.vote, vp);             // one row: the vote is the row's
         } else {
             row_sum<T, G, MCOLS, 1>(viof, sm.red, j, tid);
             vio = viof[0] != 0.f;
@@ -693,7 +712,7 @@ __global__ __launch_bounds__(T *G, (T * G == 512 && !COLS) ? 4 : ((XPOSE && C <=
         if (active && prev_unclipped && !vio) { active = false; flags = kInfoConverged; }
         if (active && it >= kMaxNewtonSteps) { active = false; flags = kInfoCapped; }
         if (Mp::SOLO) { if (!active) break; }               // row-wide flags are uniform here
-        else if (!Mp::sync_any(active)) break;
+        else if (!Mp::sync_any(active, sm.vote, vp)) break;
         steps += active ? 1 : 0;
 
         // ---- separator system (normalised to unit diagonal) and PCR
@@ -711,7 +730,7 @@ __global__ __launch_bounds__(T *G, (T * G == 512 && !COLS) ? 4 : ((XPOSE && C <=
             for (int s = 1; s < T; s <<= 1) {
                 TV_PB(cur, 0, t) = ea; TV_PB(cur, 1, t) = ec; TV_PB(cur, 2, t) = er;
                 // every equation decoupled: the right-hand sides just published are the solution
-                if (!Mp::sync_any(ea != 0.f || ec != 0.f)) { published = true; break; }
+                if (!Mp::sync_any(ea != 0.f || ec != 0.f, sm.vote, vp)) { published = true; break; }
                 float la = 0.f, lc = 0.f, lr = 0.f, ra = 0.f, rc = 0.f, rr = 0.f;
                 if (t - s >= 0) { la = TV_PB(cur, 0, t - s); lc = TV_PB(cur, 1, t - s); lr = TV_PB(cur, 2, t - s); }
                 if (t + s < T) { ra = TV_PB(cur, 0, t + s); rc = TV_PB(cur, 1, t + s); rr = TV_PB(cur, 2, t + s); }
@@ -800,7 +819,7 @@ __global__ __launch_bounds__(T *G, (T * G == 512 && !COLS) ? 4 : ((XPOSE && C <=
             const bool ok = !active || alpha == 0.f || (alpha == 1.f && !clipped) ||
                             (fc <= fcur - kArmijoSigma * alpha * dec + kArmijoSlackEps * fabsf(fcur));
             if (Mp::SOLO) { if (ok) break; }                // uniform: every thread sees the row's sums
-            else if (!Mp::sync_any(!ok)) break;
+            else if (!Mp::sync_any(!ok, sm.vote, vp)) break;
             if (!ok) {
                 if (ls >= kMaxBacktracks) {
                     alpha = 0.f;
@@ -823,7 +842,7 @@ __global__ __launch_bounds__(T *G, (T * G == 512 && !COLS) ? 4 : ((XPOSE && C <=
         }
         if (active && !changed) { active = false; flags = kInfoStalled; }
         if (Mp::SOLO) { if (!active) break; }
-        else if (!Mp::sync_any(active)) break;
+        else if (!Mp::sync_any(active, sm.vote, vp)) break;
     }
 
     if (p.dual_out) chunk_store<C>(p.dual_out, (int64_t)row * n, 1, k0, n, rvalid, u);
@@ -832,6 +851,7 @@ __global__ __launch_bounds__(T *G, (T * G == 512 && !COLS) ? 4 : ((XPOSE && C <=
     //      the value of its first sample, so that constant runs are bit-identical
     float xs[C];
     {
+        TV_NV_REFRESH();
         TV_EX(0, t) = u[C - 1];
         TV_EX(1, t) = u[0];
         Mp::sync();
@@ -914,6 +934,7 @@ __global__ __launch_bounds__(T *G, (T * G == 512 && !COLS) ? 4 : ((XPOSE && C <=
 #undef TV_EX
 #undef TV_PB
 #undef TV_LK
+#undef TV_NV_REFRESH
 }
 
 // ---------------------------------------------------------------------------------
