@@ -354,6 +354,9 @@ def dispatch_probe(dev) -> int:
          "one launch", "pass by pass on the long-row kernels")
     for name, K in (("fused32_full_planes", 1), ("fused32_full_planes_k2", 2), ("fused32_full_planes_k3", 4)):
         n = defaults[name]
+        if n > (1 << 20):           # "always": timed at the largest count that was measured
+            case(name, "at_65536_planes_k%d" % K, lambda: two_d(65536, 32, 32, K), 0, "one launch", "pass by pass")
+            continue
         case(name, "at_threshold_k%d" % K, lambda: two_d(n, 32, 32, K), 0, "one launch", "pass by pass")
         case(name, "beyond_k%d" % K, lambda: two_d(n + n // 4, 32, 32, K), big, "pass by pass", "one launch")
     n = defaults["fused32_ragged_planes"]

@@ -52,22 +52,23 @@ inline Threshold table[kCount] = {
     // 2D, planes of 17-32 samples a side: up to this many planes the 2K forward passes run one by
     // one on the thread-per-few-samples kernels (a lone row-per-lane wave per SIMD issues an
     // instruction every 9 cycles).  Forward + backward, pass by pass on those kernels against the
-    // one-launch kernel, feature-map-like data: K = 1: 256 planes 52 / 61, 768: 58 / 60, 1024:
-    // 64 / 66, 1536: 69 / 66; K = 2: 512 planes 85 / 86, 768: 90 / 98, 1024: 99 / 96; K = 4: 256
-    // planes 127 / 145, 512: 148 / 145, 768: 161 / 160, 1536: 204 / 167.
+    // one-launch kernel, feature-map-like data: K = 1: 256 planes 39 / 58, 768: 53 / 57, 1024:
+    // 58 / 62, 1536: 68 / 64; K = 2: 512 planes 75 / 84, 768: 84 / 95, 1024: 93 / 94; K = 4: 256
+    // planes 106 / 140, 512: 128 / 142, 768: 149 / 153, 1024: 167 / 155, 1536: 194 / 157.
     {"tiny_batch_planes", 768, "2D planes of 17-32 a side: pass by pass on the long-row kernels up to this many planes"},
     // 2D, planes of exactly 32 x 32: the one-launch forward kernel holds two waves per SIMD (17 KB
     // of LDS per wave) where the pass-by-pass kernels hold three, but pays no launches and no
     // memory round trips between the passes, which weighs more the more sweeps there are.
     // One launch against pass by pass, forward + backward, feature-map-like data:
-    //   K = 1:  4096 planes  75 /  80,  4608: 100 /  85,  6144: 115 /  95, 16 384: 235 / 188;
-    //   K = 2:  4096 planes 112 / 147,  6144: 187 / 178,  8192: 209 / 233, 16 384: 392 / 392, 24 576: 579 / 553;
-    //   K = 4:  4096 planes 190 / 291,  8192: 365 / 435, 16 384: 663 / 709, 32 768: 1226 / 1254.
-    // (The one launch holds 4096 planes at once: it loses ground over its second round of waves
-    // and wins it back when that round is full.)
+    //   K = 1:  4096 planes  69 /  76,  4352:  91 /  82,  6144: 115 /  95, 16 384: 235 / 188;
+    //   K = 2:  4096 planes 108 / 146, 20 480: 442 / 465, 32 768: 700 / 704, 49 152: 1000 / 975;
+    //   K = 4:  4096 planes 183 / 290, 32 768: 1162 / 1257, 65 536: 2206 / 2305, 81 920: 2767 / 2881
+    //   (with three sweeps or more the one launch wins at every count: the value means "always").
+    // (The one launch holds 4096 planes at once: with a single sweep it loses over its second
+    // round of waves what the saved launches gained.)
     {"fused32_full_planes", 4096, "2D planes of 32 x 32, one sweep: all passes in one launch up to this many planes"},
-    {"fused32_full_planes_k2", 16384, "... two sweeps"},
-    {"fused32_full_planes_k3", 32768, "... three sweeps or more"},
+    {"fused32_full_planes_k2", 32768, "... two sweeps"},
+    {"fused32_full_planes_k3", (int64_t)1 << 40, "... three sweeps or more"},
     // 2D, planes of 17-32 samples a side that do not fill 32 x 32, single sweep (with two sweeps
     // or more the one launch always wins: 28 x 28, 32 768 planes, K = 4: 1.46 ms against 1.94).
     // 28 x 28, K = 1, one launch against pass by pass, forward + backward: 2048 planes 91 / 98,

@@ -160,6 +160,29 @@ __device__ __forceinline__ float long_dpp(float v)
     return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));
 }
 
+// Rows of at most 16 threads lie inside one 16-lane DPP row (ROWS mapping: consecutive lanes are
+// consecutive threads of a row; two rows share a DPP row when T = 8): a thread then gets the
+// value of thread t - S / t + S of its own row from a row shift that rides on the reading
+// instruction, instead of a write to LDS, a fence and a read.  Beyond the ends of the row: 0.
+// Every lane of the wave must take part: a shift reads 0 from a lane that a branch has switched off.
+template <int T, int S>
+__device__ __forceinline__ float from_left(float v, int t)
+{
+    static_assert(T <= 16 && S >= 1 && S < 16, "row shifts stay inside a 16-lane row");
+    const float r = long_dpp<0x110 + S>(v);                    // row_shr:S
+    return (T < 16 && t < S) ? 0.f : r;
+}
+template <int T, int S>
+__device__ __forceinline__ float from_right(float v, int t)
+{
+    static_assert(T <= 16 && S >= 1 && S < 16, "row shifts stay inside a 16-lane row");
+    const float r = long_dpp<0x100 + S>(v);                    // row_shl:S
+    return (T < 16 && t + S >= T) ? 0.f : r;
+}
+// (Rows of 32 and 64 threads could fetch their direct neighbours by a shift of the whole wave
+// (wave_shr:1); measured, that changes nothing for them: their time goes into the PCR steps at
+// distances that no single shift covers.)
+
 // Sum over the 64 lanes of a wave, the same total in every lane, in a fixed order: four
 // exchanges inside the 16-lane rows ride on the adds themselves (DPP), two cross the rows.
 template <int LANES = 64>
@@ -408,6 +431,8 @@ __global__ __launch_bounds__(T *G, (T * G == 512 && !COLS) ? 4 : ((XPOSE && C <=
     static_assert(!XPOSE || (COLS && T <= 64), "the transposing variant is for strided rows inside one wave");
     constexpr bool MCOLS = COLS && !XPOSE;             // mapping used by the solve
     using Mp = LongMap<T, G, MCOLS>;
+    // a row inside one 16-lane DPP row: neighbours' values by row shifts, not through LDS (from_left)
+    constexpr bool DPPX = !MCOLS && T <= 16;
     __shared__ LongSmem<T, C, G, MCOLS> sm;
     // tile[row][k + k / C]: the pad after every chunk makes a wave's chunk reads conflict-free,
     // the odd pitch does the same for the transposing accesses
@@ -551,10 +576,15 @@ __global__ __launch_bounds__(T *G, (T * G == 512 && !COLS) ? 4 : ((XPOSE && C <=
 #define TV_LK(i) (((i) < nv) ? lam : 0.0f)
     TV_NV_REFRESH();
 
-    TV_EX(0, t) = y[0];
-    Mp::sync();
-    const float ynext0 = TV_EX(0, t + 1);
-    Mp::sync();
+    float ynext0;
+    if constexpr (DPPX) {
+        ynext0 = from_right<T, 1>(y[0], t);
+    } else {
+        TV_EX(0, t) = y[0];
+        Mp::sync();
+        ynext0 = TV_EX(0, t + 1);
+        Mp::sync();
+    }
     // ---- starting point: every dual at the bound its local difference points to, or the
     //      dual the addend encodes, brought into the box (duals within rounding distance of a
     //      bound onto it)
@@ -611,12 +641,18 @@ __global__ __launch_bounds__(T *G, (T * G == 512 && !COLS) ? 4 : ((XPOSE && C <=
                 }
             }
         }
-        TV_EX(0, t) = u[C - 1];
-        TV_EX(1, t) = u[0];
-        Mp::sync();
-        const float uleft = TV_EX(0, t - 1);
+        float uleft;
+        if constexpr (DPPX) {
+            uleft = from_left<T, 1>(u[C - 1], t);
+            edge_r = from_right<T, 1>(u[0], t);
+        } else {
+            TV_EX(0, t) = u[C - 1];
+            TV_EX(1, t) = u[0];
+            Mp::sync();
+            uleft = TV_EX(0, t - 1);
+            edge_r = TV_EX(1, t + 1);
+        }
         edge_l = uleft;
-        edge_r = TV_EX(1, t + 1);
         float acc[1] = {0.f};
 #pragma unroll
         for (int i = 0; i < C; ++i) {
@@ -696,9 +732,11 @@ __global__ __launch_bounds__(T *G, (T * G == 512 && !COLS) ? 4 : ((XPOSE && C <=
         const float c_alpha = sm.rtab[a];                       // 1 - (A^-1)_{first,first}
         const float c_delta = sm.rtab[pos];                     // 1 - (A^-1)_{last,last}
         const float c_beta = (a == C - 1) ? (1.0f / (float)C) : 0.f;  // (A^-1)_{first,last}
-        TV_EX(2, t) = p0;
-        TV_EX(3, t) = c_alpha;
-        TV_EX(4, t) = c_beta;
+        if constexpr (!DPPX) {
+            TV_EX(2, t) = p0;
+            TV_EX(3, t) = c_alpha;
+            TV_EX(4, t) = c_beta;
+        }
         bool vio;
         if (Mp::SOLO) {
             vio = Mp::sync_any(viof[0] != 0.f, sm.vote, vp);             // one row: the vote is the row's
@@ -707,7 +745,12 @@ __global__ __launch_bounds__(T *G, (T * G == 512 && !COLS) ? 4 : ((XPOSE && C <=
             vio = viof[0] != 0.f;
             Mp::sync();
         }
-        const float p0n = TV_EX(2, t + 1), alphan = TV_EX(3, t + 1), betan = TV_EX(4, t + 1);
+        float p0n, alphan, betan;
+        if constexpr (DPPX) {
+            p0n = from_right<T, 1>(p0, t); alphan = from_right<T, 1>(c_alpha, t); betan = from_right<T, 1>(c_beta, t);
+        } else {
+            p0n = TV_EX(2, t + 1); alphan = TV_EX(3, t + 1); betan = TV_EX(4, t + 1);
+        }
 
         if (active && prev_unclipped && !vio) { active = false; flags = kInfoConverged; }
         if (active && it >= kMaxNewtonSteps) { active = false; flags = kInfoCapped; }
@@ -724,7 +767,26 @@ __global__ __launch_bounds__(T *G, (T * G == 512 && !COLS) ? 4 : ((XPOSE && C <=
             er = (g[C - 1] + pl + p0n) * inv;
         }
         float sleft;
-        {
+        if constexpr (DPPX) {
+            // the same reduction with the neighbours' equations fetched by row shifts
+#define TV_PCR_STEP(S)                                                                              \
+            if constexpr ((S) < T) {                                                                \
+                if (going && (going = __any((ea != 0.f || ec != 0.f) ? 1 : 0) != 0)) {             \
+                    const float la = from_left<T, (S) < T ? (S) : 1>(ea, t), lc = from_left<T, (S) < T ? (S) : 1>(ec, t),      \
+                                lr = from_left<T, (S) < T ? (S) : 1>(er, t);                        \
+                    const float ra = from_right<T, (S) < T ? (S) : 1>(ea, t), rc = from_right<T, (S) < T ? (S) : 1>(ec, t),    \
+                                rr = from_right<T, (S) < T ? (S) : 1>(er, t);                       \
+                    const float inv = __builtin_amdgcn_rcpf(1.0f - ea * lc - ec * ra);              \
+                    er = (er - ea * lr - ec * rr) * inv;                                            \
+                    const float na = -ea * la * inv, nc = -ec * rc * inv;                           \
+                    ea = na; ec = nc;                                                               \
+                }                                                                                   \
+            }
+            bool going = true;
+            TV_PCR_STEP(1) TV_PCR_STEP(2) TV_PCR_STEP(4) TV_PCR_STEP(8)
+#undef TV_PCR_STEP
+            sleft = from_left<T, 1>(er, t);
+        } else {
             int cur = 0;
             bool published = false;
             for (int s = 1; s < T; s <<= 1) {
@@ -800,12 +862,18 @@ __global__ __launch_bounds__(T *G, (T * G == 512 && !COLS) ? 4 : ((XPOSE && C <=
                 ch |= (cc != u[i]);
                 uc[i] = cc;
             }
-            TV_EX(0, t) = uc[C - 1];
-            TV_EX(1, t) = uc[0];
-            Mp::sync();
-            const float ucleft = TV_EX(0, t - 1);
+            float ucleft;
+            if constexpr (DPPX) {
+                ucleft = from_left<T, 1>(uc[C - 1], t);
+                edge_r = from_right<T, 1>(uc[0], t);
+            } else {
+                TV_EX(0, t) = uc[C - 1];
+                TV_EX(1, t) = uc[0];
+                Mp::sync();
+                ucleft = TV_EX(0, t - 1);
+                edge_r = TV_EX(1, t + 1);
+            }
             edge_l = ucleft;
-            edge_r = TV_EX(1, t + 1);
 #pragma unroll
             for (int i = 0; i < C; ++i) {
                 const float xc = y[i] + uc[i] - (i > 0 ? uc[i - 1] : ucleft);
@@ -852,11 +920,17 @@ __global__ __launch_bounds__(T *G, (T * G == 512 && !COLS) ? 4 : ((XPOSE && C <=
     float xs[C];
     {
         TV_NV_REFRESH();
-        TV_EX(0, t) = u[C - 1];
-        TV_EX(1, t) = u[0];
-        Mp::sync();
-        const float uleft = TV_EX(0, t - 1);
-        const float unext0 = TV_EX(1, t + 1);
+        float uleft, unext0;
+        if constexpr (DPPX) {
+            uleft = from_left<T, 1>(u[C - 1], t);
+            unext0 = from_right<T, 1>(u[0], t);
+        } else {
+            TV_EX(0, t) = u[C - 1];
+            TV_EX(1, t) = u[0];
+            Mp::sync();
+            uleft = TV_EX(0, t - 1);
+            unext0 = TV_EX(1, t + 1);
+        }
         bool bnd[C];
         float xi = y[0] + u[0] - uleft;
 #pragma unroll
@@ -868,9 +942,16 @@ __global__ __launch_bounds__(T *G, (T * G == 512 && !COLS) ? 4 : ((XPOSE && C <=
             xi = xn;
         }
         // a sample starts a block when the dual on its left is bound; chunk-local pass first
-        TV_EX(2, t) = bnd[C - 1] ? 1.f : 0.f;
-        Mp::sync();
-        const bool start0 = (t == 0) || (TV_EX(2, t - 1) != 0.f);
+        bool start0;
+        if constexpr (DPPX) {
+            // (fetched by all lanes before any of them branches: a row shift reads 0 from a lane that is switched off)
+            const float left_bound = from_left<T, 1>(bnd[C - 1] ? 1.f : 0.f, t);
+            start0 = (t == 0) || (left_bound != 0.f);
+        } else {
+            TV_EX(2, t) = bnd[C - 1] ? 1.f : 0.f;
+            Mp::sync();
+            start0 = (t == 0) || (TV_EX(2, t - 1) != 0.f);
+        }
         bool closed = start0;
         float last = xs[0];
 #pragma unroll
