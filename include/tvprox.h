@@ -105,9 +105,11 @@ int tv1d_prox_fwd_info(const float *y, float *x, int32_t *info, tv_rows rows, tv
  *         (TV_ERR_WORKSPACE otherwise), contents undefined afterwards.  Two uses:
  *         - rows of up to 32 samples whose lambda slots form whole groups of 64 rows are
  *           processed slot by slot in the order of decreasing predicted cost, which shortens
- *           the call when the slots' lambdas differ widely and the batch is large (the order
- *           costs a 5 us kernel: worth it from about 2^18 rows); results are bit-identical
- *           with or without it;
+ *           the drain of the launch when the slots' costs differ widely (the order costs a
+ *           5 us kernel, which it has not earned back on any batch measured since single rows
+ *           stopped needing many more steps than their neighbours); with it the call always
+ *           runs the row-per-lane kernels, and its results are bit-identical to those of
+ *           the same kernels without it;
  *         - unit-stride rows of 2048 samples or more get a multilevel start: the row averaged
  *           in groups of 4 samples, with lambda / 4, is solved first (recursively, down to at
  *           most 256 samples) and its dual, prolonged, is where the Newton iteration of the
@@ -202,7 +204,10 @@ int tv1d_prox_bwd_noalloc(const float *g_up, const float *x, float *grad_y, floa
  * its partition into constant segments and the direction of every jump; the forward call
  * writes that as one 64-bit code per row and the backward call reads the code (8 bytes per
  * row) instead of x (4 * length bytes per row).  Results are bit-identical to
- * tv1d_prox_fwd / tv1d_prox_bwd.
+ * tv1d_prox_fwd / tv1d_prox_bwd on the same batch.  (Which kernels a forward call runs
+ * depends on the batch: up to tv_dispatch_threshold("thread_per_sample_1d_rows") rows of at
+ * most 32 samples get sixteen threads per row, larger batches a lane per row; the two agree
+ * to rounding, not bit for bit.)
  *   seg: device pointer, 8-byte aligned, one uint64 per row in row order
  *        (entry o * n_inner + i for the row at o * outer_stride + i * inner_stride);
  *        bit k (k < 31) is set when x[k+1] != x[k], bit 32 + k when x[k+1] > x[k].
@@ -219,7 +224,7 @@ int tv1d_prox_bwd_seg(const float *g_up, const uint64_t *seg, float *grad_y, flo
  * solve and the segment averaging run as in the fp32 kernels, the outputs are rounded to
  * nearest even): y, x, g_up and grad_y are arrays of bf16 bit patterns (uint16_t), 16-byte
  * aligned.  The paper computes in fp32; this halves the bytes the pair moves.  x is bit for bit
- * the rounded output of tv1d_prox_fwd_seg on the widened input, the codes are identical, and
+ * the rounded output of tv1d_prox_fwd_seg (its row-per-lane kernel) on the widened input, the codes are identical, and
  * the backward pass uses the codes (segments of the unrounded x), so rounding never merges or
  * splits a segment.  Only packed rows of exactly 32 samples (unit element stride, rows back
  * to back): TV_ERR_UNSUPPORTED otherwise.  ws / ws_bytes of the forward call: as in

@@ -27,6 +27,7 @@ enum {
     kFused64Planes,
     kFusedKeepsPasses,
     kThreadPerSampleWideRows,
+    kThreadPerSample1dRows,
     kMlMinLength,
     kMlCoarsest,
     kCount
@@ -95,6 +96,13 @@ inline Threshold table[kCount] = {
     // of planes asks for that): 16 threads x 2 samples up to this many rows, 8 x 4 beyond
     // (256 planes of 32 x 32, K = 10: 204 -> 180 with 16 x 2).
     {"thread_per_sample_wide_rows", 16384, "short rows on the long-row kernels: 16 threads per row up to this many rows"},
+    // 1D calls on rows of 2-32 samples (without segment codes): up to this many rows sixteen
+    // threads per row on the long-row kernels instead of a lane per row, whose few waves are bound
+    // by their dependency chains.  Forward, lane per row / threads per row: 8192 rows x 32 (the
+    // paper's timing batch) 23.6 / 11.7, 32 768 rows 25.0 / 18.0, 65 536 rows 26.6 / 26.6, 131 072
+    // rows 34.7 / 43.7; rows of 20 samples: 8192 rows 30.2 / 11.3, 65 536 rows 32.8 / 24.0; rows of
+    // 12 samples: 8192 rows 12.8 / 11.9, 32 768 rows 14.0 / 13.7, 65 536 rows 14.4 / 20.0.
+    {"thread_per_sample_1d_rows", 32768, "1D rows of at most 32 samples: a few threads per row up to this many rows"},
     // Multilevel start of unit-stride rows (workspace of tv1d_prox_fwd_ex): from this length on.
     // 4096 rows x 16384: 1410 -> 880; below 2048 samples the coarse levels cost what they save.
     {"ml_min_length", 2048, "multilevel start for unit-stride rows of this many samples or more"},

@@ -554,13 +554,14 @@ __global__ __launch_bounds__(T *G, (T * G == 512 && !COLS) ? 4 : ((XPOSE && C <=
 #pragma unroll
         for (int i = 0; i < C; ++i) ym[0] = fmaxf(ym[0], fabsf(y[i]));
         row_max<T, G, MCOLS>(ym, sm.red, j, tid);
-        // lam_max = max_k |sum_{i<=k} (mean(y) - y_i)| <= 2 n max|y|, and every lambda from
+        // lam_max = max_k |sum_{i<=k} (mean(y) - y_i)| = max_k |(k / n) sum_{i>k} y_i -
+        // ((n - k) / n) sum_{i<=k} y_i| <= 2 k (n - k) / n max|y| <= n / 2 max|y|, and every lambda from
         // lam_max on gives the same minimiser (the row's mean): a lambda beyond that bound is
         // replaced by it, which keeps the dual box, and with it the rounding errors of
         // x = y - D^T u, at the scale of the data.  Only the cold start needs it (it puts the
         // duals on the bounds); a pass that starts from an earlier dual is left alone, where the
         // extra dependency cost 3 % of the 2D operator's time.
-        if constexpr (WARM == 0) lam = fminf(lam, 2.5f * (float)n * ym[0]);
+        if constexpr (WARM == 0) lam = fminf(lam, 0.51f * (float)n * ym[0]);
         gtol = kGradNoise * (ym[0] + lam);
         Mp::sync();
     }

@@ -529,6 +529,26 @@ int run_fwd_multilevel(FwdParams p, const tv_lambda &l, int64_t n_rows, const Ml
 
 // ---- dispatch ---------------------------------------------------------------------
 
+// Segment codes read off x (rows of at most 32 samples): what tv1d_fwd_short_kernel builds from its
+// registers, for the forward calls that run on the long-row kernels.  x is bit-constant inside a
+// segment, so the code follows from x alone.  A thread per row; only small batches come here.
+__global__ __launch_bounds__(256) void seg_from_x_kernel(const float *__restrict__ x, uint2 *__restrict__ seg,
+                                                         tvk::Layout L)
+{
+    const uint32_t row = blockIdx.x * 256u + threadIdx.x;
+    if (row >= L.n_rows) return;
+    const float *xr = x + tvk::row_offset(L, row);
+    uint32_t jm = 0, up = 0;
+    float prev = xr[0];
+    for (int k = 0; k + 1 < L.n; ++k) {
+        const float next = xr[(int64_t)(k + 1) * L.elem_stride];
+        jm |= (next != prev ? 1u : 0u) << k;
+        up |= (next > prev ? 1u : 0u) << k;
+        prev = next;
+    }
+    seg[row] = make_uint2(jm, up);
+}
+
 int run_fwd(const float *y, const float *addend, float *x, float *resid, int32_t *info,
             uint2 *seg, uint32_t *order_ws, const tv_rows &r, const tv_lambda &l, int64_t n_rows,
             hipStream_t s, float *x2 = nullptr, bool warm = false, char *ml_ws = nullptr, bool io16 = false,
@@ -548,8 +568,15 @@ int run_fwd(const float *y, const float *addend, float *x, float *resid, int32_t
     // (a few thousand short rows at most: a few threads per row instead of a lane per row; the 2D
     // operator asks for it on small batches of planes, where a lone row-per-lane wave is bound by
     // its dependency chains)
-    if (thread_per_sample && r.length >= 2 && r.length <= 32 && !seg && !io16)
-        return tvk::launch_fwd_long(p, s) == hipSuccess ? TV_OK : TV_ERR_HIP;
+    if (thread_per_sample && r.length >= 2 && r.length <= 32 && !io16) {
+        p.seg = nullptr;
+        if (tvk::launch_fwd_long(p, s) != hipSuccess) return TV_ERR_HIP;
+        if (seg) {
+            hipLaunchKernelGGL(seg_from_x_kernel, dim3((uint32_t)((n_rows + 255) / 256)), dim3(256), 0, s, x, seg, p.L);
+            if (launch_status() != TV_OK) return TV_ERR_HIP;
+        }
+        return TV_OK;
+    }
     if (order_ws && r.length <= 32 && order_applies(p.tm)) {
         uint32_t lgR = 0;
         while (lgR < 6 && ((uint64_t)p.tm.count << (lgR + 1)) <= (uint64_t)kOrderMaxSlots) ++lgR;
@@ -811,8 +838,12 @@ int fwd_entry(const float *y, float *x, tv_rows rows, tv_lambda lam, const tv_fw
             return TV_ERR_WORKSPACE;
         order_ws = (uint32_t *)e.ws;
     }
+    // small batches of short rows: a few threads per row (see tv_dispatch.hpp)
+    // (not when the caller hands over the slot-order workspace or asks for the parallel step-size
+    // search: both belong to the row-per-lane kernels)
+    const bool few = n_rows <= tvd::get(tvd::kThreadPerSample1dRows) && !e.ws && !(e.flags & TV_FWD_PARALLEL_SEARCH);
     return run_fwd(y, nullptr, x, nullptr, e.info, reinterpret_cast<uint2 *>(e.seg), order_ws, rows,
-                   lam, n_rows, s, nullptr, false, (char *)e.ws, false, false,
+                   lam, n_rows, s, nullptr, false, (char *)e.ws, false, few,
                    (e.flags & TV_FWD_ORDER_READY) != 0, (e.flags & TV_FWD_PARALLEL_SEARCH) != 0);
 }
 

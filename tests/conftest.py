@@ -27,3 +27,15 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+@pytest.fixture
+def lane_per_row():
+    """For tests about the row-per-lane kernels (segment codes built in registers, slot order, bf16
+    storage, bit-identity of their variants): small batches of short rows, which the library
+    would give sixteen threads per row (`thread_per_sample_1d_rows`), are kept on those kernels."""
+    import paper_2204_03643_amd as tv
+    saved = tv.tv_dispatch_threshold("thread_per_sample_1d_rows")
+    tv.tv_dispatch_override("thread_per_sample_1d_rows", 0)
+    yield
+    tv.tv_dispatch_override("thread_per_sample_1d_rows", saved)

@@ -10,6 +10,11 @@ from parity import check_batch
 pytestmark = pytest.mark.gpu
 
 
+@pytest.fixture(autouse=True)
+def _row_per_lane_kernels(lane_per_row):
+    yield
+
+
 def _codes_from_x(xr):
     """The code as the header defines it, computed from the forward output in numpy."""
     n = xr.shape[1]

@@ -60,6 +60,7 @@ def _run(y_bits, lam, lam_div, g_bits, use_ws):
                 segf=segf.cpu().numpy())
 
 
+@pytest.mark.usefixtures("lane_per_row")
 @pytest.mark.parametrize("B,C,use_ws", [(4, 128, False), (4, 128, True), (1, 3, False)])
 def test_bf16_pair_equals_rounded_fp32_pair(B, C, use_ws):
     y, lam, g = workloads.config3(B=B, C=C)
