@@ -370,6 +370,14 @@ def dispatch_probe(dev) -> int:
          "16 threads x 2 samples per row", "8 x 4")
     case("thread_per_sample_wide_rows", "beyond_k4", lambda: two_d(n // 32 + n // 128, 32, 32, 4), big,
          "8 threads x 4 samples per row", "16 x 2")
+    # small batches of short rows: sixteen threads per row up to thread_per_sample_1d_rows rows
+    n = defaults["thread_per_sample_1d_rows"]
+    case("thread_per_sample_1d_rows", "at_threshold", lambda: one_d((n // (128 * 32), 128, 32, 32), 128, 32, False), 0,
+         "16 threads per row", "a lane per row")
+    case("thread_per_sample_1d_rows", "beyond", lambda: one_d((n // (128 * 32) + n // (128 * 128), 128, 32, 32), 128, 32, False),
+         big, "a lane per row", "16 threads per row")
+    case("thread_per_sample_1d_rows", "at_a_quarter", lambda: one_d((n // (128 * 128), 128, 32, 32), 128, 32, False), 0,
+         "16 threads per row", "a lane per row")
     # a tensor of exactly stream_bytes bytes: rows of 32 samples in 128 lambda slots
     nb = max(2, defaults["stream_bytes"] // (128 * 32 * 32 * 4))
     case("stream_bytes", "at_threshold", lambda: one_d((nb, 128, 32, 32), 128, 32, False), big,

@@ -101,8 +101,10 @@ inline Threshold table[kCount] = {
     // by their dependency chains.  Forward, lane per row / threads per row: 8192 rows x 32 (the
     // paper's timing batch) 23.6 / 11.7, 32 768 rows 25.0 / 18.0, 65 536 rows 26.6 / 26.6, 131 072
     // rows 34.7 / 43.7; rows of 20 samples: 8192 rows 30.2 / 11.3, 65 536 rows 32.8 / 24.0; rows of
-    // 12 samples: 8192 rows 12.8 / 11.9, 32 768 rows 14.0 / 13.7, 65 536 rows 14.4 / 20.0.
-    {"thread_per_sample_1d_rows", 32768, "1D rows of at most 32 samples: a few threads per row up to this many rows"},
+    // 12 samples: 8192 rows 12.8 / 11.9, 32 768 rows 14.0 / 13.7, 65 536 rows 14.4 / 20.0; N(0,1) rows
+    // of 32 samples in 128 lambda slots, forward + backward: 40 960 rows 39.6 / 38.2, 49 152 rows
+    // 38.2 / 39.6.
+    {"thread_per_sample_1d_rows", 40960, "1D rows of at most 32 samples: a few threads per row up to this many rows"},
     // Multilevel start of unit-stride rows (workspace of tv1d_prox_fwd_ex): from this length on.
     // 4096 rows x 16384: 1410 -> 880; below 2048 samples the coarse levels cost what they save.
     {"ml_min_length", 2048, "multilevel start for unit-stride rows of this many samples or more"},

@@ -1,6 +1,6 @@
 """GPU parity: rows of at most 32 samples against the oracle, through the C ABI.  Every test of
 this module runs twice: with a lane per row (the row-per-lane kernels, which large batches get)
-and with the library's own choice, which gives batches of up to 32 768 rows sixteen threads per
+and with the library's own choice, which gives batches of up to 40 960 rows sixteen threads per
 row on the long-row kernels (`thread_per_sample_1d_rows`)."""
 import numpy as np
 import pytest
