@@ -140,7 +140,8 @@ def test_multilevel_per_channel_lambda_and_strided_rows():
 
 
 @pytest.mark.parametrize("n,width", [(40, 37), (64, 16), (90, 33), (130, 17), (200, 20), (300, 18), (512, 48), (700, 17),
-                                          (1500, 9), (2000, 9), (2600, 5), (4096, 6), (9000, 3), (12000, 2)])
+                                          (1000, 20), (1024, 16), (1500, 9), (2000, 9), (2600, 5), (4096, 6), (9000, 3),
+                                          (12000, 2)])
 def test_long_columns(n, width):
     rng = np.random.default_rng(600 + n)
     y = np.stack([_mixed_rows(rng, width, n).T for _ in range(2)])        # [2, n, width]

@@ -94,10 +94,12 @@ def test_many_small_planes(shape, K):
     _check_2d(y, lam, K, g, "many small %s K=%d" % (shape, K))
 
 
-@pytest.mark.parametrize("shape", [(1, 1100, 2100), (2, 40, 9000)])
+@pytest.mark.parametrize("shape", [(1, 1100, 2100), (2, 40, 9000), (1, 1800, 70), (1, 900, 40), (1, 3000, 33)])
 def test_long_rows_and_columns_k2(shape):
     """Rows and columns beyond 1024 samples (a workgroup per row; interleaved columns), two
-    sweeps, so that the second sweep's passes start from the first sweep's duals."""
+    sweeps, so that the second sweep's passes start from the first sweep's duals; the last three
+    shapes put the warm-started variants of the strided kernels with 16 samples per thread (the
+    ones that spill registers) under the parity rules: columns of 1800, 900 and 3000 samples."""
     rng = np.random.default_rng(91 + shape[1])
     y = (np.cumsum(rng.normal(scale=0.05, size=shape), axis=-1) + rng.normal(scale=0.2, size=shape)).astype(np.float32)
     g = rng.normal(size=shape).astype(np.float32)
