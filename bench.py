@@ -347,11 +347,19 @@ def dispatch_probe(dev) -> int:
             "chosen_not_slower": a["fwd_bwd_us"] <= 1.03 * b["fwd_bwd_us"]}
 
     big = 1 << 40
-    n = defaults["tiny_batch_planes"]
-    case("tiny_batch_planes", "at_threshold_k4", lambda: two_d(n, 32, 32, 4), 0,
-         "pass by pass on the long-row kernels", "one launch")
-    case("tiny_batch_planes", "beyond_k4", lambda: two_d(n + n // 4, 32, 32, 4), big,
-         "one launch", "pass by pass on the long-row kernels")
+    # small batches: a plane per workgroup up to these plane counts
+    n = defaults["plane_per_group_planes"]
+    for K in (1, 4):
+        case("plane_per_group_planes", "at_threshold_k%d" % K, lambda: two_d(n, 32, 32, K), 0,
+             "a plane per workgroup", "the row-per-lane kernels")
+        case("plane_per_group_planes", "beyond_k%d" % K, lambda: two_d(n + n // 4, 32, 32, K), big,
+             "the row-per-lane kernels", "a plane per workgroup")
+    case("plane_per_group_planes", "at_a_fifth_k4", lambda: two_d(n // 5, 32, 32, 4), 0,
+         "a plane per workgroup", "the row-per-lane kernels")
+    for name, K in (("plane_per_group64_planes", 1), ("plane_per_group64_planes_k2", 2), ("plane_per_group64_planes_k2", 4)):
+        n = defaults[name]
+        case(name, "at_threshold_k%d" % K, lambda: two_d(n, 64, 64, K), 0, "a plane per workgroup", "pass by pass")
+        case(name, "beyond_k%d" % K, lambda: two_d(n + n // 4, 64, 64, K), big, "pass by pass", "a plane per workgroup")
     for name, K in (("fused32_full_planes", 1), ("fused32_full_planes_k2", 2), ("fused32_full_planes_k3", 4)):
         n = defaults[name]
         if n > (1 << 20):           # "always": timed at the largest count that was measured
@@ -366,9 +374,9 @@ def dispatch_probe(dev) -> int:
     case("fused16_one_sweep_planes", "at_threshold_k1", lambda: two_d(n, 16, 16, 1), 0, "one launch", "pass by pass")
     case("fused16_one_sweep_planes", "beyond_k1", lambda: two_d(n + n // 4, 16, 16, 1), big, "pass by pass", "one launch")
     n = defaults["thread_per_sample_wide_rows"]
-    case("thread_per_sample_wide_rows", "at_threshold_k4", lambda: two_d(n // 32, 32, 32, 4), 0,
+    case("thread_per_sample_wide_rows", "at_threshold", lambda: one_d((n // (128 * 32), 128, 32, 32), 128, 32, False), 0,
          "16 threads x 2 samples per row", "8 x 4")
-    case("thread_per_sample_wide_rows", "beyond_k4", lambda: two_d(n // 32 + n // 128, 32, 32, 4), big,
+    case("thread_per_sample_wide_rows", "beyond", lambda: one_d((n // (128 * 32) + 1, 128, 32, 32), 128, 32, False), big,
          "8 threads x 4 samples per row", "16 x 2")
     # small batches of short rows: sixteen threads per row up to thread_per_sample_1d_rows rows
     n = defaults["thread_per_sample_1d_rows"]

@@ -248,8 +248,10 @@ int tv1d_prox_bwd_seg_bf16(const uint16_t *g_up, const uint64_t *seg, uint16_t *
  * after tv_dispatch_override("fused_keeps_passes", 1)).  x must not alias y.
  * From the second sweep on, the correction term a pass adds to its input is D^T u of the
  * same pass one sweep earlier (x = y - D^T u), and the pass starts its Newton iteration
- * from that dual.  Planes of at most 32 x 32 run all their passes in one launch where that is
- * faster (the plane counts at which it is: csrc/tv_dispatch.hpp).
+ * from that dual.  Planes of at most 64 x 64 run all their passes in one launch where that is
+ * faster (small batches with a plane per workgroup, larger ones of planes of at most 32 x 32
+ * with a row per lane; the plane counts: csrc/tv_dispatch.hpp).  tv2d_prox_bwd must see the
+ * dispatch thresholds that the forward call saw.
  */
 size_t tv2d_workspace_bytes(int64_t planes, int64_t H, int64_t W, int sweeps);
 int tv2d_prox_fwd(const float *y, float *x, int64_t planes, int64_t H, int64_t W,

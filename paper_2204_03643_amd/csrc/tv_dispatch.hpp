@@ -18,13 +18,14 @@ struct Threshold {
 enum {
     kStreamBytes = 0,
     kOrderMinRows,
-    kTinyBatchPlanes,
     kFused32FullPlanes,
     kFused32FullPlanesK2,
     kFused32FullPlanesK3,
     kFused32RaggedPlanes,
     kFused16OneSweepPlanes,
-    kFused64Planes,
+    kPlanePerGroupPlanes,
+    kPlanePerGroup64Planes,
+    kPlanePerGroup64PlanesK2,
     kFusedKeepsPasses,
     kThreadPerSampleWideRows,
     kThreadPerSample1dRows,
@@ -50,13 +51,6 @@ inline Threshold table[kCount] = {
     // order whenever it is handed the workspace; the layer (layer.py) would hand it over from
     // this many rows on, and the value means "never".
     {"order_min_rows", (int64_t)1 << 40, "the layer passes the slot-order workspace from this many rows on"},
-    // 2D, planes of 17-32 samples a side: up to this many planes the 2K forward passes run one by
-    // one on the thread-per-few-samples kernels (a lone row-per-lane wave per SIMD issues an
-    // instruction every 9 cycles).  Forward + backward, pass by pass on those kernels against the
-    // one-launch kernel, feature-map-like data: K = 1: 256 planes 39 / 58, 768: 53 / 57, 1024:
-    // 58 / 62, 1536: 68 / 64; K = 2: 512 planes 75 / 84, 768: 84 / 95, 1024: 93 / 94; K = 4: 256
-    // planes 106 / 140, 512: 128 / 142, 768: 149 / 153, 1024: 167 / 155, 1536: 194 / 157.
-    {"tiny_batch_planes", 768, "2D planes of 17-32 a side: pass by pass on the long-row kernels up to this many planes"},
     // 2D, planes of exactly 32 x 32: the one-launch forward kernel holds two waves per SIMD (17 KB
     // of LDS per wave) where the pass-by-pass kernels hold three, but pays no launches and no
     // memory round trips between the passes, which weighs more the more sweeps there are.
@@ -79,22 +73,34 @@ inline Threshold table[kCount] = {
     // launch against 58 pass by pass, 24 576: 70 / 75, 32 768: 88 / 86 (K = 3: 166 against 206
     // forward, so several sweeps always take the one launch).
     {"fused16_one_sweep_planes", 24576, "2D planes of at most 16 x 16, one sweep: one launch up to this many planes"},
-    // 2D, planes of 33-64 samples a side: all passes in one launch, a plane per wave and a row or
-    // column per lane (the solver then fills the register file: 256 VGPRs + 256 AGPRs, one wave per
-    // SIMD), against pass by pass with eight threads per row.  The one launch never wins: 64 x 64,
-    // K = 4: 64 planes 541 / 168, 1024 planes 616 / 324, 8192 planes 3390 / 1577; 48 x 48, K = 1:
-    // 256 planes 153 / 54.  It is kept (and tested) as the stated variant for planes of up to
-    // 64 x 64; the default of 0 planes means "never".
-    {"fused64_planes", 0, "2D planes of 33-64 samples a side: one launch up to this many planes"},
+    // 2D, small batches: one plane per workgroup of 512 threads, resident in LDS for all passes,
+    // 16 threads x 2 samples per row (sides of 17-32) or 8 x 8 (sides of 33-64); tv_plane2d.hpp.
+    // A lone row-per-lane wave per SIMD issues an instruction every 9 cycles, and pass by pass a
+    // small batch pays a launch and a trip through memory per pass; this mapping has 8x the waves,
+    // short chains and one launch.  Its time is set by the slowest row of each pass (a barrier
+    // between passes), so it stops paying once the other kernels fill the chip.  Forward, this
+    // kernel / the library's choice without it, feature-map-like data:
+    //   32 x 32, K = 1:  256 planes 20 / 25,  1024: 41 /  46,  1280:  45 /  45,  1536:  51 /  46;
+    //            K = 2:  512 planes 38 / 57,  1024: 58 /  76,  1536:  78 /  81,  2048:  99 /  77;
+    //            K = 4:   64 planes 38 / 70,   256: 38 /  83,  1024:  87 / 130,  1536: 119 / 129,
+    //                    2048: 155 / 133;  K = 10: 256 planes 71 / 178;
+    //   28 x 30, K = 1: 1280 planes 42 / 59,  2048: 57 /  68;  K = 3: 2048 planes 117 / 152.
+    {"plane_per_group_planes", 1280, "2D planes of 17-32 a side: one launch, a plane per workgroup, up to this many planes"},
+    //   64 x 64, K = 1:  128 planes  47 /  49,  512:  63 /  73, 1024: 109 / 105, 1536: 157 / 128;
+    //            K = 2:  128 planes  71 /  90,  512:  99 / 125, 1024: 167 / 179, 1280: 209 / 189;
+    //            K = 4:  128 planes 110 / 157,  512: 156 / 224, 1024: 266 / 314, 2048: 500 / 472;
+    //   40 x 48, K = 1:  256 planes  40 /  45, 1024:  79 /  70;  K = 3: 256 planes 74 / 112, 1024: 156 / 185.
+    {"plane_per_group64_planes", 768, "2D planes of 33-64 a side, one sweep: one launch, a plane per workgroup, up to this many planes"},
+    {"plane_per_group64_planes_k2", 1024, "... two sweeps or more"},
     // 2D, planes of at most 32 x 32 in one launch: the reverse sweep reads the segment codes of the
     // passes, not their outputs, so the forward kernel writes only the codes and x.  1 = it also
     // writes every pass's output into the workspace, where the pass-by-pass forward leaves them (the
     // tests set it to compare each pass with the oracle's).  Not writing them: 4096 planes of
     // 32 x 32, K = 1 / 4 / 10: 56 -> 52, 156 -> 149, 403 -> 385; 16 384 planes, K = 4: 560 -> 512.
     {"fused_keeps_passes", 0, "2D one-launch forward of planes of at most 32 x 32: 1 = also write every pass's output"},
-    // Rows of at most 32 samples on the long-row kernels (only the 2D operator on small batches
-    // of planes asks for that): 16 threads x 2 samples up to this many rows, 8 x 4 beyond
-    // (256 planes of 32 x 32, K = 10: 204 -> 180 with 16 x 2).
+    // Rows of at most 32 samples on the long-row kernels (small 1D batches, see
+    // thread_per_sample_1d_rows): 16 threads x 2 samples up to this many rows, 8 x 4 beyond
+    // (8192 rows of 32 samples as 256 planes, ten passes each way: 204 -> 180 with 16 x 2).
     {"thread_per_sample_wide_rows", 16384, "short rows on the long-row kernels: 16 threads per row up to this many rows"},
     // 1D calls on rows of 2-32 samples (without segment codes): up to this many rows sixteen
     // threads per row on the long-row kernels instead of a lane per row, whose few waves are bound

@@ -347,14 +347,14 @@ struct Small2dFwdParams {
     uint32_t     stream;
 };
 
-// S, FULL: as in the reverse sweep (a wave holds 64 / S planes).
+// S, FULL: as in the reverse sweep (a wave holds 64 / S planes), S <= 32.
 // IO16: y and x are bf16 in memory; the saved pass outputs stay fp32.
-// S = 64 (planes of 33-64 samples a side, one per wave): the row-per-lane solver then holds four
-// arrays of 64 registers, the whole register file of a SIMD lane (256 VGPRs + 256 AGPRs), one wave
-// per SIMD; no segment codes are written (the reverse sweep reads the saved pass outputs).
+// (Planes of 33-64 samples a side: tv_plane2d.hpp.  A row of 64 samples per lane would take four
+// arrays of 64 registers, the whole register file of a SIMD lane, for one wave per SIMD.)
 template <int S, bool FULL, bool IO16 = false>
-__global__ __launch_bounds__(64, S <= 32 ? 2 : 1) void tv2d_fwd_small_kernel(Small2dFwdParams p)
+__global__ __launch_bounds__(64, 2) void tv2d_fwd_small_kernel(Small2dFwdParams p)
 {
+    static_assert(S <= 32, "a row or column per lane: planes of at most 32 x 32");
     constexpr int P = S + 1;
     constexpr int PP = 64 / S;
     __shared__ float T1[64 * P], T2[64 * S], gtab[S + 2], rtab[S + 2];
@@ -444,7 +444,7 @@ __global__ __launch_bounds__(64, S <= 32 ? 2 : 1) void tv2d_fwd_small_kernel(Sma
         for (int it = 0; !sv.iterate(it); ++it) {}
         sv.recover(xs);
 
-        if constexpr (S <= 32) {   // segment code of the row / column (as the short-row kernel builds it)
+        {   // segment code of the row / column (as the short-row kernel builds it)
             uint32_t jm = 0, up = 0;
 #pragma unroll
             for (int k = S - 2; k >= 0; --k) {
@@ -476,7 +476,7 @@ __global__ __launch_bounds__(64, S <= 32 ? 2 : 1) void tv2d_fwd_small_kernel(Sma
         }
         wave_lds_sync();
         // (planes of at most 32 x 32: the reverse sweep reads the codes written above)
-        if (S > 32 || p.keep_passes) put_planes(p.saved + (size_t)i * p.saved_stride + plane0 * HW);
+        if (p.keep_passes) put_planes(p.saved + (size_t)i * p.saved_stride + plane0 * HW);
         if (i + 1 == n_pass) {
             if constexpr (IO16) {
                 uint16_t *dst = reinterpret_cast<uint16_t *>(p.x) + plane0 * HW;

@@ -12,6 +12,7 @@
 #include "tv_dispatch.hpp"
 #include "tv_long.hpp"
 #include "tv_small2d.hpp"
+#include "tv_plane2d.hpp"
 #include "tv_short.hpp"
 
 // Scratch of tv1d_prox_bwd_noalloc (the per-row dL/dlam terms between the backward kernel and
@@ -1160,15 +1161,14 @@ static int small_side(int64_t H, int64_t W)
         }                                                                                           \
     } while (0)
 
-// Small batches of planes of 17-32 samples a side (up to tiny_batch_planes of tv_dispatch.hpp): the
-// forward passes run one by one on the long-row kernels (eight or sixteen threads per row), and
-// the reverse sweep reads the segments off the saved pass outputs instead of codes.  With so few
-// rows a row-per-lane wave runs alone on its SIMD and issues an instruction every 9 cycles; the
-// thread-per-few-samples mapping has 8x the waves and shorter chains (256 planes of 32 x 32,
-// K = 10: 507 -> 180 us forward); from about a thousand planes on the one launch is as fast.
-static bool tiny_batch_2d(int64_t planes, int64_t H, int64_t W)
+// Small batches of planes of 17-64 samples a side: one launch with a plane per workgroup
+// (tv_plane2d.hpp), up to the plane counts of tv_dispatch.hpp.  Planes of at most 32 x 32 leave
+// segment codes for the reverse sweep, larger ones their pass outputs.
+static bool plane_per_group_2d(int64_t planes, int64_t H, int64_t W, int sweeps)
 {
-    return small_planes(H, W) && small_side(H, W) == 32 && planes <= tvd::get(tvd::kTinyBatchPlanes);
+    if (small_planes(H, W)) return small_side(H, W) == 32 && planes <= tvd::get(tvd::kPlanePerGroupPlanes);
+    return H <= 64 && W <= 64 &&
+           planes <= tvd::get(sweeps == 1 ? tvd::kPlanePerGroup64Planes : tvd::kPlanePerGroup64PlanesK2);
 }
 
 // When the one-launch forward kernel is used: while its lower occupancy (17 KB of LDS per wave
@@ -1214,8 +1214,20 @@ int tv2d_prox_fwd(const float *y, float *x, int64_t planes, int64_t H, int64_t W
     const tv_lambda lrow = {lam.lam, lam.count, H};
     const tv_lambda lcol = {lam.lam, lam.count, W};
 
-    const bool tiny = cb && tiny_batch_2d(planes, H, W);
-    if (cb && !tiny && fused_fwd_applies(small_side(H, W), H == small_side(H, W) && W == H, planes, sweeps)) {
+    if (plane_per_group_2d(planes, H, W, sweeps)) {
+        // a small batch of planes of 17-64 samples a side: one launch, a plane per workgroup
+        tvk::Small2dFwdParams q;
+        q.y = y; q.x = x; q.saved = saved(0); q.saved_stride = tb / sizeof(float); q.keep_passes = tvd::get(tvd::kFusedKeepsPasses) != 0 ? 1u : 0u;
+        q.codes = codes(0); q.code_stride = cb / sizeof(uint2);
+        q.lam = lam.lam; q.lam_count = lam.count;
+        q.planes = (int32_t)planes; q.H = (int32_t)H; q.W = (int32_t)W; q.sweeps = sweeps;
+        q.stream = 0u;
+        const dim3 grid((uint32_t)planes);
+        if (cb) hipLaunchKernelGGL((tvk::tv2d_fwd_plane_kernel<16, 2>), grid, dim3(512), 0, stream, q);
+        else hipLaunchKernelGGL((tvk::tv2d_fwd_plane_kernel<8, 8>), grid, dim3(512), 0, stream, q);
+        return launch_status();
+    }
+    if (cb && fused_fwd_applies(small_side(H, W), H == small_side(H, W) && W == H, planes, sweeps)) {
         // planes of at most 32 x 32: all passes in one launch, the planes resident in LDS
         tvk::Small2dFwdParams q;
         q.y = y; q.x = x; q.saved = saved(0); q.saved_stride = tb / sizeof(float); q.keep_passes = tvd::get(tvd::kFusedKeepsPasses) != 0 ? 1u : 0u;
@@ -1226,21 +1238,6 @@ int tv2d_prox_fwd(const float *y, float *x, int64_t planes, int64_t H, int64_t W
         TV_SMALL2D_LAUNCH(tvk::tv2d_fwd_small_kernel, q, planes, H, W, stream);
         return launch_status();
     }
-    if (!cb && H <= 64 && W <= 64 && planes <= tvd::get(tvd::kFused64Planes)) {
-        // planes of 33-64 samples a side: all passes in one launch, a plane per wave
-        tvk::Small2dFwdParams q;
-        q.y = y; q.x = x; q.saved = saved(0); q.saved_stride = tb / sizeof(float); q.keep_passes = tvd::get(tvd::kFusedKeepsPasses) != 0 ? 1u : 0u;
-        q.codes = nullptr; q.code_stride = 0;
-        q.lam = lam.lam; q.lam_count = lam.count;
-        q.planes = (int32_t)planes; q.H = (int32_t)H; q.W = (int32_t)W; q.sweeps = sweeps;
-        q.stream = (planes * H * W >= tvd::get(tvd::kStreamBytes) / 4) ? 1u : 0u;
-        const dim3 grid((uint32_t)planes);
-        if (H == 64 && W == 64)
-            hipLaunchKernelGGL((tvk::tv2d_fwd_small_kernel<64, true>), grid, dim3(64), 0, stream, q);
-        else
-            hipLaunchKernelGGL((tvk::tv2d_fwd_small_kernel<64, false>), grid, dim3(64), 0, stream, q);
-        return launch_status();
-    }
     for (int k = 0; k < sweeps; ++k) {
         const bool last = (k == sweeps - 1);
         const float *Yk = (k == 0) ? y : saved(2 * k - 1);
@@ -1248,13 +1245,13 @@ int tv2d_prox_fwd(const float *y, float *x, int64_t planes, int64_t H, int64_t W
         // Z = proxRows(Y + P);  P <- (Y + P) - Z      (P = 0 in the first sweep)
         // From the second sweep on, P = D^T u of the row pass one sweep earlier (x = y - D^T u),
         // and likewise Q for the columns: each pass starts from that dual.
-        st = run_fwd(Yk, k == 0 ? nullptr : P, Z, last ? nullptr : P, nullptr, tiny ? nullptr : codes(2 * k), nullptr,
-                     rrow, lrow, planes * H, stream, nullptr, true, nullptr, false, tiny);
+        st = run_fwd(Yk, k == 0 ? nullptr : P, Z, last ? nullptr : P, nullptr, codes(2 * k), nullptr,
+                     rrow, lrow, planes * H, stream, nullptr, true);
         if (st != TV_OK) return st;
         // Y' = proxCols(Z + Q);  Q <- (Z + Q) - Y'
         // the last pass writes its output twice: where the reverse sweep will look for it, and to x
-        st = run_fwd(Z, k == 0 ? nullptr : Q, Yn, last ? nullptr : Q, nullptr, tiny ? nullptr : codes(2 * k + 1), nullptr,
-                     rcol, lcol, planes * W, stream, last ? x : nullptr, true, nullptr, false, tiny);
+        st = run_fwd(Z, k == 0 ? nullptr : Q, Yn, last ? nullptr : Q, nullptr, codes(2 * k + 1), nullptr,
+                     rcol, lcol, planes * W, stream, last ? x : nullptr, true);
         if (st != TV_OK) return st;
     }
     return TV_OK;
@@ -1364,13 +1361,7 @@ int tv2d_prox_bwd(const float *g_up, float *grad_y, float *grad_lam, int64_t pla
         q.partial = grad_lam ? partial(0) : nullptr;
         q.planes = (int32_t)planes; q.H = (int32_t)H; q.W = (int32_t)W; q.sweeps = sweeps;
         q.stream = (planes * H * W >= tvd::get(tvd::kStreamBytes) / 4) ? 1u : 0u;
-        if (cb && tiny_batch_2d(planes, H, W)) {
-            const dim3 grid((uint32_t)((planes + 1) / 2));
-            if (H == 32 && W == 32)
-                hipLaunchKernelGGL((tvk::tv2d_bwd_small_kernel<32, true, true>), grid, dim3(64), 0, stream, q);
-            else
-                hipLaunchKernelGGL((tvk::tv2d_bwd_small_kernel<32, false, true>), grid, dim3(64), 0, stream, q);
-        } else if (cb) {
+        if (cb) {
             TV_SMALL2D_LAUNCH(tvk::tv2d_bwd_small_kernel, q, planes, H, W, stream);
         } else {
             hipLaunchKernelGGL((tvk::tv2d_bwd_small_kernel<64, true>), dim3((uint32_t)planes), dim3(64), 0, stream, q);

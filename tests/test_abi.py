@@ -106,7 +106,7 @@ def test_step_record_validation():
 
 def test_dispatch_thresholds_are_listed_and_overridable():
     th = tv.tv_dispatch_thresholds()
-    assert {"stream_bytes", "tiny_batch_planes", "fused32_full_planes", "ml_min_length"} <= set(th)
+    assert {"stream_bytes", "plane_per_group_planes", "fused32_full_planes", "ml_min_length"} <= set(th)
     assert th["ml_min_length"] == 2048 and tv.tv_dispatch_threshold("no_such_name") == -1
     tv.tv_dispatch_override("ml_min_length", 4096)
     assert tv.tv_dispatch_threshold("ml_min_length") == 4096

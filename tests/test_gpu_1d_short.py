@@ -1,7 +1,9 @@
 """GPU parity: rows of at most 32 samples against the oracle, through the C ABI.  Every test of
-this module runs twice: with a lane per row (the row-per-lane kernels, which large batches get)
-and with the library's own choice, which gives batches of up to 40 960 rows sixteen threads per
-row on the long-row kernels (`thread_per_sample_1d_rows`)."""
+this module runs three times: with a lane per row (the row-per-lane kernels, which large batches
+get), with the library's own choice, which gives batches of up to 40 960 rows a few threads per
+row on the long-row kernels (`thread_per_sample_1d_rows`: sixteen threads with two samples each
+up to `thread_per_sample_wide_rows` rows), and with eight threads of four samples per row, which
+the library picks for the larger of those batches."""
 import numpy as np
 import pytest
 
@@ -14,14 +16,17 @@ from refmath import certificate
 pytestmark = pytest.mark.gpu
 
 
-@pytest.fixture(autouse=True, params=["lane per row", "library's choice"])
+@pytest.fixture(autouse=True, params=["lane per row", "library's choice", "eight threads per row"])
 def row_mapping(request):
     import paper_2204_03643_amd as tv
-    saved = tv.tv_dispatch_threshold("thread_per_sample_1d_rows")
+    saved = {k: tv.tv_dispatch_threshold(k) for k in ("thread_per_sample_1d_rows", "thread_per_sample_wide_rows")}
     if request.param == "lane per row":
         tv.tv_dispatch_override("thread_per_sample_1d_rows", 0)
+    elif request.param == "eight threads per row":
+        tv.tv_dispatch_override("thread_per_sample_wide_rows", 0)
     yield request.param
-    tv.tv_dispatch_override("thread_per_sample_1d_rows", saved)
+    for k, v in saved.items():
+        tv.tv_dispatch_override(k, v)
 
 
 def _check(y, lam, lam_div, g, axis, label):

@@ -154,7 +154,7 @@ def dispatch_defaults():
 @pytest.mark.parametrize("shape,K", [((70, 32, 32), 2), ((37, 28, 30), 3), ((90, 16, 16), 1), ((33, 13, 16), 2)])
 def test_every_forward_mapping_of_small_planes(shape, K, dispatch_defaults):
     """The same call through each mapping the dispatch can choose for planes of at most 32 x 32
-    (pass by pass on the thread-per-few-samples kernels, all passes in one launch, pass by pass on
+    (a plane per workgroup, all passes in one launch of the row-per-lane kernel, pass by pass on
     the row-per-lane kernels with plane columns and segment codes), forced through the thresholds:
     the choice is a matter of speed only, so each one must meet the parity rules."""
     import paper_2204_03643_amd as tv
@@ -166,35 +166,40 @@ def test_every_forward_mapping_of_small_planes(shape, K, dispatch_defaults):
              "fused16_one_sweep_planes")
     big = 1 << 40
     outs = []
-    for tiny, fused, wide in ((big, big, big), (big, big, 0), (0, big, big), (0, 0, big)):
-        tv.tv_dispatch_override("tiny_batch_planes", tiny)
-        tv.tv_dispatch_override("thread_per_sample_wide_rows", wide)
+    for per_plane, fused in ((big, big), (0, big), (0, 0)):
+        tv.tv_dispatch_override("plane_per_group_planes", per_plane)
         for nme in names:
             tv.tv_dispatch_override(nme, fused)
         out = run_2d(y, lam, K, g)
-        check_2d(y, lam, K, g, out, "forced (%d, %d, %d) %s K=%d" % (tiny > 0, fused > 0, wide > 0, shape, K))
+        check_2d(y, lam, K, g, out, "forced (%d, %d) %s K=%d" % (per_plane > 0, fused > 0, shape, K))
         outs.append(out)
     # every mapping solves the same problems to rounding: outputs agree far inside the parity bar
     for o in outs[1:]:
         assert np.abs(o["x"] - outs[0]["x"]).max() <= 2e-5 * (1 + np.abs(y).max())
 
 
-@pytest.mark.parametrize("shape,K", [((5, 64, 64), 3), ((3, 40, 56), 2), ((4, 33, 64), 2), ((2, 64, 35), 1),
-                                     ((70, 48, 48), 4), ((1, 33, 33), 1)])
-def test_one_launch_forward_for_planes_of_33_to_64(shape, K, dispatch_defaults):
-    """All 2K passes of planes of 33-64 samples a side in one launch (a plane per wave, a row or
-    column per lane): slower than pass by pass at every size measured, so the dispatch never picks
-    it by itself; forced here, it must meet the same parity rules, reverse sweep included (one
-    launch for 64 x 64, pass by pass otherwise, both from the saved pass outputs)."""
+@pytest.mark.parametrize("shape,K", [((70, 32, 32), 2), ((37, 28, 30), 3), ((9, 17, 32), 4), ((5, 32, 3), 2), ((3, 1, 20), 2),
+                                     ((4, 31, 1), 1), ((260, 32, 32), 1), ((5, 64, 64), 3), ((3, 40, 56), 2), ((4, 33, 64), 2),
+                                     ((2, 64, 35), 1), ((70, 48, 48), 4), ((1, 33, 33), 1), ((3, 2, 64), 2), ((300, 64, 64), 1)])
+def test_plane_per_workgroup_forward(shape, K, dispatch_defaults):
+    """All 2K passes in one launch with a plane per workgroup (16 threads x 2 samples per row for
+    sides of 17-32, 8 x 8 for sides of 33-64), forced through its thresholds for plane counts on
+    both sides of what the dispatch would pick: the parity rules of every other mapping, reverse
+    sweep included (from the segment codes up to 32 x 32, from the saved pass outputs beyond),
+    and agreement with the default mapping far inside the parity bar."""
     import paper_2204_03643_amd as tv
-    rng = np.random.default_rng(61 + shape[1] + shape[2])
+    rng = np.random.default_rng(211 + shape[1] + 3 * shape[2])
     y = rng.normal(size=shape).astype(np.float32)
     g = rng.normal(size=shape).astype(np.float32)
-    lam = (10 ** rng.uniform(-2, 0.3, size=2)).astype(np.float32)
+    lam = (10 ** rng.uniform(-2, 0.3, size=3)).astype(np.float32)
+    knobs = ("plane_per_group_planes", "plane_per_group64_planes", "plane_per_group64_planes_k2")
+    for k in knobs:
+        tv.tv_dispatch_override(k, 0)
     ref = run_2d(y, lam, K, g)
-    tv.tv_dispatch_override("fused64_planes", 1 << 40)
+    for k in knobs:
+        tv.tv_dispatch_override(k, 1 << 40)
     out = run_2d(y, lam, K, g)
-    check_2d(y, lam, K, g, out, "one launch %s K=%d" % (shape, K))
+    check_2d(y, lam, K, g, out, "plane per workgroup %s K=%d" % (shape, K))
     assert np.abs(out["x"] - ref["x"]).max() <= 2e-5 * (1 + np.abs(y).max())
 
 
@@ -209,7 +214,7 @@ def test_one_launch_forward_without_the_pass_outputs(shape, K, dispatch_defaults
     y = np.maximum(rng.normal(size=shape), 0).astype(np.float32)
     g = rng.normal(size=shape).astype(np.float32)
     lam = (10 ** rng.uniform(-2, 0.3, size=4)).astype(np.float32)
-    tv.tv_dispatch_override("tiny_batch_planes", 0)           # onto the one-launch kernel whatever the count
+    tv.tv_dispatch_override("plane_per_group_planes", 0)      # onto the row-per-lane one-launch kernel whatever the count
     for nme in ("fused32_full_planes", "fused32_full_planes_k2", "fused32_full_planes_k3", "fused32_ragged_planes",
                 "fused16_one_sweep_planes"):
         tv.tv_dispatch_override(nme, 1 << 40)
