@@ -80,18 +80,20 @@ inline Threshold table[kCount] = {
     // short chains and one launch.  Its time is set by the slowest row of each pass (a barrier
     // between passes), so it stops paying once the other kernels fill the chip.  Forward, this
     // kernel / the library's choice without it, feature-map-like data:
-    //   32 x 32, K = 1:  256 planes 20 / 25,  1024: 41 /  46,  1280:  45 /  45,  1536:  51 /  46;
-    //            K = 2:  512 planes 38 / 57,  1024: 58 /  76,  1536:  78 /  81,  2048:  99 /  77;
-    //            K = 4:   64 planes 38 / 70,   256: 38 /  83,  1024:  87 / 130,  1536: 119 / 129,
-    //                    2048: 155 / 133;  K = 10: 256 planes 71 / 178;
-    //   28 x 30, K = 1: 1280 planes 42 / 59,  2048: 57 /  68;  K = 3: 2048 planes 117 / 152.
-    {"plane_per_group_planes", 1280, "2D planes of 17-32 a side: one launch, a plane per workgroup, up to this many planes"},
-    //   64 x 64, K = 1:  128 planes  47 /  49,  512:  63 /  73, 1024: 109 / 105, 1536: 157 / 128;
-    //            K = 2:  128 planes  71 /  90,  512:  99 / 125, 1024: 167 / 179, 1280: 209 / 189;
-    //            K = 4:  128 planes 110 / 157,  512: 156 / 224, 1024: 266 / 314, 2048: 500 / 472;
-    //   40 x 48, K = 1:  256 planes  40 /  45, 1024:  79 /  70;  K = 3: 256 planes 74 / 112, 1024: 156 / 185.
-    {"plane_per_group64_planes", 768, "2D planes of 33-64 a side, one sweep: one launch, a plane per workgroup, up to this many planes"},
-    {"plane_per_group64_planes_k2", 1024, "... two sweeps or more"},
+    //   32 x 32, K = 1:  512 planes 22 /  42,  1024: 33 /  45,  1536:  44 /  46,  1792:  50 /  45;
+    //            K = 2:  512 planes 32 /  68,  1024: 51 /  75,  1536:  69 /  80,  2048:  88 /  77;
+    //            K = 4:  512 planes 51 / 119,  1024: 81 / 130,  1536: 110 / 129,  2048: 143 / 133;
+    //   28 x 30, K = 1: 1280 planes 37 /  59,  2048: 52 /  68;  K = 3: 2048 planes 108 / 153;
+    //   20 x 32, K = 1: 2048 planes 47 /  59,  4096: 80 /  67;  K = 4: 2048 planes 120 / 177.
+    {"plane_per_group_planes", 1536, "2D planes of 17-32 a side: one launch, a plane per workgroup, up to this many planes"},
+    //   64 x 64, K = 1:  128 planes  34 /  49, 1024:  85 / 104, 1536: 121 / 129, 2048: 158 / 159, 2560: 193 / 172;
+    //            K = 2:  128 planes  53 /  91, 1024: 134 / 181, 2048: 248 / 276, 4096: 472 / 474;
+    //            K = 4:  128 planes  83 / 157, 1024: 219 / 314, 2048: 415 / 484, 4096: 790 / 827;
+    //   48 x 48, K = 1: 1536 planes  98 /  97, 2048: 128 / 116;
+    //            K = 2: 1536 planes 162 / 177, 2048: 207 / 203, 3072: 295 / 273;
+    //            K = 4: 1536 planes 266 / 313, 2048: 350 / 360, 3072: 509 / 483.
+    {"plane_per_group64_planes", 1536, "2D planes of 33-64 a side, one sweep: one launch, a plane per workgroup, up to this many planes"},
+    {"plane_per_group64_planes_k2", 2048, "... two sweeps or more"},
     // 2D, planes of at most 32 x 32 in one launch: the reverse sweep reads the segment codes of the
     // passes, not their outputs, so the forward kernel writes only the codes and x.  1 = it also
     // writes every pass's output into the workspace, where the pass-by-pass forward leaves them (the

