@@ -44,6 +44,11 @@ def lib() -> ctypes.CDLL:
     if _lib is None:
         if _build.is_stale():
             _build.build_library()
+        # PyTorch ships a HIP runtime of its own.  Loaded first, it is the one this library binds
+        # to as well, and device pointers and streams mean the same thing to both; in the other
+        # order the process ends up with the system's runtime underneath PyTorch's libraries,
+        # and every kernel launch of this library fails.
+        import torch  # noqa: F401
         L = ctypes.CDLL(_build.LIB)
         L.tv_dispatch_name.argtypes = [ctypes.c_int]
         L.tv_dispatch_name.restype = ctypes.c_char_p

@@ -966,11 +966,15 @@ __global__ __launch_bounds__(T *G, (T * G == 512 && !COLS) ? 4 : ((XPOSE && C <=
 #pragma unroll
         for (int i = 0; i < C; ++i) {
             if (i > 0 && bnd[i - 1]) val = xs[i];
-            if (fabsf(val - xs[i]) > 2e-5f * (1.f + fabsf(y[i]) + lam)) dev[0] += 1.f;
+            // (not below four rounding floors of a difference of two x values: the floor follows
+            // the row's largest sample, and next to one large sample a converged row's small
+            // segments still carry that much noise)
+            if (fabsf(val - xs[i]) > fmaxf(2e-5f * (1.f + fabsf(y[i]) + lam), 4.f * gtol)) dev[0] += 1.f;
             u[i] = val;       // u is dead from here on: reuse it for the block values
         }
         row_sum<T, G, MCOLS, 1>(dev, sm.red, j, tid);
-        const bool use_blocks = !(flags & kInfoCapped) && dev[0] == 0.f;
+        // (an infinite sample makes the floor infinite: such a row keeps its plain output, which shows it)
+        const bool use_blocks = !(flags & kInfoCapped) && dev[0] == 0.f && gtol <= 3.0e38f;
         if (use_blocks) {
 #pragma unroll
             for (int i = 0; i < C; ++i) xs[i] = u[i];

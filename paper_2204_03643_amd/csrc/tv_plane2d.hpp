@@ -376,7 +376,8 @@ __device__ __forceinline__ int lanes_row_solve(const float (&y)[C], float (&u)[C
             blk[i] = val;
         }
         dev = wave_sum_all<T>(dev);
-        if (!(flags & kInfoCapped) && dev == 0.f) {
+        // (an infinite sample makes the floor infinite: such a row keeps its plain output, which shows it)
+        if (!(flags & kInfoCapped) && dev == 0.f && gtol <= 3.0e38f) {
 #pragma unroll
             for (int i = 0; i < C; ++i) xs[i] = blk[i];
         } else {
