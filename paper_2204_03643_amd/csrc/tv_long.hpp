@@ -1220,7 +1220,15 @@ inline hipError_t launch_bwd_long_t(const BwdParams &p, hipStream_t s)
     return hipGetLastError();
 }
 
-#define TV_LONG_DISPATCH(FN, p, s)                                                        \
+// GX: strided rows of 193-768 samples per workgroup of the transposing kernels.  Forward 8: a
+// workgroup of 512 threads (at most 128 registers each) leaves room for a second one on the CU,
+// whose loads and transposes then overlap the first one's solve (with 16 rows, 1024 threads, a CU
+// holds one workgroup and every phase waits for the slowest wave; 24 images of 512 x 512: column
+// pass 61 -> 57 us, K = 4 forward 313 -> 295; 12 of 768 x 768: 48 -> 42, 372 -> 344; columns of
+// 769-1024 samples need 139 registers that way and are slower, 44 -> 48).  Backward 16: it is
+// bound by memory, and 8 adjacent columns are 32 bytes of every image row (24 images of
+// 512 x 512, K = 4 reverse sweep: 205 us with 16 rows, 232 with 8).
+#define TV_LONG_DISPATCH(FN, p, s, GX)                                                    \
     do {                                                                                  \
         const int n = (p).L.n;                                                            \
         const bool cols = (p).L.elem_stride != 1;                                         \
@@ -1232,10 +1240,10 @@ inline hipError_t launch_bwd_long_t(const BwdParams &p, hipStream_t s)
             if (n <= 96) return FN<8, 12, 16, true>(p, s);                                \
             if (n <= 128) return FN<16, 8, 16, true>(p, s);                               \
             if (n <= 192) return FN<16, 12, 16, true>(p, s);                              \
-            if (n <= 256) return FN<32, 8, 16, true>(p, s);                               \
-            if (n <= 384) return FN<32, 12, 16, true>(p, s);                              \
-            if (n <= 512) return FN<64, 8, 16, true>(p, s);                               \
-            if (n <= 768) return FN<64, 12, 16, true>(p, s);                              \
+            if (n <= 256) return FN<32, 8, GX, true>(p, s);                               \
+            if (n <= 384) return FN<32, 12, GX, true>(p, s);                              \
+            if (n <= 512) return FN<64, 8, GX, true>(p, s);                               \
+            if (n <= 768) return FN<64, 12, GX, true>(p, s);                              \
             if (n <= 1024) return FN<64, 16, 16, true>(p, s);                             \
             if (n <= 1536) return FN<128, 12, 8, true>(p, s);                             \
             if (n <= 2048) return FN<128, 16, 8, true>(p, s);                             \
@@ -1268,7 +1276,7 @@ inline hipError_t launch_bwd_long_t(const BwdParams &p, hipStream_t s)
 
 inline hipError_t launch_fwd_long(const FwdParams &p, hipStream_t s)
 {
-    TV_LONG_DISPATCH(launch_fwd_long_t, p, s);
+    TV_LONG_DISPATCH(launch_fwd_long_t, p, s, 8);
 }
 
 // The forward launch with step records (cold start, unit-stride rows): one mapping of each kind
@@ -1291,7 +1299,7 @@ inline hipError_t launch_fwd_long_debug(const FwdParams &p, hipStream_t s)
 
 inline hipError_t launch_bwd_long(const BwdParams &p, hipStream_t s)
 {
-    TV_LONG_DISPATCH(launch_bwd_long_t, p, s);
+    TV_LONG_DISPATCH(launch_bwd_long_t, p, s, 16);
 }
 
 }  // namespace tvk

@@ -227,12 +227,13 @@ def test_one_launch_forward_without_the_pass_outputs(shape, K, dispatch_defaults
     assert np.all(np.isnan(lean["saved"]))                     # run_2d hands over a workspace of NaN bytes
 
 
-@pytest.mark.parametrize("H,W", [(60, 90), (120, 180), (250, 380), (500, 760), (1000, 1500), (2000, 3000), (4000, 6000),
-                                 (40, 8000), (16000, 40), (12000, 36), (36, 12000)])
+@pytest.mark.parametrize("H,W", [(60, 90), (120, 180), (250, 380), (380, 250), (500, 760), (760, 500), (1000, 1500),
+                                 (2000, 3000), (4000, 6000), (40, 8000), (16000, 40), (12000, 36), (36, 12000)])
 def test_every_thread_mapping_of_long_rows_cold_and_warm(H, W):
     """One plane, two sweeps, with H and W walking through the row lengths at which the long-row
     kernels change their threads-per-row x samples-per-thread mapping (8 x 8 up to 1024 x 16),
-    unit-stride rows and strided columns alike: the first sweep starts cold, the second from the
+    unit-stride rows and strided columns alike (columns of 193-768 samples: eight to a workgroup
+    in the forward kernels, sixteen in the backward ones): the first sweep starts cold, the second from the
     duals of the first, so every mapping runs in both variants under the parity rules."""
     rng = np.random.default_rng(3 * H + W)
     y = (np.cumsum(rng.normal(scale=0.05, size=(1, H, W)), axis=-1)
