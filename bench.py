@@ -270,6 +270,31 @@ def long_probe(dev) -> int:
     return 0
 
 
+def small2d_probe(dev) -> int:
+    """Three launches each of the 2D call on small batches of feature-map-like planes (the
+    plane-per-workgroup kernel and the reverse sweep that follows it), for profiler runs."""
+    import numpy as np
+    import torch
+
+    import paper_2204_03643_amd as tv
+
+    for planes, H, W, K in ((256, 32, 32, 4), (1024, 32, 32, 4), (256, 64, 64, 4), (1024, 64, 64, 2)):
+        rng = np.random.default_rng(7)
+        y = np.maximum(rng.normal(size=(planes, H, W)), 0).astype(np.float32)
+        lam = rng.uniform(0.01, 1.0, size=64).astype(np.float32)
+        yt, lt = torch.from_numpy(y).to(dev), torch.from_numpy(lam).to(dev)
+        gt = torch.randn_like(yt)
+        xt, gy, gl = torch.empty_like(yt), torch.empty_like(yt), torch.empty_like(lt)
+        L = tv.tv_lambda(lt.data_ptr(), lt.numel(), 1)
+        wsb = tv.tv2d_workspace_bytes(planes, H, W, K)
+        ws = torch.empty(wsb, dtype=torch.uint8, device=dev)
+        for _ in range(3):
+            tv.tv2d_prox_fwd(yt, xt, planes, H, W, L, K, ws, wsb)
+            tv.tv2d_prox_bwd(gt, gy, gl, planes, H, W, L, K, ws, wsb)
+        torch.cuda.synchronize()
+    return 0
+
+
 def dispatch_probe(dev) -> int:
     """Both sides of every dispatch threshold of the library, timed at the threshold and a
     quarter beyond it (the crossovers are gradual: a mapping loses its lead over a round of
@@ -438,6 +463,8 @@ def main() -> int:
     ap.add_argument("--dispatch-probe", action="store_true",
                     help="time both sides of every dispatch threshold of the library at the threshold "
                          "and exit")
+    ap.add_argument("--small2d-probe", action="store_true",
+                    help="launch the 2D call on small batches of planes a few times and exit (for rocprofv3)")
     ap.add_argument("--long-probe", action="store_true",
                     help="run the long-row kernels of workloads 4 and 5 three times each (single passes, "
                          "the forward call of workload 5 with and without its workspace, the 2D call with "
@@ -460,6 +487,8 @@ def main() -> int:
     dev = torch.device("cuda:0")
     if args.long_probe:
         return long_probe(dev)
+    if args.small2d_probe:
+        return small2d_probe(dev)
     if args.dispatch_probe:
         return dispatch_probe(dev)
     y, lam, g = workloads.config3()
