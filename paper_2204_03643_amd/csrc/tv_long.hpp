@@ -388,6 +388,21 @@ __device__ __forceinline__ void seg_scan(bool closed, float s, float n, float *b
     }
 }
 
+// Pitch of the tile through which the transposing kernels turn G strided rows: T chunks of C
+// samples with a pad word each (a wave's chunk accesses t * (C + 1) + i then hit 32 different
+// banks per half wave with any pitch), rounded up so that consecutive rows start 32 / G banks
+// apart: the transposing accesses of half a wave are G rows x 32 / G neighbouring samples, which
+// then cover the 32 banks exactly once.  (With an odd pitch, which serves only G = 32, 9 % of
+// the LDS cycles of the sixteen-row forward kernels were bank conflicts, 31 % of the backward
+// kernels' and 49 % of the eight-row forward kernels'.)
+template <int T, int C, int G>
+constexpr int xpose_tile_pitch()
+{
+    constexpr int base = T * (C + 1);
+    constexpr int want = G >= 32 ? 1 : 32 / G;
+    return base + ((want - base % 32) + 32) % 32;
+}
+
 template <int T, int C, int G, bool COLS>
 struct LongSmem {
     using Mp = LongMap<T, G, COLS>;
@@ -435,8 +450,8 @@ __global__ __launch_bounds__(T *G, (T * G == 512 && !COLS) ? 4 : ((XPOSE && C <=
     constexpr bool DPPX = !MCOLS && T <= 16;
     __shared__ LongSmem<T, C, G, MCOLS> sm;
     // tile[row][k + k / C]: the pad after every chunk makes a wave's chunk reads conflict-free,
-    // the odd pitch does the same for the transposing accesses
-    constexpr int TILE_PITCH = T * (C + 1) + 1;
+    // the pitch does the same for the transposing accesses (xpose_tile_pitch)
+    constexpr int TILE_PITCH = xpose_tile_pitch<T, C, G>();
     // The tile is in use before the solve and after it, the exchange and PCR buffers during it:
     // where it fits it lies on top of them (two barriers more), which is what lets a second
     // workgroup share the CU's LDS.
@@ -1037,7 +1052,7 @@ __global__ __launch_bounds__(T *G, (T * G == 1024 && !COLS && !HAS_SUB) ? 8 : 1)
     constexpr bool MCOLS = COLS && !XPOSE;
     using Mp = LongMap<T, G, MCOLS>;
     __shared__ LongSmemBwd<T, C, G, MCOLS> sm;
-    constexpr int TILE_PITCH = T * (C + 1) + 1;
+    constexpr int TILE_PITCH = xpose_tile_pitch<T, C, G>();
     __shared__ float tile[XPOSE ? G * TILE_PITCH : 1];
     const int tid = threadIdx.x;
     const int j = Mp::row_of(tid), t = Mp::t_of(tid);
