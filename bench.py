@@ -385,6 +385,15 @@ def dispatch_probe(dev) -> int:
         n = defaults[name]
         case(name, "at_threshold_k%d" % K, lambda: two_d(n, 64, 64, K), 0, "a plane per workgroup", "pass by pass")
         case(name, "beyond_k%d" % K, lambda: two_d(n + n // 4, 64, 64, K), big, "pass by pass", "a plane per workgroup")
+    for name, H, W, K, other in (("plane_per_group_bwd_planes", 32, 32, 4, "a row per lane"),
+                                 ("plane_per_group64_bwd_planes", 64, 64, 4, "a row per lane"),
+                                 ("plane_per_group64_bwd_ragged_planes", 40, 48, 1, "pass by pass"),
+                                 ("plane_per_group64_bwd_ragged_planes_k2", 40, 48, 3, "pass by pass")):
+        n = defaults[name]
+        case(name, "at_threshold_k%d" % K, lambda: two_d(n, H, W, K), 0, "reverse sweep: a plane per workgroup",
+             "reverse sweep: " + other)
+        case(name, "beyond_k%d" % K, lambda: two_d(n + n // 4, H, W, K), big, "reverse sweep: " + other,
+             "reverse sweep: a plane per workgroup")
     for name, K in (("fused32_full_planes", 1), ("fused32_full_planes_k2", 2), ("fused32_full_planes_k3", 4)):
         n = defaults[name]
         if n > (1 << 20):           # "always": timed at the largest count that was measured

@@ -250,8 +250,7 @@ int tv1d_prox_bwd_seg_bf16(const uint16_t *g_up, const uint64_t *seg, uint16_t *
  * same pass one sweep earlier (x = y - D^T u), and the pass starts its Newton iteration
  * from that dual.  Planes of at most 64 x 64 run all their passes in one launch where that is
  * faster (small batches with a plane per workgroup, larger ones of planes of at most 32 x 32
- * with a row per lane; the plane counts: csrc/tv_dispatch.hpp).  tv2d_prox_bwd must see the
- * dispatch thresholds that the forward call saw.
+ * with a row per lane; the plane counts: csrc/tv_dispatch.hpp).
  */
 size_t tv2d_workspace_bytes(int64_t planes, int64_t H, int64_t W, int sweeps);
 int tv2d_prox_fwd(const float *y, float *x, int64_t planes, int64_t H, int64_t W,
@@ -260,7 +259,10 @@ int tv2d_prox_fwd(const float *y, float *x, int64_t planes, int64_t H, int64_t W
 /*
  * Reverse sweep through paper Alg. 1 (replaces autograd through the loop, paper
  * Sec. 3.2).  ws is the buffer tv2d_prox_fwd filled; its two scratch tensors are
- * overwritten, the saved pass outputs are only read.  grad_lam (lam.count floats,
+ * overwritten, the saved pass outputs are only read.  Planes of at most 64 x 64 run the
+ * whole sweep in one launch (small batches with a plane per workgroup, planes of at most
+ * 32 x 32 and of 64 x 64 otherwise with a row per lane); which mapping the forward call used
+ * does not matter.  grad_lam (lam.count floats,
  * overwritten) may be NULL; it is one fp64 sum, in a fixed order, over the terms of all
  * passes.  grad_y must not alias g_up.
  */

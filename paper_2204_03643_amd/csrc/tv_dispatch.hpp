@@ -26,6 +26,10 @@ enum {
     kPlanePerGroupPlanes,
     kPlanePerGroup64Planes,
     kPlanePerGroup64PlanesK2,
+    kPlanePerGroupBwdPlanes,
+    kPlanePerGroup64BwdPlanes,
+    kPlanePerGroup64BwdRaggedPlanes,
+    kPlanePerGroup64BwdRaggedPlanesK2,
     kFusedKeepsPasses,
     kThreadPerSampleWideRows,
     kThreadPerSample1dRows,
@@ -94,6 +98,26 @@ inline Threshold table[kCount] = {
     //            K = 4: 1536 planes 266 / 313, 2048: 350 / 360, 3072: 509 / 483.
     {"plane_per_group64_planes", 1536, "2D planes of 33-64 a side, one sweep: one launch, a plane per workgroup, up to this many planes"},
     {"plane_per_group64_planes_k2", 2048, "... two sweeps or more"},
+    // 2D reverse sweep of small batches with a plane per workgroup (tv_plane2d.hpp): both adjoint
+    // state tensors of the plane in LDS, 16 x 2 or 8 x 8 threads x samples per row, the segment
+    // sums across a row's threads by row shifts.  Against the row-per-lane one-launch kernel (a
+    // chain of 32 or 64 samples per lane and pass, one or two waves per CU on such batches),
+    // backward call with its lambda reduction, this kernel / that one:
+    //   32 x 32, K = 4:  64 planes 14 / 19,  256: 14 / 20,  512: 18 / 22,  768: 23 / 24,  896: 27 / 25;
+    //            K = 10: 256 planes 23 / 38;  K = 1: 15 / 15 at every count up to 768 (launches);
+    //   28 x 30, K = 2: 512 planes 14 / 21, 1024: 21 / 26;
+    //   64 x 64, K = 4:  64 planes 31 / 54,  256: 35 / 58,  512: 43 / 62,  640: 65 / 64;
+    //            K = 1: 256 planes 15 / 21,  512: 21 / 23,  640: 29 / 27.
+    {"plane_per_group_bwd_planes", 768, "2D reverse sweep, planes of 17-32 a side: a plane per workgroup up to this many planes"},
+    {"plane_per_group64_bwd_planes", 512, "2D reverse sweep, planes of 64 x 64: a plane per workgroup up to this many planes"},
+    // ... and against the pass-by-pass reverse sweep (2K launches), which is what other planes of
+    // 33-64 samples a side get otherwise: 40 x 48, K = 1: 256 planes 14 / 20, 512: 18 / 22,
+    // 1024: 29 / 28, 2048: 53 / 40; K = 3: 256 planes 22 / 44, 1024: 52 / 74, 2048: 95 / 108.
+    // K = 4: 1024 planes 63 / 97, 4096: 219 / 245, 8192: 424 / 429; K = 2: 4096 planes 112 / 121,
+    // 8192: 242 / 211; 56 x 60, K = 2: 2048 planes 80 / 114, 8192: 293 / 401; 33 x 33, K = 2: 4096
+    // planes 103 / 111, 16 384: 418 / 381.
+    {"plane_per_group64_bwd_ragged_planes", 768, "2D reverse sweep, other planes of 33-64 a side, one sweep: a plane per workgroup up to this many planes"},
+    {"plane_per_group64_bwd_ragged_planes_k2", 4096, "... two sweeps or more"},
     // 2D, planes of at most 32 x 32 in one launch: the reverse sweep reads the segment codes of the
     // passes, not their outputs, so the forward kernel writes only the codes and x.  1 = it also
     // writes every pass's output into the workspace, where the pass-by-pass forward leaves them (the

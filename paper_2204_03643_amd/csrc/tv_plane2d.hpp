@@ -488,4 +488,190 @@ __global__ __launch_bounds__(T * T * C, C <= 4 ? 8 : 4) void tv2d_fwd_plane_kern
     put_plane(p.x + plane * HW);
 }
 
+// ---------------------------------------------------------------------------------
+// Reverse sweep through paper Alg. 1 (Sec. 3.2) for small batches: one plane per workgroup, the
+// two adjoint state tensors resident in LDS for all 2K passes, T threads x C samples per row.
+// ---------------------------------------------------------------------------------
+
+// Segmented exclusive sums over the T threads of a row, from thread 0 upwards (DIR = +1) or from
+// thread T - 1 downwards (DIR = -1), by row shifts: each thread contributes (closed, s, n) as in
+// seg_scan of tv_long.hpp (closed: its chunk holds a segment boundary; (s, n): sum and count of
+// the part of its chunk beyond the last boundary in scan direction) and gets the sum and count
+// of the open part that arrives at it (zero at the origin).
+template <int T, int DIR>
+__device__ __forceinline__ void row_open_part_before(bool closed, float s, float n, int t, float &cs, float &cn)
+{
+    float f = closed ? 1.f : 0.f;
+#define TV_STEP(D)                                                                                  \
+    if constexpr ((D) < T) {                                                                        \
+        constexpr int DD = (D) < T ? (D) : 1;                                                       \
+        const float of = DIR > 0 ? from_left<T, DD>(f, t) : from_right<T, DD>(f, t);                \
+        const float os = DIR > 0 ? from_left<T, DD>(s, t) : from_right<T, DD>(s, t);                \
+        const float on = DIR > 0 ? from_left<T, DD>(n, t) : from_right<T, DD>(n, t);                \
+        const bool has = DIR > 0 ? (t >= (D)) : (t + (D) < T);                                      \
+        if (has && f == 0.f) { s += os; n += on; f = of; }                                          \
+    }
+    TV_STEP(1) TV_STEP(2) TV_STEP(4) TV_STEP(8)
+#undef TV_STEP
+    cs = DIR > 0 ? from_left<T, 1>(s, t) : from_right<T, 1>(s, t);
+    cn = DIR > 0 ? from_left<T, 1>(n, t) : from_right<T, 1>(n, t);
+}
+
+// Segment means of one row held by T threads (paper Eq. 5-6 as segment averaging): g is the
+// thread's chunk of the averaged quantity on entry (zero past the end of the row) and of the
+// means on return.  Bit i of jm: the row's output jumps behind sample k0 + i; of up: it rises
+// there (only duals inside the row are looked at).  Returns the thread's part of the row's
+// dL/dlam term  sum over jumps of sign(x[k+1] - x[k]) (mean_left - mean_right).
+template <int T, int C>
+__device__ __forceinline__ float lanes_segment_means(float (&g)[C], uint32_t jm, uint32_t up, int n, int t)
+{
+    const int k0 = t * C;
+    const int nv = min(max(n - 1 - k0, 0), C);             // duals of this chunk inside the row
+    const uint32_t inrow = (1u << nv) - 1u;
+    const uint32_t gmask = jm & inrow;                      // jumps that count for dL/dlam
+    // the end of the row closes a segment, and samples past it are segments of their own
+    const uint32_t jmask = (jm & inrow) | ~inrow;
+#define TV_JUMP(i) ((jmask >> (i)) & 1u)
+    bool any = false;
+    float head_s = 0.f, head_n = 0.f, tail_s = 0.f, tail_n = 0.f;
+#pragma unroll
+    for (int i = 0; i < C; ++i) {
+        if (!any) { head_s += g[i]; head_n += 1.f; }
+        tail_s += g[i]; tail_n += 1.f;
+        if (TV_JUMP(i)) { any = true; tail_s = 0.f; tail_n = 0.f; }
+    }
+    float ls, ln, rs, rn;
+    row_open_part_before<T, +1>(any, tail_s, tail_n, t, ls, ln);       // open part on the left
+    row_open_part_before<T, -1>(any, head_s, head_n, t, rs, rn);       // open part on the right
+    {
+        float s = ls, c = ln;
+#pragma unroll
+        for (int i = 0; i < C; ++i) {
+            s += g[i]; c += 1.f;
+            g[i] = 0.f;
+            if (TV_JUMP(i)) { g[i] = s * __builtin_amdgcn_rcpf(c); s = 0.f; c = 0.f; }
+        }
+        // the trailing open part continues into the next chunks
+        float carry = (c > 0.f) ? (s + rs) * __builtin_amdgcn_rcpf(c + rn) : 0.f;
+#pragma unroll
+        for (int i = C - 1; i >= 0; --i) {
+            if (TV_JUMP(i)) carry = g[i];
+            g[i] = carry;
+        }
+    }
+#undef TV_JUMP
+    const float mnext0 = from_right<T, 1>(g[0], t);
+    float gl = 0.f;
+#pragma unroll
+    for (int i = 0; i < C; ++i) {
+        if ((gmask >> i) & 1u) {
+            const float mn = (i + 1 < C) ? g[i + 1] : mnext0;
+            const float d = g[i] - mn;
+            gl += ((up >> i) & 1u) ? d : -d;
+        }
+    }
+    return gl;
+}
+
+// T, C as in the forward kernel.  Planes of at most 32 x 32 read the segments of a pass from its
+// 8-byte codes, larger ones from its saved output.  p.partial gets one dL/dlam term per plane.
+template <int T, int C>
+__global__ __launch_bounds__(T * T * C, C <= 4 ? 8 : 4) void tv2d_bwd_plane_kernel(Small2dBwdParams p)
+{
+    constexpr int S = T * C, P = S + 1, NT = S * T, NW = NT / 64;
+    static_assert(NT % 64 == 0 && NT <= 1024, "whole waves");
+    __shared__ float A[S * P], B[S * P], part[NW];
+    const int tid = threadIdx.x;
+    const int j = tid / T, t = tid % T, k0 = t * C;
+    const int H = p.H, W = p.W, HW = H * W;
+    const int64_t plane = blockIdx.x;
+    {
+        const float *src = p.g_up + plane * HW;
+        for (int e = tid; e < HW; e += NT) A[(e / W) * P + e % W] = src[e];
+    }
+
+    // Segments of pass `pass` for the thread's chunk of its row (row pass) or column (column
+    // pass); fetched one pass ahead, so that the latency hides behind the pass before.
+    auto fetch = [&](int pass, uint32_t &jm, uint32_t &up) {
+        jm = 0u; up = 0u;
+        if (pass < 0) return;
+        const bool col = (pass & 1) != 0;
+        const int n = col ? H : W, rows = col ? W : H;
+        const bool valid = j < rows;
+        if constexpr (S <= 32) {
+            if (valid) {
+                const uint2 c = p.codes[(size_t)pass * p.code_stride + (size_t)plane * rows + j];
+                jm = (c.x >> k0) & ((1u << C) - 1u);
+                up = (c.y >> k0) & ((1u << C) - 1u);
+            }
+        } else {
+            const float *xs = p.saved + (size_t)pass * p.saved_stride + (size_t)plane * HW;
+            float x[C];
+#pragma unroll
+            for (int c = 0; c < C; ++c)
+                x[c] = (valid && k0 + c < n) ? (col ? xs[(k0 + c) * W + j] : xs[j * W + k0 + c]) : 0.f;
+            const float xnext0 = from_right<T, 1>(x[0], t);
+#pragma unroll
+            for (int c = 0; c < C; ++c) {
+                const float xn = (c + 1 < C) ? x[c + 1] : xnext0;
+                if (xn != x[c]) jm |= 1u << c;
+                if (xn > x[c]) up |= 1u << c;
+            }
+        }
+    };
+
+    float glam = 0.f;
+    uint32_t jm_next, up_next;
+    fetch(2 * p.sweeps - 1, jm_next, up_next);
+    __syncthreads();
+    // Adjoint of one sweep (A = Y + P, Z = R(A), P' = A - Z, B = Z + Q, Y' = C(B), Q' = B - Y'):
+    //   Bbar = Qbar' + C^T(Ybar' - Qbar'),   Abar = Pbar' + R^T(Bbar - Pbar'),   Ybar = Pbar = Abar;
+    // tile A carries Ybar = Pbar, tile B carries Qbar = Bbar.  A thread reads and writes only its
+    // own tile elements in a pass, so one barrier per pass suffices.
+    for (int k = p.sweeps - 1; k >= 0; --k) {
+        const bool first = (k == p.sweeps - 1);
+#pragma unroll
+        for (int dir = 1; dir >= 0; --dir) {
+            const bool col = dir != 0;
+            const int n = col ? H : W, rows = col ? W : H;
+            const bool valid = j < rows;
+            const int base = col ? j : j * P, step = col ? P : 1;
+            const uint32_t jm = jm_next, up = up_next;
+            fetch(2 * k + dir - 1, jm_next, up_next);
+            float *dst = col ? B : A;                    // column pass: B <- C^T(A - B) + B
+            const float *src = col ? A : B;              // row pass:    A <- R^T(B - A) + A
+            float v[C], old[C];
+#pragma unroll
+            for (int c = 0; c < C; ++c) {
+                const bool in = valid && k0 + c < n;
+                const int e = base + (k0 + c) * step;
+                old[c] = (in && !first) ? dst[e] : 0.f;
+                v[c] = in ? src[e] - old[c] : 0.f;
+            }
+            const float gl = lanes_segment_means<T, C>(v, jm, up, n, t);
+            if (valid) glam += gl;
+#pragma unroll
+            for (int c = 0; c < C; ++c)
+                if (valid && k0 + c < n) dst[base + (k0 + c) * step] = old[c] + v[c];
+            __syncthreads();
+        }
+    }
+    {
+        float *dst = p.gy + plane * HW;
+        for (int e = tid; e < HW; e += NT) dst[e] = A[(e / W) * P + e % W];
+    }
+    if (p.partial) {
+        // the plane's term: waves in a fixed order
+        const float s = wave_sum_all<64>(glam);
+        if ((tid & 63) == 0) part[tid >> 6] = s;
+        __syncthreads();
+        if (tid == 0) {
+            float tot = 0.f;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) tot += part[w];
+            p.partial[plane] = tot;
+        }
+    }
+}
+
 }  // namespace tvk

@@ -1350,6 +1350,26 @@ int tv2d_prox_bwd(const float *g_up, float *grad_y, float *grad_lam, int64_t pla
     //   Bbar = Qbar' + C^T(Ybar' - Qbar'),   Qbar = Bbar,
     //   Abar = Pbar' + R^T(Bbar - Pbar'),    Ybar = Pbar = Abar.
     // Ybar and Pbar coincide from the second reverse step on, so two tensors carry the state.
+    if ((cb && small_side(H, W) == 32 && planes <= tvd::get(tvd::kPlanePerGroupBwdPlanes)) ||
+        (!cb && H <= 64 && W <= 64 &&
+         planes <= tvd::get((H == 64 && W == 64) ? tvd::kPlanePerGroup64BwdPlanes
+                                                 : (sweeps == 1 ? tvd::kPlanePerGroup64BwdRaggedPlanes
+                                                                : tvd::kPlanePerGroup64BwdRaggedPlanesK2)))) {
+        // a small batch of planes of 17-64 samples a side: one launch, a plane per workgroup
+        tvk::Small2dBwdParams q;
+        q.g_up = g_up; q.gy = grad_y; q.codes = codes(0); q.code_stride = cb / sizeof(uint2);
+        q.saved = saved(0); q.saved_stride = tb / sizeof(float);
+        q.partial = grad_lam ? partial(0) : nullptr;
+        q.planes = (int32_t)planes; q.H = (int32_t)H; q.W = (int32_t)W; q.sweeps = sweeps;
+        q.stream = 0u;
+        const dim3 grid((uint32_t)planes);
+        if (cb) hipLaunchKernelGGL((tvk::tv2d_bwd_plane_kernel<16, 2>), grid, dim3(512), 0, stream, q);
+        else hipLaunchKernelGGL((tvk::tv2d_bwd_plane_kernel<8, 8>), grid, dim3(512), 0, stream, q);
+        if (launch_status() != TV_OK) return TV_ERR_HIP;
+        if (!grad_lam) return TV_OK;
+        const tv_lambda lp = {lam.lam, lam.count, 1};
+        return launch_reduce_lambda(partial(0), grad_lam, planes, lp, 0, stream);
+    }
     if (cb || (H == 64 && W == 64)) {
         // planes of at most 32 x 32, or of 64 x 64: the whole reverse sweep in one launch, state
         // resident in LDS (up to 32 x 32 the segments come from the codes, at 64 x 64 from the saved

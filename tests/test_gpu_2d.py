@@ -183,7 +183,7 @@ def test_every_forward_mapping_of_small_planes(shape, K, dispatch_defaults):
 @pytest.mark.parametrize("shape,K", [((70, 32, 32), 2), ((37, 28, 30), 3), ((9, 17, 32), 4), ((5, 32, 3), 2), ((3, 1, 20), 2),
                                      ((4, 31, 1), 1), ((260, 32, 32), 1), ((5, 64, 64), 3), ((3, 40, 56), 2), ((4, 33, 64), 2),
                                      ((2, 64, 35), 1), ((70, 48, 48), 4), ((1, 33, 33), 1), ((3, 2, 64), 2), ((300, 64, 64), 1)])
-def test_plane_per_workgroup_forward(shape, K, dispatch_defaults):
+def test_plane_per_workgroup_forward_and_reverse_sweep(shape, K, dispatch_defaults):
     """All 2K passes in one launch with a plane per workgroup (16 threads x 2 samples per row for
     sides of 17-32, 8 x 8 for sides of 33-64), forced through its thresholds for plane counts on
     both sides of what the dispatch would pick: the parity rules of every other mapping, reverse
@@ -194,15 +194,26 @@ def test_plane_per_workgroup_forward(shape, K, dispatch_defaults):
     y = rng.normal(size=shape).astype(np.float32)
     g = rng.normal(size=shape).astype(np.float32)
     lam = (10 ** rng.uniform(-2, 0.3, size=3)).astype(np.float32)
-    knobs = ("plane_per_group_planes", "plane_per_group64_planes", "plane_per_group64_planes_k2")
-    for k in knobs:
+    fwd_knobs = ("plane_per_group_planes", "plane_per_group64_planes", "plane_per_group64_planes_k2")
+    bwd_knobs = ("plane_per_group_bwd_planes", "plane_per_group64_bwd_planes", "plane_per_group64_bwd_ragged_planes",
+                 "plane_per_group64_bwd_ragged_planes_k2")
+    for k in fwd_knobs + bwd_knobs:
         tv.tv_dispatch_override(k, 0)
     ref = run_2d(y, lam, K, g)
-    for k in knobs:
+    for k in fwd_knobs + bwd_knobs:
         tv.tv_dispatch_override(k, 1 << 40)
     out = run_2d(y, lam, K, g)
     check_2d(y, lam, K, g, out, "plane per workgroup %s K=%d" % (shape, K))
     assert np.abs(out["x"] - ref["x"]).max() <= 2e-5 * (1 + np.abs(y).max())
+    # the plane-per-workgroup reverse sweep behind the other forward mappings (their codes, or
+    # their saved pass outputs): the same segments as the reference run, so the same gradient
+    # up to the order of the sums
+    for k in fwd_knobs:
+        tv.tv_dispatch_override(k, 0)
+    mixed = run_2d(y, lam, K, g)
+    check_2d(y, lam, K, g, mixed, "plane per workgroup, reverse sweep only, %s K=%d" % (shape, K))
+    assert np.array_equal(mixed["x"], ref["x"])
+    assert np.abs(mixed["gy"] - ref["gy"]).max() <= 1e-5 * max(np.abs(ref["gy"]).max(), 1e-30)
 
 
 @pytest.mark.parametrize("shape,K", [((900, 32, 32), 3), ((1000, 20, 27), 2), ((300, 16, 16), 2)])

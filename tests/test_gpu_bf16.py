@@ -136,6 +136,7 @@ def test_bf16_2d_pair_equals_rounded_fp32_one_launch_kernels(shape, K):
         tv.tv2d_prox_bwd_bf16(gt, gy, gl, P, H, W, L, K, ws, wsb)
         # the fp32 call on the widened input, forced onto the one-launch kernels
         tv.tv_dispatch_override("plane_per_group_planes", 0)
+        tv.tv_dispatch_override("plane_per_group_bwd_planes", 0)
         for name in ("fused32_full_planes", "fused32_full_planes_k2", "fused32_full_planes_k3",
                      "fused32_ragged_planes", "fused16_one_sweep_planes"):
             tv.tv_dispatch_override(name, 1 << 40)
