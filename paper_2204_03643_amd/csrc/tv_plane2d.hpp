@@ -1,6 +1,7 @@
-// The 2D operator (paper Alg. 1) for small batches of planes of at most 64 x 64: one plane per
-// workgroup, resident in LDS for all 2K passes of a call, each row (or column) of a pass solved
-// by T neighbouring lanes with C samples each.
+// The 2D operator (paper Alg. 1) and its reverse sweep (Sec. 3.2) for small batches of planes of
+// at most 64 x 64: one plane per workgroup, resident in LDS for all 2K passes of a call, each row
+// (or column) of a pass handled by T neighbouring lanes with C samples each.  Forward kernel
+// first, reverse sweep at the end of the file.
 //
 // With a few hundred planes the row-per-lane kernels of tv_small2d.hpp fill a fraction of the
 // chip with long dependent chains (one wave per one or two planes), and the pass-by-pass route
