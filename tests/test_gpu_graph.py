@@ -63,10 +63,12 @@ def test_forward_backward_step_replays_from_a_graph():
         assert torch.equal(xt, ref[0]) and torch.equal(gy, ref[1]) and torch.equal(gl, ref[2]), rep
 
 
-@pytest.mark.parametrize("planes,H,W,K", [(16, 32, 32, 3),       # small batch: passes on the long-row kernels
-                                          (40, 16, 16, 3),       # one-launch forward and reverse sweep
+@pytest.mark.parametrize("planes,H,W,K", [(16, 32, 32, 3),       # small batch: a plane per workgroup, both ways
+                                          (40, 16, 16, 3),       # row-per-lane one-launch forward and reverse sweep
                                           (1600, 32, 32, 2),     # the same, two planes per wave
-                                          (6, 64, 64, 2)])       # pass-by-pass forward, fused reverse sweep
+                                          (6, 64, 64, 2),        # a plane per workgroup, 8 x 8 threads x samples
+                                          (5, 40, 56, 2),        # ... reverse sweep from the saved pass outputs
+                                          (3, 100, 70, 2)])      # pass by pass both ways
 def test_2d_step_replays_from_a_graph(planes, H, W, K):
     import torch
 
