@@ -274,10 +274,11 @@ int tv2d_prox_bwd(const float *g_up, float *grad_y, float *grad_lam, int64_t pla
  * The 2D pair with bf16 storage and fp32 arithmetic, for planes of at most 32 x 32 (the paper's
  * usual feature-map size; TV_ERR_UNSUPPORTED beyond): y, x, g_up and grad_y are arrays of bf16 bit
  * patterns (2-byte aligned; 16-byte aligned plane blocks move with 16-byte accesses), widened
- * exactly on the way in and rounded to nearest even on the way out; everything between is the
- * fp32 one-launch kernel (all 2K passes with the planes resident in LDS), so x is bit for bit the
- * rounded output of that kernel on the widened input, and the reverse sweep uses the segment
- * codes of the unrounded passes.  ws: as for tv2d_prox_fwd / tv2d_prox_bwd (same size, fp32
+ * exactly on the way in and rounded to nearest even on the way out; everything between is an
+ * fp32 one-launch kernel (all 2K passes with the planes resident in LDS; a plane per workgroup
+ * for small batches of planes of 17-32 samples a side, a row per lane otherwise, as for fp32),
+ * so x is bit for bit the rounded output of that kernel on the widened input, and the reverse
+ * sweep uses the segment codes of the unrounded passes.  ws: as for tv2d_prox_fwd / tv2d_prox_bwd (same size, fp32
  * contents); grad_lam stays fp32.
  */
 int tv2d_prox_fwd_bf16(const uint16_t *y, uint16_t *x, int64_t planes, int64_t H, int64_t W,

@@ -395,7 +395,9 @@ __device__ __forceinline__ int lanes_row_solve(const float (&y)[C], float (&u)[C
 // (32 x 32 with 8 threads x 4 samples, 256 threads: 256 planes, K = 4, 52 us against 38 with
 // 16 x 2, whose chains are shorter; from 1500 planes on 8 x 4 is 5-10 % ahead, where the
 // row-per-lane kernels take over anyway.)
-template <int T, int C>
+// IO16: y and x are bf16 in memory (fp32 in the tile and in all arithmetic; the saved pass outputs
+// stay fp32).
+template <int T, int C, bool IO16 = false>
 __global__ __launch_bounds__(T * T * C, C <= 4 ? 8 : 4) void tv2d_fwd_plane_kernel(Small2dFwdParams p)
 {
     constexpr int S = T * C, P = S + 1, NT = S * T;
@@ -410,7 +412,10 @@ __global__ __launch_bounds__(T * T * C, C <= 4 ? 8 : 4) void tv2d_fwd_plane_kern
         rtab[tid] = 1.0f / (float)(tid + 1);
     }
     const float lam = fmaxf(p.lam[plane % p.lam_count], 0.f);
-    {
+    if constexpr (IO16) {
+        const uint16_t *src = reinterpret_cast<const uint16_t *>(p.y) + plane * HW;
+        for (int e = tid; e < HW; e += NT) X[(e / W) * P + e % W] = bf16_bits_to_f32(src[e]);
+    } else {
         const float *src = p.y + plane * HW;
         for (int e = tid; e < HW; e += NT) X[(e / W) * P + e % W] = src[e];
     }
@@ -486,7 +491,12 @@ __global__ __launch_bounds__(T * T * C, C <= 4 ? 8 : 4) void tv2d_fwd_plane_kern
             if (i + 1 < n_pass) __syncthreads();      // the next pass writes into the tile
         }
     }
-    put_plane(p.x + plane * HW);
+    if constexpr (IO16) {
+        uint16_t *dst = reinterpret_cast<uint16_t *>(p.x) + plane * HW;
+        for (int e = tid; e < HW; e += NT) dst[e] = f32_to_bf16_bits(X[(e / W) * P + e % W]);
+    } else {
+        put_plane(p.x + plane * HW);
+    }
 }
 
 // ---------------------------------------------------------------------------------
@@ -576,7 +586,8 @@ __device__ __forceinline__ float lanes_segment_means(float (&g)[C], uint32_t jm,
 
 // T, C as in the forward kernel.  Planes of at most 32 x 32 read the segments of a pass from its
 // 8-byte codes, larger ones from its saved output.  p.partial gets one dL/dlam term per plane.
-template <int T, int C>
+// IO16: the upstream gradient and grad_y are bf16 in memory.
+template <int T, int C, bool IO16 = false>
 __global__ __launch_bounds__(T * T * C, C <= 4 ? 8 : 4) void tv2d_bwd_plane_kernel(Small2dBwdParams p)
 {
     constexpr int S = T * C, P = S + 1, NT = S * T, NW = NT / 64;
@@ -586,7 +597,10 @@ __global__ __launch_bounds__(T * T * C, C <= 4 ? 8 : 4) void tv2d_bwd_plane_kern
     const int j = tid / T, t = tid % T, k0 = t * C;
     const int H = p.H, W = p.W, HW = H * W;
     const int64_t plane = blockIdx.x;
-    {
+    if constexpr (IO16) {
+        const uint16_t *src = reinterpret_cast<const uint16_t *>(p.g_up) + plane * HW;
+        for (int e = tid; e < HW; e += NT) A[(e / W) * P + e % W] = bf16_bits_to_f32(src[e]);
+    } else {
         const float *src = p.g_up + plane * HW;
         for (int e = tid; e < HW; e += NT) A[(e / W) * P + e % W] = src[e];
     }
@@ -657,7 +671,10 @@ __global__ __launch_bounds__(T * T * C, C <= 4 ? 8 : 4) void tv2d_bwd_plane_kern
             __syncthreads();
         }
     }
-    {
+    if constexpr (IO16) {
+        uint16_t *dst = reinterpret_cast<uint16_t *>(p.gy) + plane * HW;
+        for (int e = tid; e < HW; e += NT) dst[e] = f32_to_bf16_bits(A[(e / W) * P + e % W]);
+    } else {
         float *dst = p.gy + plane * HW;
         for (int e = tid; e < HW; e += NT) dst[e] = A[(e / W) * P + e % W];
     }

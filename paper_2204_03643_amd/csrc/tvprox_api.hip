@@ -1258,7 +1258,9 @@ int tv2d_prox_fwd(const float *y, float *x, int64_t planes, int64_t H, int64_t W
 }
 
 // ---- the 2D operator with bf16 storage of y, x, g_up and grad_y (planes of at most 32 x 32): always
-//      the one-launch kernels; the workspace (saved pass outputs, segment codes) is as for fp32.
+//      one launch each way (small batches of planes of 17-32 samples a side with a plane per
+//      workgroup, a row per lane otherwise); the workspace (saved pass outputs, segment codes) is
+//      as for fp32.
 int tv2d_prox_fwd_bf16(const uint16_t *y, uint16_t *x, int64_t planes, int64_t H, int64_t W, tv_lambda lam,
                        int sweeps, void *ws, size_t ws_bytes, hipStream_t stream)
 {
@@ -1281,7 +1283,10 @@ int tv2d_prox_fwd_bf16(const uint16_t *y, uint16_t *x, int64_t planes, int64_t H
     q.lam = lam.lam; q.lam_count = lam.count;
     q.planes = (int32_t)planes; q.H = (int32_t)H; q.W = (int32_t)W; q.sweeps = sweeps;
     q.stream = (planes * H * W >= tvd::get(tvd::kStreamBytes) / 4) ? 1u : 0u;
-    TV_SMALL2D_LAUNCH_X(tvk::tv2d_fwd_small_kernel, q, planes, H, W, stream, true);
+    if (plane_per_group_2d(planes, H, W, sweeps))       // a small batch: a plane per workgroup
+        hipLaunchKernelGGL((tvk::tv2d_fwd_plane_kernel<16, 2, true>), dim3((uint32_t)planes), dim3(512), 0, stream, q);
+    else
+        TV_SMALL2D_LAUNCH_X(tvk::tv2d_fwd_small_kernel, q, planes, H, W, stream, true);
     return launch_status();
 }
 
@@ -1308,7 +1313,10 @@ int tv2d_prox_bwd_bf16(const uint16_t *g_up, uint16_t *grad_y, float *grad_lam, 
     q.partial = grad_lam ? partial : nullptr;
     q.planes = (int32_t)planes; q.H = (int32_t)H; q.W = (int32_t)W; q.sweeps = sweeps;
     q.stream = (planes * H * W >= tvd::get(tvd::kStreamBytes) / 4) ? 1u : 0u;
-    TV_SMALL2D_LAUNCH_X(tvk::tv2d_bwd_small_kernel, q, planes, H, W, stream, false, true);
+    if (small_side(H, W) == 32 && planes <= tvd::get(tvd::kPlanePerGroupBwdPlanes))
+        hipLaunchKernelGGL((tvk::tv2d_bwd_plane_kernel<16, 2, true>), dim3((uint32_t)planes), dim3(512), 0, stream, q);
+    else
+        TV_SMALL2D_LAUNCH_X(tvk::tv2d_bwd_small_kernel, q, planes, H, W, stream, false, true);
     if (launch_status() != TV_OK) return TV_ERR_HIP;
     if (!grad_lam) return TV_OK;
     const tv_lambda lp = {lam.lam, lam.count, 1};

@@ -106,12 +106,14 @@ def test_bf16_rejects_other_shapes():
 # ---- the 2D pair with bf16 storage (planes of at most 32 x 32, one-launch kernels)
 
 
+@pytest.mark.parametrize("per_plane", [False, True])
 @pytest.mark.parametrize("shape,K", [((70, 32, 32), 3), ((5, 32, 32), 1), ((37, 28, 30), 2), ((90, 16, 16), 4),
                                      ((33, 13, 16), 2), ((130, 8, 8), 3), ((21, 5, 7), 2), ((3, 1, 32), 2)])
-def test_bf16_2d_pair_equals_rounded_fp32_one_launch_kernels(shape, K):
+def test_bf16_2d_pair_equals_rounded_fp32_one_launch_kernels(shape, K, per_plane):
     """x is bit for bit the rounded output of the fp32 one-launch kernel on the widened input, the
     saved passes and segment codes are identical, grad_y is the rounded fp32 grad_y and grad_lam
-    is identical; and the oracle's K-sweep result lies within bf16 rounding of x."""
+    is identical; and the oracle's K-sweep result lies within bf16 rounding of x.  Both calls run
+    the same mapping: a row per lane, or (planes of 17-32 samples a side) a plane per workgroup."""
     import torch
 
     import paper_2204_03643_amd as tv
@@ -130,16 +132,19 @@ def test_bf16_2d_pair_equals_rounded_fp32_one_launch_kernels(shape, K):
     xt, gy = torch.full_like(yt, -1), torch.full_like(yt, -1)
     gl = torch.full((3,), float("nan"), device=dev)
     saved_thr = tv.tv_dispatch_thresholds()
+    if per_plane and max(H, W) <= 16:
+        pytest.skip("planes of at most 16 x 16 have no plane-per-workgroup mapping")
     try:
         tv.tv_dispatch_override("fused_keeps_passes", 1)      # both calls also leave their pass outputs
-        tv.tv2d_prox_fwd_bf16(yt, xt, P, H, W, L, K, ws, wsb)
-        tv.tv2d_prox_bwd_bf16(gt, gy, gl, P, H, W, L, K, ws, wsb)
-        # the fp32 call on the widened input, forced onto the one-launch kernels
-        tv.tv_dispatch_override("plane_per_group_planes", 0)
-        tv.tv_dispatch_override("plane_per_group_bwd_planes", 0)
+        # both calls forced onto the same one-launch kernels
+        tv.tv_dispatch_override("plane_per_group_planes", (1 << 40) if per_plane else 0)
+        tv.tv_dispatch_override("plane_per_group_bwd_planes", (1 << 40) if per_plane else 0)
         for name in ("fused32_full_planes", "fused32_full_planes_k2", "fused32_full_planes_k3",
                      "fused32_ragged_planes", "fused16_one_sweep_planes"):
             tv.tv_dispatch_override(name, 1 << 40)
+        tv.tv2d_prox_fwd_bf16(yt, xt, P, H, W, L, K, ws, wsb)
+        tv.tv2d_prox_bwd_bf16(gt, gy, gl, P, H, W, L, K, ws, wsb)
+        # the fp32 call on the widened input
         yf, gf = (torch.from_numpy(_widen(b)).to(dev) for b in (y_bits, g_bits))
         wsf = torch.zeros(wsb, dtype=torch.uint8, device=dev)
         xf, gyf, glf = torch.empty_like(yf), torch.empty_like(yf), torch.empty_like(gl)
