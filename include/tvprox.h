@@ -77,6 +77,7 @@ typedef struct {
 /*
  * Forward 1D prox over a batch of rows (paper Eq. 1, solved through Eq. 3-4).
  * x may alias y exactly (same pointer, same layout); any other overlap is undefined.
+ * While the call runs the rows of x may hold intermediate data (see tv1d_prox_fwd_ex, ws).
  * length == 1 copies the row.  Zero rows: TV_OK without a launch.
  * A row whose input holds NaN/Inf gets unspecified values in that row (NaN at least at
  * the non-finite samples); other rows are unaffected and the call still terminates.
@@ -114,9 +115,13 @@ int tv1d_prox_fwd_info(const float *y, float *x, int32_t *info, tv_rows rows, tv
  *           in groups of 4 samples, with lambda / 4, is solved first (recursively, down to at
  *           most 256 samples) and its dual, prolonged, is where the Newton iteration of the
  *           row itself starts.  The paper does not fix the starting point (Sec. 3.2); the
- *           minimiser is the same, x agrees with the plain call to rounding, and rows whose
- *           lambda is large against their sample-to-sample variation take 4 steps instead of
- *           10-30.  Scratch: about two thirds of the input's size.
+ *           minimiser is the same, and rows whose lambda is large against their
+ *           sample-to-sample variation take 4 steps instead of 10-30.  Scratch: about two thirds
+ *           of the input's size.  Without ws (and in tv1d_prox_fwd) the same start is taken
+ *           with the levels of a row kept in that row of x until the fine level overwrites it,
+ *           whenever the rows are packed (no gap between them) and x does not overlap y; the
+ *           results are bit-identical to those with ws.  A call in place (x == y), rows with
+ *           gaps and strided rows start cold without ws.
  *         tv1d_fwd_workspace_bytes() returns 0 where neither applies (ws is then unused).
  *   flags: 0 or a combination of
  *         TV_FWD_ORDER_READY: ws still holds the slot order that an earlier call with

@@ -124,16 +124,20 @@ struct FwdParams {
     uint32_t     psearch;  // row-per-lane kernel, rows of up to 32 samples: parallel step-size search
     uint32_t     warm;     // 1: addend is D^T u of an earlier solve of nearly the same rows: start from that u
                            // 2: start from the dual of the row averaged in groups of kMlFactor (coarse_u)
-    // long-row kernels only (multilevel start):
-    const float *coarse_u; // warm == 2: duals of the averaged rows, coarse_n per row, packed
+    // long-row kernels only (multilevel start; the three pitches sit where the pointers' alignment
+    // left holes, so that they cost no kernel argument space):
+    int32_t      dual_pitch;   // floats between the rows of dual_out
+    const float *coarse_u; // warm == 2: duals of the averaged rows, coarse_n per row, coarse_pitch floats apart
     int32_t      coarse_n;
-    float       *dual_out; // optional: receives the final dual, L.n per row, packed (entry n - 1 is 0)
-    const uint32_t *ml_flag; // optional, per row: 0 = this row takes no part in the multilevel start
+    int32_t      coarse_pitch;
+    float       *dual_out; // optional: receives the final dual, L.n per row (entry n - 1 is 0)
+    const uint32_t *ml_flag; // optional, per row (flag_pitch words apart): 0 = this row takes no part in the multilevel start
     uint32_t     ml_skip;  // rows with ml_flag == 0 are not solved at all (the launch is a coarse level)
     float        lam_scale; // lambda of this launch = lam[slot] * lam_scale (1 / kMlFactor per level)
     // step record (kernel variants with DEBUG only; see StepRecord):
     float       *debug;     // debug_rows records of step_record_floats(L.n) floats
     uint32_t     debug_rows;
+    uint32_t     flag_pitch;
     Layout       L;
     TileMap      tm;       // row-per-lane kernels only
 };

@@ -471,7 +471,7 @@ __global__ __launch_bounds__(T *G, (T * G == 512 && !COLS) ? 4 : ((XPOSE && C <=
     bool rvalid = row < p.L.n_rows;
     bool from_coarse = false;
     if (p.ml_flag && rvalid) {
-        const bool flagged = p.ml_flag[row] != 0;
+        const bool flagged = p.ml_flag[(size_t)row * p.flag_pitch] != 0;
         if (p.ml_skip) rvalid = flagged;            // a coarse level: only rows that asked for it
         else from_coarse = WARM == 2 && flagged;
     }
@@ -573,10 +573,11 @@ __global__ __launch_bounds__(T *G, (T * G == 512 && !COLS) ? 4 : ((XPOSE && C <=
         // ((n - k) / n) sum_{i<=k} y_i| <= 2 k (n - k) / n max|y| <= n / 2 max|y|, and every lambda from
         // lam_max on gives the same minimiser (the row's mean): a lambda beyond that bound is
         // replaced by it, which keeps the dual box, and with it the rounding errors of
-        // x = y - D^T u, at the scale of the data.  Only the cold start needs it (it puts the
-        // duals on the bounds); a pass that starts from an earlier dual is left alone, where the
-        // extra dependency cost 3 % of the 2D operator's time.
-        if constexpr (WARM == 0) lam = fminf(lam, 0.51f * (float)n * ym[0]);
+        // x = y - D^T u, at the scale of the data.  The cold start needs it (it puts the duals on
+        // the bounds), and so does a start from a coarser level's dual, whose stopping tolerance
+        // scales with lambda; a pass that starts from the dual an addend encodes is left alone,
+        // where the extra dependency cost 3 % of the 2D operator's time.
+        if constexpr (WARM != 1) lam = fminf(lam, 0.51f * (float)n * ym[0]);
         gtol = kGradNoise * (ym[0] + lam);
         Mp::sync();
     }
@@ -633,7 +634,7 @@ __global__ __launch_bounds__(T *G, (T * G == 512 && !COLS) ? 4 : ((XPOSE && C <=
             static_assert(WARM != 2 || C % kMlFactor == 0, "groups must not straddle chunks");
             if (from_coarse) {
                 constexpr int F = kMlFactor;
-                const float *cu = p.coarse_u + (size_t)row * p.coarse_n;
+                const float *cu = p.coarse_u + (size_t)row * p.coarse_pitch;
                 const int j0 = k0 / F;
                 float ucl = (j0 > 0 && j0 - 1 < p.coarse_n) ? cu[j0 - 1] : 0.f;
 #pragma unroll
@@ -917,6 +918,17 @@ __global__ __launch_bounds__(T *G, (T * G == 512 && !COLS) ? 4 : ((XPOSE && C <=
 #pragma unroll
         for (int i = 0; i < C; ++i) u[i] = uc[i];
         prev_unclipped = (alpha == 1.f) && !clipped;
+        // A full Newton step lands on the minimiser of its free set only up to the rounding of
+        // the solve, which grows with the step (|d| <= 2 lam).  A cold start ends in small steps;
+        // a start from a coarser level's dual can end in its first or second step, and where
+        // lambda is large against the data the error of such a step can exceed what the output
+        // may be off by.  There a step that moved x by more than 2 % of the data's scale (in the
+        // 2-norm; the decrement is that move squared) does not end the solve: the next, small
+        // step refines it.  (The scale, 1 + max|y|, is taken back out of gtol.)
+        if constexpr (WARM == 2) {
+            const float scale = 1.f + fmaxf(gtol * (1.0f / kGradNoise) - lam, 0.f);
+            if (lam > 0.25f * scale && !(dec <= fmaxf(gtol * gtol, 4e-4f * scale * scale))) prev_unclipped = false;
+        }
         if (active) fcur = fc;
         if constexpr (DEBUG) {
             if (rec && t == 0 && active && alpha > 0.f) {
@@ -929,7 +941,7 @@ __global__ __launch_bounds__(T *G, (T * G == 512 && !COLS) ? 4 : ((XPOSE && C <=
         else if (!Mp::sync_any(active, sm.vote, vp)) break;
     }
 
-    if (p.dual_out) chunk_store<C>(p.dual_out, (int64_t)row * n, 1, k0, n, rvalid, u);
+    if (p.dual_out) chunk_store<C>(p.dual_out, (int64_t)row * p.dual_pitch, 1, k0, n, rvalid, u);
 
     // ---- primal recovery x = y - D^T u, then every block between two bound duals takes
     //      the value of its first sample, so that constant runs are bit-identical

@@ -402,7 +402,11 @@ constexpr int kMlProbeGroups = 512;        // ... judged on the row's first 2048
 struct MlPlan {
     int levels;                       // coarse levels 1 .. levels (0 = the row itself)
     int64_t n[kMlMaxLevels + 1];
+    // scratch in a workspace: every level's rows packed, level after level (byte offsets)
     size_t y_off[kMlMaxLevels + 1], u_off[kMlMaxLevels + 1], flag_off, bytes;
+    // scratch inside the output rows: all levels of a row within the row's own n floats (offsets
+    // in floats from the start of the row, multiples of 4); row_floats = 0 if they do not fit
+    int64_t row_y_off[kMlMaxLevels + 1], row_u_off[kMlMaxLevels + 1], row_flag_off, row_floats;
 };
 
 bool ml_plan(const tv_rows &r, int64_t n_rows, MlPlan *pl)
@@ -411,34 +415,43 @@ bool ml_plan(const tv_rows &r, int64_t n_rows, MlPlan *pl)
     pl->levels = 0;
     pl->n[0] = r.length;
     size_t at = 0;
+    int64_t in_row = 0;
     while (pl->n[pl->levels] > tvd::get(tvd::kMlCoarsest) && pl->levels < kMlMaxLevels) {
         const int l = ++pl->levels;
         pl->n[l] = (pl->n[l - 1] + tvk::kMlFactor - 1) / tvk::kMlFactor;
         const size_t bytes = align16((size_t)n_rows * (size_t)pl->n[l] * sizeof(float));
         pl->y_off[l] = at; at += bytes;
         pl->u_off[l] = at; at += bytes;
+        const int64_t padded = (pl->n[l] + 3) / 4 * 4;
+        pl->row_y_off[l] = in_row; in_row += padded;
+        pl->row_u_off[l] = in_row; in_row += padded;
     }
     pl->flag_off = at;
     pl->bytes = at + align16((size_t)n_rows * sizeof(uint32_t));
+    pl->row_flag_off = in_row;
+    pl->row_floats = in_row + 1 <= r.length ? in_row + 1 : 0;
     return pl->levels > 0;
 }
 
 // out[row][j] = mean of in[row][kMlFactor j ...] (the samples that exist); one workgroup per row.
 // FIRST: `in` is the caller's tensor (rows by L), and the row's flag is decided here from the mean
-// absolute difference of neighbouring samples inside the groups; otherwise `in` is packed,
-// n_in per row, and rows with flag 0 are skipped.
+// absolute difference of neighbouring samples inside the groups; otherwise `in` holds n_in samples
+// per row, in_pitch floats apart, and rows with flag 0 are skipped.  out: out_pitch floats apart;
+// flag: flag_pitch words apart.
 template <bool FIRST>
 __global__ __launch_bounds__(256) void ml_average_kernel(const float *__restrict__ in,
                                                          float *__restrict__ out,
                                                          uint32_t *__restrict__ flag,
                                                          const float *__restrict__ lam, tvk::Layout L,
-                                                         int32_t n_in, int32_t n_out)
+                                                         int32_t n_in, int32_t n_out, int64_t in_pitch,
+                                                         int64_t out_pitch, uint32_t flag_pitch)
 {
     constexpr int F = tvk::kMlFactor;
     const uint32_t row = blockIdx.x;
-    if (!FIRST && flag[row] == 0) return;
-    const float *src = in + (FIRST ? tvk::row_offset(L, row) : (int64_t)row * n_in);
-    float *dst = out + (int64_t)row * n_out;
+    flag += (size_t)row * flag_pitch;
+    if (!FIRST && flag[0] == 0) return;
+    const float *src = in + (FIRST ? tvk::row_offset(L, row) : (int64_t)row * in_pitch);
+    float *dst = out + (int64_t)row * out_pitch;
     const bool vec = ((uintptr_t)src % 16) == 0;
     auto group = [&](int j, float (&v)[F]) {
         const int k = j * F;
@@ -476,7 +489,7 @@ __global__ __launch_bounds__(256) void ml_average_kernel(const float *__restrict
             const float pairs = (float)(last - 1) * (float)(F - 1) / (float)F;
             const float l = tvk::load_lambda(lam, L, row);
             decision = (l * pairs >= kMlLambdaRatio * red[0]) ? 1u : 0u;
-            flag[row] = decision;
+            flag[0] = decision;
         }
         __syncthreads();
         if (decision == 0) return;
@@ -494,37 +507,46 @@ __global__ __launch_bounds__(256) void ml_average_kernel(const float *__restrict
 static_assert(tvk::kMlFactor == 4, "ml_average_kernel loads groups as float4");
 
 // The forward call on long rows with the multilevel start; p is the fine level, fully set up.
+// ws: the levels' scratch (MlPlan's workspace layout), or null: then every row's levels live in
+// that row of the output p.x (MlPlan's in-row layout; packed rows, p.x apart from p.y), which the
+// fine level overwrites at its very end, after the one workgroup or wave that owns the row has
+// read the row's coarse dual at its start.
 int run_fwd_multilevel(FwdParams p, const tv_lambda &l, int64_t n_rows, const MlPlan &pl, char *ws,
                        hipStream_t s)
 {
-    uint32_t *flag = (uint32_t *)(ws + pl.flag_off);
-    auto yl = [&](int lv) { return (float *)(ws + pl.y_off[lv]); };
-    auto ul = [&](int lv) { return (float *)(ws + pl.u_off[lv]); };
+    const bool in_rows = ws == nullptr;
+    const int64_t n0 = pl.n[0];
+    uint32_t *flag = in_rows ? reinterpret_cast<uint32_t *>(p.x + pl.row_flag_off) : (uint32_t *)(ws + pl.flag_off);
+    const uint32_t flag_pitch = in_rows ? (uint32_t)n0 : 1u;
+    auto yl = [&](int lv) { return in_rows ? p.x + pl.row_y_off[lv] : (float *)(ws + pl.y_off[lv]); };
+    auto ul = [&](int lv) { return in_rows ? p.x + pl.row_u_off[lv] : (float *)(ws + pl.u_off[lv]); };
+    auto pitch = [&](int lv) { return in_rows ? n0 : pl.n[lv]; };      // floats between consecutive rows of a level
     const dim3 grid((uint32_t)n_rows), block(256);
     hipLaunchKernelGGL(ml_average_kernel<true>, grid, block, 0, s, p.y, yl(1), flag, l.lam, p.L,
-                       (int32_t)pl.n[0], (int32_t)pl.n[1]);
+                       (int32_t)pl.n[0], (int32_t)pl.n[1], (int64_t)0, pitch(1), flag_pitch);
     for (int lv = 2; lv <= pl.levels; ++lv)
         hipLaunchKernelGGL(ml_average_kernel<false>, grid, block, 0, s, (const float *)yl(lv - 1), yl(lv), flag,
-                           l.lam, p.L, (int32_t)pl.n[lv - 1], (int32_t)pl.n[lv]);
+                           l.lam, p.L, (int32_t)pl.n[lv - 1], (int32_t)pl.n[lv], pitch(lv - 1), pitch(lv), flag_pitch);
     if (launch_status() != TV_OK) return TV_ERR_HIP;
     float scale = 1.0f;
     for (int lv = 1; lv <= pl.levels; ++lv) scale /= (float)tvk::kMlFactor;
     for (int lv = pl.levels; lv >= 1; --lv, scale *= (float)tvk::kMlFactor) {
         FwdParams c = p;
-        const tv_rows rc = {1, 0, n_rows, pl.n[lv], pl.n[lv], 1};
+        const tv_rows rc = {1, 0, n_rows, pitch(lv), pl.n[lv], 1};
         c.L = make_layout(rc, l, n_rows);
         c.y = yl(lv); c.addend = nullptr; c.x = nullptr; c.x2 = nullptr; c.resid = nullptr;
         c.info = nullptr; c.seg = nullptr; c.order = nullptr;
-        c.dual_out = ul(lv);
-        c.ml_flag = flag; c.ml_skip = 1;
+        c.dual_out = ul(lv); c.dual_pitch = (int32_t)pitch(lv);
+        c.ml_flag = flag; c.flag_pitch = flag_pitch; c.ml_skip = 1;
         c.lam_scale = scale;
         c.warm = lv == pl.levels ? 0u : 2u;
         c.coarse_u = lv == pl.levels ? nullptr : ul(lv + 1);
         c.coarse_n = lv == pl.levels ? 0 : (int32_t)pl.n[lv + 1];
+        c.coarse_pitch = lv == pl.levels ? 0 : (int32_t)pitch(lv + 1);
         if (tvk::launch_fwd_long(c, s) != hipSuccess) return TV_ERR_HIP;
     }
-    p.warm = 2; p.coarse_u = ul(1); p.coarse_n = (int32_t)pl.n[1];
-    p.ml_flag = flag; p.ml_skip = 0;
+    p.warm = 2; p.coarse_u = ul(1); p.coarse_n = (int32_t)pl.n[1]; p.coarse_pitch = (int32_t)pitch(1);
+    p.ml_flag = flag; p.flag_pitch = flag_pitch; p.ml_skip = 0;
     return tvk::launch_fwd_long(p, s) == hipSuccess ? TV_OK : TV_ERR_HIP;
 }
 
@@ -561,7 +583,8 @@ int run_fwd(const float *y, const float *addend, float *x, float *resid, int32_t
     p.io16 = io16 ? 1u : 0u;
     p.psearch = psearch ? 1u : 0u;
     p.warm = (warm && addend) ? 1u : 0u;
-    p.coarse_u = nullptr; p.coarse_n = 0; p.dual_out = nullptr; p.ml_flag = nullptr; p.ml_skip = 0;
+    p.coarse_u = nullptr; p.coarse_n = 0; p.coarse_pitch = 0; p.dual_out = nullptr; p.dual_pitch = 0;
+    p.ml_flag = nullptr; p.flag_pitch = 1; p.ml_skip = 0;
     p.lam_scale = 1.0f;
     p.debug = nullptr; p.debug_rows = 0;
     p.L = make_layout(r, l, n_rows);
@@ -608,7 +631,15 @@ int run_fwd(const float *y, const float *addend, float *x, float *resid, int32_t
         return launch_fwd_short<32>(p, packed, s, planes, ragged);
     }
     MlPlan pl;
-    if (ml_ws && !p.warm && ml_plan(r, n_rows, &pl)) return run_fwd_multilevel(p, l, n_rows, pl, ml_ws, s);
+    if (!p.warm && !addend && ml_plan(r, n_rows, &pl)) {
+        if (ml_ws) return run_fwd_multilevel(p, l, n_rows, pl, ml_ws, s);
+        // no workspace: the levels of a row fit into that row of x (two thirds of it), which is the
+        // call's to write anyway, if the rows are packed and x and y do not overlap
+        const float *y_end = y + n_rows * r.length;
+        const float *x_end = x + n_rows * r.length;
+        if (pl.row_floats > 0 && rows_packed(r) && (x_end <= y || y_end <= x))
+            return run_fwd_multilevel(p, l, n_rows, pl, nullptr, s);
+    }
     return tvk::launch_fwd_long(p, s) == hipSuccess ? TV_OK : TV_ERR_HIP;
 }
 
@@ -997,7 +1028,8 @@ int tv1d_prox_fwd_steps(const float *y, float *x, int32_t *info, float *record, 
     FwdParams p;
     p.y = y; p.addend = nullptr; p.x = x; p.x2 = nullptr; p.resid = nullptr; p.lam = lam.lam; p.info = info;
     p.seg = nullptr; p.order = nullptr; p.io16 = 0; p.psearch = 0; p.warm = 0;
-    p.coarse_u = nullptr; p.coarse_n = 0; p.dual_out = nullptr; p.ml_flag = nullptr; p.ml_skip = 0;
+    p.coarse_u = nullptr; p.coarse_n = 0; p.coarse_pitch = 0; p.dual_out = nullptr; p.dual_pitch = 0;
+    p.ml_flag = nullptr; p.flag_pitch = 1; p.ml_skip = 0;
     p.lam_scale = 1.0f;
     p.debug = record;
     p.debug_rows = (uint32_t)(record_rows < n_rows ? record_rows : n_rows);

@@ -11,8 +11,8 @@ from parity import FWD_TOL, check_batch, forward_errors
 pytestmark = pytest.mark.gpu
 
 
-def _check(y, lam, lam_div, g, axis, label, want_info=True, use_ws=False):
-    out = run_1d(y, lam, lam_div, g, axis=axis, want_info=want_info, use_ws=use_ws)
+def _check(y, lam, lam_div, g, axis, label, want_info=True, use_ws=False, in_place=False):
+    out = run_1d(y, lam, lam_div, g, axis=axis, want_info=want_info, use_ws=use_ws, in_place=in_place)
     yr, gr = rows_view(y, axis), rows_view(g, axis)
     lr = lam_per_row(lam, len(yr), lam_div)
     st = check_batch(yr, lr, gr, rows_view(out["x"], axis), rows_view(out["gy"], axis),
@@ -57,19 +57,27 @@ def test_every_long_length(n):
 
 @pytest.mark.parametrize("n", [2048, 2049, 3000, 4096, 5000, 8192, 10001, 16384])
 def test_multilevel_start(n):
-    """tv1d_prox_fwd_ex with its workspace on long unit-stride rows: the solve starts from the
-    duals of the averaged rows.  Same parity bar; rows with a large lambda need far fewer steps."""
+    """Long unit-stride rows start from the duals of the averaged rows: with the workspace of
+    tv1d_prox_fwd_ex, and without one when x is a buffer of its own (packed rows), whose rows then
+    hold the levels until the fine level overwrites them; both give the same bits.  A call in
+    place (x = y) has no such room and starts cold.  Same parity bar for all three; rows with a
+    large lambda need far fewer steps from the multilevel start."""
     rng = np.random.default_rng(700 + n)
     rows = 12 if n <= 4096 else 6
     y = _mixed_rows(rng, rows, n)
     g = rng.normal(size=y.shape).astype(np.float32)
     lam = (10 ** np.linspace(-2.5, 1, rows)).astype(np.float32)        # small ones start cold
-    cold = _check(y, lam, 1, g, -1, "cold n=%d" % n)
+    cold = _check(y, lam, 1, g, -1, "cold (in place) n=%d" % n, in_place=True)
     ml = _check(y, lam, 1, g, -1, "multilevel n=%d" % n, use_ws=True)
+    own = _check(y, lam, 1, g, -1, "multilevel inside x n=%d" % n)
     assert ml["ws_bytes"] > 0
     big = lam >= 1.0
     assert ml["steps"][big].max() <= 10, (ml["steps"], cold["steps"])
     assert ml["steps"][big].sum() < cold["steps"][big].sum(), (ml["steps"], cold["steps"])
+    assert np.array_equal(own["steps"], ml["steps"])
+    a = run_1d(y, lam, 1, use_ws=True)["x"]
+    b = run_1d(y, lam, 1)["x"]
+    assert np.array_equal(a, b)
 
 
 @pytest.mark.parametrize("n", [40, 90, 160, 300, 700, 3000])
@@ -83,6 +91,22 @@ def test_lambda_far_beyond_lam_max(n, lam):
     y = _mixed_rows(rng, 6, n)
     g = rng.normal(size=y.shape).astype(np.float32)
     _check(y, np.array([lam], np.float32), 1, g, -1, "n=%d lam=%g" % (n, lam))
+
+
+@pytest.mark.parametrize("n,lam", [(3000, 1e3), (5000, 1e3), (8192, 3e3)])
+def test_multilevel_start_with_lambda_of_the_order_of_lam_max(n, lam):
+    """Random-walk rows whose lam_max is in the thousands, with a lambda of that order: a few long
+    segments, duals a thousand times the data.  From the multilevel start such a row is done in
+    two or three Newton steps, and a large last step leaves more rounding error in the free duals
+    than the output may carry: the solve then takes one more, small step.  With the workspace and
+    with the levels inside x."""
+    rng = np.random.default_rng(900 + n)
+    y = _mixed_rows(rng, 6, n)
+    g = rng.normal(size=y.shape).astype(np.float32)
+    a = _check(y, np.array([lam], np.float32), 1, g, -1, "ws n=%d lam=%g" % (n, lam), use_ws=True)
+    b = _check(y, np.array([lam], np.float32), 1, g, -1, "plain n=%d lam=%g" % (n, lam))
+    assert a["max_steps"] <= 8 and np.array_equal(a["steps"], b["steps"])
+    assert a["fwd_max_err"] <= 0.5 * FWD_TOL
 
 
 def test_noise_rows_with_lambda_near_lam_max():
