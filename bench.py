@@ -381,10 +381,13 @@ def dispatch_probe(dev) -> int:
              "the row-per-lane kernels", "a plane per workgroup")
     case("plane_per_group_planes", "at_a_fifth_k4", lambda: two_d(n // 5, 32, 32, 4), 0,
          "a plane per workgroup", "the row-per-lane kernels")
-    for name, K in (("plane_per_group64_planes", 1), ("plane_per_group64_planes_k2", 2), ("plane_per_group64_planes_k2", 4)):
+    for name, S, K in (("plane_per_group64_planes", 64, 1), ("plane_per_group64_planes_k2", 48, 2),
+                       ("plane_per_group64_planes_k2", 48, 4), ("plane_per_group64_full_planes_k2", 64, 2),
+                       ("plane_per_group64_full_planes_k3", 64, 3), ("plane_per_group64_full_planes_k3", 64, 4),
+                       ("plane_per_group64_full_planes_k5", 64, 5), ("plane_per_group64_full_planes_k5", 64, 8)):
         n = defaults[name]
-        case(name, "at_threshold_k%d" % K, lambda: two_d(n, 64, 64, K), 0, "a plane per workgroup", "pass by pass")
-        case(name, "beyond_k%d" % K, lambda: two_d(n + n // 4, 64, 64, K), big, "pass by pass", "a plane per workgroup")
+        case(name, "at_threshold_%dx%d_k%d" % (S, S, K), lambda: two_d(n, S, S, K), 0, "a plane per workgroup", "pass by pass")
+        case(name, "beyond_%dx%d_k%d" % (S, S, K), lambda: two_d(n + n // 4, S, S, K), big, "pass by pass", "a plane per workgroup")
     for name, H, W, K, other in (("plane_per_group_bwd_planes", 32, 32, 4, "a row per lane"),
                                  ("plane_per_group64_bwd_planes", 64, 64, 4, "a row per lane"),
                                  ("plane_per_group64_bwd_ragged_planes", 40, 48, 1, "pass by pass"),

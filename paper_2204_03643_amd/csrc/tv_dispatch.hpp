@@ -26,6 +26,9 @@ enum {
     kPlanePerGroupPlanes,
     kPlanePerGroup64Planes,
     kPlanePerGroup64PlanesK2,
+    kPlanePerGroup64FullPlanesK2,
+    kPlanePerGroup64FullPlanesK3,
+    kPlanePerGroup64FullPlanesK5,
     kPlanePerGroupBwdPlanes,
     kPlanePerGroup64BwdPlanes,
     kPlanePerGroup64BwdRaggedPlanes,
@@ -97,7 +100,18 @@ inline Threshold table[kCount] = {
     //            K = 2: 1536 planes 162 / 177, 2048: 207 / 203, 3072: 295 / 273;
     //            K = 4: 1536 planes 266 / 313, 2048: 350 / 360, 3072: 509 / 483.
     {"plane_per_group64_planes", 1536, "2D planes of 33-64 a side, one sweep: one launch, a plane per workgroup, up to this many planes"},
-    {"plane_per_group64_planes_k2", 2048, "... two sweeps or more"},
+    {"plane_per_group64_planes_k2", 1536, "... two sweeps or more, planes smaller than 64 x 64"},
+    //   64 x 64 again, to larger batches (full planes keep every lane of the 8 x 8 mapping busy):
+    //            K = 2: 2560 planes 321 / 339, 3072: 386 / 401, 3584: 443 / 446, 4096: 503 / 488;
+    //            K = 3: 3072 planes 513 / 540, 4096: 661 / 694, 5120: 819 / 807;
+    //            K = 4: 4096 planes 820 / 876, 5120: 1011 / 1020;  K = 6: 4096: 1107 / 1218, 5120: 1364 / 1416.
+    //   (48 x 48 once more, forward + reverse sweep: K = 2, 2048 planes 291 / 275;  K = 4: 486 / 473)
+    {"plane_per_group64_full_planes_k2", 3584, "... planes of 64 x 64, two sweeps"},
+    //            K = 4: 8192 planes 1587 / 1637, 16384: 3030 / 3034, 32768: 6064 / 5790;
+    //            K = 6: 8192 planes 2121 / 2300, 16384: 4172 / 4185, 32768: 8403 / 8207;
+    //            K = 10: 8192 planes 3237 / 3479, 16384: 6377 / 6548, 32768: 12837 / 12927.
+    {"plane_per_group64_full_planes_k3", 8192, "... planes of 64 x 64, three or four sweeps"},
+    {"plane_per_group64_full_planes_k5", 12288, "... planes of 64 x 64, five sweeps or more"},
     // 2D reverse sweep of small batches with a plane per workgroup (tv_plane2d.hpp): both adjoint
     // state tensors of the plane in LDS, 16 x 2 or 8 x 8 threads x samples per row, the segment
     // sums across a row's threads by row shifts.  Against the row-per-lane one-launch kernel (a

@@ -1199,8 +1199,12 @@ static int small_side(int64_t H, int64_t W)
 static bool plane_per_group_2d(int64_t planes, int64_t H, int64_t W, int sweeps)
 {
     if (small_planes(H, W)) return small_side(H, W) == 32 && planes <= tvd::get(tvd::kPlanePerGroupPlanes);
-    return H <= 64 && W <= 64 &&
-           planes <= tvd::get(sweeps == 1 ? tvd::kPlanePerGroup64Planes : tvd::kPlanePerGroup64PlanesK2);
+    if (H > 64 || W > 64) return false;
+    if (sweeps == 1) return planes <= tvd::get(tvd::kPlanePerGroup64Planes);
+    if (H == 64 && W == 64)
+        return planes <= tvd::get(sweeps == 2 ? tvd::kPlanePerGroup64FullPlanesK2
+                                               : (sweeps <= 4 ? tvd::kPlanePerGroup64FullPlanesK3 : tvd::kPlanePerGroup64FullPlanesK5));
+    return planes <= tvd::get(tvd::kPlanePerGroup64PlanesK2);
 }
 
 // When the one-launch forward kernel is used: while its lower occupancy (17 KB of LDS per wave

@@ -194,7 +194,9 @@ def test_plane_per_workgroup_forward_and_reverse_sweep(shape, K, dispatch_defaul
     y = rng.normal(size=shape).astype(np.float32)
     g = rng.normal(size=shape).astype(np.float32)
     lam = (10 ** rng.uniform(-2, 0.3, size=3)).astype(np.float32)
-    fwd_knobs = ("plane_per_group_planes", "plane_per_group64_planes", "plane_per_group64_planes_k2")
+    fwd_knobs = ("plane_per_group_planes", "plane_per_group64_planes", "plane_per_group64_planes_k2",
+                 "plane_per_group64_full_planes_k2", "plane_per_group64_full_planes_k3",
+                 "plane_per_group64_full_planes_k5")
     bwd_knobs = ("plane_per_group_bwd_planes", "plane_per_group64_bwd_planes", "plane_per_group64_bwd_ragged_planes",
                  "plane_per_group64_bwd_ragged_planes_k2")
     for k in fwd_knobs + bwd_knobs:
