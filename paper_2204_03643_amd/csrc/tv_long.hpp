@@ -438,10 +438,29 @@ struct LongSmemBwd {
 // WARM = 2 (unit-stride rows, C a multiple of kMlFactor): rows flagged in p.ml_flag start from
 // the dual of the same row averaged in groups of kMlFactor samples (p.coarse_u), which a launch
 // on the averaged rows with lambda / kMlFactor left behind (p.dual_out of that launch).
-// (512-thread workgroups ask for 4 waves per SIMD, i.e. at most 128 VGPRs, so that a CU holds two.)
 // DEBUG: the first p.debug_rows rows leave a step record in p.debug (see step_record_floats).
+
+// Waves per SIMD that the forward kernel asks the register allocator for (the second argument
+// of __launch_bounds__; 1 = no request).  Left alone, the kernels with 8 samples per thread take
+// 85-96 VGPRs and those with 12 take 100-108: a few registers above the step to one more
+// resident wave (80 for six, 96 for five).  These kernels wait 40-50 % of their time (barriers,
+// LDS exchanges, the drain of a launch in partly filled rounds), so where the allocator can
+// get below the step with at most a handful of spilled registers the extra wave pays:
+// 12 288 columns of 512 samples 57 -> 52 us (three 512-thread workgroups per CU, two rounds
+// instead of three), warm row passes of the same 2-3 %, 3000 rows of 3000 samples 910 -> 730 us.
+// Not requested where it costs 10-18 spilled registers (128 threads x 12 samples, and the
+// transposing kernel with 32 x 12): those ran 2-3 % slower with it.
+template <int T, int C, int G, bool COLS, bool XPOSE>
+constexpr int fwd_waves_per_simd()
+{
+    if (T * G == 512 && !COLS) return 4;        // at most 128 VGPRs: a CU holds two such workgroups
+    if (XPOSE && C <= 4) return 8;
+    if (C == 8 && (T * G <= 256 || (XPOSE && T * G == 512))) return 6;
+    if (C == 12 && T * G <= 256 && T != 128 && !(XPOSE && T == 32)) return 5;
+    return 1;
+}
 template <int T, int C, int G, bool COLS, bool XPOSE = false, int WARM = 0, bool DEBUG = false>
-__global__ __launch_bounds__(T *G, (T * G == 512 && !COLS) ? 4 : ((XPOSE && C <= 4) ? 8 : 1)) void tv1d_fwd_long_kernel(FwdParams p)
+__global__ __launch_bounds__(T *G, (fwd_waves_per_simd<T, C, G, COLS, XPOSE>())) void tv1d_fwd_long_kernel(FwdParams p)
 {
     static_assert(!XPOSE || (COLS && T <= 64), "the transposing variant is for strided rows inside one wave");
     constexpr bool MCOLS = COLS && !XPOSE;             // mapping used by the solve
