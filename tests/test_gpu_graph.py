@@ -139,13 +139,17 @@ def test_long_rows_and_large_planes_replay_from_a_graph():
     wsb = tv.tv2d_workspace_bytes(planes, H, W, K)
     ws = torch.empty(wsb, dtype=torch.uint8, device=dev)
 
+    x1p = torch.empty_like(y1t)         # the plain call: the levels of a row live in that row of x
+
     def step():
         tv.tv1d_prox_fwd_ex(y1t, x1t, r1, L1, ws=fws, ws_bytes=fwsb)
+        tv.tv1d_prox_fwd(y1t, x1p, r1, L1)
         tv.tv2d_prox_fwd(y2t, x2t, planes, H, W, L2, K, ws, wsb)
         tv.tv2d_prox_bwd(g2t, gy2, gl2, planes, H, W, L2, K, ws, wsb)
 
     step()
     torch.cuda.synchronize()
+    assert torch.equal(x1p, x1t)
     ref = [t.clone() for t in (x1t, x2t, gy2, gl2)]
     graph = torch.cuda.CUDAGraph()
     side = torch.cuda.Stream()
@@ -158,8 +162,10 @@ def test_long_rows_and_large_planes_replay_from_a_graph():
         for t in (x1t, x2t, gy2, gl2):
             t.zero_()
         fws.fill_(0xff)
+        x1p.view(torch.uint8).fill_(0xff if rep % 2 else 0x01)      # stale flags and levels must not matter
         torch.cuda.synchronize()
         graph.replay()
         torch.cuda.synchronize()
         for a, b in zip((x1t, x2t, gy2, gl2), ref):
             assert torch.equal(a, b), rep
+        assert torch.equal(x1p, ref[0]), rep
