@@ -50,6 +50,18 @@ def test_mid_planes(shape, K):
     _check_2d(y, lam, K, g, "mid %s K=%d" % (shape, K))
 
 
+def test_wide_planes_whose_first_row_pass_takes_the_multilevel_start():
+    """Planes 2304 samples wide: the first row pass of the 2D call is a cold call on packed
+    unit-stride rows of 2048 samples or more, which keeps the levels of its multilevel start in the
+    rows of its output (the first saved pass output); the later row passes start from their own
+    dual, and the column passes are strided rows of 6 samples."""
+    rng = np.random.default_rng(2304)
+    y = (np.cumsum(rng.normal(scale=0.05, size=(2, 6, 2304)), axis=-1) + 0.05 * rng.normal(size=(2, 6, 2304))).astype(np.float32)
+    g = rng.normal(size=y.shape).astype(np.float32)
+    lam = np.array([0.3, 2.0], np.float32)
+    _check_2d(y, lam, 2, g, "2x6x2304 K=2")
+
+
 def test_odd_sizes_mixed_paths():
     rng = np.random.default_rng(71)
     y = rng.normal(size=(3, 19, 45)).astype(np.float32)         # rows of 45 (long path), columns of 19
