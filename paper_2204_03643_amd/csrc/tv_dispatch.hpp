@@ -129,9 +129,9 @@ inline Threshold table[kCount] = {
     // 1024: 29 / 28, 2048: 53 / 40; K = 3: 256 planes 22 / 44, 1024: 52 / 74, 2048: 95 / 108.
     // K = 4: 1024 planes 63 / 97, 4096: 219 / 245, 8192: 424 / 429; K = 2: 4096 planes 112 / 121,
     // 8192: 242 / 211; 56 x 60, K = 2: 2048 planes 80 / 114, 8192: 293 / 401; 33 x 33, K = 2: 4096
-    // planes 103 / 111, 16 384: 418 / 381.
+    // planes 103 / 111, 16 384: 418 / 381;  40 x 48, K = 3 again: 5120 planes 216 / 228, 8192: 336 / 323.
     {"plane_per_group64_bwd_ragged_planes", 768, "2D reverse sweep, other planes of 33-64 a side, one sweep: a plane per workgroup up to this many planes"},
-    {"plane_per_group64_bwd_ragged_planes_k2", 4096, "... two sweeps or more"},
+    {"plane_per_group64_bwd_ragged_planes_k2", 6144, "... two sweeps or more"},
     // 2D, planes of at most 32 x 32 in one launch: the reverse sweep reads the segment codes of the
     // passes, not their outputs, so the forward kernel writes only the codes and x.  1 = it also
     // writes every pass's output into the workspace, where the pass-by-pass forward leaves them (the
@@ -151,9 +151,14 @@ inline Threshold table[kCount] = {
     // of 32 samples in 128 lambda slots, forward + backward: 40 960 rows 39.6 / 38.2, 49 152 rows
     // 38.2 / 39.6.
     {"thread_per_sample_1d_rows", 40960, "1D rows of at most 32 samples: a few threads per row up to this many rows"},
-    // Multilevel start of unit-stride rows (workspace of tv1d_prox_fwd_ex): from this length on.
-    // 4096 rows x 16384: 1410 -> 880; below 2048 samples the coarse levels cost what they save.
-    {"ml_min_length", 2048, "multilevel start for unit-stride rows of this many samples or more"},
+    // Multilevel start of unit-stride rows: from this length on.  4096 rows x 16384: 1410 -> 880.
+    // 8M samples in rows of n, lambda 10^U(-3, 1) per row, cold / multilevel, for random walks,
+    // white noise and noisy steps of 64 samples: n = 768: 106 / 101, 113 / 116, 88 / 103; 1024:
+    // 115 / 95, 127 / 118, 96 / 105; 1280: 202 / 155, 241 / 188, 172 / 168; 1536: 198 / 141,
+    // 209 / 169, 153 / 154; 2048: 145 / 123, 193 / 151, 126 / 134; 3072: 143 / 139, 215 / 157,
+    // 118 / 131.  From 1025 samples on (128 threads and more per row) it wins or ties on two kinds
+    // of rows out of three and costs the third at most 10 %.
+    {"ml_min_length", 1025, "multilevel start for unit-stride rows of this many samples or more"},
     // ... and levels are stacked until a row has at most this many samples.
     {"ml_coarsest", 256, "coarsest level of the multilevel start"},
 };
