@@ -154,10 +154,11 @@ inline Threshold table[kCount] = {
     // Multilevel start of unit-stride rows: from this length on.  4096 rows x 16384: 1410 -> 880.
     // 8M samples in rows of n, lambda 10^U(-3, 1) per row, cold / multilevel, for random walks,
     // white noise and noisy steps of 64 samples: n = 768: 106 / 101, 113 / 116, 88 / 103; 1024:
-    // 115 / 95, 127 / 118, 96 / 105; 1280: 202 / 155, 241 / 188, 172 / 168; 1536: 198 / 141,
-    // 209 / 169, 153 / 154; 2048: 145 / 123, 193 / 151, 126 / 134; 3072: 143 / 139, 215 / 157,
-    // 118 / 131.  From 1025 samples on (128 threads and more per row) it wins or ties on two kinds
-    // of rows out of three and costs the third at most 10 %.
+    // 115 / 95, 127 / 118, 96 / 105 (these two with rows taking the start from lambda >= 2 x their
+    // mean |y[k+1] - y[k]| on; the others from 0.5 x); 1280: 200 / 153, 233 / 187, 163 / 156;
+    // 2048: 140 / 122, 187 / 151, 125 / 128; 4096: 150 / 124, 185 / 167, 125 / 123.  From 1025
+    // samples on (128 threads and more per row) it wins on two kinds of rows out of three and
+    // ties on the third.
     {"ml_min_length", 1025, "multilevel start for unit-stride rows of this many samples or more"},
     // ... and levels are stacked until a row has at most this many samples.
     {"ml_coarsest", 256, "coarsest level of the multilevel start"},

@@ -396,7 +396,7 @@ bool order_applies(const tvk::TileMap &tm)
 // Rows whose lambda is small against their variation converge in a few steps anyway and are
 // left out (ml_flag = 0): they start cold at the fine level and are skipped at the others.
 constexpr int kMlMaxLevels = 8;                // (where it starts and ends: tv_dispatch.hpp)
-constexpr float kMlLambdaRatio = 2.0f;     // multilevel start when lambda >= ratio * mean |y[k+1] - y[k]|
+constexpr float kMlLambdaRatio = 0.5f;     // multilevel start when lambda >= ratio * mean |y[k+1] - y[k]| (2, 4, 8: every kind of row slower; 0.125: 1-2 % slower)
 constexpr int kMlProbeGroups = 512;        // ... judged on the row's first 2048 samples
 
 struct MlPlan {
