@@ -160,8 +160,13 @@ inline Threshold table[kCount] = {
     // samples on (128 threads and more per row) it wins on two kinds of rows out of three and
     // ties on the third.
     {"ml_min_length", 1025, "multilevel start for unit-stride rows of this many samples or more"},
-    // ... and levels are stacked until a row has at most this many samples.
-    {"ml_coarsest", 256, "coarsest level of the multilevel start"},
+    // ... and levels are stacked (one at least) until a row has at most this many samples.  One
+    // level, solved from the cold start, is what pays: every further level is two more launches,
+    // and the cold start of a row of a few thousand samples is cheap next to the fine level.
+    // Rows as above, coarsest level at most 256 / 1024 / 4096 samples: n = 2048: 125 / 102 / -,
+    // 153 / 120 / -, 131 / 107 / -; 8192 (32M samples): - / 344 / 317, - / 343 / 316, - / 347 / 323;
+    // 16 384: 460 / 430 / 398 (8M samples), - / 445 / 412, - / 443 / 413 (32M).
+    {"ml_coarsest", 4096, "coarsest level of the multilevel start"},
 };
 
 inline int64_t get(int which) { return table[which].value; }

@@ -391,8 +391,10 @@ bool order_applies(const tvk::TileMap &tm)
 // changes a little with every step).  The same row averaged in groups of kMlFactor samples,
 // with lambda / kMlFactor, is the problem restricted to rows that are constant on the groups;
 // its dual, prolonged (see the WARM = 2 kernel), is a start from which the fine level needs
-// about 4 steps whatever lambda is.  Levels are stacked until a row has at most kMlCoarsest
-// samples; every level is an ordinary launch of the long-row kernel on packed scratch rows.
+// about 4 steps whatever lambda is.  One level at least, and further ones while a row has more
+// than kMlCoarsest samples (by default that leaves the one level: stacking them was measured
+// and costs more launches than it saves steps); every level is an ordinary launch of the
+// long-row kernel on packed scratch rows.
 // Rows whose lambda is small against their variation converge in a few steps anyway and are
 // left out (ml_flag = 0): they start cold at the fine level and are skipped at the others.
 constexpr int kMlMaxLevels = 8;                // (where it starts and ends: tv_dispatch.hpp)
@@ -416,7 +418,7 @@ bool ml_plan(const tv_rows &r, int64_t n_rows, MlPlan *pl)
     pl->n[0] = r.length;
     size_t at = 0;
     int64_t in_row = 0;
-    while (pl->n[pl->levels] > tvd::get(tvd::kMlCoarsest) && pl->levels < kMlMaxLevels) {
+    do {                                            // one level at least
         const int l = ++pl->levels;
         pl->n[l] = (pl->n[l - 1] + tvk::kMlFactor - 1) / tvk::kMlFactor;
         const size_t bytes = align16((size_t)n_rows * (size_t)pl->n[l] * sizeof(float));
@@ -425,7 +427,7 @@ bool ml_plan(const tv_rows &r, int64_t n_rows, MlPlan *pl)
         const int64_t padded = (pl->n[l] + 3) / 4 * 4;
         pl->row_y_off[l] = in_row; in_row += padded;
         pl->row_u_off[l] = in_row; in_row += padded;
-    }
+    } while (pl->n[pl->levels] > tvd::get(tvd::kMlCoarsest) && pl->levels < kMlMaxLevels);
     pl->flag_off = at;
     pl->bytes = at + align16((size_t)n_rows * sizeof(uint32_t));
     pl->row_flag_off = in_row;
@@ -633,7 +635,7 @@ int run_fwd(const float *y, const float *addend, float *x, float *resid, int32_t
     MlPlan pl;
     if (!p.warm && !addend && ml_plan(r, n_rows, &pl)) {
         if (ml_ws) return run_fwd_multilevel(p, l, n_rows, pl, ml_ws, s);
-        // no workspace: the levels of a row fit into that row of x (two thirds of it), which is the
+        // no workspace: the levels of a row fit into that row of x (half of it, two thirds with levels stacked), which is the
         // call's to write anyway, if the rows are packed and x and y do not overlap
         const float *y_end = y + n_rows * r.length;
         const float *x_end = x + n_rows * r.length;

@@ -181,10 +181,13 @@ def test_rows_along():
 
 def test_forward_workspace_of_long_rows():
     lam = tv.tv_lambda(FAKE, 1, 1)
-    # unit-stride rows of 1025 samples or more: coarse levels of n/4, n/16, ... down to <= 256
-    # samples (two arrays each) plus a flag per row
+    # unit-stride rows of 1025 samples or more: one coarse level of n/4 samples (further ones
+    # only beyond ml_coarsest = 4096 samples), two arrays, plus a flag per row
     r = tv.rows_along((10, 16384), -1)
+    assert tv.tv1d_fwd_workspace_bytes(r, lam) == 2 * 10 * 4096 * 4 + 48
+    tv.tv_dispatch_override("ml_coarsest", 256)
     assert tv.tv1d_fwd_workspace_bytes(r, lam) == 2 * 10 * (4096 + 1024 + 256) * 4 + 48
+    tv.tv_dispatch_override("ml_coarsest", 4096)
     assert tv.tv1d_fwd_workspace_bytes(tv.rows_along((10, 1024), -1), lam) == 0
     assert tv.tv1d_fwd_workspace_bytes(tv.rows_along((4096, 8), 0), lam) == 0          # strided rows
     L = tv.lib()

@@ -80,6 +80,28 @@ def test_multilevel_start(n):
     assert np.array_equal(a, b)
 
 
+@pytest.mark.parametrize("n", [2049, 5000, 16384])
+def test_multilevel_start_with_stacked_levels(n):
+    """Levels n/4, n/16, ... down to 256 samples instead of the one level that the library takes
+    by default: every level but the coarsest starts from the level below it."""
+    import paper_2204_03643_amd as tv
+    rng = np.random.default_rng(1700 + n)
+    y = _mixed_rows(rng, 6, n)
+    g = rng.normal(size=y.shape).astype(np.float32)
+    lam = (10 ** np.linspace(-2, 1, 6)).astype(np.float32)
+    default = tv.tv_dispatch_threshold("ml_coarsest")
+    tv.tv_dispatch_override("ml_coarsest", 256)
+    try:
+        ml = _check(y, lam, 1, g, -1, "stacked levels n=%d" % n, use_ws=True)
+        own = _check(y, lam, 1, g, -1, "stacked levels inside x n=%d" % n)
+        a = run_1d(y, lam, 1, use_ws=True)["x"]
+        b = run_1d(y, lam, 1)["x"]
+    finally:
+        tv.tv_dispatch_override("ml_coarsest", default)
+    assert np.array_equal(own["steps"], ml["steps"]) and np.array_equal(a, b)
+    assert ml["steps"][lam >= 1.0].max() <= 10
+
+
 @pytest.mark.parametrize("n", [40, 90, 160, 300, 700, 3000])
 @pytest.mark.parametrize("lam", [1e3, 1e5])
 def test_lambda_far_beyond_lam_max(n, lam):
