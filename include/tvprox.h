@@ -111,7 +111,7 @@ int tv1d_prox_fwd_info(const float *y, float *x, int32_t *info, tv_rows rows, tv
  *           stopped needing many more steps than their neighbours); with it the call always
  *           runs the row-per-lane kernels, and its results are bit-identical to those of
  *           the same kernels without it;
- *         - unit-stride rows of 1025 samples or more get a multilevel start: the row averaged
+ *         - unit-stride rows of 769 samples or more get a multilevel start: the row averaged
  *           in groups of 4 samples, with lambda / 4, is solved first (from the cold start; rows
  *           beyond 16384 samples do not occur) and its dual, prolonged, is where the Newton
  *           iteration of the row itself starts.  The paper does not fix the starting point (Sec. 3.2); the

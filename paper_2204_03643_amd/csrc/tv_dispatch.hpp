@@ -156,10 +156,13 @@ inline Threshold table[kCount] = {
     // white noise and noisy steps of 64 samples: n = 768: 106 / 101, 113 / 116, 88 / 103; 1024:
     // 115 / 95, 127 / 118, 96 / 105 (these two with rows taking the start from lambda >= 2 x their
     // mean |y[k+1] - y[k]| on; the others from 0.5 x); 1280: 200 / 153, 233 / 187, 163 / 156;
-    // 2048: 140 / 122, 187 / 151, 125 / 128; 4096: 150 / 124, 185 / 167, 125 / 123.  From 1025
-    // samples on (128 threads and more per row) it wins on two kinds of rows out of three and
-    // ties on the third.
-    {"ml_min_length", 1025, "multilevel start for unit-stride rows of this many samples or more"},
+    // 2048: 140 / 122, 187 / 151, 125 / 128; 4096: 150 / 124, 185 / 167, 125 / 123.  With the
+    // one coarse level of ml_coarsest below: n = 520: 135 / 123, 136 / 151, 113 / 121; 600:
+    // 123 / 114, 123 / 131, 105 / 113; 768: 105 / 100, 114 / 117, 88 / 98; 900: 136 / 105,
+    // 158 / 133, 114 / 104; 1024: 118 / 96, 127 / 115, 98 / 104; 1100: 229 / 142, 248 / 183,
+    // 195 / 152.  From 769 samples on (16 samples per thread and more) it wins on two kinds of
+    // rows out of three and is within 6 % on the third.
+    {"ml_min_length", 769, "multilevel start for unit-stride rows of this many samples or more"},
     // ... and levels are stacked (one at least) until a row has at most this many samples.  One
     // level, solved from the cold start, is what pays: every further level is two more launches,
     // and the cold start of a row of a few thousand samples is cheap next to the fine level.

@@ -107,7 +107,7 @@ def test_step_record_validation():
 def test_dispatch_thresholds_are_listed_and_overridable():
     th = tv.tv_dispatch_thresholds()
     assert {"stream_bytes", "plane_per_group_planes", "fused32_full_planes", "ml_min_length"} <= set(th)
-    assert th["ml_min_length"] == 1025 and tv.tv_dispatch_threshold("no_such_name") == -1
+    assert th["ml_min_length"] == 769 and tv.tv_dispatch_threshold("no_such_name") == -1
     tv.tv_dispatch_override("ml_min_length", 4096)
     assert tv.tv_dispatch_threshold("ml_min_length") == 4096
     assert tv.tv1d_fwd_workspace_bytes(tv.rows_along((10, 2048), -1), tv.tv_lambda(FAKE, 1, 1)) == 0
@@ -181,14 +181,14 @@ def test_rows_along():
 
 def test_forward_workspace_of_long_rows():
     lam = tv.tv_lambda(FAKE, 1, 1)
-    # unit-stride rows of 1025 samples or more: one coarse level of n/4 samples (further ones
+    # unit-stride rows of 769 samples or more: one coarse level of n/4 samples (further ones
     # only beyond ml_coarsest = 4096 samples), two arrays, plus a flag per row
     r = tv.rows_along((10, 16384), -1)
     assert tv.tv1d_fwd_workspace_bytes(r, lam) == 2 * 10 * 4096 * 4 + 48
     tv.tv_dispatch_override("ml_coarsest", 256)
     assert tv.tv1d_fwd_workspace_bytes(r, lam) == 2 * 10 * (4096 + 1024 + 256) * 4 + 48
     tv.tv_dispatch_override("ml_coarsest", 4096)
-    assert tv.tv1d_fwd_workspace_bytes(tv.rows_along((10, 1024), -1), lam) == 0
+    assert tv.tv1d_fwd_workspace_bytes(tv.rows_along((10, 768), -1), lam) == 0
     assert tv.tv1d_fwd_workspace_bytes(tv.rows_along((4096, 8), 0), lam) == 0          # strided rows
     L = tv.lib()
     need = tv.tv1d_fwd_workspace_bytes(r, lam)

@@ -55,7 +55,7 @@ def test_every_long_length(n):
     _check(y, lam, 1, g, -1, "n=%d" % n)
 
 
-@pytest.mark.parametrize("n", [1025, 1280, 1536, 1537, 2048, 2049, 3000, 4096, 5000, 8192, 10001, 16384])
+@pytest.mark.parametrize("n", [769, 900, 1024, 1025, 1280, 1536, 1537, 2048, 2049, 3000, 4096, 5000, 8192, 10001, 16384])
 def test_multilevel_start(n):
     """Long unit-stride rows start from the duals of the averaged rows: with the workspace of
     tv1d_prox_fwd_ex, and without one when x is a buffer of its own (packed rows), whose rows then

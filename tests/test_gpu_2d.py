@@ -52,7 +52,7 @@ def test_mid_planes(shape, K):
 
 def test_wide_planes_whose_first_row_pass_takes_the_multilevel_start():
     """Planes 2304 samples wide: the first row pass of the 2D call is a cold call on packed
-    unit-stride rows of 1025 samples or more, which keeps the levels of its multilevel start in the
+    unit-stride rows of 769 samples or more, which keeps the levels of its multilevel start in the
     rows of its output (the first saved pass output); the later row passes start from their own
     dual, and the column passes are strided rows of 6 samples."""
     rng = np.random.default_rng(2304)

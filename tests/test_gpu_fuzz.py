@@ -22,7 +22,7 @@ def _gen(rng, shape):
 
 def _case_1d(rng):
     nd = int(rng.integers(2, 4))
-    n = int(rng.choice([rng.integers(1, 40), rng.integers(33, 700), rng.integers(1025, 1600), rng.integers(2048, 2600)]))
+    n = int(rng.choice([rng.integers(1, 40), rng.integers(33, 700), rng.integers(769, 1600), rng.integers(2048, 2600)]))
     pos = int(rng.integers(0, nd))
     shape = [int(rng.integers(1, 7)) for _ in range(nd)]
     if rng.random() < 0.5:
