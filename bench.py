@@ -161,8 +161,8 @@ def other_workloads(dev, reps: int = 25):
         extra = {}
         fwsb = tv.tv1d_fwd_workspace_bytes(rows, L)
         if fwsb:
-            # the forward call with its workspace (slot order on short rows, multilevel start on
-            # long ones)
+            # the forward call with its workspace (slot order on short rows; on long ones the level
+            # of the multilevel start in the workspace instead of in the rows of x)
             fws = torch.empty(fwsb, dtype=torch.uint8, device=dev)
             te, te_min = timed(lambda k: tv.tv1d_prox_fwd_ex(yt[k], xt[k], rows, L, ws=fws, ws_bytes=fwsb))
             extra = {"fwd_ex_ws_us": te, "fwd_ex_ws_us_min": te_min, "fwd_ws_bytes": fwsb}
