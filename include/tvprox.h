@@ -112,16 +112,15 @@ int tv1d_prox_fwd_info(const float *y, float *x, int32_t *info, tv_rows rows, tv
  *           runs the row-per-lane kernels, and its results are bit-identical to those of
  *           the same kernels without it;
  *         - unit-stride rows of 769 samples or more get a multilevel start: the row averaged
- *           in groups of 4 samples, with lambda / 4, is solved first (from the cold start; rows
- *           beyond 16384 samples do not occur) and its dual, prolonged, is where the Newton
- *           iteration of the row itself starts.  The paper does not fix the starting point (Sec. 3.2); the
- *           minimiser is the same, and rows whose lambda is large against their
- *           sample-to-sample variation take 4 steps instead of 10-30.  Scratch: half of the
- *           input's size.  Without ws (and in tv1d_prox_fwd) the same start is taken
+ *           in groups of 4 samples, with lambda / 4, is solved first, from the cold start, and
+ *           its dual, prolonged, is where the Newton iteration of the row itself starts.  The
+ *           paper does not fix the starting point (Sec. 3.2); the minimiser is the same, and
+ *           rows whose lambda is large against their sample-to-sample variation take 4 steps
+ *           instead of 10-30.  Scratch: half of the input's size.  Without ws (and in tv1d_prox_fwd) the same start is taken
  *           with the levels of a row kept in that row of x until the fine level overwrites it,
  *           whenever the rows are packed (no gap between them) and x does not overlap y; the
- *           results are bit-identical to those with ws.  A call in place (x == y), rows with
- *           gaps and strided rows start cold without ws.
+ *           results are bit-identical to those with ws.  A call in place (x == y) and rows
+ *           with gaps between them start cold without ws; strided rows always do.
  *         tv1d_fwd_workspace_bytes() returns 0 where neither applies (ws is then unused).
  *   flags: 0 or a combination of
  *         TV_FWD_ORDER_READY: ws still holds the slot order that an earlier call with
