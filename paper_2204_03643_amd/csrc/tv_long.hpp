@@ -457,6 +457,9 @@ constexpr int fwd_waves_per_simd()
     if (XPOSE && C <= 4) return 8;
     if (C == 8 && (T * G <= 256 || (XPOSE && T * G == 512))) return 6;
     if (C == 12 && T * G <= 256 && T != 128 && !(XPOSE && T == 32)) return 5;
+    // (64 threads x 16 samples from an addend's dual: 130 VGPRs left alone, 128 and a fourth wave
+    // on request; six images of 1024 x 1024, K = 3: 434 -> 418 us)
+    if (C == 16 && T * G <= 256) return 4;
     return 1;
 }
 template <int T, int C, int G, bool COLS, bool XPOSE = false, int WARM = 0, bool DEBUG = false>
