@@ -410,6 +410,10 @@ def dispatch_probe(dev) -> int:
     n = defaults["fused16_one_sweep_planes"]
     case("fused16_one_sweep_planes", "at_threshold_k1", lambda: two_d(n, 16, 16, 1), 0, "one launch", "pass by pass")
     case("fused16_one_sweep_planes", "beyond_k1", lambda: two_d(n + n // 4, 16, 16, 1), big, "pass by pass", "one launch")
+    n = defaults["fused16_dense_planes"]
+    case("fused16_dense_planes", "at_threshold_k2", lambda: two_d(n, 16, 16, 2), big, "four waves per SIMD", "three")
+    case("fused16_dense_planes", "just_below_k2", lambda: two_d(n - n // 4, 16, 16, 2), 0, "three waves per SIMD", "four")
+    case("fused16_dense_planes", "at_four_times_k4", lambda: two_d(4 * n, 16, 16, 4), big, "four waves per SIMD", "three")
     n = defaults["thread_per_sample_wide_rows"]
     case("thread_per_sample_wide_rows", "at_threshold", lambda: one_d((n // (128 * 32), 128, 32, 32), 128, 32, False), 0,
          "16 threads x 2 samples per row", "8 x 4")

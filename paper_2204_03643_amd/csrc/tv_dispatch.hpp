@@ -23,6 +23,7 @@ enum {
     kFused32FullPlanesK3,
     kFused32RaggedPlanes,
     kFused16OneSweepPlanes,
+    kFused16DensePlanes,
     kPlanePerGroupPlanes,
     kPlanePerGroup64Planes,
     kPlanePerGroup64PlanesK2,
@@ -78,8 +79,15 @@ inline Threshold table[kCount] = {
     {"fused32_ragged_planes", 4096, "2D ragged planes padded to 32 x 32, one sweep: one launch up to this many planes"},
     // 2D, planes of 9-16 samples a side, single sweep, forward + backward: 16 384 planes 58 in one
     // launch against 58 pass by pass, 24 576: 70 / 75, 32 768: 88 / 86 (K = 3: 166 against 206
-    // forward, so several sweeps always take the one launch).
-    {"fused16_one_sweep_planes", 24576, "2D planes of at most 16 x 16, one sweep: one launch up to this many planes"},
+    // forward, so several sweeps always take the one launch).  With the four-waves variant of
+    // the one-launch kernel (fused16_dense_planes below): 49 152 planes 110 / 113, 61 440: 132 / 134.
+    {"fused16_one_sweep_planes", 49152, "2D planes of at most 16 x 16, one sweep: one launch up to this many planes"},
+    // ... and from this many planes on the one-launch kernel for planes of 9-16 a side is the
+    // variant held to 128 VGPRs (four waves per SIMD, 16-54 registers spilled): 8192 planes do not
+    // fill the three waves that the other variant allows (K = 2: 43 us against 45), 65 536 do
+    // (K = 4: 334 against 302).  The crossover is where the waves outnumber three per SIMD: 4
+    // planes per wave x 3 x 1024 SIMDs.
+    {"fused16_dense_planes", 24576, "2D planes of 9-16 a side in one launch: the four-waves-per-SIMD variant from this many planes on"},
     // 2D, small batches: one plane per workgroup of 512 threads, resident in LDS for all passes,
     // 16 threads x 2 samples per row (sides of 17-32) or 8 x 8 (sides of 33-64); tv_plane2d.hpp.
     // A lone row-per-lane wave per SIMD issues an instruction every 9 cycles, and pass by pass a

@@ -353,11 +353,11 @@ struct Small2dFwdParams {
 // arrays of 64 registers, the whole register file of a SIMD lane, for one wave per SIMD.)
 // Waves per SIMD asked of the register allocator: two at least; six for planes of 8 x 8 (80 VGPRs
 // instead of 87-96 at the price of 3-5 spilled registers: 65 536 planes, K = 4: 98 -> 95 us).
-// Four for planes of 16 x 16 (128 VGPRs instead of 145-168, 16-54 spilled) would take 65 536
-// planes with K = 4 from 334 to 302 us but 8192 planes with K = 2, which do not fill three waves
-// per SIMD anyway, from 43 to 45: not requested.
-template <int S, bool FULL, bool IO16 = false>
-__global__ __launch_bounds__(64, (S == 8 ? 6 : 2)) void tv2d_fwd_small_kernel(Small2dFwdParams p)
+// Four for planes of 16 x 16 (128 VGPRs instead of 145-168, 16-54 spilled) take 65 536 planes
+// with K = 4 from 334 to 302 us but 8192 planes with K = 2, which do not fill three waves per SIMD
+// anyway, from 43 to 45: that is the variant DENSE, which the dispatch takes for large batches.
+template <int S, bool FULL, bool IO16 = false, bool DENSE = false>
+__global__ __launch_bounds__(64, (S == 8 ? 6 : ((S == 16 && DENSE) ? 4 : 2))) void tv2d_fwd_small_kernel(Small2dFwdParams p)
 {
     static_assert(S <= 32, "a row or column per lane: planes of at most 32 x 32");
     constexpr int P = S + 1;

@@ -1273,6 +1273,12 @@ int tv2d_prox_fwd(const float *y, float *x, int64_t planes, int64_t H, int64_t W
         q.lam = lam.lam; q.lam_count = lam.count;
         q.planes = (int32_t)planes; q.H = (int32_t)H; q.W = (int32_t)W; q.sweeps = sweeps;
         q.stream = (planes * H * W >= tvd::get(tvd::kStreamBytes) / 4) ? 1u : 0u;
+        if (small_side(H, W) == 16 && planes >= tvd::get(tvd::kFused16DensePlanes)) {
+            const dim3 grid((uint32_t)((planes + 3) / 4));
+            if (H == 16 && W == 16) hipLaunchKernelGGL((tvk::tv2d_fwd_small_kernel<16, true, false, true>), grid, dim3(64), 0, stream, q);
+            else hipLaunchKernelGGL((tvk::tv2d_fwd_small_kernel<16, false, false, true>), grid, dim3(64), 0, stream, q);
+            return launch_status();
+        }
         TV_SMALL2D_LAUNCH(tvk::tv2d_fwd_small_kernel, q, planes, H, W, stream);
         return launch_status();
     }

@@ -192,6 +192,25 @@ def test_every_forward_mapping_of_small_planes(shape, K, dispatch_defaults):
         assert np.abs(o["x"] - outs[0]["x"]).max() <= 2e-5 * (1 + np.abs(y).max())
 
 
+@pytest.mark.parametrize("shape,K", [((70, 16, 16), 1), ((70, 16, 16), 3), ((33, 12, 14), 2), ((9, 9, 16), 4)])
+def test_one_launch_forward_of_16_side_planes_in_its_large_batch_variant(shape, K, dispatch_defaults):
+    """Planes of 9-16 a side: from `fused16_dense_planes` planes on the one-launch forward kernel is
+    the variant built for four waves per SIMD.  Same source, other register allocation: forced
+    onto a small batch, it must give the bits of the ordinary variant and pass the parity rules."""
+    import paper_2204_03643_amd as tv
+    rng = np.random.default_rng(160 + shape[1] * 16 + shape[2] + K)
+    y = rng.normal(size=shape).astype(np.float32)
+    g = rng.normal(size=shape).astype(np.float32)
+    lam = (10 ** rng.uniform(-2, 0.3, size=3)).astype(np.float32)
+    tv.tv_dispatch_override("fused16_one_sweep_planes", 1 << 40)
+    tv.tv_dispatch_override("fused16_dense_planes", 1 << 40)
+    ref = run_2d(y, lam, K, g)
+    tv.tv_dispatch_override("fused16_dense_planes", 0)
+    out = run_2d(y, lam, K, g)
+    check_2d(y, lam, K, g, out, "dense 16-side variant %s K=%d" % (shape, K))
+    assert np.array_equal(out["x"], ref["x"]) and np.array_equal(out["gy"], ref["gy"])
+
+
 @pytest.mark.parametrize("shape,K", [((70, 32, 32), 2), ((37, 28, 30), 3), ((9, 17, 32), 4), ((5, 32, 3), 2), ((3, 1, 20), 2),
                                      ((4, 31, 1), 1), ((260, 32, 32), 1), ((5, 64, 64), 3), ((3, 40, 56), 2), ((4, 33, 64), 2),
                                      ((2, 64, 35), 1), ((70, 48, 48), 4), ((1, 33, 33), 1), ((3, 2, 64), 2), ((300, 64, 64), 1)])
