@@ -435,6 +435,8 @@ struct LongSmemBwd {
 // are transposed through an LDS tile on the way in and out, and the solve itself runs in the
 // ROWS mapping with one row per wave, i.e. without any workgroup barrier.
 // WARM = 1: p.addend is given and the solve starts from the dual it encodes.
+// WARM = 3: the cold start picks between two candidates (see there); for long rows that cannot
+// take the multilevel start.
 // WARM = 2 (unit-stride rows, C a multiple of kMlFactor): rows flagged in p.ml_flag start from
 // the dual of the same row averaged in groups of kMlFactor samples (p.coarse_u), which a launch
 // on the averaged rows with lambda / kMlFactor left behind (p.dual_out of that launch).
@@ -645,6 +647,46 @@ __global__ __launch_bounds__(T *G, (fwd_waves_per_simd<T, C, G, COLS, XPOSE>()))
                 const float dy = ((i + 1 < C) ? y[i + 1] : ynext0) - y[i];
                 u[i] = __builtin_amdgcn_fmed3f(dy * 1e30f, -l, l);
             }
+            if constexpr (WARM == 3) {
+                // The other candidate: the dual of the constant row, u_k = sum_{i <= k} (mean(y) -
+                // y_i), clipped into the box.  It is the solution whenever lam >= lam_max =
+                // max_k |u_k|, and from lam_max / 4 on it is the better start by far (few segments:
+                // from the bounds every Newton step frees only a few more duals, and random-walk
+                // rows of 5000-16 384 samples with lambda from 0.3 lam_max on were still moving
+                // after 128 steps; from here they take a handful).  Below lam_max / 4 the bounds
+                // win.  Three more row-wide reductions: only the long rows that cannot take the
+                // multilevel start pay for it (5-15 % of a cold call).
+                int ns = min(max(n - k0, 0), C);               // samples of this chunk inside the row
+                asm volatile("" : "+v"(ns));
+                float tot[1] = {0.f};
+#pragma unroll
+                for (int i = 0; i < C; ++i) tot[0] += (i < ns) ? y[i] : 0.f;
+                row_sum<T, G, MCOLS, 1>(tot, sm.red, j, tid);
+                const float mean = tot[0] / (float)n;
+                float mine = 0.f;
+#pragma unroll
+                for (int i = 0; i < C; ++i) mine += (i < ns) ? mean - y[i] : 0.f;
+                float before, unused;
+                seg_scan<T, G, MCOLS, +1, true>(false, mine, 0.f, sm.buf, j, t, before, unused);
+                float run = before;
+                float am[1] = {0.f};
+#pragma unroll
+                for (int i = 0; i < C; ++i) {
+                    run += mean - y[i];
+                    if (i < nv) am[0] = fmaxf(am[0], fabsf(run));
+                }
+                row_max<T, G, MCOLS>(am, sm.red, j, tid);
+                if (lam >= 0.25f * am[0]) {                    // (never with a NaN or Inf in the row)
+                    run = before;
+#pragma unroll
+                    for (int i = 0; i < C; ++i) {
+                        const float l = TV_LK(i);
+                        run += mean - y[i];
+                        u[i] = __builtin_amdgcn_fmed3f(run, -l, l);
+                    }
+                }
+                Mp::sync();
+            }
         }
         if constexpr (WARM == 2) {
             // Prolongation of the coarse dual.  The coarse row is this row with every group of
@@ -705,6 +747,7 @@ __global__ __launch_bounds__(T *G, (fwd_waves_per_simd<T, C, G, COLS, XPOSE>()))
 
     bool active = rvalid;
     bool prev_unclipped = false;
+    bool prev_tiny = false;          // WARM = 3: the step before moved x by less than the rounding floor
     int steps = 0, flags = 0;
     int par = 0, vp = 0;
     float *rec = nullptr;
@@ -792,6 +835,13 @@ __global__ __launch_bounds__(T *G, (fwd_waves_per_simd<T, C, G, COLS, XPOSE>()))
         }
 
         if (active && prev_unclipped && !vio) { active = false; flags = kInfoConverged; }
+        // (the constant row's dual can leave a dual exactly on its bound with a gradient that is
+        // rounding noise, lambda = lam_max being the extreme case: such a dual changes sides with
+        // every step and no step is ever clipped-free; a step whose decrement, the squared move of
+        // x, is below the floor of a difference of two x values ends the solve there)
+        if constexpr (WARM == 3) {
+            if (active && prev_tiny && !vio) { active = false; flags = kInfoConverged; }
+        }
         if (active && it >= kMaxNewtonSteps) { active = false; flags = kInfoCapped; }
         if (Mp::SOLO) { if (!active) break; }               // row-wide flags are uniform here
         else if (!Mp::sync_any(active, sm.vote, vp)) break;
@@ -940,6 +990,7 @@ __global__ __launch_bounds__(T *G, (fwd_waves_per_simd<T, C, G, COLS, XPOSE>()))
 #pragma unroll
         for (int i = 0; i < C; ++i) u[i] = uc[i];
         prev_unclipped = (alpha == 1.f) && !clipped;
+        if constexpr (WARM == 3) prev_tiny = dec <= gtol * gtol;
         // A full Newton step lands on the minimiser of its free set only up to the rounding of
         // the solve, which grows with the step (|d| <= 2 lam).  A cold start ends in small steps;
         // a start from a coarser level's dual can end in its first or second step, and where
@@ -1250,7 +1301,11 @@ inline hipError_t launch_fwd_long_t(const FwdParams &p, hipStream_t s)
             hipLaunchKernelGGL((tv1d_fwd_long_kernel<T, C, G, COLS, XP, 2>), grid, block, 0, s, p);
         else
             return hipErrorInvalidValue;
-    } else if (p.warm)
+    } else if (p.warm == 3 && T * C > 768) {
+        // (cold, with the constant row's dual as a second candidate: rows of 769 samples and more)
+        if constexpr (T * C > 768)
+            hipLaunchKernelGGL((tv1d_fwd_long_kernel<T, C, G, COLS, XP, 3>), grid, block, 0, s, p);
+    } else if (p.warm == 1)
         hipLaunchKernelGGL((tv1d_fwd_long_kernel<T, C, G, COLS, XP, 1>), grid, block, 0, s, p);
     else
         hipLaunchKernelGGL((tv1d_fwd_long_kernel<T, C, G, COLS, XP, 0>), grid, block, 0, s, p);

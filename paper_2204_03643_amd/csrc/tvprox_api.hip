@@ -642,6 +642,10 @@ int run_fwd(const float *y, const float *addend, float *x, float *resid, int32_t
         if (pl.row_floats > 0 && rows_packed(r) && (x_end <= y || y_end <= x))
             return run_fwd_multilevel(p, l, n_rows, pl, nullptr, s);
     }
+    // long rows that start cold after all (in place, with gaps between them, strided): the cold
+    // start with two candidates, which does not run into the step cap when lambda is of the
+    // order of the row's lam_max
+    if (!p.warm && r.length > 768) p.warm = 3;
     return tvk::launch_fwd_long(p, s) == hipSuccess ? TV_OK : TV_ERR_HIP;
 }
 

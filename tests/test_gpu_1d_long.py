@@ -131,6 +131,26 @@ def test_multilevel_start_with_lambda_of_the_order_of_lam_max(n, lam):
     assert a["fwd_max_err"] <= 0.5 * FWD_TOL
 
 
+@pytest.mark.parametrize("n,fac", [(5000, 0.3), (5000, 1.0), (12000, 1.0), (12000, 3.0), (16384, 3.0)])
+@pytest.mark.parametrize("layout", ["in place", "strided"])
+def test_cold_long_rows_with_lambda_of_the_order_of_lam_max(n, fac, layout):
+    """Long rows that cannot take the multilevel start (a call in place, strided rows) start cold
+    with two candidates: every dual on the bound its local difference points to, or the clipped
+    dual of the constant row, which is the solution from lam_max on.  Random-walk rows with
+    lambda = 0.3-3 lam_max ran into the step cap from the first candidate alone."""
+    rng = np.random.default_rng(4000 + n)
+    rows = 4
+    y = np.cumsum(0.05 * rng.normal(size=(rows, n)), axis=-1).astype(np.float32)
+    lmax = np.abs(np.cumsum(y.mean(1, keepdims=True) - y.astype(np.float64), axis=1)).max(1)
+    lam = (fac * lmax).astype(np.float32)
+    g = rng.normal(size=y.shape).astype(np.float32)
+    if layout == "in place":
+        st = _check(y, lam, 1, g, -1, "in place n=%d fac=%g" % (n, fac), in_place=True)
+    else:
+        st = _check(np.ascontiguousarray(y.T), lam, 1, np.ascontiguousarray(g.T), 0, "strided n=%d fac=%g" % (n, fac))
+    assert st["max_steps"] <= (100 if fac < 1 else 20)
+
+
 def test_noise_rows_with_lambda_near_lam_max():
     """Noise-like long rows with lambda a third of their lam_max are the worst case of the cold
     start (every dual on the bound its local difference points to): dozens of Newton steps.
